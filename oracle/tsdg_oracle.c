@@ -1,0 +1,604 @@
+/*
+ * CPU oracle for the two-stage diversified graph (TSDG) build and the
+ * best-first k-NN search over it.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, obviously-correct
+ * statement of what the GPU path must compute.  Only the tests, the smoke
+ * check and the benchmark's "cpu_baseline" leg may call it.  It shares no
+ * code, header, table or helper with the HIP library, and the HIP library
+ * never calls it.
+ *
+ * What is followed, and where the paper fixes it:
+ *   - k-NN graph: the plain definition (all pairs, sort, keep K).  The paper
+ *     starts from an approximate k-NN graph built by another method (Sec. 5.2);
+ *     this build uses the exact one.
+ *   - stage 1, relaxed diversification: Sec. 3.2, Eq. 2, with the checking
+ *     order of Sec. 3.1 (closest first, each next edge against all kept ones).
+ *   - reverse edges, then stage 2 (occlusion factor lambda by Eq. 1, sort by
+ *     (lambda, distance), drop lambda > lambda0): Sec. 3.3.
+ *   - search: best-first walk over one bounded sorted rank-list that serves
+ *     as result list and expansion queue (the CPU procedure named in Sec. 4 /
+ *     Sec. 5.3, started from 32 random seeds as in Alg. 2), visiting only the
+ *     prefix of each neighbour list whose lambda is below a threshold
+ *     (Sec. 3.3 last paragraph, Sec. 5.4).
+ *   - recall: Eq. 3.
+ *
+ * Deterministic readings where the paper is silent (ties, seeds, caps) are
+ * listed at each function.  Order everywhere: key (s, id), smaller id first.
+ *
+ * Distances are SQUARED L2.  The canonical value is
+ *     s(a,b) = fl32( sum_j (double)( fl32(a_j - b_j) )^2 )
+ * i.e. the difference is rounded once to fp32, its square (exact in fp64) is
+ * accumulated in fp64 and the sum is rounded once to fp32.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py
+ * (closed forms, brute force written independently in numpy, invariants).
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (see build.py).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_F32 0
+#define ORC_U8 1
+
+typedef struct {
+    float s;
+    int32_t id;
+} pair_t;
+
+/* (s, id) order: smaller distance first, then smaller id. */
+static int pair_less(pair_t a, pair_t b)
+{
+    if (a.s < b.s) return 1;
+    if (a.s > b.s) return 0;
+    return a.id < b.id;
+}
+
+static int pair_cmp(const void* pa, const void* pb)
+{
+    pair_t a = *(const pair_t*)pa, b = *(const pair_t*)pb;
+    if (pair_less(a, b)) return -1;
+    if (pair_less(b, a)) return 1;
+    return 0;
+}
+
+/* Row i of the base set as fp32 (uint8 converts exactly). */
+static const float* row_f32(const void* base, int dtype, int64_t i, int d, float* tmp)
+{
+    if (dtype == ORC_F32) return (const float*)base + i * (int64_t)d;
+    const uint8_t* r = (const uint8_t*)base + i * (int64_t)d;
+    for (int j = 0; j < d; ++j) tmp[j] = (float)r[j];
+    return tmp;
+}
+
+/* Canonical squared L2 distance (see the header). */
+float orc_sqdist(const float* a, const float* b, int d)
+{
+    double acc = 0.0;
+    for (int j = 0; j < d; ++j) {
+        float t = a[j] - b[j];
+        acc += (double)t * (double)t;
+    }
+    return (float)acc;
+}
+
+static float sqdist_rows(const void* base, int dtype, int d, int64_t i, int64_t j,
+                         float* tmp_i, float* tmp_j)
+{
+    const float* a = row_f32(base, dtype, i, d, tmp_i);
+    const float* b = row_f32(base, dtype, j, d, tmp_j);
+    return orc_sqdist(a, b, d);
+}
+
+static int use_threads(int threads)
+{
+#ifdef _OPENMP
+    if (threads <= 0) threads = omp_get_max_threads();
+    return threads;
+#else
+    (void)threads;
+    return 1;
+#endif
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------
+ * Exact top-k of each query against the whole base set (plain definition).
+ * exclude_self != 0: query i is base row i and id i is left out (k-NN graph).
+ * out_ids/out_s are [nq,k]; missing entries (N too small) are -1 / +inf.
+ * ---------------------------------------------------------------------- */
+int orc_bruteforce(const void* base, int dtype, int64_t N, int d,
+                   const float* queries, int64_t nq, int k, int exclude_self,
+                   int32_t* out_ids, float* out_s, int threads)
+{
+    if (!base || N <= 0 || d <= 0 || k <= 0 || nq < 0) return 1;
+    threads = use_threads(threads);
+    int failed = 0;
+#pragma omp parallel num_threads(threads)
+    {
+        pair_t* all = (pair_t*)malloc(sizeof(pair_t) * (size_t)N);
+        float* tq = (float*)malloc(sizeof(float) * (size_t)d);
+        float* tb = (float*)malloc(sizeof(float) * (size_t)d);
+        if (!all || !tq || !tb) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t qi = 0; qi < nq; ++qi) {
+                const float* q = exclude_self ? row_f32(base, dtype, qi, d, tq)
+                                              : queries + qi * (int64_t)d;
+                int64_t m = 0;
+                for (int64_t j = 0; j < N; ++j) {
+                    if (exclude_self && j == qi) continue;
+                    const float* b = row_f32(base, dtype, j, d, tb);
+                    all[m].s = orc_sqdist(q, b, d);
+                    all[m].id = (int32_t)j;
+                    ++m;
+                }
+                qsort(all, (size_t)m, sizeof(pair_t), pair_cmp);
+                for (int t = 0; t < k; ++t) {
+                    if (t < m) {
+                        out_ids[qi * k + t] = all[t].id;
+                        out_s[qi * k + t] = all[t].s;
+                    } else {
+                        out_ids[qi * k + t] = -1;
+                        out_s[qi * k + t] = INFINITY;
+                    }
+                }
+            }
+        }
+        free(all);
+        free(tq);
+        free(tb);
+    }
+    return failed ? 2 : 0;
+}
+
+/* Exact k-NN graph: row i = the K nearest other points by (s, id). */
+int orc_knn(const void* base, int dtype, int64_t N, int d, int K,
+            int32_t* knn_id, float* knn_s, int threads)
+{
+    return orc_bruteforce(base, dtype, N, d, NULL, N, K, 1, knn_id, knn_s, threads);
+}
+
+/* ------------------------------------------------------------------------
+ * Stage 1 (Sec. 3.2, Eq. 2; order rule of Sec. 3.1).
+ * The list of x0 is in (s,id) order.  The closest neighbour is kept; edge j
+ * is dropped iff some already-kept edge i has
+ *      alpha2 * s(x0,xi) < s(x0,xj)   and   alpha2 * s(xi,xj) < s(x0,xj)
+ * with alpha2 = fl32(alpha*alpha) (the paper states the rule on the L2
+ * distance m; squaring both sides gives alpha^2 on squared distances) and
+ * each product one fp32 multiply.  Output g1_* is [N,K], kept edges first in
+ * their original order, padded with -1 / +inf; g1_deg[N] = number kept.
+ * ---------------------------------------------------------------------- */
+int orc_stage1(const void* base, int dtype, int64_t N, int d, int K,
+               const int32_t* knn_id, const float* knn_s, float alpha,
+               int32_t* g1_id, float* g1_s, int32_t* g1_deg, int threads)
+{
+    if (!base || !knn_id || !knn_s || N <= 0 || K <= 0) return 1;
+    threads = use_threads(threads);
+    const float alpha2 = alpha * alpha;
+#pragma omp parallel num_threads(threads)
+    {
+        float* ti = (float*)malloc(sizeof(float) * (size_t)d);
+        float* tj = (float*)malloc(sizeof(float) * (size_t)d);
+#pragma omp for schedule(dynamic, 64)
+        for (int64_t x0 = 0; x0 < N; ++x0) {
+            const int32_t* ids = knn_id + x0 * K;
+            const float* ss = knn_s + x0 * K;
+            int32_t* oid = g1_id + x0 * K;
+            float* os = g1_s + x0 * K;
+            int nk = 0;
+            for (int j = 0; j < K; ++j) {
+                if (ids[j] < 0) break;
+                int occluded = 0;
+                for (int t = 0; t < nk && !occluded; ++t) {
+                    float s0i = os[t];
+                    float s0j = ss[j];
+                    if (alpha2 * s0i < s0j) {
+                        float sij = sqdist_rows(base, dtype, d, oid[t], ids[j], ti, tj);
+                        if (alpha2 * sij < s0j) occluded = 1;
+                    }
+                }
+                if (!occluded) {
+                    oid[nk] = ids[j];
+                    os[nk] = ss[j];
+                    ++nk;
+                }
+            }
+            g1_deg[x0] = nk;
+            for (int t = nk; t < K; ++t) {
+                oid[t] = -1;
+                os[t] = INFINITY;
+            }
+        }
+        free(ti);
+        free(tj);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Reverse edges (Sec. 3.3, second sentence): list(x0) = kept(x0) united with
+ * { y : x0 in kept(y) }.  Reading where the paper is silent: duplicates are
+ * removed by id, the list is sorted by (s,id) with s = s(x0,y) computed
+ * directly, and it is cut to rev_cap entries (hub nodes have unbounded
+ * in-degree).  Output g2_* is [N,rev_cap] padded -1 / +inf, g2_deg[N].
+ * ---------------------------------------------------------------------- */
+int orc_reverse(const void* base, int dtype, int64_t N, int d, int K,
+                const int32_t* g1_id, const int32_t* g1_deg, int rev_cap,
+                int32_t* g2_id, float* g2_s, int32_t* g2_deg, int threads)
+{
+    if (!base || !g1_id || !g1_deg || N <= 0 || K <= 0 || rev_cap <= 0) return 1;
+    threads = use_threads(threads);
+    int64_t* start = (int64_t*)calloc((size_t)N + 1, sizeof(int64_t));
+    if (!start) return 2;
+    for (int64_t y = 0; y < N; ++y)
+        for (int t = 0; t < g1_deg[y]; ++t) start[g1_id[y * K + t] + 1]++;
+    for (int64_t i = 0; i < N; ++i) start[i + 1] += start[i];
+    int64_t total = start[N];
+    int32_t* src = (int32_t*)malloc(sizeof(int32_t) * (size_t)(total > 0 ? total : 1));
+    int64_t* cur = (int64_t*)malloc(sizeof(int64_t) * (size_t)N);
+    if (!src || !cur) {
+        free(start); free(src); free(cur);
+        return 2;
+    }
+    memcpy(cur, start, sizeof(int64_t) * (size_t)N);
+    for (int64_t y = 0; y < N; ++y)
+        for (int t = 0; t < g1_deg[y]; ++t) src[cur[g1_id[y * K + t]]++] = (int32_t)y;
+
+#pragma omp parallel num_threads(threads)
+    {
+        float* ti = (float*)malloc(sizeof(float) * (size_t)d);
+        float* tj = (float*)malloc(sizeof(float) * (size_t)d);
+#pragma omp for schedule(dynamic, 64)
+        for (int64_t x0 = 0; x0 < N; ++x0) {
+            int64_t nin = start[x0 + 1] - start[x0];
+            int64_t cap = g1_deg[x0] + nin;
+            pair_t* lst = (pair_t*)malloc(sizeof(pair_t) * (size_t)(cap > 0 ? cap : 1));
+            int64_t m = 0;
+            for (int t = 0; t < g1_deg[x0]; ++t) lst[m++].id = g1_id[x0 * K + t];
+            for (int64_t t = start[x0]; t < start[x0 + 1]; ++t) {
+                int32_t y = src[t];
+                int dup = 0;
+                for (int64_t u = 0; u < m && !dup; ++u) dup = (lst[u].id == y);
+                if (!dup) lst[m++].id = y;
+            }
+            for (int64_t t = 0; t < m; ++t)
+                lst[t].s = sqdist_rows(base, dtype, d, x0, lst[t].id, ti, tj);
+            qsort(lst, (size_t)m, sizeof(pair_t), pair_cmp);
+            int keep = (int)(m < rev_cap ? m : rev_cap);
+            for (int t = 0; t < rev_cap; ++t) {
+                g2_id[x0 * rev_cap + t] = t < keep ? lst[t].id : -1;
+                g2_s[x0 * rev_cap + t] = t < keep ? lst[t].s : INFINITY;
+            }
+            g2_deg[x0] = keep;
+            free(lst);
+        }
+        free(ti);
+        free(tj);
+    }
+    free(start);
+    free(src);
+    free(cur);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Stage 2 (Sec. 3.3): occlusion factor of edge j of node x0
+ *   lambda_j = #{ i != j in the list : s(x0,xi) < s(x0,xj) and s(xi,xj) < s(x0,xj) }
+ * (Eq. 1, counted over the whole list, strict comparisons), then the list is
+ * sorted by (lambda, s, id), entries with lambda > lambda0 are removed, the
+ * list is cut to K and padded with id -1 / lambda 255.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t lam;
+    float s;
+    int32_t id;
+} lam_t;
+
+static int lam_cmp(const void* pa, const void* pb)
+{
+    const lam_t* a = (const lam_t*)pa;
+    const lam_t* b = (const lam_t*)pb;
+    if (a->lam != b->lam) return a->lam < b->lam ? -1 : 1;
+    if (a->s < b->s) return -1;
+    if (a->s > b->s) return 1;
+    if (a->id != b->id) return a->id < b->id ? -1 : 1;
+    return 0;
+}
+
+int orc_stage2(const void* base, int dtype, int64_t N, int d, int rev_cap,
+               const int32_t* g2_id, const float* g2_s, const int32_t* g2_deg,
+               int lambda0, int K, int32_t* adj, uint8_t* lam, int threads)
+{
+    if (!base || !g2_id || !g2_s || !g2_deg || N <= 0 || K <= 0 || rev_cap <= 0) return 1;
+    threads = use_threads(threads);
+#pragma omp parallel num_threads(threads)
+    {
+        float* ti = (float*)malloc(sizeof(float) * (size_t)d);
+        float* tj = (float*)malloc(sizeof(float) * (size_t)d);
+        lam_t* lst = (lam_t*)malloc(sizeof(lam_t) * (size_t)rev_cap);
+#pragma omp for schedule(dynamic, 64)
+        for (int64_t x0 = 0; x0 < N; ++x0) {
+            const int32_t* ids = g2_id + x0 * rev_cap;
+            const float* ss = g2_s + x0 * rev_cap;
+            int m = g2_deg[x0];
+            for (int j = 0; j < m; ++j) {
+                int cnt = 0;
+                for (int i = 0; i < m; ++i) {
+                    if (i == j) continue;
+                    if (ss[i] < ss[j]) {
+                        float sij = sqdist_rows(base, dtype, d, ids[i], ids[j], ti, tj);
+                        if (sij < ss[j]) ++cnt;
+                    }
+                }
+                lst[j].lam = cnt;
+                lst[j].s = ss[j];
+                lst[j].id = ids[j];
+            }
+            qsort(lst, (size_t)m, sizeof(lam_t), lam_cmp);
+            int out = 0;
+            for (int j = 0; j < m && out < K; ++j) {
+                if (lst[j].lam > lambda0) break;
+                adj[x0 * K + out] = lst[j].id;
+                lam[x0 * K + out] = (uint8_t)lst[j].lam;
+                ++out;
+            }
+            for (; out < K; ++out) {
+                adj[x0 * K + out] = -1;
+                lam[x0 * K + out] = 255;
+            }
+        }
+        free(ti);
+        free(tj);
+        free(lst);
+    }
+    return 0;
+}
+
+/* Whole build: exact k-NN -> stage 1 -> reverse edges -> stage 2.
+ * Optional outputs (may be NULL): knn_id/knn_s [N,K] and g1_id [N,K],
+ * g1_deg [N], g2_id/g2_s [N,rev_cap], g2_deg [N] for per-stage parity. */
+int orc_build(const void* base, int dtype, int64_t N, int d, int K, float alpha,
+              int lambda0, int rev_cap, int32_t* adj, uint8_t* lam,
+              int32_t* knn_id_out, float* knn_s_out, int32_t* g1_id_out, int32_t* g1_deg_out,
+              int32_t* g2_id_out, float* g2_s_out, int32_t* g2_deg_out, int threads)
+{
+    if (!base || !adj || !lam || N <= K || K <= 0 || rev_cap <= 0) return 1;
+    size_t nk = (size_t)N * (size_t)K, nr = (size_t)N * (size_t)rev_cap;
+    int32_t* knn_id = (int32_t*)malloc(sizeof(int32_t) * nk);
+    float* knn_s = (float*)malloc(sizeof(float) * nk);
+    int32_t* g1_id = (int32_t*)malloc(sizeof(int32_t) * nk);
+    float* g1_s = (float*)malloc(sizeof(float) * nk);
+    int32_t* g1_deg = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t* g2_id = (int32_t*)malloc(sizeof(int32_t) * nr);
+    float* g2_s = (float*)malloc(sizeof(float) * nr);
+    int32_t* g2_deg = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int rc = 2;
+    if (knn_id && knn_s && g1_id && g1_s && g1_deg && g2_id && g2_s && g2_deg) {
+        rc = orc_knn(base, dtype, N, d, K, knn_id, knn_s, threads);
+        if (!rc) rc = orc_stage1(base, dtype, N, d, K, knn_id, knn_s, alpha, g1_id, g1_s, g1_deg, threads);
+        if (!rc) rc = orc_reverse(base, dtype, N, d, K, g1_id, g1_deg, rev_cap, g2_id, g2_s, g2_deg, threads);
+        if (!rc) rc = orc_stage2(base, dtype, N, d, rev_cap, g2_id, g2_s, g2_deg, lambda0, K, adj, lam, threads);
+        if (!rc) {
+            if (knn_id_out) memcpy(knn_id_out, knn_id, sizeof(int32_t) * nk);
+            if (knn_s_out) memcpy(knn_s_out, knn_s, sizeof(float) * nk);
+            if (g1_id_out) memcpy(g1_id_out, g1_id, sizeof(int32_t) * nk);
+            if (g1_deg_out) memcpy(g1_deg_out, g1_deg, sizeof(int32_t) * (size_t)N);
+            if (g2_id_out) memcpy(g2_id_out, g2_id, sizeof(int32_t) * nr);
+            if (g2_s_out) memcpy(g2_s_out, g2_s, sizeof(float) * nr);
+            if (g2_deg_out) memcpy(g2_deg_out, g2_deg, sizeof(int32_t) * (size_t)N);
+        }
+    }
+    free(knn_id); free(knn_s); free(g1_id); free(g1_s); free(g1_deg);
+    free(g2_id); free(g2_s); free(g2_deg);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * Seed generator.  The paper draws 32 random start nodes (Alg. 2, first
+ * line) and names no generator.  Reading: a counter-based one, so the seeds
+ * of query qi do not depend on scheduling.  Seed j of query qi:
+ *     x = seed + GOLDEN*(qi*2^32 + j + 1)            (mod 2^64)
+ *     x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9
+ *     x = (x ^ (x >> 27)) * 0x94D049BB133111EB
+ *     x =  x ^ (x >> 31)
+ *     id = floor( x * N / 2^64 )                      (high half of the product)
+ * GOLDEN = 0x9E3779B97F4A7C15.  (The three-step finaliser is the published
+ * splitmix64 output function.)
+ * ---------------------------------------------------------------------- */
+int64_t orc_seed_id(uint64_t seed, uint64_t qi, uint64_t j, int64_t N)
+{
+    uint64_t x = seed + 0x9E3779B97F4A7C15ULL * ((qi << 32) + j + 1ULL);
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBULL;
+    x = x ^ (x >> 31);
+    return (int64_t)(((unsigned __int128)x * (unsigned __int128)(uint64_t)N) >> 64);
+}
+
+/* ------------------------------------------------------------------------
+ * Best-first search of one query over the diversified graph.
+ *
+ * One sorted list of at most L entries (s, id, expanded) is both the result
+ * list and the expansion queue.
+ *   1. the n_seeds seed nodes (repeats skipped) are scored and inserted;
+ *   2. u = first entry not yet expanded; none -> stop; hop limit T reached
+ *      (max_hops > 0 and hops == max_hops) -> stop; mark u expanded;
+ *   3. the neighbours of u are taken in stored order while id >= 0 and
+ *      lambda < lambda_visit (prefix rule of Sec. 3.3 / Sec. 5.4); one already
+ *      visited is skipped; otherwise it is marked visited, scored, and
+ *      inserted if the list has room or (s,id) precedes the last entry; the
+ *      last entry is dropped when the list exceeds L; an id already present
+ *      in the list is never inserted twice;
+ *   4. the first k entries are returned (id -1 / s +inf when fewer exist).
+ *
+ * visited_cap == 0: exact visited bitmap.  visited_cap > 0: a lossy
+ * direct-mapped table of that many slots (id % cap, overwritten on conflict)
+ * -- results must not depend on it; only the evaluation counts do.
+ * reverse_hop != 0 scores each hop's neighbours in reverse stored order --
+ * results must not depend on that either.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    float s;
+    int32_t id;
+    int expanded;
+} entry_t;
+
+static void search_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K,
+                       const void* base, int dtype, int d, const float* q, int k, int L,
+                       int lambda_visit, int n_seeds, uint64_t seed, uint64_t qi,
+                       int max_hops, int visited_cap, int reverse_hop,
+                       uint8_t* bitmap, int32_t* vtab, entry_t* lst, float* tmp,
+                       int32_t* out_ids, float* out_s, uint32_t* stats,
+                       int32_t* trace, int trace_cap)
+{
+    int n = 0;
+    uint32_t hops = 0, evals = 0, dedup = 0;
+    if (visited_cap == 0) memset(bitmap, 0, (size_t)((N + 7) / 8));
+    else for (int t = 0; t < visited_cap; ++t) vtab[t] = -1;
+
+    /* returns 1 if e was already visited, else marks it and returns 0 */
+#define VISIT(e, was)                                                        \
+    do {                                                                     \
+        if (visited_cap == 0) {                                              \
+            was = (bitmap[(e) >> 3] >> ((e) & 7)) & 1;                       \
+            bitmap[(e) >> 3] |= (uint8_t)(1u << ((e) & 7));                  \
+        } else {                                                             \
+            was = (vtab[(e) % visited_cap] == (e));                          \
+            vtab[(e) % visited_cap] = (e);                                   \
+        }                                                                    \
+    } while (0)
+
+#define SCORE_AND_INSERT(e)                                                  \
+    do {                                                                     \
+        const float* xb = row_f32(base, dtype, (e), d, tmp);                 \
+        pair_t c;                                                            \
+        c.s = orc_sqdist(q, xb, d);                                          \
+        c.id = (e);                                                          \
+        ++evals;                                                             \
+        int present = 0;                                                     \
+        for (int t = 0; t < n && !present; ++t) present = (lst[t].id == c.id); \
+        if (!present) {                                                      \
+            pair_t last = {0.0f, -1};                                        \
+            if (n > 0) { last.s = lst[n - 1].s; last.id = lst[n - 1].id; }   \
+            if (n < L || pair_less(c, last)) {                               \
+                int pos = n;                                                 \
+                while (pos > 0) {                                            \
+                    pair_t p; p.s = lst[pos - 1].s; p.id = lst[pos - 1].id;  \
+                    if (pair_less(c, p)) --pos; else break;                  \
+                }                                                            \
+                int end = n < L ? n : L - 1;                                 \
+                for (int t = end; t > pos; --t) lst[t] = lst[t - 1];         \
+                lst[pos].s = c.s; lst[pos].id = c.id; lst[pos].expanded = 0; \
+                if (n < L) ++n;                                              \
+            }                                                                \
+        }                                                                    \
+    } while (0)
+
+    for (int j = 0; j < n_seeds; ++j) {
+        int32_t e = (int32_t)orc_seed_id(seed, qi, (uint64_t)j, N);
+        int was;
+        VISIT(e, was);
+        if (was) { ++dedup; continue; }
+        SCORE_AND_INSERT(e);
+    }
+    for (;;) {
+        int ui = -1;
+        for (int t = 0; t < n; ++t)
+            if (!lst[t].expanded) { ui = t; break; }
+        if (ui < 0) break;
+        if (max_hops > 0 && (int)hops == max_hops) break;
+        lst[ui].expanded = 1;
+        int32_t u = lst[ui].id;
+        if (trace && (int)hops < trace_cap) trace[hops] = u;
+        ++hops;
+        int deg = 0;
+        while (deg < K && adj[(int64_t)u * K + deg] >= 0 &&
+               (int)lam[(int64_t)u * K + deg] < lambda_visit) ++deg;
+        for (int t = 0; t < deg; ++t) {
+            int tt = reverse_hop ? deg - 1 - t : t;
+            int32_t e = adj[(int64_t)u * K + tt];
+            int was;
+            VISIT(e, was);
+            if (was) { ++dedup; continue; }
+            SCORE_AND_INSERT(e);
+        }
+    }
+    for (int t = 0; t < k; ++t) {
+        out_ids[t] = t < n ? lst[t].id : -1;
+        out_s[t] = t < n ? lst[t].s : INFINITY;
+    }
+    if (stats) { stats[0] = hops; stats[1] = evals; stats[2] = dedup; }
+#undef VISIT
+#undef SCORE_AND_INSERT
+}
+
+/* Batch of queries.  out_ids/out_s [nq,k]; stats (may be NULL) [nq,3] =
+ * hops, distance evaluations, visited hits.  trace (may be NULL) [nq,trace_cap]
+ * receives the ids expanded, in order (unused slots untouched). */
+int orc_search(const int32_t* adj, const uint8_t* lam, int64_t N, int K,
+               const void* base, int dtype, int d, const float* queries, int64_t nq,
+               int k, int L, int lambda_visit, int n_seeds, uint64_t seed, int max_hops,
+               int visited_cap, int reverse_hop, int64_t qi_offset,
+               int32_t* out_ids, float* out_s, uint32_t* stats,
+               int32_t* trace, int trace_cap, int threads)
+{
+    if (!adj || !lam || !base || !queries || !out_ids || !out_s) return 1;
+    if (N <= 0 || K <= 0 || d <= 0 || k <= 0 || L < k || n_seeds <= 0 || nq < 0) return 1;
+    threads = use_threads(threads);
+    int failed = 0;
+#pragma omp parallel num_threads(threads)
+    {
+        uint8_t* bitmap = visited_cap == 0 ? (uint8_t*)malloc((size_t)((N + 7) / 8)) : NULL;
+        int32_t* vtab = visited_cap > 0 ? (int32_t*)malloc(sizeof(int32_t) * (size_t)visited_cap) : NULL;
+        entry_t* lst = (entry_t*)malloc(sizeof(entry_t) * (size_t)L);
+        float* tmp = (float*)malloc(sizeof(float) * (size_t)d);
+        if ((visited_cap == 0 && !bitmap) || (visited_cap > 0 && !vtab) || !lst || !tmp) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 8)
+            for (int64_t qi = 0; qi < nq; ++qi) {
+                search_one(adj, lam, N, K, base, dtype, d, queries + qi * (int64_t)d, k, L,
+                           lambda_visit, n_seeds, seed, (uint64_t)(qi + qi_offset), max_hops,
+                           visited_cap, reverse_hop, bitmap, vtab, lst, tmp,
+                           out_ids + qi * k, out_s + qi * k, stats ? stats + qi * 3 : NULL,
+                           trace ? trace + qi * (int64_t)trace_cap : NULL, trace_cap);
+            }
+        }
+        free(bitmap);
+        free(vtab);
+        free(lst);
+        free(tmp);
+    }
+    return failed ? 2 : 0;
+}
+
+/* Recall@k (Eq. 3): found[nq,k] against truth[nq,k]; -1 entries never match. */
+double orc_recall(const int32_t* found, const int32_t* truth, int64_t nq, int k)
+{
+    int64_t hit = 0;
+    for (int64_t i = 0; i < nq; ++i)
+        for (int a = 0; a < k; ++a) {
+            int32_t f = found[i * k + a];
+            if (f < 0) continue;
+            for (int b = 0; b < k; ++b)
+                if (truth[i * k + b] == f) { ++hit; break; }
+        }
+    return nq > 0 ? (double)hit / ((double)nq * (double)k) : 0.0;
+}

@@ -1,0 +1,185 @@
+"""Seeded synthetic inputs for the graph-based k-NN search path.
+
+This module only draws input arrays.  It holds none of the method's arithmetic
+(no distances, no graph rules, no search) and is the one module both the CPU
+oracle's tests and the HIP path's tests/bench may import.
+
+Every generator is a pure function of its integer seed (numpy PCG64 streams),
+so the same arrays can be rebuilt on any machine.  The workloads stand in, by
+shape only, for the public datasets of the paper's Table 1 (SIFT1M: d=128,
+integer-valued; GIST1M: d=960; DEEP10M: d=96, unit norm), which are not
+available here.
+
+Shapes:
+  tiny()        N=10,000  d=32   16 isotropic components        (parity case)
+  sift_like()   N=1e6     d=128  256 components, integers 0..255 (headline)
+  gist_like()   N=1e6     d=960  128 anisotropic components
+  deep_like()   N=1e7     d=96   1,024 components, unit norm
+  scale_u8_chunks()  N=1e8  d=128 uint8, 4,096 components, generated in chunks
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "tiny", "sift_like", "gist_like", "deep_like", "scale_u8_chunks",
+    "single_gaussian", "integer_lattice", "line_points",
+]
+
+
+def _rng(seed: int, stream: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64([int(seed), int(stream)]))
+
+
+# --------------------------------------------------------------------------
+# Tiny: 16 isotropic Gaussian components, centres U[-10,10]^d, sigma = 1.
+# --------------------------------------------------------------------------
+def tiny(N: int = 10_000, nq: int = 100, d: int = 32, components: int = 16,
+         seed: int = 1234):
+    """Returns (base[N,d] f32, queries[nq,d] f32).  Well separated components:
+    the k-NN graph of this set is disconnected, which is intended (it makes
+    the seed-coverage ceiling on recall visible)."""
+    g = _rng(seed, 0)
+    centres = g.uniform(-10.0, 10.0, size=(components, d))
+    cb = g.integers(0, components, size=N)
+    base = centres[cb] + g.standard_normal((N, d))
+    cq = g.integers(0, components, size=nq)
+    queries = centres[cq] + g.standard_normal((nq, d))
+    return base.astype(np.float32), queries.astype(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Latent-factor mixtures (shared loading matrix): low intrinsic dimension,
+# overlapping components, one connected cloud.
+# --------------------------------------------------------------------------
+class _LatentMixture:
+    """x = mu + A (w_m + sigma_m * z) + eps, z ~ N(0, I_r), eps ~ N(0, noise^2 I_d).
+
+    A (d x r) is shared by all components; component m has a latent centre w_m
+    and per-axis latent scales sigma_m.  All parameters are drawn from
+    stream 0 of the seed; samples are drawn from later streams so that chunks
+    can be regenerated independently.
+    """
+
+    def __init__(self, d, r, components, seed, mu, col_norm=(20.0, 60.0),
+                 centre_scale=2.0, sigma=(0.5, 1.5), noise=2.0):
+        g = _rng(seed, 0)
+        A = g.standard_normal((d, r))
+        A /= np.linalg.norm(A, axis=0, keepdims=True)
+        A *= g.uniform(col_norm[0], col_norm[1], size=(1, r))
+        self.A = A.astype(np.float32)
+        self.w = (centre_scale * g.standard_normal((components, r))).astype(np.float32)
+        self.sig = g.uniform(sigma[0], sigma[1], size=(components, r)).astype(np.float32)
+        self.mu = np.float32(mu)
+        self.noise = np.float32(noise)
+        self.components = components
+        self.d, self.r, self.seed = d, r, seed
+
+    def draw(self, n: int, stream: int) -> np.ndarray:
+        g = _rng(self.seed, stream)
+        out = np.empty((n, self.d), dtype=np.float32)
+        step = 262_144
+        for lo in range(0, n, step):
+            m = min(step, n - lo)
+            c = g.integers(0, self.components, size=m)
+            lat = self.w[c] + self.sig[c] * g.standard_normal((m, self.r), dtype=np.float32)
+            x = lat @ self.A.T
+            x += self.mu
+            x += self.noise * g.standard_normal((m, self.d), dtype=np.float32)
+            out[lo:lo + m] = x
+        return out
+
+
+def sift_like(N: int = 1_000_000, nq: int = 10_000, d: int = 128,
+              components: int = 256, seed: int = 2204):
+    """Integer-valued fp32 in [0,255] (clipped, rounded), 256-component mixture
+    over a shared 16-dimensional latent space.  Returns (base, queries)."""
+    mix = _LatentMixture(d, 16, components, seed, mu=128.0)
+    base = np.rint(np.clip(mix.draw(N, 1), 0.0, 255.0)).astype(np.float32)
+    queries = np.rint(np.clip(mix.draw(nq, 2), 0.0, 255.0)).astype(np.float32)
+    return base, queries
+
+
+def gist_like(N: int = 1_000_000, nq: int = 1_000, d: int = 960,
+              components: int = 128, seed: int = 960):
+    """Real-valued fp32, 128 components with per-component anisotropic diagonal
+    variances U[0.1,1]; centres N(0, 0.5^2) so that components overlap."""
+    g = _rng(seed, 0)
+    centres = (0.5 * g.standard_normal((components, d))).astype(np.float32)
+    std = np.sqrt(g.uniform(0.1, 1.0, size=(components, d))).astype(np.float32)
+
+    def draw(n, stream):
+        gg = _rng(seed, stream)
+        out = np.empty((n, d), dtype=np.float32)
+        step = 65_536
+        for lo in range(0, n, step):
+            m = min(step, n - lo)
+            c = gg.integers(0, components, size=m)
+            out[lo:lo + m] = centres[c] + std[c] * gg.standard_normal((m, d), dtype=np.float32)
+        return out
+
+    return draw(N, 1), draw(nq, 2)
+
+
+def deep_like(N: int = 10_000_000, nq: int = 10_000, d: int = 96,
+              components: int = 1024, seed: int = 96):
+    """Unit-normalised fp32 vectors from a 1,024-component mixture over a
+    shared 16-dimensional latent space (normalised after sampling)."""
+    mix = _LatentMixture(d, 16, components, seed, mu=0.0, col_norm=(0.5, 1.5),
+                         centre_scale=2.0, noise=0.05)
+
+    def unit(x):
+        n = np.linalg.norm(x, axis=1, keepdims=True)
+        n[n == 0] = 1.0
+        return (x / n).astype(np.float32)
+
+    return unit(mix.draw(N, 1)), unit(mix.draw(nq, 2))
+
+
+def scale_u8_chunks(N: int = 100_000_000, d: int = 128, components: int = 4096,
+                    seed: int = 100, chunk: int = 4_000_000):
+    """Yields (offset, uint8[chunk_n, d]) blocks of the 1e8-point set; chunk c
+    depends only on (seed, c).  Also usable for queries via `scale_u8_queries`."""
+    mix = _LatentMixture(d, 16, components, seed, mu=128.0)
+    c = 0
+    for lo in range(0, N, chunk):
+        m = min(chunk, N - lo)
+        x = np.rint(np.clip(mix.draw(m, 10 + c), 0.0, 255.0)).astype(np.uint8)
+        yield lo, x
+        c += 1
+
+
+def scale_u8_queries(nq: int = 10_000, d: int = 128, components: int = 4096,
+                     seed: int = 100):
+    mix = _LatentMixture(d, 16, components, seed, mu=128.0)
+    return np.rint(np.clip(mix.draw(nq, 2), 0.0, 255.0)).astype(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Small structured sets used by the pins.
+# --------------------------------------------------------------------------
+def single_gaussian(N: int, d: int, seed: int, nq: int = 0):
+    """One isotropic Gaussian: a connected cloud for the exhaustive-search pins."""
+    g = _rng(seed, 0)
+    base = g.standard_normal((N, d)).astype(np.float32)
+    if nq:
+        return base, g.standard_normal((nq, d)).astype(np.float32)
+    return base
+
+
+def integer_lattice(side: int, dims: int = 2):
+    """All points of {0..side-1}^dims in row-major id order, as fp32.  Many
+    exactly equal distances: exercises the smaller-id tie rule."""
+    axes = np.meshgrid(*[np.arange(side)] * dims, indexing="ij")
+    return np.stack([a.ravel() for a in axes], axis=1).astype(np.float32)
+
+
+def line_points(N: int, seed: int):
+    """N distinct sorted points on a line (d=1 padded to 4 columns of zeros
+    so rows are 16 bytes), with irregular gaps."""
+    g = _rng(seed, 0)
+    gaps = g.uniform(0.5, 1.5, size=N)
+    x = np.cumsum(gaps)
+    out = np.zeros((N, 4), dtype=np.float32)
+    out[:, 0] = x
+    return out
