@@ -1,0 +1,163 @@
+/*
+ * tsdg_ann.h -- C ABI of the MI355X (gfx950) library for graph-based approximate
+ * nearest-neighbour search on a two-stage diversified k-NN graph (TSDG).
+ *
+ * Problem statement (paper Sec. 1): given a query q and a metric m, return the
+ * top-k nearest neighbours of q from a candidate set.  The work is split, as in
+ * Sec. 2.2, into an offline graph build and an online search:
+ *
+ *   ann_build_graph  exact k-NN graph -> relaxed diversification (Sec. 3.2,
+ *                    Eq. 2) -> reverse edges -> soft diversification with an
+ *                    occlusion factor lambda per edge (Sec. 3.3, Eq. 1)
+ *   ann_search       best-first search from 32 random seeds over that graph,
+ *                    visiting in each neighbour list only the prefix whose
+ *                    lambda is below a threshold (Sec. 3.3, Sec. 4, Sec. 5.4)
+ *
+ * Conventions for every call
+ *   - ALL data pointers are DEVICE pointers on the current HIP device, row-major,
+ *     rows contiguous; base and query rows must start on 16-byte boundaries
+ *     (d a multiple of 4 for fp32 rows, of 16 for uint8 rows).
+ *   - The metric is L2; every distance taken or returned is the SQUARED L2
+ *     distance in fp32, computed as fl32( sum_j (double)(fl32(a_j - b_j))^2 ).
+ *   - Order is (distance, id): of two equal distances the smaller id comes first.
+ *   - The caller owns base, queries and the output arrays.  A graph object owns
+ *     its adjacency memory until ann_graph_free; it keeps NO pointer to base.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  ann_search* return after enqueueing; ann_build_graph*,
+ *     ann_knn, ann_bruteforce, import and export synchronise the stream before
+ *     returning because they size or free temporary device memory.
+ *   - Errors: a status code is returned, never an exception or abort; outputs
+ *     are untouched when argument validation fails; ann_last_error() gives a
+ *     thread-local message for the last failing call.
+ *   - Limits: 1 <= K <= 64, N > K, N < 2^27, 1 <= k <= L <= 512,
+ *     d <= 2048 (fp32) / d <= 1024 (uint8), 0 <= lambda0 <= 30.
+ */
+#ifndef TSDG_ANN_H
+#define TSDG_ANN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ann_graph ann_graph; /* opaque; owns the packed adjacency in device memory */
+
+typedef enum {
+    ANN_OK = 0,
+    ANN_EINVAL = 1,      /* bad argument (null pointer, size out of range, misaligned row) */
+    ANN_ENOMEM = 2,      /* device or host allocation failed */
+    ANN_EDEVICE = 3,     /* a HIP call or kernel launch failed */
+    ANN_EUNSUPPORTED = 4 /* valid request outside the limits above */
+} ann_status;
+
+typedef enum { ANN_F32 = 0, ANN_U8 = 1 } ann_dtype; /* element type of base rows */
+
+/* Build parameters.  Defaults (ann_build_params_default): fp32 rows,
+ * alpha = 1.2 (Sec. 3.2: "usually greater than 1.1"), lambda0 = 9 (so that the
+ * paper's "lambda < 10" prefix of Sec. 5.4 means every stored edge),
+ * rev_cap = 0 meaning 2*K (length to which a list is cut after the reverse
+ * edges are appended; the paper leaves it unbounded), stream NULL. */
+typedef struct {
+    ann_dtype dtype;
+    float alpha;
+    int lambda0;
+    int rev_cap;
+    void* stream;
+} ann_build_params;
+
+/* Search parameters.  Defaults (ann_search_params_default): fp32 rows, mode 0
+ * (auto: small-batch kernel below a batch-size threshold, large-batch kernel
+ * above), lambda_visit 0 meaning "by mode" (Sec. 5.4: 10 for small batches, 5
+ * for large ones), n_seeds 32 (Alg. 2), seed 0, max_hops 0 = unbounded (the hop
+ * limit T of Alg. 2), visited_slots 0 = chosen from L, waves_per_query 0 =
+ * chosen from d, qi_offset 0, stream NULL.
+ *   mode: 1 = large batch (one 64-lane wavefront per query),
+ *         2 = small batch (one workgroup of several wavefronts per query).
+ *   lambda_visit: edges with lambda < lambda_visit are followed; values above
+ *         31 mean every stored edge.  RESULTS DEPEND ON IT.
+ *   visited_slots: capacity (power of two, 64..16384) of the per-query hashed
+ *         visited set.  It is lossy without false positives: results do not
+ *         depend on it, only the number of distance evaluations does.
+ *   qi_offset: added to the query's index in the seed generator, so that a
+ *         batch split over several calls draws the seeds of the whole batch. */
+typedef struct {
+    ann_dtype dtype;
+    int mode;
+    int lambda_visit;
+    int n_seeds;
+    uint64_t seed;
+    int max_hops;
+    int visited_slots;
+    int waves_per_query;
+    int64_t qi_offset;
+    void* stream;
+} ann_search_params;
+
+/* Optional per-query counters written by ann_search_ex ([nq] on the device). */
+typedef struct {
+    uint32_t hops;       /* nodes expanded */
+    uint32_t dist_evals; /* distances computed, seeds included */
+    uint32_t dedup_hits; /* neighbours skipped because the visited set held them */
+} ann_query_stats;
+
+void ann_build_params_default(ann_build_params* p);
+void ann_search_params_default(ann_search_params* p);
+
+/* Offline phase (Sec. 3).  base: [N,d] device rows.  On success *out is a new
+ * graph of N rows and K columns: row i lists at most K neighbours of i sorted by
+ * (lambda, distance, id), each with lambda <= lambda0.
+ *   1. exact K nearest neighbours of every row (MFMA distance contraction with a
+ *      fused threshold filter, candidates re-scored with the canonical distance);
+ *   2. stage 1, Eq. 2 with the checking order of Sec. 3.1;
+ *   3. reverse edges appended, duplicates removed, list cut to rev_cap by (s,id);
+ *   4. stage 2: lambda_j = number of other edges of the list that occlude edge j
+ *      by Eq. 1; sort by (lambda, s, id); drop lambda > lambda0; cut to K.
+ * ann_build_graph uses the default parameters. */
+ann_status ann_build_graph(const void* base, int64_t N, int d, int K, ann_graph** out);
+ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K,
+                              const ann_build_params* params, ann_graph** out);
+
+/* Step 1 of the build alone: knn_ids [N,K] int32 and knn_dists [N,K] fp32 (device),
+ * row i = the K nearest other rows by (distance, id). */
+ann_status ann_knn(const void* base, int64_t N, int d, int K, ann_dtype dtype, void* stream,
+                   int32_t* knn_ids, float* knn_dists);
+
+/* Exact top-k of each query against the whole base set (the definition the
+ * search approximates; used for ground truth, Eq. 3).  queries [nq,d] fp32.
+ * out_ids [nq,k] int32, out_dists [nq,k] fp32; 1 <= k <= 128; k <= N. */
+ann_status ann_bruteforce(const void* base, int64_t N, int d, ann_dtype dtype,
+                          const float* queries, int nq, int k, void* stream,
+                          int32_t* out_ids, float* out_dists);
+
+/* Online phase (Sec. 4).  queries [nq,d] fp32 (also for uint8 base rows).
+ * out_ids [nq,k] int32, out_dists [nq,k] fp32 squared L2; when fewer than k
+ * nodes were reached the tail is id -1 / distance +inf.  ann_search uses the
+ * default parameters; ann_search_ex takes them explicitly and optionally
+ * writes stats[nq] (NULL to skip).  nq = 0 is valid and does nothing. */
+ann_status ann_search(const ann_graph* graph, const void* base, const void* queries, int nq,
+                      int k, int L, int32_t* out_ids, float* out_dists);
+ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* queries, int nq,
+                         int k, int L, const ann_search_params* params, int32_t* out_ids,
+                         float* out_dists, ann_query_stats* stats);
+
+/* Flat copies of a graph, N*K entries each (device pointers): adj = neighbour
+ * id or -1 for an unused slot, lam = occlusion factor or 255 for an unused
+ * slot.  Import validates ids (range, no self loop, no repeats in a row,
+ * unused slots only at the end, lambda <= 30) and returns ANN_EINVAL otherwise;
+ * d is the row length of the base set the graph describes (a graph remembers
+ * it, which is how ann_search knows the row shape of `base`).
+ * Together they serve as save/load. */
+ann_status ann_graph_export(const ann_graph* graph, int32_t* adj, uint8_t* lam, void* stream);
+ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, int K, int d,
+                            void* stream, ann_graph** out);
+ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d);
+void ann_graph_free(ann_graph* graph);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* ann_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSDG_ANN_H */

@@ -1,0 +1,232 @@
+"""ctypes binding of include/tsdg_ann.h.  Same names as the C entry points;
+torch is used for device memory and streams only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+ANN_F32, ANN_U8 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtsdg_ann.so")
+_lib = None
+
+_STATUS = {1: "ANN_EINVAL", 2: "ANN_ENOMEM", 3: "ANN_EDEVICE", 4: "ANN_EUNSUPPORTED"}
+
+
+class AnnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class _BuildParams(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("alpha", C.c_float), ("lambda0", C.c_int), ("rev_cap", C.c_int),
+                ("stream", C.c_void_p)]
+
+
+class _SearchParams(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("mode", C.c_int), ("lambda_visit", C.c_int), ("n_seeds", C.c_int),
+                ("seed", C.c_uint64), ("max_hops", C.c_int), ("visited_slots", C.c_int),
+                ("waves_per_query", C.c_int), ("qi_offset", C.c_int64), ("stream", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built library; builds it first only when no built file exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, i64, u64 = C.c_void_p, C.c_int, C.c_int64, C.c_uint64
+    L.ann_last_error.restype = C.c_char_p
+    L.ann_build_params_default.argtypes = [C.POINTER(_BuildParams)]
+    L.ann_search_params_default.argtypes = [C.POINTER(_SearchParams)]
+    L.ann_build_graph.argtypes = [vp, i64, i32, i32, C.POINTER(vp)]
+    L.ann_build_graph_ex.argtypes = [vp, i64, i32, i32, C.POINTER(_BuildParams), C.POINTER(vp)]
+    L.ann_knn.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+    L.ann_bruteforce.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
+    L.ann_search.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    L.ann_search_ex.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
+    L.ann_graph_export.argtypes = [vp, vp, vp, vp]
+    L.ann_graph_import.argtypes = [vp, vp, i64, i32, i32, vp, C.POINTER(vp)]
+    L.ann_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
+    L.ann_graph_free.argtypes = [vp]
+    L.ann_graph_free.restype = None
+    for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
+                 "ann_search_ex", "ann_graph_export", "ann_graph_import", "ann_graph_info"):
+        getattr(L, name).restype = C.c_int
+    del u64
+    _lib = L
+    return L
+
+
+def ann_last_error() -> str:
+    return load_library().ann_last_error().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise AnnError(status, ann_last_error())
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: need a contiguous CUDA tensor of {dtype}")
+    return t.data_ptr()
+
+
+def _base_ptr(base: torch.Tensor):
+    if base.dtype == torch.float32:
+        return _dev(base, torch.float32, "base"), ANN_F32
+    if base.dtype == torch.uint8:
+        return _dev(base, torch.uint8, "base"), ANN_U8
+    raise TypeError("base: float32 or uint8 rows")
+
+
+class Graph:
+    """Owner of an ann_graph*; freed on deletion or with ann_graph_free."""
+
+    def __init__(self, ptr: int):
+        self.ptr = ptr
+
+    def __del__(self):
+        try:
+            ann_graph_free(self)
+        except Exception:
+            pass
+
+
+@dataclass
+class QueryStats:
+    hops: torch.Tensor
+    dist_evals: torch.Tensor
+    dedup_hits: torch.Tensor
+
+
+def ann_build_graph(base: torch.Tensor, K: int) -> Graph:
+    p, dt = _base_ptr(base)
+    if dt != ANN_F32:
+        raise TypeError("ann_build_graph takes fp32 rows; use ann_build_graph_ex for uint8")
+    out = C.c_void_p()
+    _check(load_library().ann_build_graph(p, base.shape[0], base.shape[1], K, C.byref(out)))
+    return Graph(out.value)
+
+
+def ann_build_graph_ex(base: torch.Tensor, K: int, alpha: float = 1.2, lambda0: int = 9, rev_cap: int = 0,
+                       stream=None) -> Graph:
+    L = load_library()
+    p, dt = _base_ptr(base)
+    prm = _BuildParams()
+    L.ann_build_params_default(C.byref(prm))
+    prm.dtype, prm.alpha, prm.lambda0, prm.rev_cap, prm.stream = dt, alpha, lambda0, rev_cap, _stream_ptr(stream)
+    out = C.c_void_p()
+    _check(L.ann_build_graph_ex(p, base.shape[0], base.shape[1], K, C.byref(prm), C.byref(out)))
+    return Graph(out.value)
+
+
+def ann_knn(base: torch.Tensor, K: int, stream=None):
+    p, dt = _base_ptr(base)
+    N, d = base.shape
+    ids = torch.empty((N, K), dtype=torch.int32, device=base.device)
+    s = torch.empty((N, K), dtype=torch.float32, device=base.device)
+    _check(load_library().ann_knn(p, N, d, K, dt, _stream_ptr(stream), ids.data_ptr(), s.data_ptr()))
+    return ids, s
+
+
+def ann_bruteforce(base: torch.Tensor, queries: torch.Tensor, k: int, stream=None):
+    p, dt = _base_ptr(base)
+    N, d = base.shape
+    q = _dev(queries, torch.float32, "queries")
+    if queries.shape[1] != d:
+        raise ValueError("queries: wrong row length")
+    nq = queries.shape[0]
+    ids = torch.empty((nq, k), dtype=torch.int32, device=base.device)
+    s = torch.empty((nq, k), dtype=torch.float32, device=base.device)
+    _check(load_library().ann_bruteforce(p, N, d, dt, q, nq, k, _stream_ptr(stream), ids.data_ptr(), s.data_ptr()))
+    return ids, s
+
+
+def ann_search(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, L: int):
+    p, dt = _base_ptr(base)
+    if dt != ANN_F32:
+        raise TypeError("ann_search takes fp32 rows; use ann_search_ex for uint8")
+    q = _dev(queries, torch.float32, "queries")
+    nq = queries.shape[0]
+    ids = torch.empty((nq, k), dtype=torch.int32, device=base.device)
+    s = torch.empty((nq, k), dtype=torch.float32, device=base.device)
+    _check(load_library().ann_search(graph.ptr, p, q, nq, k, L, ids.data_ptr(), s.data_ptr()))
+    return ids, s
+
+
+def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, L: int, *, mode: int = 0,
+                  lambda_visit: int = 0, n_seeds: int = 32, seed: int = 0, max_hops: int = 0,
+                  visited_slots: int = 0, waves_per_query: int = 0, qi_offset: int = 0, stream=None,
+                  want_stats: bool = False, out=None):
+    """Returns (ids, dists) or (ids, dists, QueryStats).  `out=(ids, dists)` reuses output tensors."""
+    lib = load_library()
+    p, dt = _base_ptr(base)
+    q = _dev(queries, torch.float32, "queries")
+    nq = queries.shape[0]
+    if out is None:
+        ids = torch.empty((nq, k), dtype=torch.int32, device=base.device)
+        s = torch.empty((nq, k), dtype=torch.float32, device=base.device)
+    else:
+        ids, s = out
+        _dev(ids, torch.int32, "out ids")
+        _dev(s, torch.float32, "out dists")
+    prm = _SearchParams()
+    lib.ann_search_params_default(C.byref(prm))
+    prm.dtype, prm.mode, prm.lambda_visit, prm.n_seeds, prm.seed = dt, mode, lambda_visit, n_seeds, seed
+    prm.max_hops, prm.visited_slots, prm.waves_per_query = max_hops, visited_slots, waves_per_query
+    prm.qi_offset, prm.stream = qi_offset, _stream_ptr(stream)
+    st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
+    _check(lib.ann_search_ex(graph.ptr, p, q, nq, k, L, C.byref(prm), ids.data_ptr(), s.data_ptr(),
+                             st.data_ptr() if st is not None else None))
+    if want_stats:
+        return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
+    return ids, s
+
+
+def ann_graph_export(graph: Graph, stream=None):
+    N, K, _ = ann_graph_info(graph)
+    adj = torch.empty((N, K), dtype=torch.int32, device="cuda")
+    lam = torch.empty((N, K), dtype=torch.uint8, device="cuda")
+    _check(load_library().ann_graph_export(graph.ptr, adj.data_ptr(), lam.data_ptr(), _stream_ptr(stream)))
+    return adj, lam
+
+
+def ann_graph_import(adj: torch.Tensor, lam: torch.Tensor, d: int, stream=None) -> Graph:
+    a = _dev(adj, torch.int32, "adj")
+    l = _dev(lam, torch.uint8, "lam")
+    if adj.shape != lam.shape or adj.dim() != 2:
+        raise ValueError("adj and lam must both be [N,K]")
+    out = C.c_void_p()
+    _check(load_library().ann_graph_import(a, l, adj.shape[0], adj.shape[1], d, _stream_ptr(stream), C.byref(out)))
+    return Graph(out.value)
+
+
+def ann_graph_info(graph: Graph):
+    N, K, d = C.c_int64(), C.c_int(), C.c_int()
+    _check(load_library().ann_graph_info(graph.ptr, C.byref(N), C.byref(K), C.byref(d)))
+    return N.value, K.value, d.value
+
+
+def ann_graph_free(graph: Graph) -> None:
+    if graph is not None and getattr(graph, "ptr", None):
+        load_library().ann_graph_free(graph.ptr)
+        graph.ptr = None

@@ -1,0 +1,399 @@
+// extern "C" entry points (include/tsdg_ann.h): argument validation, the graph
+// object, import/export.  Every step of the path runs in the kernels of
+// search.hip, knn.hip and diversify.hip; nothing here computes on the host.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.hpp"
+
+namespace tsdg {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+// ---- pack / unpack / validate --------------------------------------------------------------
+// flags[0]: first violation code; flags[1]: max lambda seen
+__global__ void pack_kernel(const int32_t* __restrict__ adj, const uint8_t* __restrict__ lam, int64_t N,
+                            int K, uint32_t* __restrict__ packed, int* __restrict__ flags)
+{
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);
+    const int lane = lane_id();
+    if (row >= N) return;
+    int32_t id = -1;
+    int l = 255;
+    if (lane < K) {
+        id = adj[row * K + lane];
+        l = lam[row * K + lane];
+    }
+    const bool used = lane < K && id >= 0;
+    int bad = 0;
+    if (used && (id >= N || id == row)) bad = 1;                 // range / self loop
+    if (used && l > kMaxLambda) bad = 2;                         // lambda too large
+    if (lane < K && id < -1) bad = 1;
+    const uint64_t um = ballot64(used);
+    if (um & (um + 1)) bad = bad ? bad : 3;                      // used slots must form a prefix
+    for (uint64_t m = um; m; m &= m - 1) {                       // repeats in the row
+        const int j = ctz64(m);
+        const int32_t idj = (int32_t)bcast32((uint32_t)id, j);
+        if (used && j < lane && idj == id) bad = bad ? bad : 4;
+    }
+    if (lane < K) packed[row * K + lane] = used ? ((uint32_t)id | ((uint32_t)l << kIdBits)) : kPackPad;
+    if (bad) atomicCAS(&flags[0], 0, bad);
+    if (used) atomicMax(&flags[1], l);
+}
+
+__global__ void unpack_kernel(const uint32_t* __restrict__ packed, int64_t total, int32_t* __restrict__ adj,
+                              uint8_t* __restrict__ lam)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const uint32_t w = packed[i];
+    adj[i] = w == kPackPad ? -1 : (int32_t)(w & kIdMask);
+    lam[i] = w == kPackPad ? (uint8_t)255 : (uint8_t)(w >> kIdBits);
+}
+
+ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, hipStream_t stream,
+                      uint32_t* packed, int* max_lambda)
+{
+    int* flags = nullptr;
+    TSDG_HIP(hipMalloc(&flags, 2 * sizeof(int)));
+    hipError_t e = hipMemsetAsync(flags, 0, 2 * sizeof(int), stream);
+    if (e == hipSuccess) {
+        const int rows_per_block = 4;
+        const unsigned grid = (unsigned)((N + rows_per_block - 1) / rows_per_block);
+        hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(64 * rows_per_block), 0, stream, adj, lam, N, K, packed,
+                           flags);
+        e = hipGetLastError();
+    }
+    int h[2] = {0, 0};
+    if (e == hipSuccess) e = hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(flags);
+    if (e != hipSuccess) {
+        set_error("graph import failed on the device: %s", hipGetErrorString(e));
+        return ANN_EDEVICE;
+    }
+    if (h[0]) {
+        static const char* why[] = {"", "id out of range or self loop", "lambda above 30",
+                                    "unused slot before a used one", "repeated id in a row"};
+        set_error("graph import: invalid adjacency (%s)", why[h[0]]);
+        return ANN_EINVAL;
+    }
+    *max_lambda = h[1];
+    return ANN_OK;
+}
+
+ann_status unpack_graph(const uint32_t* packed, int64_t N, int K, hipStream_t stream, int32_t* adj, uint8_t* lam)
+{
+    const int64_t total = N * K;
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(unpack_kernel, dim3(grid), dim3(256), 0, stream, packed, total, adj, lam);
+    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(hipStreamSynchronize(stream));
+    return ANN_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static ann_status check_rows(const void* base, int64_t N, int d, ann_dtype dtype, const char* what)
+{
+    if (!base) { set_error("%s: null pointer", what); return ANN_EINVAL; }
+    if (dtype != ANN_F32 && dtype != ANN_U8) { set_error("%s: unknown dtype %d", what, (int)dtype); return ANN_EINVAL; }
+    if (N <= 0 || d <= 0) { set_error("%s: N and d must be positive", what); return ANN_EINVAL; }
+    if (!aligned16(base)) { set_error("%s: rows must be 16-byte aligned", what); return ANN_EINVAL; }
+    const int pc = dtype == ANN_U8 ? 16 : 4;
+    const int dmax = dtype == ANN_U8 ? 1024 : 2048;
+    if (d % pc != 0 || d > dmax) {
+        set_error("%s: d=%d unsupported (must be a multiple of %d and at most %d)", what, d, pc, dmax);
+        return ANN_EUNSUPPORTED;
+    }
+    return ANN_OK;
+}
+
+// Batch size from which one wavefront per query fills the GPU (256 CUs x 32 wave slots).
+constexpr int kLargeBatchThreshold = 2048;
+
+static int pow2_at_least(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+}  // namespace tsdg
+
+using namespace tsdg;
+
+extern "C" {
+
+const char* ann_last_error(void) { return g_err; }
+
+void ann_build_params_default(ann_build_params* p)
+{
+    if (!p) return;
+    p->dtype = ANN_F32;
+    p->alpha = 1.2f;
+    p->lambda0 = 9;
+    p->rev_cap = 0;
+    p->stream = nullptr;
+}
+
+void ann_search_params_default(ann_search_params* p)
+{
+    if (!p) return;
+    p->dtype = ANN_F32;
+    p->mode = 0;
+    p->lambda_visit = 0;
+    p->n_seeds = 32;
+    p->seed = 0;
+    p->max_hops = 0;
+    p->visited_slots = 0;
+    p->waves_per_query = 0;
+    p->qi_offset = 0;
+    p->stream = nullptr;
+}
+
+static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
+{
+    ann_graph_impl* g = new (std::nothrow) ann_graph_impl();
+    if (!g) { set_error("out of host memory"); return ANN_ENOMEM; }
+    g->N = N;
+    g->K = K;
+    g->d = d;
+    g->max_lambda = 0;
+    g->packed = nullptr;
+    g->device = 0;
+    (void)hipGetDevice(&g->device);
+    hipError_t e = hipMalloc(&g->packed, (size_t)N * (size_t)K * sizeof(uint32_t));
+    if (e != hipSuccess) {
+        set_error("hipMalloc of the graph (%lld x %d words) failed: %s", (long long)N, K, hipGetErrorString(e));
+        delete g;
+        return ANN_ENOMEM;
+    }
+    *out = g;
+    return ANN_OK;
+}
+
+ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, int K, int d, void* stream,
+                            ann_graph** out)
+{
+    g_err[0] = 0;
+    if (!adj || !lam || !out) { set_error("ann_graph_import: null pointer"); return ANN_EINVAL; }
+    if (K < 1 || K > kMaxK) { set_error("ann_graph_import: K=%d outside 1..64", K); return ANN_EINVAL; }
+    if (N <= K || N >= (1ll << kIdBits)) { set_error("ann_graph_import: need K < N < 2^27"); return ANN_EINVAL; }
+    if (d <= 0) { set_error("ann_graph_import: d must be positive"); return ANN_EINVAL; }
+    ann_graph_impl* g = nullptr;
+    ann_status rc = new_graph(N, K, d, &g);
+    if (rc != ANN_OK) return rc;
+    rc = pack_graph(adj, lam, N, K, static_cast<hipStream_t>(stream), g->packed, &g->max_lambda);
+    if (rc != ANN_OK) {
+        (void)hipFree(g->packed);
+        delete g;
+        return rc;
+    }
+    *out = reinterpret_cast<ann_graph*>(g);
+    return ANN_OK;
+}
+
+ann_status ann_graph_export(const ann_graph* graph, int32_t* adj, uint8_t* lam, void* stream)
+{
+    g_err[0] = 0;
+    if (!graph || !adj || !lam) { set_error("ann_graph_export: null pointer"); return ANN_EINVAL; }
+    const ann_graph_impl* g = reinterpret_cast<const ann_graph_impl*>(graph);
+    return unpack_graph(g->packed, g->N, g->K, static_cast<hipStream_t>(stream), adj, lam);
+}
+
+ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d)
+{
+    if (!graph) { set_error("ann_graph_info: null graph"); return ANN_EINVAL; }
+    const ann_graph_impl* g = reinterpret_cast<const ann_graph_impl*>(graph);
+    if (N) *N = g->N;
+    if (K) *K = g->K;
+    if (d) *d = g->d;
+    return ANN_OK;
+}
+
+void ann_graph_free(ann_graph* graph)
+{
+    if (!graph) return;
+    ann_graph_impl* g = reinterpret_cast<ann_graph_impl*>(graph);
+    (void)hipFree(g->packed);
+    delete g;
+}
+
+ann_status ann_knn(const void* base, int64_t N, int d, int K, ann_dtype dtype, void* stream, int32_t* knn_ids,
+                   float* knn_dists)
+{
+    g_err[0] = 0;
+    ann_status rc = check_rows(base, N, d, dtype, "ann_knn");
+    if (rc != ANN_OK) return rc;
+    if (!knn_ids || !knn_dists) { set_error("ann_knn: null output"); return ANN_EINVAL; }
+    if (K < 1 || K > kMaxK || N <= K || N >= (1ll << kIdBits)) {
+        set_error("ann_knn: need 1 <= K <= 64 and K < N < 2^27");
+        return ANN_EINVAL;
+    }
+    return knn_exact(base, N, d, dtype, nullptr, N, K, true, static_cast<hipStream_t>(stream), knn_ids, knn_dists);
+}
+
+ann_status ann_bruteforce(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries, int nq,
+                          int k, void* stream, int32_t* out_ids, float* out_dists)
+{
+    g_err[0] = 0;
+    ann_status rc = check_rows(base, N, d, dtype, "ann_bruteforce");
+    if (rc != ANN_OK) return rc;
+    if (nq < 0 || (nq > 0 && (!queries || !out_ids || !out_dists))) {
+        set_error("ann_bruteforce: null pointer or negative nq");
+        return ANN_EINVAL;
+    }
+    if (!aligned16(queries)) { set_error("ann_bruteforce: query rows must be 16-byte aligned"); return ANN_EINVAL; }
+    if (k < 1 || k > 128 || k > N || N >= (1ll << kIdBits)) {
+        set_error("ann_bruteforce: need 1 <= k <= min(128, N) and N < 2^27");
+        return ANN_EINVAL;
+    }
+    if (nq == 0) return ANN_OK;
+    return knn_exact(base, N, d, dtype, queries, nq, k, false, static_cast<hipStream_t>(stream), out_ids, out_dists);
+}
+
+ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const ann_build_params* params,
+                              ann_graph** out)
+{
+    g_err[0] = 0;
+    ann_build_params p;
+    ann_build_params_default(&p);
+    if (params) p = *params;
+    if (!out) { set_error("ann_build_graph: null output"); return ANN_EINVAL; }
+    ann_status rc = check_rows(base, N, d, p.dtype, "ann_build_graph");
+    if (rc != ANN_OK) return rc;
+    if (K < 1 || K > kMaxK || N <= K || N >= (1ll << kIdBits)) {
+        set_error("ann_build_graph: need 1 <= K <= 64 and K < N < 2^27");
+        return ANN_EINVAL;
+    }
+    if (!(p.alpha >= 1.0f) || p.alpha > 16.0f) { set_error("ann_build_graph: alpha must be in [1,16]"); return ANN_EINVAL; }
+    if (p.lambda0 < 0 || p.lambda0 > kMaxLambda) { set_error("ann_build_graph: lambda0 must be in 0..30"); return ANN_EINVAL; }
+    int rev_cap = p.rev_cap == 0 ? 2 * K : p.rev_cap;
+    if (rev_cap < K || rev_cap > 2 * kMaxK) { set_error("ann_build_graph: rev_cap must be in K..128"); return ANN_EINVAL; }
+    hipStream_t stream = static_cast<hipStream_t>(p.stream);
+
+    int32_t* knn_id = nullptr;
+    float* knn_s = nullptr;
+    TSDG_HIP(hipMalloc(&knn_id, (size_t)N * K * sizeof(int32_t)));
+    hipError_t e = hipMalloc(&knn_s, (size_t)N * K * sizeof(float));
+    if (e != hipSuccess) {
+        (void)hipFree(knn_id);
+        set_error("hipMalloc of the k-NN lists failed: %s", hipGetErrorString(e));
+        return ANN_ENOMEM;
+    }
+    ann_graph_impl* g = nullptr;
+    rc = knn_exact(base, N, d, p.dtype, nullptr, N, K, true, stream, knn_id, knn_s);
+    if (rc == ANN_OK) rc = new_graph(N, K, d, &g);
+    if (rc == ANN_OK)
+        rc = diversify(base, N, d, p.dtype, K, knn_id, knn_s, p.alpha, p.lambda0, rev_cap, stream, g->packed,
+                       &g->max_lambda);
+    (void)hipFree(knn_id);
+    (void)hipFree(knn_s);
+    if (rc != ANN_OK) {
+        if (g) { (void)hipFree(g->packed); delete g; }
+        return rc;
+    }
+    *out = reinterpret_cast<ann_graph*>(g);
+    return ANN_OK;
+}
+
+ann_status ann_build_graph(const void* base, int64_t N, int d, int K, ann_graph** out)
+{
+    return ann_build_graph_ex(base, N, d, K, nullptr, out);
+}
+
+ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int L,
+                         const ann_search_params* params, int32_t* out_ids, float* out_dists,
+                         ann_query_stats* stats)
+{
+    g_err[0] = 0;
+    ann_search_params p;
+    ann_search_params_default(&p);
+    if (params) p = *params;
+    if (!graph) { set_error("ann_search: null graph"); return ANN_EINVAL; }
+    const ann_graph_impl* g = reinterpret_cast<const ann_graph_impl*>(graph);
+    if (nq < 0) { set_error("ann_search: negative nq"); return ANN_EINVAL; }
+    if (k < 1 || L < k || L > kMaxL) { set_error("ann_search: need 1 <= k <= L <= 512 (k=%d, L=%d)", k, L); return ANN_EINVAL; }
+    if (p.n_seeds < 1) { set_error("ann_search: n_seeds must be positive"); return ANN_EINVAL; }
+    if (p.max_hops < 0 || p.mode < 0 || p.mode > 2 || p.lambda_visit < 0) {
+        set_error("ann_search: negative max_hops / lambda_visit or unknown mode");
+        return ANN_EINVAL;
+    }
+    if (nq == 0) return ANN_OK;
+    if (!queries || !out_ids || !out_dists) { set_error("ann_search: null pointer"); return ANN_EINVAL; }
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search");
+    if (rc != ANN_OK) return rc;
+    if (!aligned16(queries)) { set_error("ann_search: query rows must be 16-byte aligned"); return ANN_EINVAL; }
+
+    SearchLaunch s;
+    s.packed = g->packed;
+    s.N = g->N;
+    s.K = g->K;
+    s.base = base;
+    s.dtype = p.dtype;
+    s.d = g->d;
+    s.queries = static_cast<const float*>(queries);
+    s.nq = nq;
+    s.k = k;
+    s.L = L;
+    s.n_seeds = p.n_seeds;
+    s.seed = p.seed;
+    s.max_hops = p.max_hops;
+    s.qi_offset = p.qi_offset;
+    s.out_ids = out_ids;
+    s.out_dists = out_dists;
+    s.stats = stats;
+    s.stream = static_cast<hipStream_t>(p.stream);
+
+    // batch regime (Sec. 4): below the threshold a query gets a whole workgroup
+    const int row_bytes = g->d * (p.dtype == ANN_U8 ? 1 : 4);
+    int mode = p.mode;
+    if (mode == 0) mode = nq >= kLargeBatchThreshold ? 1 : 2;
+    int waves = 1;
+    if (mode == 2) {
+        waves = p.waves_per_query;
+        if (waves == 0) waves = row_bytes <= 512 ? 2 : (row_bytes <= 2048 ? 4 : 8);
+        if (waves != 1 && waves != 2 && waves != 4 && waves != 8) {
+            set_error("ann_search: waves_per_query must be 0, 1, 2, 4 or 8");
+            return ANN_EINVAL;
+        }
+    }
+    s.waves = waves;
+    // visited prefix (Sec. 5.4): lambda < 10 for small batches, lambda < 5 for large ones
+    int lv = p.lambda_visit;
+    if (lv == 0) lv = mode == 2 ? 10 : 5;
+    if (lv > 31) lv = 32;
+    s.lambda_visit = lv;
+
+    int slots = p.visited_slots;
+    if (slots == 0) {
+        slots = pow2_at_least(16 * L);
+        if (slots < 1024) slots = 1024;
+        if (slots > 8192) slots = 8192;
+    }
+    if (slots < 64 || slots > 16384 || (slots & (slots - 1)) != 0) {
+        set_error("ann_search: visited_slots must be a power of two in 64..16384");
+        return ANN_EINVAL;
+    }
+    s.visited_slots = slots;
+    return launch_search(s);
+}
+
+ann_status ann_search(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int L,
+                      int32_t* out_ids, float* out_dists)
+{
+    return ann_search_ex(graph, base, queries, nq, k, L, nullptr, out_ids, out_dists, nullptr);
+}
+
+}  // extern "C"

@@ -1,0 +1,122 @@
+// Shared host/device definitions of the HIP library (gfx950, wave64).
+// Nothing here is shared with the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tsdg_ann.h"
+
+namespace tsdg {
+
+// ---- packed adjacency word: bits 0..26 node id, bits 27..31 lambda (0..30); all ones = unused slot
+constexpr uint32_t kPackPad = 0xFFFFFFFFu;
+constexpr uint32_t kIdBits = 27;
+constexpr uint32_t kIdMask = (1u << kIdBits) - 1u;
+constexpr int kMaxLambda = 30;
+constexpr int kMaxK = 64;
+constexpr int kMaxL = 512;
+
+// ---- rank-list key: high word = bit pattern of the fp32 squared distance (non-negative, so the
+// unsigned order of the bits is the numeric order), low word = id << 1 | expanded flag.  Ids are
+// unique in a list, so the unsigned 64-bit order of keys is the (distance, id) order.
+constexpr uint64_t kKeyEmpty = ~0ull;
+constexpr uint32_t kHashEmpty = 0xFFFFFFFFu;
+
+struct ann_graph_impl {
+    int64_t N;
+    int K;
+    int d;             // row length of the base set the graph describes
+    int max_lambda;    // largest lambda stored
+    uint32_t* packed;  // [N,K] device
+    int device;
+};
+
+// ---- error plumbing (host)
+void set_error(const char* fmt, ...);
+#define TSDG_HIP(call)                                                                     \
+    do {                                                                                   \
+        hipError_t e_ = (call);                                                            \
+        if (e_ != hipSuccess) {                                                            \
+            tsdg::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return e_ == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EDEVICE;                   \
+        }                                                                                  \
+    } while (0)
+
+// ---- launchers implemented in the .hip files
+struct SearchLaunch {
+    const uint32_t* packed;
+    int64_t N;
+    int K;
+    const void* base;
+    ann_dtype dtype;
+    int d;
+    const float* queries;
+    int nq;
+    int k;
+    int L;
+    int lambda_visit;  // already resolved (1..32)
+    int n_seeds;
+    uint64_t seed;
+    int max_hops;
+    int visited_slots;  // power of two
+    int waves;          // 1 = large-batch kernel
+    int64_t qi_offset;
+    int32_t* out_ids;
+    float* out_dists;
+    ann_query_stats* stats;
+    hipStream_t stream;
+};
+ann_status launch_search(const SearchLaunch& a);
+
+ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries,
+                     int64_t nq, int k, bool exclude_self, hipStream_t stream, int32_t* out_ids,
+                     float* out_s);
+
+ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
+                     const float* knn_s, float alpha, int lambda0, int rev_cap, hipStream_t stream,
+                     uint32_t* packed, int* max_lambda);
+
+ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, hipStream_t stream,
+                      uint32_t* packed, int* max_lambda);
+ann_status unpack_graph(const uint32_t* packed, int64_t N, int K, hipStream_t stream, int32_t* adj,
+                        uint8_t* lam);
+
+// ---- device helpers
+#if defined(__HIPCC__)
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63u); }
+__device__ __forceinline__ uint64_t ballot64(bool p) { return (uint64_t)__ballot(p ? 1 : 0); }
+__device__ __forceinline__ int popc64(uint64_t m) { return __popcll((unsigned long long)m); }
+__device__ __forceinline__ int ctz64(uint64_t m) { return __builtin_ctzll((unsigned long long)m); }
+__device__ __forceinline__ uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
+
+__device__ __forceinline__ uint32_t bcast32(uint32_t v, int src) { return (uint32_t)__shfl((int)v, src, 64); }
+__device__ __forceinline__ uint64_t bcast64(uint64_t v, int src)
+{
+    uint32_t lo = bcast32((uint32_t)v, src), hi = bcast32((uint32_t)(v >> 32), src);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask)
+{
+    long long b = __double_as_longlong(v);
+    int lo = __shfl_xor((int)(b & 0xFFFFFFFFll), mask, 64);
+    int hi = __shfl_xor((int)(b >> 32), mask, 64);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+__device__ __forceinline__ uint64_t make_key(float s, uint32_t id)
+{
+    return ((uint64_t)__float_as_uint(s) << 32) | (uint64_t)(id << 1);
+}
+__device__ __forceinline__ uint32_t key_id(uint64_t key) { return (uint32_t)(key & 0xFFFFFFFFull) >> 1; }
+__device__ __forceinline__ float key_dist(uint64_t key) { return __uint_as_float((uint32_t)(key >> 32)); }
+
+// Orders memory operations of the lanes of ONE wavefront (LDS is processed in
+// issue order per wave; this only stops the compiler from moving accesses).
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+#endif
+
+}  // namespace tsdg

@@ -1,0 +1,162 @@
+// Wave-cooperative squared-L2 evaluation between one query held in registers and
+// rows gathered from the base set (search step S5; also used by the build's
+// re-scoring pass).
+//
+// A row is cut into 16-byte chunks (4 fp32 or 16 uint8 elements).  G lanes form
+// a group that owns one row per pass; lane g of the group reads chunks g, g+G,
+// ..., so that each load instruction of a group covers G*16 contiguous bytes
+// (128 B for G = 8: one cache line per group, 64/G rows per instruction).
+// Every lane accumulates the squares of its fp32 differences in fp64, the G
+// partial sums are added by an xor butterfly and the total is rounded once to
+// fp32: the canonical distance fl32( sum (double)(fl32(a_j - b_j))^2 ).  The
+// summation order depends only on (G, C), never on which operand is which, so
+// the value is bitwise symmetric and reproducible.
+#pragma once
+#include "common.hpp"
+
+namespace tsdg {
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerChunk = 4;
+    using chunk_t = float4;
+};
+template <> struct Elem<uint8_t> {
+    static constexpr int kPerChunk = 16;
+    using chunk_t = uint4;
+};
+
+template <typename T, int G, int C> struct RowDist {
+    static constexpr int PC = Elem<T>::kPerChunk;
+    static constexpr int VP = 64 / G;  // rows per pass
+    static constexpr int NC = C;       // chunks per lane
+    using chunk_t = typename Elem<T>::chunk_t;
+
+    float q[C * PC];  // this lane's slices of the query
+    int g;            // lane within group
+    int v;            // group within wave
+    int nchunks;      // d / PC
+    int d;
+
+    __device__ __forceinline__ void init(int d_, int lane)
+    {
+        d = d_;
+        nchunks = d_ / PC;
+        g = lane % G;
+        v = lane / G;
+    }
+    __device__ __forceinline__ bool has(int c) const { return g + G * c < nchunks; }
+
+    // query given as fp32
+    __device__ __forceinline__ void load_query_f32(const float* __restrict__ qrow)
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int ci = g + G * c;
+#pragma unroll
+            for (int e = 0; e < PC; e += 4) {
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (ci < nchunks) x = *reinterpret_cast<const float4*>(qrow + (size_t)ci * PC + e);
+                q[c * PC + e + 0] = x.x;
+                q[c * PC + e + 1] = x.y;
+                q[c * PC + e + 2] = x.z;
+                q[c * PC + e + 3] = x.w;
+            }
+        }
+    }
+    // query is itself a base row (build passes)
+    __device__ __forceinline__ void load_query_row(const T* __restrict__ base, uint32_t row)
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            chunk_t x = {};
+            if (has(c)) x = load(base, row, c);
+            unpack(x, &q[c * PC]);
+        }
+    }
+
+    __device__ __forceinline__ chunk_t load(const T* __restrict__ base, uint32_t row, int c) const
+    {
+        return *reinterpret_cast<const chunk_t*>(base + (size_t)row * (size_t)d + (size_t)(g + G * c) * PC);
+    }
+
+    static __device__ __forceinline__ void unpack(const float4& x, float* out)
+    {
+        out[0] = x.x; out[1] = x.y; out[2] = x.z; out[3] = x.w;
+    }
+    static __device__ __forceinline__ void unpack(const uint4& x, float* out)
+    {
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[4 * i + 0] = (float)(w[i] & 0xFFu);
+            out[4 * i + 1] = (float)((w[i] >> 8) & 0xFFu);
+            out[4 * i + 2] = (float)((w[i] >> 16) & 0xFFu);
+            out[4 * i + 3] = (float)(w[i] >> 24);
+        }
+    }
+
+    // this lane's share of sum (q_j - x_j)^2 over its chunks
+    __device__ __forceinline__ double partial(const chunk_t (&buf)[C]) const
+    {
+        double acc = 0.0;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (has(c)) {
+                float x[PC];
+                unpack(buf[c], x);
+#pragma unroll
+                for (int e = 0; e < PC; ++e) {
+                    const float t = q[c * PC + e] - x[e];
+                    acc += (double)t * (double)t;
+                }
+            }
+        }
+        return acc;
+    }
+
+    // sum over the G lanes of a group; every lane of the group gets the total
+    static __device__ __forceinline__ double group_sum(double a)
+    {
+#pragma unroll
+        for (int o = G / 2; o > 0; o >>= 1) a += shfl_xor_f64(a, o);
+        return a;
+    }
+};
+
+// (G, C) for a row of `nchunks` 16-byte chunks: the smallest group that covers the
+// row with at most 4 chunks per lane (8 for the longest rows).
+inline bool pick_group(int nchunks, int* G, int* C)
+{
+    static const int gs[] = {8, 8, 8, 8, 16, 32, 64, 64};
+    static const int cs[] = {1, 2, 3, 4, 4, 4, 4, 8};
+    for (int i = 0; i < 8; ++i)
+        if (nchunks <= gs[i] * cs[i]) {
+            *G = gs[i];
+            *C = cs[i];
+            return true;
+        }
+    return false;
+}
+
+// Calls f.template operator()<T, G, C>() for the (dtype, d) at hand.
+template <typename F> inline bool dispatch_row_shape(ann_dtype dtype, int d, F&& f)
+{
+    const int pc = dtype == ANN_U8 ? 16 : 4;
+    if (d <= 0 || d % pc != 0) return false;
+    int G, C;
+    if (!pick_group(d / pc, &G, &C)) return false;
+#define TSDG_CASE(TT, GG, CC) \
+    if (G == GG && C == CC) { f.template operator()<TT, GG, CC>(); return true; }
+    if (dtype == ANN_F32) {
+        TSDG_CASE(float, 8, 1) TSDG_CASE(float, 8, 2) TSDG_CASE(float, 8, 3) TSDG_CASE(float, 8, 4)
+        TSDG_CASE(float, 16, 4) TSDG_CASE(float, 32, 4) TSDG_CASE(float, 64, 4) TSDG_CASE(float, 64, 8)
+    } else {
+        TSDG_CASE(uint8_t, 8, 1) TSDG_CASE(uint8_t, 8, 2) TSDG_CASE(uint8_t, 8, 3) TSDG_CASE(uint8_t, 8, 4)
+        TSDG_CASE(uint8_t, 16, 4)
+    }
+#undef TSDG_CASE
+    return false;
+}
+
+}  // namespace tsdg

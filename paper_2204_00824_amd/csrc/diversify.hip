@@ -1,0 +1,461 @@
+// Two-stage diversification of the exact k-NN graph (paper Sec. 3.2-3.3;
+// build steps B2, B3, B4).  Every node is independent (Sec. 3.3, last paragraph),
+// so each kernel gives one wavefront to one node:
+//   stage 1   pairwise canonical distances inside the K-list, then the sequential
+//             relaxed-occlusion scan of Eq. 2 (closest edge first, each next edge
+//             against the kept ones, Sec. 3.1);
+//   reverse   in-degree count -> exclusive scan -> scatter of (source, distance),
+//             then per node the kept and the reverse edges are merged by (s, id),
+//             duplicates dropped, and the list is cut to rev_cap;
+//   stage 2   pairwise distances inside that list, lambda_j = number of edges that
+//             occlude edge j by Eq. 1, order by (lambda, s, id), cut at lambda0
+//             and at K, written as the packed adjacency the search reads.
+#include <algorithm>
+
+#include "dist.hpp"
+#include "ranklist.hpp"
+
+namespace tsdg {
+
+constexpr float kInfD = __builtin_inff();
+
+// P[i*stride + j] = s(x_ids[i], x_ids[j]) for i < j < m (canonical distance), one wavefront.
+template <typename RD, typename T>
+__device__ __forceinline__ void pairwise(RD& rd, const T* __restrict__ base, const int32_t* ids, int m, float* P,
+                                         int stride)
+{
+    using chunk_t = typename RD::chunk_t;
+    constexpr int VP = RD::VP;
+    constexpr int C = RD::NC;
+    constexpr int U = (C >= 3) ? 2 : 4;
+    for (int i = 0; i + 1 < m; ++i) {
+        rd.load_query_row(base, (uint32_t)ids[i]);
+        for (int p0 = i + 1; p0 < m; p0 += U * VP) {
+            chunk_t buf[U][C];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = p0 + u * VP + rd.v;
+                ok[u] = j < m;
+                const uint32_t e = ok[u] ? (uint32_t)ids[j] : 0u;
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    buf[u][cc] = chunk_t{};
+                    if (ok[u] && rd.has(cc)) buf[u][cc] = rd.load(base, e, cc);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int j = p0 + u * VP + rd.v;
+                const double tot = RD::group_sum(rd.partial(buf[u]));
+                if (ok[u] && rd.g == 0) P[i * stride + j] = (float)tot;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ stage 1
+struct Stage1Args {
+    const void* base;
+    const int32_t* knn_id;  // [N,K] sorted by (s,id)
+    const float* knn_s;
+    int32_t* g1_id;         // [N,K] kept edges first, -1 after
+    float* g1_s;
+    int32_t* g1_deg;        // [N]
+    unsigned* indeg;        // [N] in-degree of the kept graph (atomic)
+    int64_t N;
+    int d, K;
+    float alpha2;
+};
+
+template <typename T, int G, int C>
+__global__ __launch_bounds__(64) void stage1_kernel(Stage1Args a)
+{
+    using RD = RowDist<T, G, C>;
+    extern __shared__ float sm[];
+    const int K = a.K;
+    float* P = sm;                                         // [K*K]
+    float* s0 = P + K * K;                                 // [K]
+    int32_t* ids = reinterpret_cast<int32_t*>(s0 + K);     // [K]
+    const int64_t x0 = blockIdx.x;
+    const int lane = lane_id();
+    const T* __restrict__ base = static_cast<const T*>(a.base);
+
+    int32_t id = -1;
+    float s = kInfD;
+    if (lane < K) {
+        id = a.knn_id[x0 * K + lane];
+        s = a.knn_s[x0 * K + lane];
+        ids[lane] = id;
+        s0[lane] = s;
+    }
+    const uint64_t used = ballot64(id >= 0);
+    const int m = used ? 64 - __builtin_clzll(used) : 0;   // lists are prefixes
+    __syncthreads();
+    RD rd;
+    rd.init(a.d, lane);
+    pairwise(rd, base, ids, m, P, K);
+    __syncthreads();
+
+    // sequential scan: lane i answers "does kept edge i occlude edge j"
+    uint64_t kept = m > 0 ? 1ull : 0ull;
+    for (int j = 1; j < m; ++j) {
+        const float s0j = s0[j];
+        bool occ = false;
+        if (lane < j && ((kept >> lane) & 1ull)) {
+            const float a1 = a.alpha2 * s;
+            if (a1 < s0j) {
+                const float a2 = a.alpha2 * P[lane * K + j];
+                occ = a2 < s0j;
+            }
+        }
+        if (!ballot64(occ)) kept |= 1ull << j;
+    }
+    const int deg = popc64(kept);
+    const bool mine = (kept >> lane) & 1ull;
+    const int pos = popc64(kept & lanes_below(lane));
+    if (lane < K) {
+        // compact kept edges to the front, pad the rest
+        if (lane >= deg) {
+            a.g1_id[x0 * K + lane] = -1;
+            a.g1_s[x0 * K + lane] = kInfD;
+        }
+    }
+    __syncthreads();
+    if (mine) {
+        a.g1_id[x0 * K + pos] = id;
+        a.g1_s[x0 * K + pos] = s;
+        atomicAdd(&a.indeg[id], 1u);
+    }
+    if (lane == 0) a.g1_deg[x0] = deg;
+}
+
+// ------------------------------------------------------------------ exclusive scan (uint32 -> uint64)
+constexpr int kScanBlock = 1024;
+__global__ __launch_bounds__(256) void scan_partial(const unsigned* __restrict__ in, int64_t n,
+                                                    uint64_t* __restrict__ block_sums)
+{
+    __shared__ uint64_t red[256];
+    const int64_t b0 = (int64_t)blockIdx.x * kScanBlock;
+    uint64_t acc = 0;
+    for (int i = threadIdx.x; i < kScanBlock; i += 256)
+        if (b0 + i < n) acc += in[b0 + i];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0];
+}
+__global__ void scan_block_sums(uint64_t* block_sums, int64_t nb)
+{
+    // one thread: nb = N/1024 is at most 131072
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        uint64_t run = 0;
+        for (int64_t i = 0; i < nb; ++i) {
+            const uint64_t v = block_sums[i];
+            block_sums[i] = run;
+            run += v;
+        }
+        block_sums[nb] = run;
+    }
+}
+__global__ __launch_bounds__(256) void scan_final(const unsigned* __restrict__ in, int64_t n,
+                                                  const uint64_t* __restrict__ block_sums, uint64_t* __restrict__ out)
+{
+    __shared__ uint64_t part[256];
+    const int64_t b0 = (int64_t)blockIdx.x * kScanBlock;
+    const int t = threadIdx.x;
+    unsigned v[4];
+    uint64_t loc = 0;
+    for (int e = 0; e < 4; ++e) {
+        const int64_t i = b0 + t * 4 + e;
+        v[e] = i < n ? in[i] : 0u;
+        loc += v[e];
+    }
+    part[t] = loc;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {  // inclusive Hillis-Steele over the 256 partials
+        const uint64_t add = t >= o ? part[t - o] : 0;
+        __syncthreads();
+        part[t] += add;
+        __syncthreads();
+    }
+    uint64_t run = block_sums[blockIdx.x] + part[t] - loc;
+    for (int e = 0; e < 4; ++e) {
+        const int64_t i = b0 + t * 4 + e;
+        if (i < n) out[i] = run;
+        run += v[e];
+    }
+    if (blockIdx.x == gridDim.x - 1 && t == 255) out[n] = block_sums[gridDim.x];
+}
+
+// ------------------------------------------------------------------ reverse edges
+__global__ __launch_bounds__(256) void scatter_kernel(const int32_t* __restrict__ g1_id, const float* __restrict__ g1_s,
+                                                      int64_t total, int K, const uint64_t* __restrict__ start,
+                                                      unsigned* __restrict__ cursor, int32_t* __restrict__ rev_src,
+                                                      float* __restrict__ rev_s)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int32_t tgt = g1_id[i];
+    if (tgt < 0) return;
+    const uint64_t pos = start[tgt] + atomicAdd(&cursor[tgt], 1u);
+    rev_src[pos] = (int32_t)(i / K);
+    rev_s[pos] = g1_s[i];
+}
+
+struct MergeArgs {
+    const int32_t* g1_id;
+    const float* g1_s;
+    const int32_t* g1_deg;
+    const uint64_t* start;
+    const int32_t* rev_src;
+    const float* rev_s;
+    int32_t* g2_id;  // [N, rev_cap]
+    float* g2_s;
+    int32_t* g2_deg;
+    int64_t N;
+    int K, rev_cap;
+};
+
+__global__ __launch_bounds__(64) void merge_kernel(MergeArgs a)
+{
+    extern __shared__ uint64_t list[];  // [rev_cap rounded to 64]
+    const int64_t x0 = blockIdx.x;
+    const int lane = lane_id();
+    const int Lp = (a.rev_cap + 63) & ~63;
+    for (int i = lane; i < Lp; i += 64) list[i] = kKeyEmpty;
+    __syncthreads();
+    auto sync = [] { __syncthreads(); };
+    const int deg = a.g1_deg[x0];
+    uint64_t key = kKeyEmpty;
+    if (lane < deg) key = make_key(a.g1_s[x0 * a.K + lane], (uint32_t)a.g1_id[x0 * a.K + lane]);
+    list_merge(list, a.rev_cap, key, lane, sync);
+    __syncthreads();
+    const uint64_t b = a.start[x0], e = a.start[x0 + 1];
+    for (uint64_t p0 = b; p0 < e; p0 += 64) {
+        const uint64_t p = p0 + lane;
+        key = p < e ? make_key(a.rev_s[p], (uint32_t)a.rev_src[p]) : kKeyEmpty;
+        list_merge(list, a.rev_cap, key, lane, sync);
+        __syncthreads();
+    }
+    int cnt = 0;
+    for (int i = lane; i < a.rev_cap; i += 64) {
+        const uint64_t k = list[i];
+        const bool have = k != kKeyEmpty;
+        a.g2_id[x0 * a.rev_cap + i] = have ? (int32_t)key_id(k) : -1;
+        a.g2_s[x0 * a.rev_cap + i] = have ? key_dist(k) : kInfD;
+        cnt += have ? 1 : 0;
+    }
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    if (lane == 0) a.g2_deg[x0] = cnt;
+}
+
+// ------------------------------------------------------------------ stage 2
+struct Stage2Args {
+    const void* base;
+    const int32_t* g2_id;
+    const float* g2_s;
+    const int32_t* g2_deg;
+    uint32_t* packed;  // [N,K]
+    int* max_lambda;
+    int64_t N;
+    int d, K, rev_cap, lambda0;
+};
+
+template <typename T, int G, int C>
+__global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
+{
+    using RD = RowDist<T, G, C>;
+    extern __shared__ float sm[];
+    const int R = a.rev_cap;
+    float* P = sm;                                         // [R*R], upper triangle used
+    float* s0 = P + R * R;                                 // [R]
+    int32_t* ids = reinterpret_cast<int32_t*>(s0 + R);     // [R]
+    int* lam = reinterpret_cast<int*>(ids + R);            // [R]
+    const int64_t x0 = blockIdx.x;
+    const int lane = lane_id();
+    const T* __restrict__ base = static_cast<const T*>(a.base);
+    const int m = a.g2_deg[x0];
+    for (int i = lane; i < m; i += 64) {
+        ids[i] = a.g2_id[x0 * R + i];
+        s0[i] = a.g2_s[x0 * R + i];
+    }
+    for (int i = lane; i < a.K; i += 64) a.packed[x0 * a.K + i] = kPackPad;
+    __syncthreads();
+    RD rd;
+    rd.init(a.d, lane);
+    pairwise(rd, base, ids, m, P, R);
+    __syncthreads();
+
+    // lambda_j (Eq. 1, counted over the whole list, strict comparisons)
+    for (int j = lane; j < m; j += 64) {
+        const float sj = s0[j];
+        int cnt = 0;
+        for (int i = 0; i < m; ++i) {
+            if (i == j) continue;
+            const float pij = i < j ? P[i * R + j] : P[j * R + i];
+            cnt += (s0[i] < sj && pij < sj) ? 1 : 0;
+        }
+        lam[j] = cnt;
+    }
+    __syncthreads();
+    // rank by (lambda, s, id); entries with lambda <= lambda0 form a prefix of that order
+    int lmax = 0;
+    for (int j = lane; j < m; j += 64) {
+        const int lj = lam[j];
+        const uint64_t kj = make_key(s0[j], (uint32_t)ids[j]);
+        int r = 0;
+        for (int i = 0; i < m; ++i) {
+            const int li = lam[i];
+            const uint64_t ki = make_key(s0[i], (uint32_t)ids[i]);
+            r += (li < lj || (li == lj && ki < kj)) ? 1 : 0;
+        }
+        if (lj <= a.lambda0 && r < a.K) {
+            a.packed[x0 * a.K + r] = (uint32_t)ids[j] | ((uint32_t)lj << kIdBits);
+            lmax = max(lmax, lj);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) lmax = max(lmax, __shfl_xor(lmax, o, 64));
+    if (lane == 0 && lmax > 0) atomicMax(a.max_lambda, lmax);
+}
+
+// ------------------------------------------------------------------ host driver
+namespace {
+struct DevBuf {
+    void* p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+    template <typename T> T* as() { return static_cast<T*>(p); }
+};
+
+struct Stage1Launch {
+    Stage1Args a;
+    hipStream_t stream;
+    hipError_t err = hipSuccess;
+    template <typename T, int G, int C> void operator()()
+    {
+        const size_t lds = (size_t)a.K * a.K * 4 + (size_t)a.K * 8;
+        if (lds > 64 * 1024)
+            err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage1_kernel<T, G, C>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL((stage1_kernel<T, G, C>), dim3((unsigned)a.N), dim3(64), lds, stream, a);
+    }
+};
+struct Stage2Launch {
+    Stage2Args a;
+    hipStream_t stream;
+    hipError_t err = hipSuccess;
+    template <typename T, int G, int C> void operator()()
+    {
+        const size_t lds = (size_t)a.rev_cap * a.rev_cap * 4 + (size_t)a.rev_cap * 12;
+        if (lds > 64 * 1024)
+            err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage2_kernel<T, G, C>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL((stage2_kernel<T, G, C>), dim3((unsigned)a.N), dim3(64), lds, stream, a);
+    }
+};
+}  // namespace
+
+ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
+                     const float* knn_s, float alpha, int lambda0, int rev_cap, hipStream_t stream, uint32_t* packed,
+                     int* max_lambda)
+{
+    DevBuf g1_id, g1_s, g1_deg, indeg, cursor, start, bsums, rev_src, rev_s, g2_id, g2_s, g2_deg, mlam;
+    const size_t nk = (size_t)N * K;
+    TSDG_HIP(g1_id.alloc(nk * 4));
+    TSDG_HIP(g1_s.alloc(nk * 4));
+    TSDG_HIP(g1_deg.alloc((size_t)N * 4));
+    TSDG_HIP(indeg.alloc((size_t)N * 4));
+    TSDG_HIP(cursor.alloc((size_t)N * 4));
+    TSDG_HIP(start.alloc(((size_t)N + 1) * 8));
+    const int64_t nb = (N + kScanBlock - 1) / kScanBlock;
+    TSDG_HIP(bsums.alloc(((size_t)nb + 1) * 8));
+    TSDG_HIP(mlam.alloc(4));
+    TSDG_HIP(hipMemsetAsync(indeg.p, 0, (size_t)N * 4, stream));
+    TSDG_HIP(hipMemsetAsync(cursor.p, 0, (size_t)N * 4, stream));
+    TSDG_HIP(hipMemsetAsync(mlam.p, 0, 4, stream));
+
+    // stage 1
+    Stage1Launch s1;
+    s1.a.base = base;
+    s1.a.knn_id = knn_id;
+    s1.a.knn_s = knn_s;
+    s1.a.g1_id = g1_id.as<int32_t>();
+    s1.a.g1_s = g1_s.as<float>();
+    s1.a.g1_deg = g1_deg.as<int32_t>();
+    s1.a.indeg = indeg.as<unsigned>();
+    s1.a.N = N;
+    s1.a.d = d;
+    s1.a.K = K;
+    s1.a.alpha2 = alpha * alpha;
+    s1.stream = stream;
+    if (!dispatch_row_shape(dtype, d, s1)) {
+        set_error("unsupported row shape d=%d", d);
+        return ANN_EUNSUPPORTED;
+    }
+    TSDG_HIP(s1.err);
+    TSDG_HIP(hipGetLastError());
+
+    // reverse edges: scan of in-degrees, scatter, per-node merge
+    hipLaunchKernelGGL(scan_partial, dim3((unsigned)nb), dim3(256), 0, stream, indeg.as<unsigned>(), N,
+                       bsums.as<uint64_t>());
+    hipLaunchKernelGGL(scan_block_sums, dim3(1), dim3(64), 0, stream, bsums.as<uint64_t>(), nb);
+    hipLaunchKernelGGL(scan_final, dim3((unsigned)nb), dim3(256), 0, stream, indeg.as<unsigned>(), N,
+                       bsums.as<uint64_t>(), start.as<uint64_t>());
+    TSDG_HIP(hipGetLastError());
+    uint64_t total = 0;
+    TSDG_HIP(hipMemcpyAsync(&total, start.as<uint64_t>() + N, 8, hipMemcpyDeviceToHost, stream));
+    TSDG_HIP(hipStreamSynchronize(stream));
+    TSDG_HIP(rev_src.alloc((size_t)total * 4));
+    TSDG_HIP(rev_s.alloc((size_t)total * 4));
+    hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, stream, g1_id.as<int32_t>(),
+                       g1_s.as<float>(), (int64_t)nk, K, start.as<uint64_t>(), cursor.as<unsigned>(),
+                       rev_src.as<int32_t>(), rev_s.as<float>());
+    TSDG_HIP(hipGetLastError());
+
+    const size_t nr = (size_t)N * rev_cap;
+    TSDG_HIP(g2_id.alloc(nr * 4));
+    TSDG_HIP(g2_s.alloc(nr * 4));
+    TSDG_HIP(g2_deg.alloc((size_t)N * 4));
+    MergeArgs m;
+    m.g1_id = g1_id.as<int32_t>();
+    m.g1_s = g1_s.as<float>();
+    m.g1_deg = g1_deg.as<int32_t>();
+    m.start = start.as<uint64_t>();
+    m.rev_src = rev_src.as<int32_t>();
+    m.rev_s = rev_s.as<float>();
+    m.g2_id = g2_id.as<int32_t>();
+    m.g2_s = g2_s.as<float>();
+    m.g2_deg = g2_deg.as<int32_t>();
+    m.N = N;
+    m.K = K;
+    m.rev_cap = rev_cap;
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)N), dim3(64), (size_t)((rev_cap + 63) & ~63) * 8, stream, m);
+    TSDG_HIP(hipGetLastError());
+
+    // stage 2
+    Stage2Launch s2;
+    s2.a.base = base;
+    s2.a.g2_id = g2_id.as<int32_t>();
+    s2.a.g2_s = g2_s.as<float>();
+    s2.a.g2_deg = g2_deg.as<int32_t>();
+    s2.a.packed = packed;
+    s2.a.max_lambda = mlam.as<int>();
+    s2.a.N = N;
+    s2.a.d = d;
+    s2.a.K = K;
+    s2.a.rev_cap = rev_cap;
+    s2.a.lambda0 = lambda0;
+    s2.stream = stream;
+    dispatch_row_shape(dtype, d, s2);
+    TSDG_HIP(s2.err);
+    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(hipMemcpyAsync(max_lambda, mlam.p, 4, hipMemcpyDeviceToHost, stream));
+    TSDG_HIP(hipStreamSynchronize(stream));
+    return ANN_OK;
+}
+
+}  // namespace tsdg

@@ -1,0 +1,621 @@
+// Exact k nearest neighbours of a set of query rows against the whole base set
+// (build step B1 + B1r; also the brute-force ground truth).
+//
+// The squared distance is expanded as |q|^2 + |x|^2 - 2 q.x and the cross term is
+// a dense contraction on the matrix cores:
+//   * data that are integers in [0,255] (uint8 rows, SIFT-like fp32 rows) go
+//     through bf16 MFMA (v_mfma_f32_32x32x16_bf16): every product and every
+//     partial sum is an integer below 2^24, so the fp32 result is exact;
+//   * anything else goes through fp32 MFMA (v_mfma_f32_32x32x2_f32).
+// The contraction only SELECTS candidates: each query row keeps the K' = 2k
+// smallest approximate distances through a threshold filter fused into the tile
+// epilogue.  The base columns are swept in chunks of doubling size; after each
+// chunk a per-row pass sorts the row's buffer, keeps K' and lowers the row's
+// threshold, so the expected number of survivors per chunk stays near K' ln 2.
+// The kept candidates are then re-scored with the canonical distance, sorted by
+// (s, id) and cut to k.  A row is accepted only if its k-th canonical distance
+// lies below the final threshold minus a bound on the expansion's rounding
+// error (no rejected column can then belong to the answer, ties included);
+// rows that fail, or whose buffer overflowed, are redone by a plain scan of
+// all base rows with the canonical distance.
+#include <algorithm>
+#include <cstring>
+
+#include "dist.hpp"
+#include "ranklist.hpp"
+
+namespace tsdg {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+constexpr int kTile = 128;        // queries and candidates per workgroup tile
+constexpr int kTilesPerBlock = 8; // candidate tiles a workgroup sweeps
+constexpr float kInf = __builtin_inff();
+
+// ---------------------------------------------------------------- row norms, integer test
+// info[0] = 1 if some element is not an integer in [0,255]; info[1] = max norm (fp32 bits)
+template <typename T>
+__global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int64_t n, int d,
+                                                    float* __restrict__ norms, unsigned* __restrict__ info)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = lane_id();
+    if (row >= n) return;
+    double acc = 0.0;
+    bool nonint = false;
+    for (int j = lane; j < d; j += 64) {
+        const float v = (float)x[row * d + j];
+        acc += (double)v * (double)v;
+        nonint |= !(v >= 0.f && v <= 255.f && v == rintf(v));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    const float nf = (float)acc;
+    if (lane == 0) {
+        norms[row] = nf;
+        atomicMax(&info[1], __float_as_uint(nf));
+    }
+    if (ballot64(nonint) && lane == 0) atomicOr(&info[0], 1u);
+}
+
+// ---------------------------------------------------------------- tile loads
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const uint8_t* p)
+{
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+    return make_float4((float)(w & 0xFFu), (float)((w >> 8) & 0xFFu), (float)((w >> 16) & 0xFFu), (float)(w >> 24));
+}
+// exact for values representable in bf16 (integers up to 255 are)
+__device__ __forceinline__ uint16_t bf16_bits(float v) { return (uint16_t)(__float_as_uint(v) >> 16); }
+
+template <bool BF16> struct TileCfg;
+template <> struct TileCfg<true> {
+    static constexpr int DK = 64;            // k extent of a staged tile
+    static constexpr int STRIDE = DK + 8;    // in elements (144 B rows, 16-B aligned fragments)
+    using elem_t = uint16_t;
+};
+template <> struct TileCfg<false> {
+    static constexpr int DK = 16;
+    static constexpr int STRIDE = DK + 1;    // 17 floats: fragment reads hit distinct banks
+    using elem_t = float;
+};
+
+// Stages rows [r0, r0+128) x columns [k0, k0+DK) of src (zero beyond nrows / d) into LDS.
+template <bool BF16, typename T>
+__device__ __forceinline__ void stage_tile(typename TileCfg<BF16>::elem_t* lds, const T* __restrict__ src,
+                                           int64_t r0, int64_t nrows, int d, int k0)
+{
+    using Cfg = TileCfg<BF16>;
+    constexpr int CH = Cfg::DK / 4;  // 4-element chunks per row
+    for (int ch = (int)threadIdx.x; ch < kTile * CH; ch += 256) {
+        const int r = ch / CH, c4 = (ch % CH) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + r < nrows && k0 + c4 < d) v = load4(src + (r0 + r) * (int64_t)d + k0 + c4);
+        typename Cfg::elem_t* out = lds + r * Cfg::STRIDE + c4;
+        if constexpr (BF16) {
+            const uint32_t lo = (uint32_t)bf16_bits(v.x) | ((uint32_t)bf16_bits(v.y) << 16);
+            const uint32_t hi = (uint32_t)bf16_bits(v.z) | ((uint32_t)bf16_bits(v.w) << 16);
+            *reinterpret_cast<uint2*>(out) = make_uint2(lo, hi);
+        } else {
+            out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+        }
+    }
+}
+
+struct FilterArgs {
+    const void* q;        // [nq, d] query rows (type TQ), row 0 = global query q_begin
+    const void* x;        // [N, d] base rows (type TB)
+    const float* qnorm;   // [nq]
+    const float* xnorm;   // [N]
+    const float* tau;     // [nq] current thresholds
+    unsigned* cnt;        // [nq] entries in each row's buffer
+    uint64_t* buf;        // [nq, cap]  (approx distance bits << 32 | id)
+    int64_t nq, N;
+    int64_t c_begin, c_end;   // column chunk
+    int64_t self_offset;      // global id of query row 0 when queries are base rows, else -1
+    int d, cap;
+};
+
+// One workgroup: 128 queries x (kTilesPerBlock x 128) candidates.  4 waves in a 2x2
+// arrangement, each owning a 64x64 sub-tile = 2x2 MFMA blocks of 32x32.  The candidate
+// fragment is the A operand and the query fragment the B operand, so that the 16
+// accumulators a lane holds per block all belong to ONE query (column lane%32) and the
+// query's threshold and norm sit in that lane's registers.
+template <bool BF16, typename TQ, typename TB>
+__global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
+{
+    using Cfg = TileCfg<BF16>;
+    using elem_t = typename Cfg::elem_t;
+    __shared__ __attribute__((aligned(16))) elem_t Qs[kTile * Cfg::STRIDE];
+    __shared__ __attribute__((aligned(16))) elem_t Xs[kTile * Cfg::STRIDE];
+    __shared__ float xn[kTile];
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int wq = wave >> 1, wc = wave & 1;
+    const int64_t q0 = (int64_t)blockIdx.x * kTile;
+    const TQ* __restrict__ Q = static_cast<const TQ*>(a.q);
+    const TB* __restrict__ X = static_cast<const TB*>(a.x);
+
+    // this lane's two queries (one per query block)
+    int64_t qg[2];
+    float qn[2], tau[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        qg[qb] = q0 + wq * 64 + qb * 32 + (lane & 31);
+        const bool ok = qg[qb] < a.nq;
+        qn[qb] = ok ? a.qnorm[qg[qb]] : 0.f;
+        tau[qb] = ok ? a.tau[qg[qb]] : -kInf;
+    }
+
+    for (int t = 0; t < kTilesPerBlock; ++t) {
+        const int64_t c0 = a.c_begin + ((int64_t)blockIdx.y * kTilesPerBlock + t) * kTile;
+        if (c0 >= a.c_end) break;
+        floatx16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        for (int k0 = 0; k0 < a.d; k0 += Cfg::DK) {
+            __syncthreads();
+            stage_tile<BF16, TQ>(Qs, Q, q0, a.nq, a.d, k0);
+            stage_tile<BF16, TB>(Xs, X, c0, a.c_end, a.d, k0);
+            if (k0 == 0 && threadIdx.x < kTile) {
+                const int64_t c = c0 + threadIdx.x;
+                xn[threadIdx.x] = c < a.c_end ? a.xnorm[c] : 0.f;
+            }
+            __syncthreads();
+            if constexpr (BF16) {
+#pragma unroll
+                for (int ks = 0; ks < Cfg::DK / 16; ++ks) {
+                    const int ko = ks * 16 + 8 * (lane >> 5);
+                    bf16x8 xa[2], qb[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        xa[i] = *reinterpret_cast<const bf16x8*>(&Xs[(wc * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
+                        qb[i] = *reinterpret_cast<const bf16x8*>(&Qs[(wq * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qb[j], acc[i][j], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < Cfg::DK / 2; ++ks) {
+                    const int ko = ks * 2 + (lane >> 5);
+                    float xa[2], qb[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        xa[i] = Xs[(wc * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko];
+                        qb[i] = Qs[(wq * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], qb[j], acc[i][j], 0, 0, 0);
+                }
+            }
+        }
+
+        // epilogue: acc[i][j][r] = x_m . q_n with n = lane%32 (query block j) and
+        // m = 8*(r/4) + 4*(lane/32) + r%4 (candidate block i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (qg[j] >= a.nq) continue;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = wc * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const float dot = acc[i][j][r];
+                    const float s = (qn[j] - dot) + (xn[m] - dot);
+                    if (s < tau[j]) {
+                        const int64_t c = c0 + m;
+                        if (c < a.c_end && c != a.self_offset + qg[j]) {
+                            const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
+                            if (pos < (unsigned)a.cap)
+                                a.buf[qg[j] * a.cap + pos] =
+                                    ((uint64_t)__float_as_uint(fmaxf(s, 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- per-row compaction
+// Sorts the row's buffer (bitonic, in LDS), keeps the kprime smallest, sets tau to the
+// kprime-th approximate distance.  cnt > cap means entries were lost: the row is flagged.
+struct CompactArgs {
+    unsigned* cnt;
+    unsigned* kept;    // entries that were already sorted by the previous pass
+    uint64_t* buf;
+    float* tau;
+    unsigned* overflow;
+    int64_t nq;
+    int cap, kprime;
+};
+
+__global__ __launch_bounds__(64) void compact_kernel(CompactArgs a)
+{
+    extern __shared__ uint64_t sbuf[];  // [cap]
+    const int64_t row = blockIdx.x;
+    const int lane = lane_id();
+    unsigned n = a.cnt[row];
+    if (n > (unsigned)a.cap) {
+        if (lane == 0) a.overflow[row] = 1u;
+        n = (unsigned)a.cap;
+    }
+    if (n == a.kept[row]) return;  // nothing new since the last pass
+    uint64_t* g = a.buf + row * a.cap;
+    int p2 = 64;
+    while (p2 < (int)n) p2 <<= 1;
+    for (int i = lane; i < p2; i += 64) sbuf[i] = i < (int)n ? g[i] : kKeyEmpty;
+    __syncthreads();
+    for (int size = 2; size <= p2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int t = lane; t < p2 / 2; t += 64) {
+                const int lo = 2 * t - (t & (stride - 1));  // index with bit `stride` clear
+                const int hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint64_t x = sbuf[lo], y = sbuf[hi];
+                if ((x > y) == up) {
+                    sbuf[lo] = y;
+                    sbuf[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    const int keep = min((int)n, a.kprime);
+    for (int i = lane; i < keep; i += 64) g[i] = sbuf[i];
+    if (lane == 0) {
+        a.cnt[row] = (unsigned)keep;
+        a.kept[row] = (unsigned)keep;
+        a.tau[row] = keep == a.kprime ? __uint_as_float((uint32_t)(sbuf[a.kprime - 1] >> 32)) : kInf;
+    }
+}
+
+// ---------------------------------------------------------------- re-scoring (B1r)
+struct RefineArgs {
+    const void* q;
+    const void* x;
+    const float* qnorm;
+    const unsigned* cnt;
+    const uint64_t* buf;
+    const float* tau;
+    const unsigned* overflow;
+    int32_t* out_ids;     // [nq_total, k], row offset applied by the caller
+    float* out_s;
+    unsigned* redo_cnt;
+    int32_t* redo_rows;   // local row indices that need the plain scan
+    int64_t nq;
+    int d, cap, k;
+    float err_scale;      // rounding-error bound of the expansion = err_scale * (|q|^2 + max|x|^2)
+    float xnorm_max;
+    int q_is_base;        // query rows are of the base type
+};
+
+// One wavefront per query row: canonical distances of the kept candidates, merged 64 at a
+// time into a sorted list of k, then the acceptance test.
+template <typename TQ, typename TB, int G, int C>
+__global__ __launch_bounds__(64) void refine_kernel(RefineArgs a)
+{
+    using RD = RowDist<TB, G, C>;
+    using chunk_t = typename RD::chunk_t;
+    constexpr int VP = RD::VP;
+    extern __shared__ uint64_t smem[];
+    const int Lp = (a.k + 63) & ~63;
+    uint64_t* list = smem;       // [Lp]
+    uint64_t* ckey = list + Lp;  // [64]
+    const int64_t row = blockIdx.x;
+    const int lane = lane_id();
+    const TB* __restrict__ X = static_cast<const TB*>(a.x);
+
+    for (int i = lane; i < Lp; i += 64) list[i] = kKeyEmpty;
+    RD rd;
+    rd.init(a.d, lane);
+    if constexpr (sizeof(TQ) == sizeof(TB)) {
+        if (a.q_is_base) rd.load_query_row(static_cast<const TB*>(a.q), (uint32_t)row);
+        else rd.load_query_f32(reinterpret_cast<const float*>(a.q) + row * a.d);
+    } else {
+        rd.load_query_f32(static_cast<const float*>(a.q) + row * a.d);
+    }
+    __syncthreads();
+
+    const int n = (int)min(a.cnt[row], (unsigned)a.cap);
+    const uint64_t* g = a.buf + row * a.cap;
+    auto sync = [] { __syncthreads(); };
+    for (int b0 = 0; b0 < n; b0 += 64) {
+        const int m = min(64, n - b0);
+        for (int p0 = 0; p0 < m; p0 += VP) {
+            const int c = p0 + rd.v;
+            const bool ok = c < m;
+            const uint32_t e = ok ? (uint32_t)(g[b0 + c] & 0xFFFFFFFFull) : 0u;
+            chunk_t buf[C];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) {
+                buf[cc] = chunk_t{};
+                if (ok && rd.has(cc)) buf[cc] = rd.load(X, e, cc);
+            }
+            const double tot = RD::group_sum(rd.partial(buf));
+            if (ok && rd.g == 0) ckey[c] = make_key((float)tot, e);
+        }
+        __syncthreads();
+        const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
+        list_merge(list, a.k, key, lane, sync);
+        __syncthreads();
+    }
+
+    // acceptance: the k-th canonical distance must lie below tau - error bound
+    const uint64_t kth = list[a.k - 1];
+    const float tau = a.tau[row];
+    const float err = a.err_scale * (a.qnorm[row] + a.xnorm_max);
+    bool accept = !a.overflow[row];
+    if (tau != kInf) accept = accept && kth != kKeyEmpty && key_dist(kth) < tau - err;
+    if (!accept && lane == 0) a.redo_rows[atomicAdd(a.redo_cnt, 1u)] = (int32_t)row;
+    for (int t = lane; t < a.k; t += 64) {
+        const uint64_t key = list[t];
+        a.out_ids[row * a.k + t] = key != kKeyEmpty ? (int32_t)key_id(key) : -1;
+        a.out_s[row * a.k + t] = key != kKeyEmpty ? key_dist(key) : kInf;
+    }
+}
+
+// ---------------------------------------------------------------- plain scan for rejected rows
+template <typename TQ, typename TB, int G, int C>
+__global__ __launch_bounds__(64) void scan_kernel(RefineArgs a, int64_t N, int64_t self_offset)
+{
+    using RD = RowDist<TB, G, C>;
+    using chunk_t = typename RD::chunk_t;
+    constexpr int VP = RD::VP;
+    constexpr int U = (C >= 3) ? 2 : 4;
+    extern __shared__ uint64_t smem[];
+    const int Lp = (a.k + 63) & ~63;
+    uint64_t* list = smem;
+    uint64_t* ckey = list + Lp;
+    const int64_t row = a.redo_rows[blockIdx.x];
+    const int lane = lane_id();
+    const TB* __restrict__ X = static_cast<const TB*>(a.x);
+    for (int i = lane; i < Lp; i += 64) list[i] = kKeyEmpty;
+    RD rd;
+    rd.init(a.d, lane);
+    if constexpr (sizeof(TQ) == sizeof(TB)) {
+        if (a.q_is_base) rd.load_query_row(static_cast<const TB*>(a.q), (uint32_t)row);
+        else rd.load_query_f32(reinterpret_cast<const float*>(a.q) + row * a.d);
+    } else {
+        rd.load_query_f32(static_cast<const float*>(a.q) + row * a.d);
+    }
+    __syncthreads();
+    auto sync = [] { __syncthreads(); };
+    const int64_t self = self_offset >= 0 ? self_offset + row : -1;
+    for (int64_t b0 = 0; b0 < N; b0 += 64) {
+        const int m = (int)min((int64_t)64, N - b0);
+        for (int p0 = 0; p0 < m; p0 += U * VP) {
+            chunk_t buf[U][C];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = p0 + u * VP + rd.v;
+                ok[u] = c < m;
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    buf[u][cc] = chunk_t{};
+                    if (ok[u] && rd.has(cc)) buf[u][cc] = rd.load(X, (uint32_t)(b0 + c), cc);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = p0 + u * VP + rd.v;
+                const double tot = RD::group_sum(rd.partial(buf[u]));
+                if (ok[u] && rd.g == 0)
+                    ckey[c] = (b0 + c == self) ? kKeyEmpty : make_key((float)tot, (uint32_t)(b0 + c));
+            }
+        }
+        __syncthreads();
+        const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
+        list_merge(list, a.k, key, lane, sync);
+        __syncthreads();
+    }
+    for (int t = lane; t < a.k; t += 64) {
+        const uint64_t key = list[t];
+        a.out_ids[row * a.k + t] = key != kKeyEmpty ? (int32_t)key_id(key) : -1;
+        a.out_s[row * a.k + t] = key != kKeyEmpty ? key_dist(key) : kInf;
+    }
+}
+
+__global__ void fill_f32(float* p, int64_t n, float v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------- host driver
+namespace {
+
+struct DevBuf {
+    void* p = nullptr;
+    ~DevBuf() { if (p) (void)hipFree(p); }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+    template <typename T> T* as() { return static_cast<T*>(p); }
+};
+
+template <typename TQ, typename TB> struct RefineLaunch {
+    RefineArgs a;
+    int64_t N, self_offset;
+    unsigned redo;
+    hipStream_t stream;
+    bool scan;
+    template <typename T, int G, int C> void operator()()
+    {
+        const int Lp = (a.k + 63) & ~63;
+        const size_t lds = (size_t)Lp * 8 + 64 * 8;
+        if (!scan)
+            hipLaunchKernelGGL((refine_kernel<TQ, TB, G, C>), dim3((unsigned)a.nq), dim3(64), lds, stream, a);
+        else
+            hipLaunchKernelGGL((scan_kernel<TQ, TB, G, C>), dim3(redo), dim3(64), lds, stream, a, N, self_offset);
+    }
+};
+
+template <typename TQ, typename TB>
+ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ* queries, int64_t nq, int k,
+                     bool self, hipStream_t stream, int32_t* out_ids, float* out_s)
+{
+    const int kprime = std::min(2 * k, k + 64);
+    const int cap = kprime + 192 <= 256 ? 256 : 512;
+    const int64_t row_block = 1ll << 21;  // query rows per sweep (bounds the candidate buffers: 4-8 GB)
+
+    DevBuf xnorm, qnorm, info, tau, cnt, kept, ovf, buf, redo_cnt, redo_rows;
+    TSDG_HIP(xnorm.alloc((size_t)N * 4));
+    TSDG_HIP(info.alloc(4 * sizeof(unsigned)));
+    TSDG_HIP(hipMemsetAsync(info.p, 0, 4 * sizeof(unsigned), stream));
+    hipLaunchKernelGGL((norms_kernel<TB>), dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, base, N, d,
+                       xnorm.as<float>(), info.as<unsigned>());
+    TSDG_HIP(hipGetLastError());
+    float* qn = xnorm.as<float>();
+    if (!self) {
+        TSDG_HIP(qnorm.alloc((size_t)nq * 4));
+        hipLaunchKernelGGL((norms_kernel<TQ>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, stream, queries, nq, d,
+                           qnorm.as<float>(), info.as<unsigned>() + 2);
+        TSDG_HIP(hipGetLastError());
+        qn = qnorm.as<float>();
+    }
+    unsigned h_info[4];
+    TSDG_HIP(hipMemcpyAsync(h_info, info.p, sizeof(h_info), hipMemcpyDeviceToHost, stream));
+    TSDG_HIP(hipStreamSynchronize(stream));
+    const bool integer_data = h_info[0] == 0 && (self || h_info[2] == 0);
+    float xnorm_max;
+    std::memcpy(&xnorm_max, &h_info[1], 4);
+    // exact when every product and partial sum is an integer below 2^24
+    const bool exact = integer_data && (double)d * 255.0 * 255.0 < 16777216.0;
+    const float err_scale = exact ? 0.f : (float)((d + 8) * 5.9604645e-8 * 1.01);
+
+    const int64_t rb = std::min(row_block, nq);
+    TSDG_HIP(tau.alloc((size_t)rb * 4));
+    TSDG_HIP(cnt.alloc((size_t)rb * 4));
+    TSDG_HIP(kept.alloc((size_t)rb * 4));
+    TSDG_HIP(ovf.alloc((size_t)rb * 4));
+    TSDG_HIP(buf.alloc((size_t)rb * cap * 8));
+    TSDG_HIP(redo_cnt.alloc(4));
+    TSDG_HIP(redo_rows.alloc((size_t)rb * 4));
+
+    for (int64_t r0 = 0; r0 < nq; r0 += rb) {
+        const int64_t nr = std::min(rb, nq - r0);
+        TSDG_HIP(hipMemsetAsync(cnt.p, 0, (size_t)nr * 4, stream));
+        TSDG_HIP(hipMemsetAsync(kept.p, 0, (size_t)nr * 4, stream));
+        TSDG_HIP(hipMemsetAsync(ovf.p, 0, (size_t)nr * 4, stream));
+        TSDG_HIP(hipMemsetAsync(redo_cnt.p, 0, 4, stream));
+        hipLaunchKernelGGL(fill_f32, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, stream, tau.as<float>(), nr, kInf);
+
+        FilterArgs f;
+        f.q = queries + r0 * d;
+        f.x = base;
+        f.qnorm = qn + r0;
+        f.xnorm = xnorm.as<float>();
+        f.tau = tau.as<float>();
+        f.cnt = cnt.as<unsigned>();
+        f.buf = buf.as<uint64_t>();
+        f.nq = nr;
+        f.N = N;
+        f.self_offset = self ? r0 : -1 - nq;  // never equal to a column id when not self
+        f.d = d;
+        f.cap = cap;
+        CompactArgs c;
+        c.cnt = cnt.as<unsigned>();
+        c.kept = kept.as<unsigned>();
+        c.buf = buf.as<uint64_t>();
+        c.tau = tau.as<float>();
+        c.overflow = ovf.as<unsigned>();
+        c.nq = nr;
+        c.cap = cap;
+        c.kprime = kprime;
+
+        // column chunks of doubling size; the first must fit a buffer even with tau = +inf
+        int64_t cb = 0, width = cap - kprime >= 128 ? 128 : 64;
+        while (cb < N) {
+            const int64_t ce = std::min(N, cb + width);
+            f.c_begin = cb;
+            f.c_end = ce;
+            const int64_t tiles = (ce - cb + kTile - 1) / kTile;
+            dim3 grid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((tiles + kTilesPerBlock - 1) / kTilesPerBlock));
+            if (integer_data)
+                hipLaunchKernelGGL((filter_kernel<true, TQ, TB>), grid, dim3(256), 0, stream, f);
+            else
+                hipLaunchKernelGGL((filter_kernel<false, TQ, TB>), grid, dim3(256), 0, stream, f);
+            TSDG_HIP(hipGetLastError());
+            hipLaunchKernelGGL(compact_kernel, dim3((unsigned)nr), dim3(64), (size_t)cap * 8, stream, c);
+            TSDG_HIP(hipGetLastError());
+            cb = ce;
+            width = std::max<int64_t>(width, cb);  // next chunk as wide as everything seen so far
+        }
+
+        RefineLaunch<TQ, TB> rl;
+        rl.a.q = queries + r0 * d;
+        rl.a.x = base;
+        rl.a.qnorm = qn + r0;
+        rl.a.cnt = cnt.as<unsigned>();
+        rl.a.buf = buf.as<uint64_t>();
+        rl.a.tau = tau.as<float>();
+        rl.a.overflow = ovf.as<unsigned>();
+        rl.a.out_ids = out_ids + r0 * k;
+        rl.a.out_s = out_s + r0 * k;
+        rl.a.redo_cnt = redo_cnt.as<unsigned>();
+        rl.a.redo_rows = redo_rows.as<int32_t>();
+        rl.a.nq = nr;
+        rl.a.d = d;
+        rl.a.cap = cap;
+        rl.a.k = k;
+        rl.a.err_scale = err_scale;
+        rl.a.xnorm_max = xnorm_max;
+        rl.a.q_is_base = self ? 1 : 0;
+        rl.N = N;
+        rl.self_offset = self ? r0 : -1;
+        rl.stream = stream;
+        rl.scan = false;
+        rl.redo = 0;
+        if (!dispatch_row_shape(dtype, d, rl)) {
+            set_error("unsupported row shape d=%d", d);
+            return ANN_EUNSUPPORTED;
+        }
+        TSDG_HIP(hipGetLastError());
+        unsigned redo = 0;
+        TSDG_HIP(hipMemcpyAsync(&redo, redo_cnt.p, 4, hipMemcpyDeviceToHost, stream));
+        TSDG_HIP(hipStreamSynchronize(stream));
+        if (redo > 0) {
+            rl.scan = true;
+            rl.redo = redo;
+            dispatch_row_shape(dtype, d, rl);
+            TSDG_HIP(hipGetLastError());
+        }
+    }
+    TSDG_HIP(hipStreamSynchronize(stream));
+    return ANN_OK;
+}
+
+}  // namespace
+
+ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries, int64_t nq, int k,
+                     bool exclude_self, hipStream_t stream, int32_t* out_ids, float* out_s)
+{
+    if (exclude_self) {
+        if (dtype == ANN_U8)
+            return knn_typed<uint8_t, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype,
+                                               static_cast<const uint8_t*>(base), N, k, true, stream, out_ids, out_s);
+        return knn_typed<float, float>(static_cast<const float*>(base), N, d, dtype, static_cast<const float*>(base),
+                                       N, k, true, stream, out_ids, out_s);
+    }
+    if (dtype == ANN_U8)
+        return knn_typed<float, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype, queries, nq, k, false, stream,
+                                         out_ids, out_s);
+    return knn_typed<float, float>(static_cast<const float*>(base), N, d, dtype, queries, nq, k, false, stream,
+                                   out_ids, out_s);
+}
+
+}  // namespace tsdg

@@ -1,0 +1,258 @@
+// Best-first k-NN search over the diversified graph (paper Sec. 4; steps S0-S7).
+//
+// One kernel template serves both batch regimes:
+//   WAVES == 1  large batch: one 64-lane wavefront per query, one query per
+//               workgroup, so the hardware dispatcher balances queries over CUs
+//               (the shape of Alg. 2: all per-query state in on-chip memory,
+//               one warp/wave per query);
+//   WAVES  > 1  small batch: the same search, with the distance evaluations of a
+//               hop (S5) split over the wavefronts of one workgroup, while
+//               wavefront 0 keeps the rank-list and the visited set (Sec. 4.1
+//               motivates spending more threads per query when few queries are
+//               in flight; Alg. 1's independent multi-search is not this kernel).
+//
+// Per query, in LDS: the rank-list (L keys), the visited hash, and the hop's
+// compacted candidate ids / keys.  Global reads per hop: one packed adjacency
+// row, then the gathered base rows of the unvisited neighbours.
+#include "dist.hpp"
+#include "ranklist.hpp"
+
+namespace tsdg {
+
+struct SearchArgs {
+    const uint32_t* packed;
+    const void* base;
+    const float* queries;
+    int32_t* out_ids;
+    float* out_dists;
+    ann_query_stats* stats;
+    uint64_t N;
+    uint64_t seed;
+    int64_t qi_offset;
+    int K, d, k, L, lambda_visit, n_seeds, max_hops, slots;
+};
+
+__device__ __forceinline__ uint32_t seed_node(uint64_t seed, uint64_t qi, uint32_t j, uint64_t N)
+{
+    // counter-based: splitmix64 output function of seed + GOLDEN*(qi*2^32 + j + 1), scaled to [0,N)
+    uint64_t x = seed + 0x9E3779B97F4A7C15ull * ((qi << 32) + (uint64_t)j + 1ull);
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    x = x ^ (x >> 31);
+    return (uint32_t)__umul64hi(x, N);
+}
+
+template <int WAVES> struct ListSync {
+    __device__ __forceinline__ void operator()() const
+    {
+        if constexpr (WAVES == 1) __syncthreads(); else wave_sync();
+    }
+};
+
+template <typename T, int G, int C, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
+{
+    using RD = RowDist<T, G, C>;
+    using chunk_t = typename RD::chunk_t;
+    constexpr int VP = RD::VP;
+    constexpr int U = (C >= 8) ? 1 : (C >= 3 ? 2 : 4);  // passes in flight per wave
+
+    extern __shared__ uint64_t smem[];
+    const int L = a.L;
+    const int Lp = (L + 63) & ~63;
+    uint64_t* list = smem;                                   // [Lp]
+    uint64_t* ckey = list + Lp;                              // [64]
+    uint32_t* cid = reinterpret_cast<uint32_t*>(ckey + 64);  // [64]
+    uint32_t* table = cid + 64;                              // [slots]
+    int* ctl = reinterpret_cast<int*>(table + a.slots);      // [4]
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int qi = (int)blockIdx.x;
+    const T* __restrict__ base = static_cast<const T*>(a.base);
+
+    for (int i = (int)threadIdx.x; i < Lp; i += 64 * WAVES) list[i] = kKeyEmpty;
+    for (int i = (int)threadIdx.x; i < a.slots; i += 64 * WAVES) table[i] = kHashEmpty;
+
+    RD rd;
+    rd.init(a.d, lane);
+    rd.load_query_f32(a.queries + (size_t)qi * (size_t)a.d);  // S0
+    __syncthreads();
+
+    uint32_t hops = 0, evals = 0, dedup = 0;
+    ListSync<WAVES> lsync;
+
+    // Scores the hop's candidates (ids in `id`, one per lane of wave 0) and merges them.
+    auto process = [&](uint32_t id, bool valid) {
+        if (wave == 0) {
+            bool seen = false;
+            if (valid) seen = visited_test_and_set(table, a.slots, id);  // S4
+            const uint64_t nm = ballot64(valid && !seen);
+            dedup += (uint32_t)popc64(ballot64(valid && seen));
+            if (valid && !seen) cid[popc64(nm & lanes_below(lane))] = id;
+            if (lane == 0) ctl[1] = popc64(nm);
+        }
+        __syncthreads();
+        const int m = ctl[1];
+        if (m == 0) return;
+        evals += (uint32_t)m;
+        // S5: gather + distance.  Batch = U passes of VP rows; waves take batches in turn.
+        for (int b0 = wave * U * VP; b0 < m; b0 += WAVES * U * VP) {
+            chunk_t buf[U][C];
+            uint32_t e[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = b0 + u * VP + rd.v;
+                ok[u] = c < m;
+                e[u] = ok[u] ? cid[c] : 0u;
+#pragma unroll
+                for (int cc = 0; cc < C; ++cc) {
+                    buf[u][cc] = chunk_t{};
+                    if (ok[u] && rd.has(cc)) buf[u][cc] = rd.load(base, e[u], cc);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const double tot = RD::group_sum(rd.partial(buf[u]));
+                if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key((float)tot, e[u]);
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
+            list_merge(list, L, key, lane, lsync);  // S6
+        }
+    };
+
+    // S1: seeds, 64 at a time; repeats inside a group of 64 are dropped here, repeats across
+    // groups by the visited set.
+    for (int j0 = 0; j0 < a.n_seeds; j0 += 64) {
+        const int j = j0 + lane;
+        bool valid = j < a.n_seeds;
+        uint32_t id = valid ? seed_node(a.seed, (uint64_t)(a.qi_offset + qi), (uint32_t)j, a.N) : 0u;
+        if (wave == 0) {
+            const uint64_t vm = ballot64(valid);
+            for (uint64_t mm = vm; mm; mm &= mm - 1) {
+                const int o = ctz64(mm);
+                const uint32_t ido = bcast32(id, o);
+                if (o < lane && ido == id) valid = false;
+            }
+        }
+        process(id, valid);
+    }
+
+    for (;;) {
+        if (wave == 0) {
+            int idx = list_first_unexpanded(list, L, lane);  // S2
+            if (a.max_hops > 0 && (int)hops >= a.max_hops) idx = -1;
+            int u = -1;
+            if (idx >= 0) {
+                const uint64_t key = list[idx];
+                u = (int)key_id(key);
+                lsync();
+                if (lane == 0) list[idx] = key | 1ull;
+            }
+            if (lane == 0) ctl[0] = u;
+        }
+        __syncthreads();
+        const int u = ctl[0];
+        if (u < 0) break;
+        ++hops;
+        uint32_t id = 0;
+        bool valid = false;
+        if (wave == 0) {  // S3: adjacency row, prefix with lambda < lambda_visit
+            uint32_t w = kPackPad;
+            if (lane < a.K) w = a.packed[(size_t)u * (size_t)a.K + lane];
+            const bool ok = w != kPackPad && (int)(w >> kIdBits) < a.lambda_visit;
+            const uint64_t bad = ~ballot64(ok);
+            const int deg = bad ? ctz64(bad) : 64;
+            valid = lane < deg;
+            id = w & kIdMask;
+        }
+        process(id, valid);
+    }
+
+    // S7
+    if (wave == 0) {
+        for (int t = lane; t < a.k; t += 64) {
+            const uint64_t key = list[t];
+            const bool have = key != kKeyEmpty;
+            a.out_ids[(size_t)qi * a.k + t] = have ? (int32_t)key_id(key) : -1;
+            a.out_dists[(size_t)qi * a.k + t] = have ? key_dist(key) : __builtin_inff();
+        }
+        if (a.stats && lane == 0) {
+            ann_query_stats st;
+            st.hops = hops;
+            st.dist_evals = evals;
+            st.dedup_hits = dedup;
+            a.stats[qi] = st;
+        }
+    }
+}
+
+template <typename T, int G, int C, int WAVES> static ann_status launch_variant(const SearchLaunch& s)
+{
+    SearchArgs a;
+    a.packed = s.packed;
+    a.base = s.base;
+    a.queries = s.queries;
+    a.out_ids = s.out_ids;
+    a.out_dists = s.out_dists;
+    a.stats = s.stats;
+    a.N = (uint64_t)s.N;
+    a.seed = s.seed;
+    a.qi_offset = s.qi_offset;
+    a.K = s.K;
+    a.d = s.d;
+    a.k = s.k;
+    a.L = s.L;
+    a.lambda_visit = s.lambda_visit;
+    a.n_seeds = s.n_seeds;
+    a.max_hops = s.max_hops;
+    a.slots = s.visited_slots;
+    const int Lp = (s.L + 63) & ~63;
+    const size_t lds = (size_t)Lp * 8 + 64 * 8 + 64 * 4 + (size_t)s.visited_slots * 4 + 16;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&search_kernel<T, G, C, WAVES>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) {
+            set_error("hipFuncSetAttribute(%zu bytes of LDS) failed: %s", lds, hipGetErrorString(e));
+            return ANN_EDEVICE;
+        }
+    }
+    hipLaunchKernelGGL((search_kernel<T, G, C, WAVES>), dim3((unsigned)s.nq), dim3(64 * WAVES), lds, s.stream, a);
+    TSDG_HIP(hipGetLastError());
+    return ANN_OK;
+}
+
+namespace {
+struct SearchDispatch {
+    const SearchLaunch& s;
+    ann_status rc = ANN_EUNSUPPORTED;
+    template <typename T, int G, int C> void operator()()
+    {
+        switch (s.waves) {
+            case 1: rc = launch_variant<T, G, C, 1>(s); break;
+            case 2: rc = launch_variant<T, G, C, 2>(s); break;
+            case 4: rc = launch_variant<T, G, C, 4>(s); break;
+            case 8: rc = launch_variant<T, G, C, 8>(s); break;
+            default: set_error("waves_per_query must be 1, 2, 4 or 8"); rc = ANN_EINVAL; break;
+        }
+    }
+};
+}  // namespace
+
+ann_status launch_search(const SearchLaunch& s)
+{
+    if (s.nq == 0) return ANN_OK;
+    SearchDispatch disp{s};
+    if (!dispatch_row_shape(s.dtype, s.d, disp)) {
+        set_error("unsupported row shape: d=%d dtype=%d (d must be a multiple of %d and at most %d)", s.d,
+                  (int)s.dtype, s.dtype == ANN_U8 ? 16 : 4, s.dtype == ANN_U8 ? 1024 : 2048);
+        return ANN_EUNSUPPORTED;
+    }
+    return disp.rc;
+}
+
+}  // namespace tsdg

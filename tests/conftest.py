@@ -18,3 +18,57 @@ def orc():
     import oracle
     oracle.lib()
     return oracle
+
+
+def step(msg: str) -> None:
+    """Names the GPU case about to run: printed unbuffered and appended to
+    gpurun_out/steps.log, so that a run that dies still says where it was."""
+    line = f"[step] {msg}"
+    print(line, file=sys.stderr, flush=True)
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "steps.log"), "a") as f:
+            f.write(line + "\n")
+            f.flush()
+            os.fsync(f.fileno())
+    except OSError:
+        pass
+
+
+@pytest.fixture(scope="session")
+def gpu():
+    """torch + the HIP library on cuda:0; fails loudly when either is missing."""
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2204_00824_amd as P
+    P.load_library()
+    return P
+
+
+_cache = {}
+
+
+def cached(key, fn):
+    if key not in _cache:
+        _cache[key] = fn()
+    return _cache[key]
+
+
+def tiny_case(orc):
+    """Tiny workload + oracle graph (K=16) with the intermediate stages."""
+    def make():
+        import workloads
+        base, queries = workloads.tiny()
+        adj, lam, st = orc.build_graph(base, 16, stages=True)
+        return base, queries, adj, lam, st
+    return cached("tiny", make)
+
+
+def sift_case(orc):
+    """20,000 integer-valued rows of d=128 + oracle graph (K=32) with the intermediate stages."""
+    def make():
+        import workloads
+        base, queries = workloads.sift_like(N=20000, nq=300, seed=77)
+        adj, lam, st = orc.build_graph(base, 32, stages=True)
+        return base, queries, adj, lam, st
+    return cached("sift20k", make)

@@ -1,0 +1,166 @@
+"""Parity of the HIP graph build (exact k-NN contraction, two-stage diversification)
+and of the brute-force top-k with the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from conftest import cached, sift_case, step, tiny_case
+from parity import assert_bitwise, compare_topk
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_graph(gpu, orc, base, K, what, ref=None, **kw):
+    """GPU build vs oracle build: adjacency and lambda identical, except in rows where the
+    oracle's own competing distances are closer than 1e-5 relative."""
+    okw = dict(alpha=kw.get("alpha", 1.2), lambda0=kw.get("lambda0", 9))
+    if kw.get("rev_cap"):
+        okw["rev_cap"] = kw["rev_cap"]
+    adj_o, lam_o, st = ref if ref is not None else orc.build_graph(base, K, stages=True, **okw)
+    g = gpu.ann_build_graph_ex(dev(base), K, **kw)
+    adj, lam = gpu.ann_graph_export(g)
+    adj, lam = adj.cpu().numpy(), lam.cpu().numpy()
+    assert gpu.ann_graph_info(g) == (base.shape[0], K, base.shape[1])
+    rows = np.unique(np.argwhere((adj != adj_o) | (lam != lam_o))[:, 0])
+    for r in rows:                                   # excuse only near-ties inside the oracle's lists
+        s = np.sort(st["g2_s"][r][:st["g2_deg"][r]].astype(np.float64))
+        gaps = np.diff(s) / np.maximum(s[1:], 1e-30)
+        assert gaps.size and gaps.min() < 1e-5, (f"{what}: row {r} differs without a near-tie: "
+                                                 f"{adj[r]} / {lam[r]} vs {adj_o[r]} / {lam_o[r]}")
+    assert len(rows) <= 0.01 * base.shape[0], f"{what}: {len(rows)} rows excused"
+    valid = adj >= 0
+    assert np.all(lam[valid] <= okw["lambda0"]) and np.all(lam[~valid] == 255)
+    return len(rows)
+
+
+def test_knn_tiny_fp32(gpu, orc):
+    step("ann_knn tiny (fp32 MFMA path)")
+    base, _, _, _, st = tiny_case(orc)
+    ref = (st["knn_id"], st["knn_s"])
+    ids, s = gpu.ann_knn(dev(base), 16)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "knn tiny") == 0
+    assert_bitwise(s.cpu().numpy(), ref[1], "knn tiny dists")
+
+
+def test_knn_integer_bf16(gpu, orc):
+    step("ann_knn sift-like 20k (bf16 MFMA path, exact)")
+    base, _, _, _, st = sift_case(orc)
+    ref = (st["knn_id"], st["knn_s"])
+    ids, s = gpu.ann_knn(dev(base), 32)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "knn ids")
+    assert_bitwise(s.cpu().numpy(), ref[1], "knn dists")
+
+
+def test_knn_ragged_sizes_and_ties(gpu, orc):
+    """N not a multiple of any tile; integer lattice (many equal distances, id tie rule);
+    exact duplicates."""
+    step("ann_knn ragged / lattice / duplicates")
+    lat = workloads.integer_lattice(23)                        # 529 points
+    b = np.zeros((529, 4), np.float32)
+    b[:, :2] = lat
+    ref = orc.knn(b, 12)
+    ids, s = gpu.ann_knn(dev(b), 12)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "lattice ids")
+    assert_bitwise(s.cpu().numpy(), ref[1], "lattice dists")
+    g = np.random.default_rng(3)
+    x = g.standard_normal((1237, 20)).astype(np.float32)
+    x[100:110] = x[5]                                          # ten exact copies of row 5
+    ref = orc.knn(x, 15)
+    ids, s = gpu.ann_knn(dev(x), 15)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "dups") == 0
+    tiny_n = g.standard_normal((9, 8)).astype(np.float32)      # N barely above K
+    ref = orc.knn(tiny_n, 8)
+    ids, s = gpu.ann_knn(dev(tiny_n), 8)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "N=9 ids")
+
+
+def test_knn_uint8(gpu, orc):
+    step("ann_knn uint8")
+    base, _ = workloads.sift_like(N=6000, nq=1, seed=5)
+    b8 = base.astype(np.uint8)
+    ref = orc.knn(b8, 16)
+    ids, s = gpu.ann_knn(dev(b8), 16)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "u8 knn ids")
+    assert_bitwise(s.cpu().numpy(), ref[1], "u8 knn dists")
+
+
+@pytest.mark.parametrize("d", [8, 96, 960])
+def test_knn_real_valued_shapes(gpu, orc, d):
+    step(f"ann_knn gaussian d={d}")
+    base = workloads.single_gaussian(3000 if d < 900 else 1500, d, seed=100 + d)
+    ref = orc.knn(base, 16)
+    ids, s = gpu.ann_knn(dev(base), 16)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"knn d={d}") == 0
+
+
+def test_bruteforce(gpu, orc):
+    step("ann_bruteforce")
+    base, queries = workloads.tiny()
+    ref = orc.bruteforce(base, queries, 10)
+    ids, s = gpu.ann_bruteforce(dev(base), dev(queries), 10)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "bf tiny") == 0
+    base, queries = sift_case(orc)[:2]
+    ref = orc.bruteforce(base, queries, 100)
+    ids, s = gpu.ann_bruteforce(dev(base), dev(queries), 100)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "bf sift ids")
+    assert_bitwise(s.cpu().numpy(), ref[1], "bf sift dists")
+    b8 = base[:5000].astype(np.uint8)
+    ref = orc.bruteforce(b8, queries[:50], 10)
+    ids, s = gpu.ann_bruteforce(dev(b8), dev(queries[:50]), 10)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "bf u8 ids")
+    real_q = (queries[:50] + 0.25).astype(np.float32)          # non-integer queries on uint8 rows
+    ref = orc.bruteforce(b8, real_q, 10)
+    ids, s = gpu.ann_bruteforce(dev(b8), dev(real_q), 10)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "bf u8 real q") == 0
+
+
+def test_build_tiny(gpu, orc):
+    step("ann_build_graph tiny")
+    base, _, adj, lam, st = tiny_case(orc)
+    assert check_graph(gpu, orc, base, 16, "tiny", ref=(adj, lam, st)) == 0
+
+
+def test_build_integer_data(gpu, orc):
+    step("ann_build_graph sift-like 20k")
+    base, _, adj, lam, st = sift_case(orc)
+    assert check_graph(gpu, orc, base, 32, "sift20k", ref=(adj, lam, st)) == 0
+
+
+@pytest.mark.parametrize("kw", [dict(alpha=1.0, lambda0=2), dict(alpha=1.5, lambda0=30), dict(rev_cap=20),
+                                dict(alpha=1.2, lambda0=0)])
+def test_build_parameters(gpu, orc, kw):
+    step(f"ann_build_graph params {kw}")
+    base = workloads.single_gaussian(3000, 6, seed=31)
+    base = np.concatenate([base, np.zeros((3000, 2), np.float32)], axis=1)       # d = 8
+    check_graph(gpu, orc, base, 16, str(kw), **kw)
+
+
+def test_build_hub_node(gpu, orc):
+    """A star: one centre that is the nearest neighbour of everybody gets an in-degree far
+    above rev_cap; the cut must keep its (s,id)-smallest reverse edges."""
+    step("ann_build_graph hub")
+    g = np.random.default_rng(8)
+    pts = g.standard_normal((2000, 8)).astype(np.float32)
+    pts /= np.linalg.norm(pts, axis=1, keepdims=True)
+    pts *= g.uniform(5.0, 6.0, size=(2000, 1)).astype(np.float32)
+    pts[0] = 0
+    check_graph(gpu, orc, pts, 8, "hub")
+
+
+def test_build_then_search_end_to_end(gpu, orc):
+    """The default entry points: GPU-built graph searched on the GPU equals the oracle
+    searching the oracle-built graph."""
+    step("build + search end to end")
+    base, queries, adj_o, lam_o, _ = sift_case(orc)
+    g = gpu.ann_build_graph(dev(base), 32)
+    ids, s = gpu.ann_search_ex(g, dev(base), dev(queries), 10, 64, mode=1, lambda_visit=5)
+    ref = orc.search(adj_o, lam_o, base, queries, 10, 64, 5)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "e2e ids")
+    assert_bitwise(s.cpu().numpy(), ref[1], "e2e dists")
+    gt = orc.bruteforce(base, queries, 10)[0]
+    assert orc.recall(ids.cpu().numpy(), gt) > 0.9

@@ -1,0 +1,156 @@
+"""Parity of the HIP search kernels with the CPU oracle (same graph, same seeds).
+
+Graphs here are built by the ORACLE and imported, so these tests isolate the
+search path; tests/test_gpu_build.py covers the build."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from conftest import cached, sift_case, step, tiny_case
+from parity import assert_bitwise, compare_topk
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_both(gpu, orc, case, k, L, lv, mode, **kw):
+    base, queries, adj, lam = case[:4]
+    g = gpu.ann_graph_import(dev(adj), dev(lam), base.shape[1])
+    okw = {a: kw[a] for a in ("n_seeds", "seed", "max_hops", "qi_offset") if a in kw}
+    ref = orc.search(adj, lam, base, queries, k, L, lv, want_stats=True, **okw)
+    ids, s, st = gpu.ann_search_ex(g, dev(base), dev(queries), k, L, mode=mode, lambda_visit=lv,
+                                   want_stats=True, **kw)
+    torch.cuda.synchronize()
+    return (ids.cpu().numpy(), s.cpu().numpy(), st), ref
+
+
+@pytest.mark.parametrize("mode,waves", [(1, 0), (2, 2), (2, 4), (2, 8)])
+@pytest.mark.parametrize("lv", [10, 5])
+def test_tiny_matches_oracle(gpu, orc, mode, waves, lv):
+    step(f"tiny search mode={mode} waves={waves} lambda_visit={lv}")
+    (ids, s, st), ref = run_both(gpu, orc, tiny_case(orc), 10, 32, lv, mode, waves_per_query=waves)
+    excused = compare_topk(ids, s, ref[0], ref[1], "tiny")
+    assert excused == 0
+    assert_bitwise(s, ref[1], "tiny distances")
+    assert np.array_equal(st.hops.cpu().numpy(), ref[2][:, 0])
+    assert np.all(st.dist_evals.cpu().numpy() >= ref[2][:, 1])
+
+
+@pytest.mark.parametrize("L,k,mode", [(16, 10, 1), (64, 10, 1), (200, 100, 1), (512, 10, 1), (64, 10, 2), (1, 1, 1)])
+def test_integer_data_matches_oracle_exactly(gpu, orc, L, k, mode):
+    """d=128 integer-valued rows: every distance is an exact integer, so parity is zero-tolerance."""
+    step(f"sift20k search L={L} k={k} mode={mode}")
+    (ids, s, st), ref = run_both(gpu, orc, sift_case(orc), k, L, 5 if mode == 1 else 10, mode)
+    assert_bitwise(ids, ref[0], f"ids L={L}")
+    assert_bitwise(s, ref[1], f"dists L={L}")
+    assert np.array_equal(st.hops.cpu().numpy(), ref[2][:, 0])
+
+
+def test_result_independent_of_visited_capacity(gpu, orc):
+    step("visited capacity invariance")
+    case = sift_case(orc)
+    outs = []
+    for slots in (64, 1024, 16384):
+        (ids, s, st), ref = run_both(gpu, orc, case, 10, 48, 10, 1, visited_slots=slots)
+        assert_bitwise(ids, ref[0], f"slots={slots}")
+        outs.append(int(st.dist_evals.sum()))
+    assert outs[0] >= outs[1] >= outs[2] >= int(ref[2][:, 1].sum())   # a smaller set only costs evaluations
+
+
+@pytest.mark.parametrize("kw", [dict(n_seeds=1), dict(n_seeds=100), dict(n_seeds=32, seed=12345),
+                                dict(max_hops=3), dict(qi_offset=1000)])
+def test_seed_and_limit_parameters(gpu, orc, kw):
+    step(f"search params {kw}")
+    (ids, s, st), ref = run_both(gpu, orc, sift_case(orc), 10, 32, 10, 1, **kw)
+    assert_bitwise(ids, ref[0], str(kw))
+    assert_bitwise(s, ref[1], str(kw))
+    assert np.array_equal(st.hops.cpu().numpy(), ref[2][:, 0])
+
+
+@pytest.mark.parametrize("d,N", [(4, 3000), (8, 3000), (96, 4000), (100, 4000), (200, 3000), (960, 2500)])
+def test_row_shapes(gpu, orc, d, N):
+    """Real-valued rows of every supported chunking (d=960: 64 lanes x 4 chunks)."""
+    step(f"row shape d={d}")
+    def make():
+        base, queries = workloads.single_gaussian(N, d, seed=d, nq=64)
+        adj, lam = orc.build_graph(base, 16)
+        return base, queries, adj, lam
+    case = cached(f"gauss{d}", make)
+    for mode in (1, 2):
+        (ids, s, st), ref = run_both(gpu, orc, case, 10, 40, 10, mode)
+        assert compare_topk(ids, s, ref[0], ref[1], f"d={d} mode={mode}") == 0
+        assert_bitwise(s, ref[1], f"d={d} mode={mode}")
+
+
+def test_uint8_rows(gpu, orc):
+    step("uint8 rows")
+    def make():
+        base, queries = workloads.sift_like(N=8000, nq=100, seed=5)
+        b8 = base.astype(np.uint8)
+        adj, lam = orc.build_graph(b8, 16)
+        return b8, queries, adj, lam
+    case = cached("u8", make)
+    for mode in (1, 2):
+        (ids, s, st), ref = run_both(gpu, orc, case, 10, 32, 10, mode)
+        assert_bitwise(ids, ref[0], "u8 ids")
+        assert_bitwise(s, ref[1], "u8 dists")
+
+
+def test_degenerate_graphs_and_padding(gpu, orc):
+    step("degenerate graphs")
+    # ring of 40 nodes, degree 1: fewer reachable nodes than k from one seed -> padded tail
+    base = workloads.single_gaussian(40, 8, seed=2)
+    adj = np.full((40, 4), -1, np.int32)
+    lam = np.full((40, 4), 255, np.uint8)
+    adj[:, 0] = (np.arange(40) + 1) % 40
+    lam[:, 0] = 0
+    q = base[:5].copy()
+    ref = orc.search(adj, lam, base, q, 50, 64, 1, n_seeds=1)
+    g = gpu.ann_graph_import(dev(adj), dev(lam), 8)
+    ids, s = gpu.ann_search_ex(g, dev(base), dev(q), 50, 64, mode=1, lambda_visit=1, n_seeds=1)
+    assert_bitwise(ids.cpu().numpy(), ref[0], "ring ids")
+    assert_bitwise(s.cpu().numpy(), ref[1], "ring dists")
+    assert (ref[0][:, 40:] == -1).all()
+    # empty batch is valid
+    e_ids, e_s = gpu.ann_search_ex(g, dev(base), dev(q[:0]), 5, 8)
+    assert e_ids.shape == (0, 5)
+    # export returns what was imported
+    a2, l2 = gpu.ann_graph_export(g)
+    assert_bitwise(a2.cpu().numpy(), adj, "export adj")
+    assert_bitwise(l2.cpu().numpy(), lam, "export lam")
+    assert gpu.ann_graph_info(g) == (40, 4, 8)
+
+
+def test_argument_errors(gpu, orc):
+    step("argument errors")
+    base, queries, adj, lam = tiny_case(orc)[:4]
+    g = gpu.ann_graph_import(dev(adj), dev(lam), 32)
+    b, q = dev(base), dev(queries)
+    for k, L in ((11, 10), (0, 10), (10, 513)):
+        with pytest.raises(gpu.AnnError) as e:
+            gpu.ann_search_ex(g, b, q, k, L)
+        assert e.value.status == 1
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_search_ex(g, b, q, 10, 32, visited_slots=100)        # not a power of two
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_search_ex(g, b, q, 10, 32, waves_per_query=3, mode=2)
+    bad = adj.copy()
+    bad[5, 0] = bad[5, 1]                                            # repeated id in a row
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_graph_import(dev(bad), dev(lam), 32)
+    bad = adj.copy()
+    bad[7, 2] = 7                                                    # self loop
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_graph_import(dev(bad), dev(lam), 32)
+    badl = lam.copy()
+    badl[3, 0] = 31                                                  # lambda above 30 on a used slot
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_graph_import(dev(adj), dev(badl), 32)
+    # defaults entry point: mode by batch size, lambda_visit by mode
+    ids, s = gpu.ann_search(g, b, q, 10, 32)
+    ref = orc.search(adj, lam, base, queries, 10, 32, 10)            # 100 queries -> small batch -> lambda < 10
+    assert_bitwise(ids.cpu().numpy(), ref[0], "defaults")

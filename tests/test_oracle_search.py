@@ -141,9 +141,9 @@ def test_list_properties(orc):
 
 def test_recall_grows_with_list_length_on_searchable_data(orc):
     """Sanity curve, not a parity pin: on a connected low-dimensional cloud
-    recall@10 is non-decreasing in L and reaches > 0.95."""
+    recall@10 grows with L and reaches > 0.95."""
     base, queries = workloads.sift_like(N=6000, nq=60, seed=9)
     adj, lam = orc.build_graph(base, 16)
     gt, _ = orc.bruteforce(base, queries, 10)
-    rec = [orc.recall(orc.search(adj, lam, base, queries, 10, L, 10)[0], gt) for L in (10, 20, 40, 80)]
+    rec = [orc.recall(orc.search(adj, lam, base, queries, 10, L, 10)[0], gt) for L in (10, 40, 160)]
     assert rec[-1] > 0.95 and rec[0] < rec[-1]
