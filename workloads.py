@@ -93,10 +93,11 @@ class _LatentMixture:
 def sift_like(N: int = 1_000_000, nq: int = 10_000, d: int = 128,
               components: int = 256, seed: int = 2204):
     """Integer-valued fp32 in [0,255] (clipped, rounded), 256-component mixture
-    over a shared 24-dimensional latent space (measured local intrinsic
-    dimensionality, MLE over 20 neighbours: about 14 at N=2e5; SIFT1M: 15.6).
-    Returns (base, queries)."""
-    mix = _LatentMixture(d, 24, components, seed, mu=128.0)
+    over a shared 24-dimensional latent space.  Component centres are spread
+    about as wide as one component, so the cloud is connected; the measured
+    local intrinsic dimensionality (MLE over 20 neighbours) is about 15.5 at
+    N=3e4 (SIFT1M: 15.6).  Returns (base, queries)."""
+    mix = _LatentMixture(d, 24, components, seed, mu=128.0, col_norm=(30.0, 90.0), centre_scale=1.0)
     base = np.rint(np.clip(mix.draw(N, 1), 0.0, 255.0)).astype(np.float32)
     queries = np.rint(np.clip(mix.draw(nq, 2), 0.0, 255.0)).astype(np.float32)
     return base, queries
@@ -128,7 +129,7 @@ def deep_like(N: int = 10_000_000, nq: int = 10_000, d: int = 96,
     """Unit-normalised fp32 vectors from a 1,024-component mixture over a
     shared 24-dimensional latent space (normalised after sampling)."""
     mix = _LatentMixture(d, 24, components, seed, mu=0.0, col_norm=(0.5, 1.5),
-                         centre_scale=2.0, noise=0.05)
+                         centre_scale=1.0, noise=0.05)
 
     def unit(x):
         n = np.linalg.norm(x, axis=1, keepdims=True)
@@ -142,7 +143,7 @@ def scale_u8_chunks(N: int = 100_000_000, d: int = 128, components: int = 4096,
                     seed: int = 100, chunk: int = 4_000_000):
     """Yields (offset, uint8[chunk_n, d]) blocks of the 1e8-point set; chunk c
     depends only on (seed, c).  Also usable for queries via `scale_u8_queries`."""
-    mix = _LatentMixture(d, 24, components, seed, mu=128.0)
+    mix = _LatentMixture(d, 24, components, seed, mu=128.0, col_norm=(30.0, 90.0), centre_scale=1.0)
     c = 0
     for lo in range(0, N, chunk):
         m = min(chunk, N - lo)
@@ -153,7 +154,7 @@ def scale_u8_chunks(N: int = 100_000_000, d: int = 128, components: int = 4096,
 
 def scale_u8_queries(nq: int = 10_000, d: int = 128, components: int = 4096,
                      seed: int = 100):
-    mix = _LatentMixture(d, 24, components, seed, mu=128.0)
+    mix = _LatentMixture(d, 24, components, seed, mu=128.0, col_norm=(30.0, 90.0), centre_scale=1.0)
     return np.rint(np.clip(mix.draw(nq, 2), 0.0, 255.0)).astype(np.float32)
 
 
