@@ -231,6 +231,204 @@ __global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
     }
 }
 
+
+// ---------------------------------------------------------------- bf16 fast path (integer rows, d <= 128)
+// Rows are first rewritten as bf16 (exact for integers up to 255), padded to KS*16 elements.
+// One workgroup = 4 waves x 64 queries; each wave keeps the fragments of its 64 queries in
+// registers for the whole sweep, so only the candidate tile (64 rows) goes through LDS, double
+// buffered: the global loads of tile t+1 are in flight while tile t is multiplied.  Per tile and
+// wave: 2 candidate blocks x 2 query blocks x KS MFMAs (32x32x16), then the threshold filter.
+template <typename T>
+__global__ __launch_bounds__(256) void to_bf16_kernel(const T* __restrict__ src, int64_t n, int d, int dp,
+                                                      uint16_t* __restrict__ dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 4-element group
+    const int groups = dp / 4;
+    if (i >= n * groups) return;
+    const int64_t r = i / groups;
+    const int c = (int)(i % groups) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < d) v = load4(src + r * d + c);
+    const uint32_t lo = (uint32_t)bf16_bits(v.x) | ((uint32_t)bf16_bits(v.y) << 16);
+    const uint32_t hi = (uint32_t)bf16_bits(v.z) | ((uint32_t)bf16_bits(v.w) << 16);
+    *reinterpret_cast<uint2*>(dst + r * dp + c) = make_uint2(lo, hi);
+}
+
+struct FastArgs {
+    const uint16_t* qb;   // [nq, DP] bf16 query rows (row 0 = first query of this sweep)
+    const uint16_t* xb;   // [N, DP] bf16 base rows
+    const float* qnorm;
+    const float* xnorm;
+    const float* tau;
+    unsigned* cnt;
+    uint64_t* buf;
+    int64_t nq;
+    int64_t c_begin, c_end;
+    int64_t self_offset;
+    int cap, tiles_per_block;
+};
+
+constexpr int kFastRows = 64;  // candidate rows per LDS tile
+constexpr int kQueue = 1024;    // survivor queue entries per workgroup
+
+template <int KS>
+__global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
+{
+    constexpr int DP = KS * 16;
+    constexpr int XS = DP + 8;                       // LDS row stride (elements): 16-B aligned, staggers banks
+    constexpr int CHUNKS = kFastRows * DP / 8;       // 16-byte chunks per tile
+    constexpr int PER_THREAD = (CHUNKS + 255) / 256;
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][kFastRows * XS];
+    __shared__ __attribute__((aligned(16))) float xn[2][kFastRows];
+    __shared__ uint64_t q_key[kQueue];
+    __shared__ uint16_t q_row[kQueue];
+    __shared__ unsigned q_cnt;
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t q0 = (int64_t)blockIdx.x * 256 + wave * 64;
+    if (threadIdx.x == 0) q_cnt = 0u;
+
+    bf16x8 qf[2][KS];
+    int64_t qg[2];
+    float qn[2], tq[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        qg[j] = q0 + j * 32 + (lane & 31);
+        const bool ok = qg[j] < a.nq;
+        qn[j] = ok ? a.qnorm[qg[j]] : 0.f;
+        tq[j] = ok ? a.tau[qg[j]] - qn[j] : -kInf;   // survivors satisfy |x|^2 - 2 q.x < tau - |q|^2
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint4 w = make_uint4(0u, 0u, 0u, 0u);
+            if (ok) w = *reinterpret_cast<const uint4*>(a.qb + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
+            qf[j][ks] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kFastRows;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kFastRows);
+    if (span0 >= span1) return;
+    const int ntiles = (int)((span1 - span0 + kFastRows - 1) / kFastRows);
+
+    uint4 stage[PER_THREAD];
+    float stage_n = 0.f;
+    auto fetch = [&](int t) {       // global -> registers
+        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int ch = (int)threadIdx.x + i * 256;
+            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
+            stage[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (ch < CHUNKS && c0 + r < span1)
+                stage[i] = *reinterpret_cast<const uint4*>(a.xb + (c0 + r) * DP + c8 * 8);
+        }
+        if (threadIdx.x < kFastRows) stage_n = c0 + threadIdx.x < span1 ? a.xnorm[c0 + threadIdx.x] : 0.f;
+    };
+    auto commit = [&](int b) {      // registers -> LDS buffer b
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int ch = (int)threadIdx.x + i * 256;
+            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
+            if (ch < CHUNKS) *reinterpret_cast<uint4*>(&Xs[b][r * XS + c8 * 8]) = stage[i];
+        }
+        if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = stage_n;
+    };
+
+    fetch(0);
+    commit(0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int cur = t & 1;
+        if (t + 1 < ntiles) fetch(t + 1);
+        floatx16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 xa[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                xa[i] = *reinterpret_cast<const bf16x8*>(&Xs[cur][(i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5)]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qf[j][ks], acc[i][j], 0, 0, 0);
+        }
+        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+        // filter: u = |x|^2 - 2 q.x (exact: integers < 2^24); survivors have u < tau - |q|^2.
+        // Branch-free pass mask first; the rare survivors go to a queue in LDS that is flushed
+        // to the per-query global buffers by the whole workgroup.
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            float xv[16];
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint32_t mask = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float u = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
+                    mask |= (u < tq[j]) ? (1u << r) : 0u;
+                }
+                if (ballot64(mask != 0u)) {
+                    // rare: walk the set bits; the accumulator is picked by a select chain so
+                    // that the loop needs no indexed register access
+#pragma unroll 1
+                    while (ballot64(mask != 0u)) {
+                        const int rr = mask ? (int)__builtin_ctz(mask) : 16;
+                        mask &= mask - 1u;
+                        float av = 0.f, xr = 0.f;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            av = rr == r ? acc[i][j][r] : av;
+                            xr = rr == r ? xv[r] : xr;
+                        }
+                        const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
+                        const int64_t c = c0 + m;
+                        if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
+                            const float u = __builtin_fmaf(-2.f, av, xr);
+                            const uint64_t key =
+                                ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                            const unsigned slot = atomicAdd(&q_cnt, 1u);
+                            if (slot < (unsigned)kQueue) {
+                                q_key[slot] = key;
+                                q_row[slot] = (uint16_t)(wave * 64 + j * 32 + (lane & 31));
+                            } else {  // queue full: straight to the global buffer
+                                const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
+                                if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (t + 1 < ntiles) commit(cur ^ 1);
+        __syncthreads();
+        const unsigned queued = q_cnt;
+        if (queued >= (unsigned)kQueue / 2 || (t + 1 == ntiles && queued > 0)) {
+            const unsigned n = min(queued, (unsigned)kQueue);
+            for (unsigned e = threadIdx.x; e < n; e += 256) {
+                const int64_t row = (int64_t)blockIdx.x * 256 + q_row[e];
+                const unsigned pos = atomicAdd(&a.cnt[row], 1u);
+                if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) q_cnt = 0u;
+            __syncthreads();
+        }
+    }
+}
+
 // ---------------------------------------------------------------- per-row compaction
 // Sorts the row's buffer (bitonic, in LDS), keeps the kprime smallest, sets tau to the
 // kprime-th approximate distance.  cnt > cap means entries were lost: the row is flagged.
@@ -497,6 +695,22 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     const bool exact = integer_data && (double)d * 255.0 * 255.0 < 16777216.0;
     const float err_scale = exact ? 0.f : (float)((d + 8) * 5.9604645e-8 * 1.01);
 
+    // bf16 fast path: integer rows with d <= 128 are rewritten once as padded bf16
+    const bool fast = exact && d <= 128;
+    const int ks = (d + 15) / 16, dp = ks * 16;
+    DevBuf xb, qb;
+    if (fast) {
+        TSDG_HIP(xb.alloc((size_t)N * dp * 2));
+        hipLaunchKernelGGL((to_bf16_kernel<TB>), dim3((unsigned)((N * (dp / 4) + 255) / 256)), dim3(256), 0, stream,
+                           base, N, d, dp, xb.as<uint16_t>());
+        if (!self) {
+            TSDG_HIP(qb.alloc((size_t)nq * dp * 2));
+            hipLaunchKernelGGL((to_bf16_kernel<TQ>), dim3((unsigned)((nq * (dp / 4) + 255) / 256)), dim3(256), 0,
+                               stream, queries, nq, d, dp, qb.as<uint16_t>());
+        }
+        TSDG_HIP(hipGetLastError());
+    }
+
     const int64_t rb = std::min(row_block, nq);
     TSDG_HIP(tau.alloc((size_t)rb * 4));
     TSDG_HIP(cnt.alloc((size_t)rb * 4));
@@ -545,7 +759,29 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             f.c_end = ce;
             const int64_t tiles = (ce - cb + kTile - 1) / kTile;
             dim3 grid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((tiles + kTilesPerBlock - 1) / kTilesPerBlock));
-            if (integer_data)
+            if (fast) {
+                FastArgs fa;
+                fa.qb = (self ? xb.as<uint16_t>() : qb.as<uint16_t>()) + r0 * dp;
+                fa.xb = xb.as<uint16_t>();
+                fa.qnorm = f.qnorm;
+                fa.xnorm = f.xnorm;
+                fa.tau = f.tau;
+                fa.cnt = f.cnt;
+                fa.buf = f.buf;
+                fa.nq = nr;
+                fa.c_begin = cb;
+                fa.c_end = ce;
+                fa.self_offset = f.self_offset;
+                fa.cap = cap;
+                const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
+                fa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
+                dim3 fgrid((unsigned)((nr + 255) / 256), (unsigned)((ftiles + fa.tiles_per_block - 1) / fa.tiles_per_block));
+                switch (ks) {
+#define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_bf16_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
+                    TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
+#undef TSDG_KS
+                }
+            } else if (integer_data)
                 hipLaunchKernelGGL((filter_kernel<true, TQ, TB>), grid, dim3(256), 0, stream, f);
             else
                 hipLaunchKernelGGL((filter_kernel<false, TQ, TB>), grid, dim3(256), 0, stream, f);
