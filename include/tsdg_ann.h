@@ -70,7 +70,7 @@ typedef struct {
  * (auto: small-batch kernel below a batch-size threshold, large-batch kernel
  * above), lambda_visit 0 meaning "by mode" (Sec. 5.4: 10 for small batches, 5
  * for large ones), n_seeds 32 (Alg. 2), seed 0, max_hops 0 = unbounded (the hop
- * limit T of Alg. 2), visited_slots 0 = chosen from L, waves_per_query 0 =
+ * limit T of Alg. 2), visited_slots 0 = chosen from mode and L, waves_per_query 0 =
  * chosen from d, qi_offset 0, stream NULL.
  *   mode: 1 = large batch (one 64-lane wavefront per query),
  *         2 = small batch (one workgroup of several wavefronts per query).

@@ -376,11 +376,18 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     if (lv > 31) lv = 32;
     s.lambda_visit = lv;
 
+    // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds,
+    // and 1,024 slots measured fastest for every L (a smaller set re-scores more rows, a larger
+    // one lowers occupancy); a workgroup per query has LDS to spare.
     int slots = p.visited_slots;
     if (slots == 0) {
-        slots = pow2_at_least(16 * L);
-        if (slots < 1024) slots = 1024;
-        if (slots > 8192) slots = 8192;
+        if (mode == 1) {
+            slots = 1024;
+        } else {
+            slots = pow2_at_least(16 * L);
+            if (slots < 1024) slots = 1024;
+            if (slots > 8192) slots = 8192;
+        }
     }
     if (slots < 64 || slots > 16384 || (slots & (slots - 1)) != 0) {
         set_error("ann_search: visited_slots must be a power of two in 64..16384");

@@ -95,6 +95,23 @@ __device__ __forceinline__ uint64_t bcast64(uint64_t v, int src)
     uint32_t lo = bcast32((uint32_t)v, src), hi = bcast32((uint32_t)(v >> 32), src);
     return ((uint64_t)hi << 32) | lo;
 }
+// broadcast from a lane whose index is wave-uniform (v_readlane: no LDS round trip)
+__device__ __forceinline__ uint32_t readlane32(uint32_t v, int src)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, src);
+}
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, int src)
+{
+    return ((uint64_t)readlane32((uint32_t)(v >> 32), src) << 32) | readlane32((uint32_t)v, src);
+}
+// value of the lane given by a DPP control word (quad_perm / row_mirror / row_half_mirror)
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xFFFFFFFFll), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
 __device__ __forceinline__ double shfl_xor_f64(double v, int mask)
 {
     long long b = __double_as_longlong(v);

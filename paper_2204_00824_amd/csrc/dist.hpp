@@ -115,11 +115,17 @@ template <typename T, int G, int C> struct RowDist {
         return acc;
     }
 
-    // sum over the G lanes of a group; every lane of the group gets the total
+    // sum over the G lanes of a group; every lane of the group gets the total.  Butterfly over
+    // lane pairs 1, 2 apart (quad permutes), then the mirrored lane of the 8- and 16-lane row
+    // (which already holds the other half's total), then xor 16 / 32 through the LDS crossbar.
     static __device__ __forceinline__ double group_sum(double a)
     {
-#pragma unroll
-        for (int o = G / 2; o > 0; o >>= 1) a += shfl_xor_f64(a, o);
+        a += dpp_f64<0xB1>(a);                     // quad_perm [1,0,3,2]
+        a += dpp_f64<0x4E>(a);                     // quad_perm [2,3,0,1]
+        if constexpr (G >= 8) a += dpp_f64<0x141>(a);   // row_half_mirror
+        if constexpr (G >= 16) a += dpp_f64<0x140>(a);  // row_mirror
+        if constexpr (G >= 32) a += shfl_xor_f64(a, 16);
+        if constexpr (G >= 64) a += shfl_xor_f64(a, 32);
         return a;
     }
 };

@@ -9,63 +9,83 @@
 
 namespace tsdg {
 
-// S2: index of the first entry not yet expanded, or -1.  All 64 lanes call.
-__device__ __forceinline__ int list_first_unexpanded(const uint64_t* list, int L, int lane)
+// S2: index of the first entry not yet expanded, or -1; *key_out receives that entry.  All 64
+// lanes call.
+__device__ __forceinline__ int list_first_unexpanded(const uint64_t* list, int L, int lane, uint64_t* key_out)
 {
     for (int i0 = 0; i0 < L; i0 += 64) {
         const int i = i0 + lane;
         const uint64_t a = i < L ? list[i] : kKeyEmpty;
         const uint64_t m = ballot64(a != kKeyEmpty && (a & 1ull) == 0ull);
-        if (m) return i0 + ctz64(m);
+        if (m) {
+            const int b = ctz64(m);
+            *key_out = readlane64(a, b);
+            return i0 + b;
+        }
         if (ballot64(a == kKeyEmpty)) return -1;  // reached the unused tail
     }
     return -1;
 }
 
-// S6: merges up to 64 scored candidates (one per lane, kKeyEmpty = none; ids
-// distinct among the lanes) into the list, keeping the L smallest.  A candidate
-// whose id is already in the list (same distance, same id) is dropped.
-// Positions: with r_j = #{a in list : a < c_j} and t_j = #{c_i < c_j}, candidate
-// j lands at r_j + t_j and list entry i at i + #{j : r_j <= i}; together these
-// are the positions of the merged sequence, and everything at L or beyond falls
-// off.  `sync` must order LDS accesses among the calling lanes.
+// S6: merges up to 64 scored candidates (one per lane, kKeyEmpty = none; ids distinct among
+// the lanes) into the list, keeping the L smallest.  A candidate whose id is already in the
+// list (same distance, same id) is dropped.
+// Positions: with r_j = #{a in list : a < c_j} and t_j = #{c_i < c_j}, candidate j lands at
+// r_j + t_j and list entry i at i + #{j : r_j <= i}; together these are the positions of the
+// merged sequence, and everything at L or beyond falls off.  Candidates are broadcast one at
+// a time with v_readlane (their lane index is wave-uniform) and every lane compares its own
+// list entries against them, so a rank is one ballot + popcount and needs no dependent LDS
+// reads.  `sync` must order LDS accesses among the calling lanes.
 template <typename Sync>
 __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, int lane, Sync sync)
 {
     const uint64_t worst = list[L - 1] | 1ull;
-    bool valid = (key | 1ull) < worst;
-    if (!ballot64(valid)) return;
-
-    int r = 0;
-    if (valid) {
-        int lo = 0, hi = L;
-        const uint64_t kk = key | 1ull;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if ((list[mid] | 1ull) < kk) lo = mid + 1; else hi = mid;
-        }
-        r = lo;
-        if (r < L && (list[r] | 1ull) == kk) valid = false;  // already present
-    }
-    const uint64_t vm = ballot64(valid);
+    const uint64_t kk = key | 1ull;
+    bool valid = kk < worst;
+    uint64_t vm = ballot64(valid);
     if (!vm) return;
 
-    int t = 0;
+    const int top = ((L - 1) / 64) * 64;
+    int r = 0;
+    bool dup = false;
+    for (int i0 = 0; i0 <= top; i0 += 64) {
+        const int i = i0 + lane;
+        const uint64_t am = (i < L ? list[i] : kKeyEmpty) | 1ull;
+        bool more = false;  // some candidate lies beyond this whole block
+        for (uint64_t m = vm; m; m &= m - 1) {
+            const int j = ctz64(m);
+            const uint64_t kj = readlane64(kk, j);
+            const uint64_t lt = ballot64(am < kj);
+            const uint64_t eq = ballot64(am == kj);
+            if (lane == j) {
+                r += popc64(lt);
+                dup = dup || eq != 0ull;
+            }
+            more = more || lt == ~0ull;
+        }
+        if (!more) break;
+    }
+    valid = valid && !dup;  // already present
+    vm = ballot64(valid);
+    if (!vm) return;
+
+    int t = 0, rmin = L;
     for (uint64_t m = vm; m; m &= m - 1) {
         const int j = ctz64(m);
-        const uint64_t kj = bcast64(key, j);
+        const uint64_t kj = readlane64(key, j);
         t += (kj < key || (kj == key && j < lane)) ? 1 : 0;
+        rmin = min(rmin, (int)readlane32((uint32_t)r, j));
     }
 
-    // move list entries, highest block first (entries only move towards the end)
-    for (int i0 = ((L - 1) / 64) * 64; i0 >= 0; i0 -= 64) {
+    // move list entries, highest block first (entries only move towards the end); blocks that
+    // lie wholly before the smallest insertion point stay
+    for (int i0 = top; i0 >= (rmin & ~63); i0 -= 64) {
         const int i = i0 + lane;
         const uint64_t a = i < L ? list[i] : kKeyEmpty;
         int u = 0;
         for (uint64_t m = vm; m; m &= m - 1) {
             const int j = ctz64(m);
-            const int rj = (int)bcast32((uint32_t)r, j);
-            u += (rj <= i) ? 1 : 0;
+            u += ((int)readlane32((uint32_t)r, j) <= i) ? 1 : 0;
         }
         sync();
         if (i < L && u > 0 && i + u < L) list[i + u] = a;

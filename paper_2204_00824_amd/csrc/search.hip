@@ -135,7 +135,7 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
             const uint64_t vm = ballot64(valid);
             for (uint64_t mm = vm; mm; mm &= mm - 1) {
                 const int o = ctz64(mm);
-                const uint32_t ido = bcast32(id, o);
+                const uint32_t ido = readlane32(id, o);
                 if (o < lane && ido == id) valid = false;
             }
         }
@@ -144,14 +144,14 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
 
     for (;;) {
         if (wave == 0) {
-            int idx = list_first_unexpanded(list, L, lane);  // S2
+            uint64_t key = kKeyEmpty;
+            int idx = list_first_unexpanded(list, L, lane, &key);  // S2
             if (a.max_hops > 0 && (int)hops >= a.max_hops) idx = -1;
             int u = -1;
             if (idx >= 0) {
-                const uint64_t key = list[idx];
                 u = (int)key_id(key);
-                lsync();
                 if (lane == 0) list[idx] = key | 1ull;
+                lsync();
             }
             if (lane == 0) ctl[0] = u;
         }
