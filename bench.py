@@ -100,6 +100,12 @@ def main():
     log(f"ground truth in {time.time() - t0:.2f}s")
     gt_h = gt.cpu().numpy()
 
+    # local intrinsic dimensionality of the base set (MLE over the 20 nearest neighbours of 2,000 rows)
+    _, nn_s = P.ann_bruteforce(base, base[:2000].contiguous(), 21)
+    r = torch.sqrt(nn_s[:, 1:].double())
+    lid = float((-1.0 / torch.log(r[:, :-1] / r[:, -1:]).mean(dim=1)).mean().item())
+    build["lid_mle20"] = round(lid, 2)
+
     def recall_of(ids_t):
         found = ids_t.cpu().numpy()
         hit = (found[:, :, None] == gt_h[:, None, :]).any(axis=2).sum()
@@ -129,8 +135,6 @@ def main():
         log(str(row))
         if chosen is None and rec >= args.target_recall:
             chosen = (L, rec, hops, evals)
-            if not args.L:
-                break
     if chosen is None:
         L = Ls[-1]
         chosen = (L, sweep[-1]["recall@10"], sweep[-1]["hops"], sweep[-1]["dist_evals"])
@@ -204,24 +208,32 @@ def main():
         "build": build,
     }
 
-    # ---- small-batch latency (batch 1 / 16 / 100; lambda_visit 10, workgroup per query)
+    # ---- small-batch regime (batch 1 / 16 / 100; lambda_visit 10, one workgroup per query):
+    # median latency of single calls (launch included) and recall, per L
     if not args.skip_small:
         small = {}
         for bs in (1, 16, 100):
-            n_calls = min(200, args.nq // bs)
+            n_calls = min(100, args.nq // bs)
             o = (torch.empty((bs, k), dtype=torch.int32, device=dev), torch.empty((bs, k), dtype=torch.float32, device=dev))
             qs = [queries[i * bs:(i + 1) * bs].contiguous() for i in range(n_calls)]
-            for i in range(3):
-                P.ann_search_ex(graph, base, qs[i % n_calls], k, L, mode=2, lambda_visit=10, out=o, qi_offset=i * bs)
-            torch.cuda.synchronize()
-            lat = []
-            for i in range(n_calls):
-                t0 = time.perf_counter()
-                P.ann_search_ex(graph, base, qs[i], k, L, mode=2, lambda_visit=10, out=o, qi_offset=i * bs)
+            rows = []
+            for Ls_ in ([L] if args.L else [16, 32, 64, 128]):
+                for i in range(3):
+                    P.ann_search_ex(graph, base, qs[i % n_calls], k, Ls_, mode=2, lambda_visit=10, out=o, qi_offset=i * bs)
                 torch.cuda.synchronize()
-                lat.append(time.perf_counter() - t0)
-            small[f"batch{bs}"] = {"median_latency_ms": round(float(np.median(lat)) * 1e3, 4),
-                                   "qps": round(bs / float(np.median(lat)))}
+                lat, hit = [], 0
+                for i in range(n_calls):
+                    t0 = time.perf_counter()
+                    P.ann_search_ex(graph, base, qs[i], k, Ls_, mode=2, lambda_visit=10, out=o, qi_offset=i * bs)
+                    torch.cuda.synchronize()
+                    lat.append(time.perf_counter() - t0)
+                    found = o[0].cpu().numpy()
+                    hit += (found[:, :, None] == gt_h[i * bs:(i + 1) * bs, None, :]).any(axis=2).sum()
+                med = float(np.median(lat))
+                rows.append({"L": Ls_, "recall@10": round(float(hit) / (n_calls * bs * k), 4),
+                             "median_latency_ms": round(med * 1e3, 4), "qps": round(bs / med)})
+            small[f"batch{bs}"] = rows
+            log(f"batch {bs}: {rows}")
         result["small_batch"] = small
 
     # ---- the oracle on the host cores, same graph, same queries (a baseline, not the target)
@@ -238,11 +250,14 @@ def main():
             t_cpu += time.perf_counter() - t0
             reps += 1
         same = bool(np.array_equal(ref[0], ids.cpu().numpy()[:sample]))
+        t0 = time.perf_counter()
+        oracle.search(adj_h, lam_h, base_h, queries_h[:2000], k, L, lambda_visit, threads=1)
+        one_thread = 2000 / (time.perf_counter() - t0)
         result["cpu_baseline"] = {"value": round(sample * reps / t_cpu), "unit": "queries/s", "cores": threads,
                                   "kind": "oracle",
                                   "sample": f"{sample} queries x {reps} passes, L={L}, lambda_visit={lambda_visit}, "
                                             f"same graph (exported from the GPU build)",
-                                  "ids_equal_gpu": same}
+                                  "ids_equal_gpu": same, "value_1_thread": round(one_thread)}
         # ground-truth spot check: oracle brute force on 100 queries
         bf = oracle.bruteforce(base_h, queries_h[:100], k, threads=threads)[0]
         result["ground_truth_checked_on_100_queries"] = bool(np.array_equal(bf, gt_h[:100]))

@@ -193,6 +193,26 @@ def search(adj, lam, base, queries, k, L, lambda_visit, n_seeds=32, seed=0, max_
     return tuple(out)
 
 
+def search_multi(adj, lam, base, queries, k, t0, max_hops=16, lambda_visit=10, seed=0, qi_offset=0, threads=0,
+                 want_stats=False):
+    """Small-batch multi-search (Alg. 1): t0 greedy searches per query, merged."""
+    adj = _c(adj, np.int32)
+    lam = _c(lam, np.uint8)
+    base = _c(base)
+    queries = _c(queries, np.float32)
+    N, d = base.shape
+    K = adj.shape[1]
+    nq = queries.shape[0]
+    ids = np.empty((nq, k), np.int32)
+    s = np.empty((nq, k), np.float32)
+    stats = np.zeros((nq, 3), np.uint32) if want_stats else None
+    rc = lib().orc_search_multi(_p(adj), _p(lam), C.c_int64(N), K, _p(base), _dtype_code(base), d, _p(queries),
+                                C.c_int64(nq), k, t0, max_hops, lambda_visit, C.c_uint64(seed),
+                                C.c_int64(qi_offset), _p(ids), _p(s), _p(stats), threads)
+    _check(rc, "search_multi")
+    return (ids, s, stats) if want_stats else (ids, s)
+
+
 def recall(found, truth) -> float:
     found = _c(found, np.int32)
     truth = _c(truth, np.int32)

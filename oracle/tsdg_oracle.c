@@ -589,6 +589,140 @@ int orc_search(const int32_t* adj, const uint8_t* lam, int64_t N, int K,
     return failed ? 2 : 0;
 }
 
+/* ------------------------------------------------------------------------
+ * Small-batch multi-search (Alg. 1 with the merge described in Sec. 4.1).
+ *
+ * For one query, t0 independent greedy searches are run and their rankings
+ * merged.  Search j:
+ *   - U = 32 start nodes, seed numbers 32*j .. 32*j+31 of the query; all are
+ *     scored and u = the closest by (s,id);  R (32 slots) starts empty;
+ *   - while improved and hops < T:
+ *       R_temp = 32 empty slots; the neighbours of u are taken in stored order
+ *       over the prefix with lambda < lambda_visit; the neighbour at position
+ *       p competes only for slot p mod 32 and replaces it when its (s,id) is
+ *       smaller ("every 32 neighbours ... R_temp[warp_id]");
+ *       update: R <- sort( R[0..16) united with the 16 smallest of R_temp ),
+ *       cut to 32 ("the last 16 elements of R are replaced with the top-16
+ *       of R_temp", then a complete sort);
+ *       u <- the closest node in R_temp;  no neighbours at all -> stop.
+ *   - readings where the listing is silent: an id already among the kept 16 is
+ *     not entered twice; "R is not updated" means that no id entered the first
+ *     16 entries of R that was not among them before the update; order is
+ *     (s,id) as everywhere.
+ * The t0 rankings are united, repeated ids removed, sorted by (s,id) and cut
+ * to k (k <= 32).  stats (may be NULL) [nq,3]: hops summed over the searches,
+ * distance evaluations (seeds included), 0.
+ * ---------------------------------------------------------------------- */
+static int greedy_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, const void* base,
+                      int dtype, int d, const float* q, int lambda_visit, uint64_t seed,
+                      uint64_t qi, int j, int T, float* tmp, pair_t* R, uint32_t* hops_out,
+                      uint32_t* evals_out)
+{
+    int nR = 0;
+    pair_t best;
+    best.s = INFINITY;
+    best.id = -1;
+    for (int t = 0; t < 32; ++t) {
+        pair_t c;
+        c.id = (int32_t)orc_seed_id(seed, qi, (uint64_t)(32 * j + t), N);
+        c.s = orc_sqdist(q, row_f32(base, dtype, c.id, d, tmp), d);
+        ++*evals_out;
+        if (best.id < 0 || pair_less(c, best)) best = c;
+    }
+    int32_t u = best.id;
+    int improved = 1, hops = 0;
+    while (improved && hops < T) {
+        pair_t Rt[32];
+        int used[32];
+        for (int t = 0; t < 32; ++t) used[t] = 0;
+        int deg = 0;
+        while (deg < K && adj[(int64_t)u * K + deg] >= 0 && (int)lam[(int64_t)u * K + deg] < lambda_visit) ++deg;
+        for (int p = 0; p < deg; ++p) {
+            pair_t c;
+            c.id = adj[(int64_t)u * K + p];
+            c.s = orc_sqdist(q, row_f32(base, dtype, c.id, d, tmp), d);
+            ++*evals_out;
+            int slot = p % 32;
+            if (!used[slot] || pair_less(c, Rt[slot])) { Rt[slot] = c; used[slot] = 1; }
+        }
+        ++hops;
+        pair_t cand[32];
+        int nc = 0;
+        for (int t = 0; t < 32; ++t) if (used[t]) cand[nc++] = Rt[t];
+        if (nc == 0) break;
+        qsort(cand, (size_t)nc, sizeof(pair_t), pair_cmp);
+        int take = nc < 16 ? nc : 16;
+        int keep = nR < 16 ? nR : 16;
+        pair_t merged[32];
+        int nm = 0;
+        for (int t = 0; t < keep; ++t) merged[nm++] = R[t];
+        for (int t = 0; t < take; ++t) {
+            int dupl = 0;
+            for (int a = 0; a < keep && !dupl; ++a) dupl = (R[a].id == cand[t].id);
+            if (!dupl) merged[nm++] = cand[t];
+        }
+        qsort(merged, (size_t)nm, sizeof(pair_t), pair_cmp);
+        improved = 0;
+        int top = nm < 16 ? nm : 16;
+        for (int t = 0; t < top && !improved; ++t) {
+            int was = 0;
+            for (int a = 0; a < keep && !was; ++a) was = (R[a].id == merged[t].id);
+            if (!was) improved = 1;
+        }
+        nR = nm;
+        for (int t = 0; t < nm; ++t) R[t] = merged[t];
+        u = cand[0].id;
+    }
+    *hops_out += (uint32_t)hops;
+    return nR;
+}
+
+int orc_search_multi(const int32_t* adj, const uint8_t* lam, int64_t N, int K, const void* base, int dtype,
+                     int d, const float* queries, int64_t nq, int k, int t0, int T, int lambda_visit,
+                     uint64_t seed, int64_t qi_offset, int32_t* out_ids, float* out_s, uint32_t* stats,
+                     int threads)
+{
+    if (!adj || !lam || !base || !queries || !out_ids || !out_s) return 1;
+    if (N <= 0 || K <= 0 || d <= 0 || k <= 0 || k > 32 || t0 <= 0 || T < 0 || nq < 0) return 1;
+    threads = use_threads(threads);
+    int failed = 0;
+#pragma omp parallel num_threads(threads)
+    {
+        float* tmp = (float*)malloc(sizeof(float) * (size_t)d);
+        pair_t* all = (pair_t*)malloc(sizeof(pair_t) * (size_t)t0 * 32);
+        if (!tmp || !all) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 8)
+            for (int64_t qi = 0; qi < nq; ++qi) {
+                const float* q = queries + qi * (int64_t)d;
+                uint32_t hops = 0, evals = 0;
+                int n = 0;
+                for (int j = 0; j < t0; ++j)
+                    n += greedy_one(adj, lam, N, K, base, dtype, d, q, lambda_visit, seed,
+                                    (uint64_t)(qi + qi_offset), j, T, tmp, all + n, &hops, &evals);
+                qsort(all, (size_t)n, sizeof(pair_t), pair_cmp);
+                int out = 0;
+                for (int t = 0; t < n && out < k; ++t) {
+                    if (t > 0 && all[t].id == all[t - 1].id) continue; /* same id => same key: adjacent */
+                    out_ids[qi * k + out] = all[t].id;
+                    out_s[qi * k + out] = all[t].s;
+                    ++out;
+                }
+                for (; out < k; ++out) {
+                    out_ids[qi * k + out] = -1;
+                    out_s[qi * k + out] = INFINITY;
+                }
+                if (stats) { stats[qi * 3] = hops; stats[qi * 3 + 1] = evals; stats[qi * 3 + 2] = 0; }
+            }
+        }
+        free(tmp);
+        free(all);
+    }
+    return failed ? 2 : 0;
+}
+
 /* Recall@k (Eq. 3): found[nq,k] against truth[nq,k]; -1 entries never match. */
 double orc_recall(const int32_t* found, const int32_t* truth, int64_t nq, int k)
 {
