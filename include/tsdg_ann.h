@@ -141,6 +141,18 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
                          int k, int L, const ann_search_params* params, int32_t* out_ids,
                          float* out_dists, ann_query_stats* stats);
 
+/* Small-batch multi-search (Sec. 4.1, Alg. 1): t0 independent greedy searches per query, each
+ * on its own workgroup from its own 32 random start nodes, merged into the top-k.  It trades
+ * distance evaluations for latency (a search converges in a handful of hops) and lets a batch
+ * of one use many compute units; its result is NOT the best-first result of ann_search.
+ * 1 <= k <= 32, 1 <= t0 <= 1024, nq <= 65535.  Of params it reads dtype, lambda_visit
+ * (0 = 10), seed, max_hops (the hop limit T; 0 = 16), qi_offset and stream.  The graph keeps a
+ * grow-only scratch buffer for the t0 rankings (hence the non-const graph): calls on one
+ * graph must not overlap, and the first call (or a larger nq*t0) allocates. */
+ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k,
+                            int t0, const ann_search_params* params, int32_t* out_ids,
+                            float* out_dists, ann_query_stats* stats);
+
 /* Flat copies of a graph, N*K entries each (device pointers): adj = neighbour
  * id or -1 for an unused slot, lam = occlusion factor or 255 for an unused
  * slot.  Import validates ids (range, no self loop, no repeats in a row,

@@ -56,13 +56,14 @@ def load_library():
     L.ann_bruteforce.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
     L.ann_search.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     L.ann_search_ex.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
+    L.ann_search_multi.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
     L.ann_graph_export.argtypes = [vp, vp, vp, vp]
     L.ann_graph_import.argtypes = [vp, vp, i64, i32, i32, vp, C.POINTER(vp)]
     L.ann_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
     L.ann_graph_free.argtypes = [vp]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_graph_export", "ann_graph_import", "ann_graph_info"):
+                 "ann_search_ex", "ann_search_multi", "ann_graph_export", "ann_graph_import", "ann_graph_info"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -197,6 +198,33 @@ def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: in
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
     _check(lib.ann_search_ex(graph.ptr, p, q, nq, k, L, C.byref(prm), ids.data_ptr(), s.data_ptr(),
                              st.data_ptr() if st is not None else None))
+    if want_stats:
+        return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
+    return ids, s
+
+
+def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, t0: int, *,
+                     lambda_visit: int = 0, seed: int = 0, max_hops: int = 0, qi_offset: int = 0, stream=None,
+                     want_stats: bool = False, out=None):
+    """Small-batch multi-search (Alg. 1).  Returns (ids, dists) or (ids, dists, QueryStats)."""
+    lib = load_library()
+    p, dt = _base_ptr(base)
+    q = _dev(queries, torch.float32, "queries")
+    nq = queries.shape[0]
+    if out is None:
+        ids = torch.empty((nq, k), dtype=torch.int32, device=base.device)
+        s = torch.empty((nq, k), dtype=torch.float32, device=base.device)
+    else:
+        ids, s = out
+        _dev(ids, torch.int32, "out ids")
+        _dev(s, torch.float32, "out dists")
+    prm = _SearchParams()
+    lib.ann_search_params_default(C.byref(prm))
+    prm.dtype, prm.lambda_visit, prm.seed, prm.max_hops = dt, lambda_visit, seed, max_hops
+    prm.qi_offset, prm.stream = qi_offset, _stream_ptr(stream)
+    st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
+    _check(lib.ann_search_multi(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(),
+                                st.data_ptr() if st is not None else None))
     if want_stats:
         return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
     return ids, s

@@ -172,6 +172,8 @@ static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
     g->max_lambda = 0;
     g->packed = nullptr;
     g->device = 0;
+    g->ws = nullptr;
+    g->ws_bytes = 0;
     (void)hipGetDevice(&g->device);
     hipError_t e = hipMalloc(&g->packed, (size_t)N * (size_t)K * sizeof(uint32_t));
     if (e != hipSuccess) {
@@ -227,6 +229,7 @@ void ann_graph_free(ann_graph* graph)
     if (!graph) return;
     ann_graph_impl* g = reinterpret_cast<ann_graph_impl*>(graph);
     (void)hipFree(g->packed);
+    if (g->ws) (void)hipFree(g->ws);
     delete g;
 }
 
@@ -395,6 +398,63 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     }
     s.visited_slots = slots;
     return launch_search(s);
+}
+
+ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k, int t0,
+                            const ann_search_params* params, int32_t* out_ids, float* out_dists,
+                            ann_query_stats* stats)
+{
+    g_err[0] = 0;
+    ann_search_params p;
+    ann_search_params_default(&p);
+    if (params) p = *params;
+    if (!graph) { set_error("ann_search_multi: null graph"); return ANN_EINVAL; }
+    ann_graph_impl* g = reinterpret_cast<ann_graph_impl*>(graph);
+    if (nq < 0) { set_error("ann_search_multi: negative nq"); return ANN_EINVAL; }
+    if (k < 1 || k > 32) { set_error("ann_search_multi: need 1 <= k <= 32 (k=%d)", k); return ANN_EINVAL; }
+    if (t0 < 1 || t0 > 1024) { set_error("ann_search_multi: need 1 <= t0 <= 1024 (t0=%d)", t0); return ANN_EINVAL; }
+    if (p.max_hops < 0 || p.lambda_visit < 0) { set_error("ann_search_multi: negative max_hops / lambda_visit"); return ANN_EINVAL; }
+    if (nq == 0) return ANN_OK;
+    if (!queries || !out_ids || !out_dists) { set_error("ann_search_multi: null pointer"); return ANN_EINVAL; }
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_multi");
+    if (rc != ANN_OK) return rc;
+    if (!aligned16(queries)) { set_error("ann_search_multi: query rows must be 16-byte aligned"); return ANN_EINVAL; }
+    if ((int64_t)nq * t0 > 65535ll * 1024) { set_error("ann_search_multi: nq * t0 too large"); return ANN_EUNSUPPORTED; }
+    if (nq > 65535) { set_error("ann_search_multi: at most 65535 queries per call"); return ANN_EUNSUPPORTED; }
+    const size_t need = (size_t)nq * (size_t)t0 * 33 * sizeof(uint64_t);
+    if (need > g->ws_bytes) {
+        hipStream_t st = static_cast<hipStream_t>(p.stream);
+        TSDG_HIP(hipStreamSynchronize(st));
+        if (g->ws) (void)hipFree(g->ws);
+        g->ws = nullptr;
+        g->ws_bytes = 0;
+        hipError_t e = hipMalloc(&g->ws, need);
+        if (e != hipSuccess) { set_error("hipMalloc of the multi-search scratch failed: %s", hipGetErrorString(e)); return ANN_ENOMEM; }
+        g->ws_bytes = need;
+    }
+    MultiLaunch s;
+    s.packed = g->packed;
+    s.N = g->N;
+    s.K = g->K;
+    s.base = base;
+    s.dtype = p.dtype;
+    s.d = g->d;
+    s.queries = static_cast<const float*>(queries);
+    s.nq = nq;
+    s.k = k;
+    s.t0 = t0;
+    int lv = p.lambda_visit == 0 ? 10 : p.lambda_visit;   // small-batch prefix (Sec. 5.4)
+    if (lv > 31) lv = 32;
+    s.lambda_visit = lv;
+    s.max_hops = p.max_hops == 0 ? 16 : p.max_hops;
+    s.seed = p.seed;
+    s.qi_offset = p.qi_offset;
+    s.scratch = static_cast<uint64_t*>(g->ws);
+    s.out_ids = out_ids;
+    s.out_dists = out_dists;
+    s.stats = stats;
+    s.stream = static_cast<hipStream_t>(p.stream);
+    return launch_search_multi(s);
 }
 
 ann_status ann_search(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int L,

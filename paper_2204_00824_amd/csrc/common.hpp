@@ -29,6 +29,8 @@ struct ann_graph_impl {
     int max_lambda;    // largest lambda stored
     uint32_t* packed;  // [N,K] device
     int device;
+    void* ws;          // grow-only scratch of the multi-search (rankings of the t0 searches)
+    size_t ws_bytes;
 };
 
 // ---- error plumbing (host)
@@ -67,6 +69,25 @@ struct SearchLaunch {
     hipStream_t stream;
 };
 ann_status launch_search(const SearchLaunch& a);
+
+struct MultiLaunch {
+    const uint32_t* packed;
+    int64_t N;
+    int K;
+    const void* base;
+    ann_dtype dtype;
+    int d;
+    const float* queries;
+    int nq, k, t0, lambda_visit, max_hops;
+    uint64_t seed;
+    int64_t qi_offset;
+    uint64_t* scratch;  // [nq, t0, 33]
+    int32_t* out_ids;
+    float* out_dists;
+    ann_query_stats* stats;
+    hipStream_t stream;
+};
+ann_status launch_search_multi(const MultiLaunch& a);
 
 ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries,
                      int64_t nq, int k, bool exclude_self, hipStream_t stream, int32_t* out_ids,
