@@ -236,6 +236,33 @@ def main():
             log(f"batch {bs}: {rows}")
         result["small_batch"] = small
 
+    # ---- small-batch multi-search (Alg. 1): t0 greedy searches per query on separate workgroups
+    if not args.skip_small:
+        multi = {}
+        for bs in (1, 16, 100):
+            n_calls = min(100, args.nq // bs)
+            o = (torch.empty((bs, k), dtype=torch.int32, device=dev), torch.empty((bs, k), dtype=torch.float32, device=dev))
+            qs = [queries[i * bs:(i + 1) * bs].contiguous() for i in range(n_calls)]
+            rows = []
+            for t0 in (8, 16, 32, 64, 128):
+                for i in range(3):
+                    P.ann_search_multi(graph, base, qs[i % n_calls], k, t0, max_hops=6, out=o, qi_offset=i * bs)
+                torch.cuda.synchronize()
+                lat, hit = [], 0
+                for i in range(n_calls):
+                    t0_ = time.perf_counter()
+                    P.ann_search_multi(graph, base, qs[i], k, t0, max_hops=6, out=o, qi_offset=i * bs)
+                    torch.cuda.synchronize()
+                    lat.append(time.perf_counter() - t0_)
+                    found = o[0].cpu().numpy()
+                    hit += (found[:, :, None] == gt_h[i * bs:(i + 1) * bs, None, :]).any(axis=2).sum()
+                med = float(np.median(lat))
+                rows.append({"t0": t0, "T": 6, "recall@10": round(float(hit) / (n_calls * bs * k), 4),
+                             "median_latency_ms": round(med * 1e3, 4), "qps": round(bs / med)})
+            multi[f"batch{bs}"] = rows
+            log(f"multi-search batch {bs}: {rows}")
+        result["small_batch_multi_search"] = multi
+
     # ---- the oracle on the host cores, same graph, same queries (a baseline, not the target)
     if not args.skip_cpu:
         import oracle

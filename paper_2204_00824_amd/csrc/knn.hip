@@ -19,6 +19,8 @@
 // rows that fail, or whose buffer overflowed, are redone by a plain scan of
 // all base rows with the canonical distance.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "dist.hpp"
@@ -711,6 +713,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(hipGetLastError());
     }
 
+    const char* prog_env = getenv("TSDG_PROGRESS");
+    const bool progress = prog_env && prog_env[0] == '1';
     const int64_t rb = std::min(row_block, nq);
     TSDG_HIP(tau.alloc((size_t)rb * 4));
     TSDG_HIP(cnt.alloc((size_t)rb * 4));
@@ -789,7 +793,14 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             hipLaunchKernelGGL(compact_kernel, dim3((unsigned)nr), dim3(64), (size_t)cap * 8, stream, c);
             TSDG_HIP(hipGetLastError());
             cb = ce;
-            width = std::max<int64_t>(width, cb);  // next chunk as wide as everything seen so far
+            // next chunk as wide as everything seen so far, up to 2M columns per launch
+            width = std::min<int64_t>(std::max<int64_t>(width, cb), 1ll << 21);
+            if (progress) {  // TSDG_PROGRESS=1: long sweeps report each finished chunk
+                TSDG_HIP(hipStreamSynchronize(stream));
+                fprintf(stderr, "[tsdg] k-NN sweep: rows %lld..%lld, columns done %lld / %lld\n", (long long)r0,
+                        (long long)(r0 + nr), (long long)cb, (long long)N);
+                fflush(stderr);
+            }
         }
 
         RefineLaunch<TQ, TB> rl;
