@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Measurements on the other workload shapes (one MI355X): gist-like 1M x 960,
+deep-like 10M x 96, and the 100M x 128 uint8 set.  bench.py stays the headline
+(sift-like 1M x 128); this script prints one JSON line per run with the same
+kind of fields.  Long builds print progress (TSDG_PROGRESS=1 is set here).
+
+The 100M set cannot get an exact k-NN graph in one session (2.6e18 flop), so it
+is built as 25 independent blocks of 4M rows, each an exact TSDG of its block,
+and a query is answered by searching every block and merging the per-block
+top-k by (distance, id) -- the sharded form described in the design doc.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+os.environ.setdefault("TSDG_PROGRESS", "1")
+
+
+def log(msg):
+    print(f"[bench_configs] {msg}", file=sys.stderr, flush=True)
+
+
+def recall(found, gt):
+    return float((found[:, :, None] == gt[:, None, :]).any(axis=2).sum()) / gt.size
+
+
+def timed_search(fn, reps=3):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def run_single_graph(args, name, base_h, queries_h, ks, Ls):
+    import torch
+    import paper_2204_00824_amd as P
+    K = 32
+    base = torch.from_numpy(base_h).cuda()
+    queries = torch.from_numpy(queries_h).cuda()
+    N, d = base.shape
+    nq = queries.shape[0]
+    t0 = time.time()
+    graph = P.ann_build_graph_ex(base, K)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    log(f"{name}: build {build_s:.1f}s")
+    adj, _ = P.ann_graph_export(graph)
+    deg = (adj >= 0).sum(dim=1).float().mean().item()
+    del adj
+    out = {"workload": name, "N": N, "d": d, "nq": nq, "K": K, "build_seconds": round(build_s, 2),
+           "knn_tflops": round(2.0 * N * N * d / build_s / 1e12, 1), "avg_degree": round(deg, 2), "curves": {}}
+    for k in ks:
+        gt, _ = P.ann_bruteforce(base, queries, k)
+        gt_h = gt.cpu().numpy()
+        for mode, lv in ((1, 5), (2, 10)):
+            rows = []
+            for L in Ls:
+                if L < k:
+                    continue
+                ids, s, st = P.ann_search_ex(graph, base, queries, k, L, mode=mode, lambda_visit=lv, want_stats=True)
+                ms = timed_search(lambda: P.ann_search_ex(graph, base, queries, k, L, mode=mode, lambda_visit=lv, out=(ids, s)))
+                ev = st.dist_evals.double().mean().item()
+                hp = st.hops.double().mean().item()
+                alg = (ev * d * base.element_size() + hp * K * 4) * nq
+                rows.append({"L": L, f"recall@{k}": round(recall(ids.cpu().numpy(), gt_h), 4), "qps": round(nq / ms * 1e3),
+                             "ms": round(ms, 3), "dist_evals": round(ev, 1), "alg_TBps": round(alg / ms / 1e9, 2)})
+                log(f"{name} k={k} mode={mode}: {rows[-1]}")
+            out["curves"][f"k{k}_mode{mode}_lambda{lv}"] = rows
+    print(json.dumps(out), flush=True)
+
+
+def run_sharded_u8(args):
+    import torch
+    import workloads
+    import paper_2204_00824_amd as P
+    N, d, K, k, block = args.n or 100_000_000, 128, 32, 10, 4_000_000
+    nq = 10_000
+    _, queries = next(workloads.scale_u8_torch(N=N, nq=nq))
+    shards = []
+    t_build = 0.0
+    t0 = time.time()
+    for lo, x in workloads.scale_u8_torch(N=N, chunk=block):
+        torch.cuda.synchronize()
+        t1 = time.time()
+        g = P.ann_build_graph_ex(x, K)
+        torch.cuda.synchronize()
+        t_build += time.time() - t1
+        shards.append((lo, x, g))
+        log(f"block at {lo}: {x.shape[0]} rows, build total {t_build:.1f}s, wall {time.time() - t0:.1f}s")
+    # ground truth: exact top-k per block (ann_bruteforce), merged by (distance, id)
+    def merge(parts_ids, parts_s):
+        ids = torch.cat(parts_ids, dim=1).long()
+        s = torch.cat(parts_s, dim=1)
+        key = (s.view(torch.int32).long() << 32) | ids.clamp(min=0)
+        key = torch.where(ids < 0, torch.full_like(key, 2 ** 62), key)
+        order = torch.sort(key, dim=1).indices[:, :k]
+        return torch.gather(ids, 1, order), torch.gather(s, 1, order)
+    gi, gs = [], []
+    for lo, x, g in shards:
+        i, s = P.ann_bruteforce(x, queries, k)
+        gi.append(i + lo)
+        gs.append(s)
+    gt_h = merge(gi, gs)[0].cpu().numpy()
+    log("ground truth done")
+    out = {"workload": f"scale N={N} d={d} uint8, {len(shards)} blocks of {block}, sharded search", "nq": nq, "K": K,
+           "build_seconds": round(t_build, 1),
+           "knn_tflops": round(sum(2.0 * x.shape[0] ** 2 * d for _, x, _ in shards) / t_build / 1e12, 1), "curves": {}}
+
+    def search_all(q, L, mode, lv, qi_offset=0):
+        pi, ps = [], []
+        for lo, x, g in shards:
+            i, s = P.ann_search_ex(g, x, q, k, L, mode=mode, lambda_visit=lv, qi_offset=qi_offset)
+            pi.append(torch.where(i >= 0, i + lo, i))
+            ps.append(s)
+        return merge(pi, ps)
+
+    rows = []
+    for L in (16, 32, 64, 128, 256):
+        ids, _ = search_all(queries, L, 1, 5)
+        ms = timed_search(lambda: search_all(queries, L, 1, 5), reps=2)
+        rows.append({"L": L, "recall@10": round(recall(ids.cpu().numpy(), gt_h), 4), "qps": round(nq / ms * 1e3), "ms": round(ms, 2)})
+        log(f"sharded large batch: {rows[-1]}")
+    out["curves"]["large_batch_lambda5"] = rows
+    for bs in (1, 16):
+        rows = []
+        for L in (32, 64):
+            lat, hit = [], 0
+            for c in range(30):
+                q = queries[c * bs:(c + 1) * bs].contiguous()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                ids, _ = search_all(q, L, 2, 10, qi_offset=c * bs)
+                torch.cuda.synchronize()
+                lat.append(time.perf_counter() - t1)
+                hit += recall(ids.cpu().numpy(), gt_h[c * bs:(c + 1) * bs]) * bs
+            rows.append({"L": L, "recall@10": round(hit / (30 * bs), 4), "median_latency_ms": round(float(np.median(lat)) * 1e3, 3)})
+            log(f"sharded batch {bs}: {rows[-1]}")
+        out["curves"][f"batch{bs}_lambda10"] = rows
+    print(json.dumps(out), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m"])
+    ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
+    args = ap.parse_args()
+    import workloads
+    if args.workload == "gist1m":
+        base, q = workloads.gist_like(N=args.n or 1_000_000)
+        run_single_graph(args, "gist-like", base, q, (10,), (32, 64, 128, 256, 512))
+    elif args.workload == "deep10m":
+        base, q = workloads.deep_like(N=args.n or 10_000_000)
+        run_single_graph(args, "deep-like", base, q, (10, 100), (64, 128, 256, 512))
+    else:
+        run_sharded_u8(args)
+
+
+if __name__ == "__main__":
+    main()

@@ -431,6 +431,237 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
     }
 }
 
+// ---------------------------------------------------------------- bf16 split path (real-valued rows, d <= 128)
+// A real-valued row is centred (global mean removed: distances do not change, norms shrink) and
+// written as x = hi + lo with hi = bf16(x), lo = bf16(x - hi), both round-to-nearest; what is
+// left is below 2^-16 |x|.  q.x is taken as hi.hi + hi.lo + lo.hi on the bf16 matrix cores
+// (three MFMAs per k-step, products exact in fp32), which is 16/3 times the fp32-MFMA rate at
+// nearly the same accuracy: |error of q.x| <= (3*2^-16 + 3d*2^-24) sum|q_j||x_j|.  The
+// result only SELECTS candidates; the acceptance test of the re-scoring pass carries the
+// bound.  One wave owns 32 queries (hi and lo fragments in registers), four waves share a
+// 64-row candidate tile (hi and lo) in LDS, double buffered.
+__device__ __forceinline__ uint16_t bf16_rne(float v)
+{
+    const uint32_t b = __float_as_uint(v);
+    return (uint16_t)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <typename T>
+__global__ __launch_bounds__(128) void colsum_kernel(const T* __restrict__ x, int64_t n, int d, double* __restrict__ sums)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * 512;
+    for (int c = (int)threadIdx.x; c < d; c += 128) {
+        double acc = 0.0;
+        for (int64_t r = r0; r < min(n, r0 + 512); ++r) acc += (double)(float)x[r * d + c];
+        atomicAdd(&sums[c], acc);
+    }
+}
+__global__ void mean_kernel(const double* sums, int d, int64_t n, float* mean)
+{
+    const int c = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (c < d) mean[c] = (float)(sums[c] / (double)n);
+}
+
+// one wave per row: centred hi / lo rows (padded to dp), centred squared norm, max norm
+template <typename T>
+__global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
+                                                         const float* __restrict__ mean, uint16_t* __restrict__ xh,
+                                                         uint16_t* __restrict__ xl, float* __restrict__ norms,
+                                                         unsigned* __restrict__ maxnorm)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = lane_id();
+    if (row >= n) return;
+    double acc = 0.0;
+    for (int j = lane; j < dp; j += 64) {
+        float c = 0.f;
+        if (j < d) c = (float)x[row * d + j] - mean[j];
+        const uint16_t h = bf16_rne(c);
+        const uint16_t l = bf16_rne(c - bf16_to_f32(h));
+        xh[row * dp + j] = h;
+        xl[row * dp + j] = l;
+        acc += (double)c * (double)c;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    if (lane == 0) {
+        const float nf = (float)acc;
+        norms[row] = nf;
+        atomicMax(maxnorm, __float_as_uint(nf));
+    }
+}
+
+struct SplitArgs {
+    const uint16_t* qh;   // [nq, DP] hi / lo parts of the centred query rows
+    const uint16_t* ql;
+    const uint16_t* xh;   // [N, DP] hi / lo parts of the centred base rows
+    const uint16_t* xl;
+    const float* qnorm;   // centred norms
+    const float* xnorm;
+    const float* tau;
+    unsigned* cnt;
+    uint64_t* buf;
+    int64_t nq;
+    int64_t c_begin, c_end;
+    int64_t self_offset;
+    int cap, tiles_per_block;
+};
+
+constexpr int kSplitQueue = 512;
+
+template <int KS>
+__global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
+{
+    constexpr int DP = KS * 16;
+    constexpr int XS = DP + 8;
+    constexpr int CHUNKS = kFastRows * DP / 8;       // 16-byte chunks per part of a tile
+    constexpr int PER_THREAD = (CHUNKS + 255) / 256;
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][kFastRows * XS];   // [buffer][hi|lo]
+    __shared__ __attribute__((aligned(16))) float xn[2][kFastRows];
+    __shared__ uint64_t q_key[kSplitQueue];
+    __shared__ uint16_t q_row[kSplitQueue];
+    __shared__ unsigned q_cnt;
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t qg = (int64_t)blockIdx.x * 128 + wave * 32 + (lane & 31);
+    if (threadIdx.x == 0) q_cnt = 0u;
+
+    bf16x8 qfh[KS], qfl[KS];
+    const bool qok = qg < a.nq;
+    const float qn = qok ? a.qnorm[qg] : 0.f;
+    const float tq = qok ? a.tau[qg] - qn : -kInf;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        uint4 wh = make_uint4(0u, 0u, 0u, 0u), wl = wh;
+        if (qok) {
+            wh = *reinterpret_cast<const uint4*>(a.qh + qg * DP + ks * 16 + 8 * (lane >> 5));
+            wl = *reinterpret_cast<const uint4*>(a.ql + qg * DP + ks * 16 + 8 * (lane >> 5));
+        }
+        qfh[ks] = __builtin_bit_cast(bf16x8, wh);
+        qfl[ks] = __builtin_bit_cast(bf16x8, wl);
+    }
+
+    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kFastRows;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kFastRows);
+    if (span0 >= span1) return;
+    const int ntiles = (int)((span1 - span0 + kFastRows - 1) / kFastRows);
+
+    uint4 stage[2][PER_THREAD];
+    float stage_n = 0.f;
+    auto fetch = [&](int t) {
+        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int ch = (int)threadIdx.x + i * 256;
+            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
+            stage[0][i] = make_uint4(0u, 0u, 0u, 0u);
+            stage[1][i] = stage[0][i];
+            if (ch < CHUNKS && c0 + r < span1) {
+                stage[0][i] = *reinterpret_cast<const uint4*>(a.xh + (c0 + r) * DP + c8 * 8);
+                stage[1][i] = *reinterpret_cast<const uint4*>(a.xl + (c0 + r) * DP + c8 * 8);
+            }
+        }
+        if (threadIdx.x < kFastRows) stage_n = c0 + threadIdx.x < span1 ? a.xnorm[c0 + threadIdx.x] : 0.f;
+    };
+    auto commit = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int ch = (int)threadIdx.x + i * 256;
+            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
+            if (ch < CHUNKS) {
+                *reinterpret_cast<uint4*>(&Xs[b][0][r * XS + c8 * 8]) = stage[0][i];
+                *reinterpret_cast<uint4*>(&Xs[b][1][r * XS + c8 * 8]) = stage[1][i];
+            }
+        }
+        if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = stage_n;
+    };
+
+    fetch(0);
+    commit(0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+        const int cur = t & 1;
+        if (t + 1 < ntiles) fetch(t + 1);
+        floatx16 acc[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int off = (i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
+                const bf16x8 xh = *reinterpret_cast<const bf16x8*>(&Xs[cur][0][off]);
+                const bf16x8 xl = *reinterpret_cast<const bf16x8*>(&Xs[cur][1][off]);
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[ks], acc[i], 0, 0, 0);
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[ks], acc[i], 0, 0, 0);
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[ks], acc[i], 0, 0, 0);
+            }
+        }
+        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            float xv[16];
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
+            }
+            uint32_t mask = 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float u = __builtin_fmaf(-2.f, acc[i][r], xv[r]);
+                mask |= (u < tq) ? (1u << r) : 0u;
+            }
+            if (ballot64(mask != 0u)) {
+#pragma unroll 1
+                while (ballot64(mask != 0u)) {
+                    const int rr = mask ? (int)__builtin_ctz(mask) : 16;
+                    mask &= mask - 1u;
+                    float av = 0.f, xr = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        av = rr == r ? acc[i][r] : av;
+                        xr = rr == r ? xv[r] : xr;
+                    }
+                    const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
+                    const int64_t c = c0 + m;
+                    if (rr < 16 && c < span1 && c != a.self_offset + qg) {
+                        const float u = __builtin_fmaf(-2.f, av, xr);
+                        const uint64_t key =
+                            ((uint64_t)__float_as_uint(fmaxf(u + qn, 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                        const unsigned slot = atomicAdd(&q_cnt, 1u);
+                        if (slot < (unsigned)kSplitQueue) {
+                            q_key[slot] = key;
+                            q_row[slot] = (uint16_t)(wave * 32 + (lane & 31));
+                        } else {
+                            const unsigned pos = atomicAdd(&a.cnt[qg], 1u);
+                            if (pos < (unsigned)a.cap) a.buf[qg * a.cap + pos] = key;
+                        }
+                    }
+                }
+            }
+        }
+        if (t + 1 < ntiles) commit(cur ^ 1);
+        __syncthreads();
+        const unsigned queued = q_cnt;
+        if (queued >= (unsigned)kSplitQueue / 2 || (t + 1 == ntiles && queued > 0)) {
+            const unsigned n = min(queued, (unsigned)kSplitQueue);
+            for (unsigned e = threadIdx.x; e < n; e += 256) {
+                const int64_t row = (int64_t)blockIdx.x * 128 + q_row[e];
+                const unsigned pos = atomicAdd(&a.cnt[row], 1u);
+                if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) q_cnt = 0u;
+            __syncthreads();
+        }
+    }
+}
+
 // ---------------------------------------------------------------- per-row compaction
 // Sorts the row's buffer (bitonic, in LDS), keeps the kprime smallest, sets tau to the
 // kprime-th approximate distance.  cnt > cap means entries were lost: the row is flagged.
@@ -713,6 +944,44 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(hipGetLastError());
     }
 
+    // bf16 split path: real-valued rows with d <= 128 are centred and written as hi + lo
+    const bool split = !integer_data && d <= 128;
+    DevBuf xh, xl, qh, ql, csum, cmean, cxnorm, cqnorm, cinfo;
+    float split_xmax = 0.f;
+    if (split) {
+        TSDG_HIP(csum.alloc((size_t)d * 8));
+        TSDG_HIP(cmean.alloc((size_t)d * 4));
+        TSDG_HIP(cinfo.alloc(4));
+        TSDG_HIP(xh.alloc((size_t)N * dp * 2));
+        TSDG_HIP(xl.alloc((size_t)N * dp * 2));
+        TSDG_HIP(cxnorm.alloc((size_t)N * 4));
+        TSDG_HIP(hipMemsetAsync(csum.p, 0, (size_t)d * 8, stream));
+        TSDG_HIP(hipMemsetAsync(cinfo.p, 0, 4, stream));
+        hipLaunchKernelGGL((colsum_kernel<TB>), dim3((unsigned)((N + 511) / 512)), dim3(128), 0, stream, base, N, d,
+                           csum.as<double>());
+        hipLaunchKernelGGL(mean_kernel, dim3((unsigned)((d + 63) / 64)), dim3(64), 0, stream, csum.as<double>(), d, N,
+                           cmean.as<float>());
+        hipLaunchKernelGGL((split_prep_kernel<TB>), dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, base, N, d, dp,
+                           cmean.as<float>(), xh.as<uint16_t>(), xl.as<uint16_t>(), cxnorm.as<float>(),
+                           cinfo.as<unsigned>());
+        unsigned h_max = 0;
+        TSDG_HIP(hipMemcpyAsync(&h_max, cinfo.p, 4, hipMemcpyDeviceToHost, stream));
+        if (!self) {
+            TSDG_HIP(qh.alloc((size_t)nq * dp * 2));
+            TSDG_HIP(ql.alloc((size_t)nq * dp * 2));
+            TSDG_HIP(cqnorm.alloc((size_t)nq * 4));
+            hipLaunchKernelGGL((split_prep_kernel<TQ>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, stream, queries, nq,
+                               d, dp, cmean.as<float>(), qh.as<uint16_t>(), ql.as<uint16_t>(), cqnorm.as<float>(),
+                               cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
+        }
+        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(hipStreamSynchronize(stream));
+        std::memcpy(&split_xmax, &h_max, 4);
+    }
+    // rounding-error bound of the split expansion, as a multiple of (|q|^2 + max|x|^2) of the centred rows:
+    // dropped terms 3*2^-16, fp32 accumulation over 3*dp products, norms and centring a few 2^-24
+    const float split_err = (float)(1.05 * (3.0 / 65536.0 + (3.0 * dp + 32.0) * 5.9604645e-8));
+
     const char* prog_env = getenv("TSDG_PROGRESS");
     const bool progress = prog_env && prog_env[0] == '1';
     const int64_t rb = std::min(row_block, nq);
@@ -785,6 +1054,30 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
 #undef TSDG_KS
                 }
+            } else if (split) {
+                SplitArgs sa;
+                sa.qh = (self ? xh.as<uint16_t>() : qh.as<uint16_t>()) + r0 * dp;
+                sa.ql = (self ? xl.as<uint16_t>() : ql.as<uint16_t>()) + r0 * dp;
+                sa.xh = xh.as<uint16_t>();
+                sa.xl = xl.as<uint16_t>();
+                sa.qnorm = (self ? cxnorm.as<float>() : cqnorm.as<float>()) + r0;
+                sa.xnorm = cxnorm.as<float>();
+                sa.tau = f.tau;
+                sa.cnt = f.cnt;
+                sa.buf = f.buf;
+                sa.nq = nr;
+                sa.c_begin = cb;
+                sa.c_end = ce;
+                sa.self_offset = f.self_offset;
+                sa.cap = cap;
+                const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
+                sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
+                dim3 sgrid((unsigned)((nr + 127) / 128), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
+                switch (ks) {
+#define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_split_kernel<n>), sgrid, dim3(256), 0, stream, sa); break;
+                    TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
+#undef TSDG_KS
+                }
             } else if (integer_data)
                 hipLaunchKernelGGL((filter_kernel<true, TQ, TB>), grid, dim3(256), 0, stream, f);
             else
@@ -806,7 +1099,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         RefineLaunch<TQ, TB> rl;
         rl.a.q = queries + r0 * d;
         rl.a.x = base;
-        rl.a.qnorm = qn + r0;
+        rl.a.qnorm = split ? (self ? cxnorm.as<float>() : cqnorm.as<float>()) + r0 : qn + r0;
         rl.a.cnt = cnt.as<unsigned>();
         rl.a.buf = buf.as<uint64_t>();
         rl.a.tau = tau.as<float>();
@@ -819,8 +1112,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         rl.a.d = d;
         rl.a.cap = cap;
         rl.a.k = k;
-        rl.a.err_scale = err_scale;
-        rl.a.xnorm_max = xnorm_max;
+        rl.a.err_scale = split ? split_err : err_scale;
+        rl.a.xnorm_max = split ? split_xmax : xnorm_max;
         rl.a.q_is_base = self ? 1 : 0;
         rl.N = N;
         rl.self_offset = self ? r0 : -1;

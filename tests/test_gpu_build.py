@@ -164,3 +164,25 @@ def test_build_then_search_end_to_end(gpu, orc):
     assert_bitwise(s.cpu().numpy(), ref[1], "e2e dists")
     gt = orc.bruteforce(base, queries, 10)[0]
     assert orc.recall(ids.cpu().numpy(), gt) > 0.9
+
+
+def test_knn_real_valued_with_large_offset_and_near_ties(gpu, orc):
+    """The contraction only selects candidates; exactness must survive (a) rows far from the
+    origin (norms much larger than distances) and (b) many almost-equal distances, where the
+    acceptance test of the re-scoring pass fails and rows are redone by the plain scan."""
+    step("ann_knn offset / near ties")
+    g = np.random.default_rng(12)
+    x = (g.standard_normal((3000, 16)) + 1000.0).astype(np.float32)
+    ref = orc.knn(x, 16)
+    ids, s = gpu.ann_knn(dev(x), 16)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "offset") == 0
+    lat = workloads.integer_lattice(40)                                  # 1,600 points, massive ties ...
+    y = np.zeros((1600, 4), np.float32)
+    y[:, :2] = lat + g.uniform(-1e-4, 1e-4, size=lat.shape)              # ... broken by tiny real jitter
+    ref = orc.knn(y, 12)
+    ids, s = gpu.ann_knn(dev(y), 12)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "near ties") == 0
+    q = (y[:50] + 0.3).astype(np.float32)
+    ref = orc.bruteforce(y, q, 10)
+    ids, s = gpu.ann_bruteforce(dev(y), dev(q), 10)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "near ties bf") == 0

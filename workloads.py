@@ -186,3 +186,40 @@ def line_points(N: int, seed: int):
     out = np.zeros((N, 4), dtype=np.float32)
     out[:, 0] = x
     return out
+
+
+# --------------------------------------------------------------------------
+# Device-side generator for the 1e8-point set (numpy would need ~10 minutes).
+# Same mixture family as sift_like; the draws come from torch's Philox stream,
+# so the arrays are a function of (seed, chunk index, torch version).
+# --------------------------------------------------------------------------
+def scale_u8_torch(N: int = 100_000_000, d: int = 128, components: int = 4096, seed: int = 100,
+                   chunk: int = 4_000_000, device: str = "cuda", nq: int = 0):
+    """Yields (offset, uint8 tensor [m, d] on `device`) for the base set; with nq > 0
+    yields a single (None, float32 tensor [nq, d]) of queries instead."""
+    import torch
+    mix = _LatentMixture(d, 24, components, seed, mu=128.0, col_norm=(30.0, 90.0), centre_scale=1.0)
+    A = torch.from_numpy(mix.A).to(device)
+    w = torch.from_numpy(mix.w).to(device)
+    sig = torch.from_numpy(mix.sig).to(device)
+
+    def draw(m, stream):
+        g = torch.Generator(device=device)
+        g.manual_seed(int(seed) * 1_000_003 + int(stream))
+        out = torch.empty((m, d), dtype=torch.uint8, device=device)
+        step = 1_000_000
+        for lo in range(0, m, step):
+            n = min(step, m - lo)
+            c = torch.randint(0, components, (n,), generator=g, device=device)
+            lat = w[c] + sig[c] * torch.randn((n, mix.r), generator=g, device=device)
+            x = lat @ A.T + 128.0 + 2.0 * torch.randn((n, d), generator=g, device=device)
+            out[lo:lo + n] = torch.round(torch.clamp(x, 0.0, 255.0)).to(torch.uint8)
+        return out
+
+    if nq:
+        yield None, draw(nq, 2).to(torch.float32)
+        return
+    c = 0
+    for lo in range(0, N, chunk):
+        yield lo, draw(min(chunk, N - lo), 10 + c)
+        c += 1
