@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X.
 
-Workload (benchmark configs[1]): N = 1,000,000 integer-valued fp32 rows of
+Headline workload: N = 1,000,000 integer-valued fp32 rows of
 d = 128 (seeded 256-component mixture, clipped to [0,255] and rounded), 10,000
 queries, L2, K = 32, k = 10, large batch (all 10,000 queries in one call).
 
@@ -10,7 +10,9 @@ smallest swept L whose recall@10 against brute-force ground truth is >= 0.95.
 The graph build (exact k-NN contraction + two-stage diversification) runs once
 before the timed region and is reported in the same line under "build".
 
-Prints ONE JSON line; see the design doc for every field.
+Prints ONE JSON line.  value = queries/s of the timed launches; roofline.achieved =
+algorithmic bytes per launch / average launch time (HIP events); cpu_baseline =
+the CPU oracle searching the same exported graph on the host cores.
 """
 from __future__ import annotations
 

@@ -7,7 +7,8 @@ kind of fields.  Long builds print progress (TSDG_PROGRESS=1 is set here).
 The 100M set cannot get an exact k-NN graph in one session (2.6e18 flop), so it
 is built as 25 independent blocks of 4M rows, each an exact TSDG of its block,
 and a query is answered by searching every block and merging the per-block
-top-k by (distance, id) -- the sharded form described in the design doc.
+top-k by (distance, id): the form a base set split over several devices would
+also take.
 """
 from __future__ import annotations
 

@@ -21,8 +21,9 @@ def orc():
 
 
 def step(msg: str) -> None:
-    """Names the GPU case about to run: printed unbuffered and appended to
-    gpurun_out/steps.log, so that a run that dies still says where it was."""
+    """Names the GPU case about to run: printed unbuffered and appended to a
+    steps.log in the run's output folder, so that a run that dies still says
+    where it was."""
     line = f"[step] {msg}"
     print(line, file=sys.stderr, flush=True)
     try:
