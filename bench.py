@@ -265,6 +265,33 @@ def main():
             log(f"multi-search batch {bs}: {rows}")
         result["small_batch_multi_search"] = multi
 
+    # ---- the same rows stored as uint8 (exact for this integer-valued set): a quarter of the bytes per row
+    if not args.skip_small:
+        base8 = base.to(torch.uint8)
+        t0 = time.time()
+        graph8 = P.ann_build_graph_ex(base8, K)
+        torch.cuda.synchronize()
+        build8_s = time.time() - t0
+        adj8, lam8 = P.ann_graph_export(graph8)
+        same_graph = bool(torch.equal(adj8, adj) and torch.equal(lam8, lam))
+        rows = []
+        for L8 in ([L] if args.L else [16, 24, 32, 48, 64, 128]):
+            ids8, s8, st8 = P.ann_search_ex(graph8, base8, queries, k, L8, mode=1, lambda_visit=lambda_visit, want_stats=True)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                P.ann_search_ex(graph8, base8, queries, k, L8, mode=1, lambda_visit=lambda_visit, out=(ids8, s8))
+            e1.record()
+            torch.cuda.synchronize()
+            ms8 = e0.elapsed_time(e1) / 5
+            b8 = (st8.dist_evals.double().mean().item() * d + st8.hops.double().mean().item() * K * 4) * args.nq
+            rows.append({"L": L8, "recall@10": round(recall_of(ids8), 4), "qps": round(args.nq / ms8 * 1e3),
+                         "ms": round(ms8, 4), "alg_GBps": round(b8 / ms8 / 1e6, 1)})
+        result["uint8_storage"] = {"build_seconds": round(build8_s, 3), "graph_equals_fp32_graph": same_graph, "sweep": rows}
+        log(f"uint8 storage: graph equal {same_graph}; {rows}")
+        del base8, graph8, adj8, lam8
+
     # ---- the oracle on the host cores, same graph, same queries (a baseline, not the target)
     if not args.skip_cpu:
         import oracle
