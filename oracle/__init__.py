@@ -213,6 +213,26 @@ def search_multi(adj, lam, base, queries, k, t0, max_hops=16, lambda_visit=10, s
     return (ids, s, stats) if want_stats else (ids, s)
 
 
+def search_alg2(adj, lam, base, queries, k, delta, m_c=16, m_v=16, max_hops=0, lambda_visit=5, seed=0, qi_offset=0,
+                threads=0, want_stats=False):
+    """Large-batch search with the paper's own R / C / V structures and the Delta stop (Alg. 2)."""
+    adj = _c(adj, np.int32)
+    lam = _c(lam, np.uint8)
+    base = _c(base)
+    queries = _c(queries, np.float32)
+    N, d = base.shape
+    K = adj.shape[1]
+    nq = queries.shape[0]
+    ids = np.empty((nq, k), np.int32)
+    s = np.empty((nq, k), np.float32)
+    stats = np.zeros((nq, 3), np.uint32) if want_stats else None
+    rc = lib().orc_search_alg2(_p(adj), _p(lam), C.c_int64(N), K, _p(base), _dtype_code(base), d, _p(queries),
+                               C.c_int64(nq), k, m_c, m_v, C.c_float(delta), max_hops, lambda_visit,
+                               C.c_uint64(seed), C.c_int64(qi_offset), _p(ids), _p(s), _p(stats), threads)
+    _check(rc, "search_alg2")
+    return (ids, s, stats) if want_stats else (ids, s)
+
+
 def recall(found, truth) -> float:
     found = _c(found, np.int32)
     truth = _c(truth, np.int32)

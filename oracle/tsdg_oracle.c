@@ -723,6 +723,145 @@ int orc_search_multi(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
     return failed ? 2 : 0;
 }
 
+/* ------------------------------------------------------------------------
+ * Large-batch search with the paper's own structures (Alg. 2 and Sec. 4.2):
+ * a top ranking array R of fixed size k, an expansion queue C cut into m_c
+ * segments of 32, a look-up table V cut into m_v segments of 32 that holds only
+ * expanded nodes, and the probe threshold Delta as termination.
+ *
+ *   U = 32 seeds; u = the closest; R = {u}; C = {u}; V = {}; t = 0
+ *   while C not empty and t < T:
+ *       t++;  u = pop the nearest of C;  f = furthest of R
+ *       if s(u) > s(f) + delta: stop
+ *       V.add(u)
+ *       for each neighbour e of u (lambda-prefix, stored order):
+ *           if e in V or e in C: skip
+ *           f = furthest of R
+ *           if s(e) < s(f) or |R| < k:  R.push(e); C.push(e); if |R| > k drop the furthest
+ *   return R
+ *
+ * C: segment id % m_c, each kept sorted by (s,id), at most 32 entries; a push
+ * into a full segment drops that segment's most distant entry; pop = the
+ * smallest head over the segments.  V: segment id % m_v, 32 slots written
+ * round-robin (the oldest is overwritten).
+ * Readings where the paper is silent: distances are squared, so delta is in
+ * squared units; an id already in R is neither pushed to R nor to C (R would
+ * hold it twice otherwise); all orders are (s,id).  T = 0 means no hop limit.
+ * stats [nq,3]: hops t, distance evaluations (seeds included), skips by V or C.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    pair_t e[32];
+    int n;
+} cseg_t;
+
+static void alg2_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, const void* base, int dtype,
+                     int d, const float* q, int k, int m_c, int m_v, float delta, int T, int lambda_visit,
+                     uint64_t seed, uint64_t qi, cseg_t* C, int32_t* V, int* vpos, pair_t* R, float* tmp,
+                     int32_t* out_ids, float* out_s, uint32_t* stats)
+{
+    uint32_t hops = 0, evals = 0, skips = 0;
+    int nR = 0;
+    for (int g = 0; g < m_c; ++g) C[g].n = 0;
+    for (int g = 0; g < m_v * 32; ++g) V[g] = -1;
+    for (int g = 0; g < m_v; ++g) vpos[g] = 0;
+    pair_t best;
+    best.s = INFINITY;
+    best.id = -1;
+    for (int t = 0; t < 32; ++t) {
+        pair_t c;
+        c.id = (int32_t)orc_seed_id(seed, qi, (uint64_t)t, N);
+        c.s = orc_sqdist(q, row_f32(base, dtype, c.id, d, tmp), d);
+        ++evals;
+        if (best.id < 0 || pair_less(c, best)) best = c;
+    }
+    R[nR++] = best;
+    C[best.id % m_c].e[0] = best;
+    C[best.id % m_c].n = 1;
+    for (;;) {
+        if (T > 0 && (int)hops >= T) break;
+        int gbest = -1;
+        for (int g = 0; g < m_c; ++g)
+            if (C[g].n > 0 && (gbest < 0 || pair_less(C[g].e[0], C[gbest].e[0]))) gbest = g;
+        if (gbest < 0) break;
+        ++hops;
+        pair_t u = C[gbest].e[0];
+        for (int t = 1; t < C[gbest].n; ++t) C[gbest].e[t - 1] = C[gbest].e[t];
+        --C[gbest].n;
+        if (u.s > R[nR - 1].s + delta) break;
+        int gv = u.id % m_v;
+        V[gv * 32 + vpos[gv]] = u.id;
+        vpos[gv] = (vpos[gv] + 1) % 32;
+        int deg = 0;
+        while (deg < K && adj[(int64_t)u.id * K + deg] >= 0 && (int)lam[(int64_t)u.id * K + deg] < lambda_visit) ++deg;
+        for (int p = 0; p < deg; ++p) {
+            int32_t e = adj[(int64_t)u.id * K + p];
+            int found = 0;
+            for (int t = 0; t < 32 && !found; ++t) found = (V[(e % m_v) * 32 + t] == e);
+            cseg_t* sg = &C[e % m_c];
+            for (int t = 0; t < sg->n && !found; ++t) found = (sg->e[t].id == e);
+            if (found) { ++skips; continue; }
+            pair_t c;
+            c.id = e;
+            c.s = orc_sqdist(q, row_f32(base, dtype, e, d, tmp), d);
+            ++evals;
+            if (!(nR < k || c.s < R[nR - 1].s)) continue;
+            int inR = 0;
+            for (int t = 0; t < nR && !inR; ++t) inR = (R[t].id == e);
+            if (inR) continue;
+            /* R.push, drop the furthest when over k */
+            int pos = nR;
+            while (pos > 0 && pair_less(c, R[pos - 1])) --pos;
+            int end = nR < k ? nR : k - 1;
+            for (int t = end; t > pos; --t) R[t] = R[t - 1];
+            if (pos < k) R[pos] = c;
+            if (nR < k) ++nR;
+            /* C.push into its segment, drop that segment's most distant when over 32 */
+            pos = sg->n;
+            while (pos > 0 && pair_less(c, sg->e[pos - 1])) --pos;
+            end = sg->n < 32 ? sg->n : 31;
+            for (int t = end; t > pos; --t) sg->e[t] = sg->e[t - 1];
+            if (pos < 32) sg->e[pos] = c;
+            if (sg->n < 32) ++sg->n;
+        }
+    }
+    for (int t = 0; t < k; ++t) {
+        out_ids[t] = t < nR ? R[t].id : -1;
+        out_s[t] = t < nR ? R[t].s : INFINITY;
+    }
+    if (stats) { stats[0] = hops; stats[1] = evals; stats[2] = skips; }
+}
+
+int orc_search_alg2(const int32_t* adj, const uint8_t* lam, int64_t N, int K, const void* base, int dtype, int d,
+                    const float* queries, int64_t nq, int k, int m_c, int m_v, float delta, int T,
+                    int lambda_visit, uint64_t seed, int64_t qi_offset, int32_t* out_ids, float* out_s,
+                    uint32_t* stats, int threads)
+{
+    if (!adj || !lam || !base || !queries || !out_ids || !out_s) return 1;
+    if (N <= 0 || K <= 0 || d <= 0 || k <= 0 || m_c <= 0 || m_v <= 0 || T < 0 || nq < 0 || !(delta >= 0.0f)) return 1;
+    threads = use_threads(threads);
+    int failed = 0;
+#pragma omp parallel num_threads(threads)
+    {
+        cseg_t* C = (cseg_t*)malloc(sizeof(cseg_t) * (size_t)m_c);
+        int32_t* V = (int32_t*)malloc(sizeof(int32_t) * (size_t)m_v * 32);
+        int* vpos = (int*)malloc(sizeof(int) * (size_t)m_v);
+        pair_t* R = (pair_t*)malloc(sizeof(pair_t) * (size_t)(k + 1));
+        float* tmp = (float*)malloc(sizeof(float) * (size_t)d);
+        if (!C || !V || !vpos || !R || !tmp) {
+#pragma omp atomic write
+            failed = 1;
+        } else {
+#pragma omp for schedule(dynamic, 8)
+            for (int64_t qi = 0; qi < nq; ++qi)
+                alg2_one(adj, lam, N, K, base, dtype, d, queries + qi * (int64_t)d, k, m_c, m_v, delta, T,
+                         lambda_visit, seed, (uint64_t)(qi + qi_offset), C, V, vpos, R, tmp, out_ids + qi * k,
+                         out_s + qi * k, stats ? stats + qi * 3 : NULL);
+        }
+        free(C); free(V); free(vpos); free(R); free(tmp);
+    }
+    return failed ? 2 : 0;
+}
+
 /* Recall@k (Eq. 3): found[nq,k] against truth[nq,k]; -1 entries never match. */
 double orc_recall(const int32_t* found, const int32_t* truth, int64_t nq, int k)
 {
