@@ -292,6 +292,27 @@ def main():
         log(f"uint8 storage: graph equal {same_graph}; {rows}")
         del base8, graph8, adj8, lam8
 
+    # ---- the paper's own structures (Alg. 2: R of size k, segmented queue C, segmented table V, Delta stop)
+    if not args.skip_small:
+        typical = float(P.ann_bruteforce(base, queries[:512].contiguous(), k)[1][:, -1].median().item())
+        rows = []
+        for k2, frac in ((16, 0.0), (32, 0.0), (32, 0.1), (64, 0.0)):
+            i2, s2, st2 = P.ann_search_alg2(graph, base, queries, k2, frac * typical, want_stats=True)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                P.ann_search_alg2(graph, base, queries, k2, frac * typical, out=(i2, s2))
+            e1.record()
+            torch.cuda.synchronize()
+            ms2 = e0.elapsed_time(e1) / 3
+            rows.append({"k": k2, "delta_over_typical_10th_dist": frac, "recall@10": round(recall_of(i2[:, :k].contiguous()), 4),
+                         "qps": round(args.nq / ms2 * 1e3), "ms": round(ms2, 4),
+                         "hops": round(st2.hops.double().mean().item(), 1),
+                         "dist_evals": round(st2.dist_evals.double().mean().item(), 1)})
+        result["alg2_structures"] = rows
+        log(f"Alg. 2 structures: {rows}")
+
     # ---- the oracle on the host cores, same graph, same queries (a baseline, not the target)
     if not args.skip_cpu:
         import oracle

@@ -153,6 +153,19 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
                             int t0, const ann_search_params* params, int32_t* out_ids,
                             float* out_dists, ann_query_stats* stats);
 
+/* Large-batch search with the structures of Alg. 2 / Sec. 4.2 as printed: a ranking array R of
+ * fixed size k (k <= 64), an expansion queue C of m_c segments of 32 sorted entries (segment =
+ * id mod m_c; a push into a full segment drops its most distant entry; pop = smallest head), a
+ * look-up table V of m_v segments of 32 slots holding only expanded nodes (round-robin
+ * overwrite), start from the closest of 32 seeds, stop when the popped candidate is further
+ * than the furthest of R by more than delta (in squared-distance units), when C is empty or at
+ * the hop limit.  1 <= m_c, m_v <= 64.  Unlike ann_search its result depends on m_c and m_v.
+ * Of params it reads dtype, lambda_visit (0 = 5), seed, max_hops (0 = unbounded), qi_offset,
+ * stream; stats->dedup_hits counts neighbours skipped because V or C held them. */
+ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void* queries, int nq, int k,
+                           float delta, int m_c, int m_v, const ann_search_params* params,
+                           int32_t* out_ids, float* out_dists, ann_query_stats* stats);
+
 /* Flat copies of a graph, N*K entries each (device pointers): adj = neighbour
  * id or -1 for an unused slot, lam = occlusion factor or 255 for an unused
  * slot.  Import validates ids (range, no self loop, no repeats in a row,

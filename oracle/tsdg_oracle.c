@@ -739,6 +739,7 @@ int orc_search_multi(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
  *           f = furthest of R
  *           if s(e) < s(f) or |R| < k:  R.push(e); C.push(e); if |R| > k drop the furthest
  *   return R
+ * (the V / C tests of all neighbours of u are made before any of them is pushed)
  *
  * C: segment id % m_c, each kept sorted by (s,id), at most 32 entries; a push
  * into a full segment drops that segment's most distant entry; pop = the
@@ -793,6 +794,10 @@ static void alg2_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
         vpos[gv] = (vpos[gv] + 1) % 32;
         int deg = 0;
         while (deg < K && adj[(int64_t)u.id * K + deg] >= 0 && (int)lam[(int64_t)u.id * K + deg] < lambda_visit) ++deg;
+        /* the look-ups of all neighbours come first (on the GPU the lanes test in parallel,
+         * Sec. 4.2), then the survivors are scored, then pushed one by one in stored order */
+        pair_t fresh[64];
+        int nf = 0;
         for (int p = 0; p < deg; ++p) {
             int32_t e = adj[(int64_t)u.id * K + p];
             int found = 0;
@@ -800,13 +805,17 @@ static void alg2_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
             cseg_t* sg = &C[e % m_c];
             for (int t = 0; t < sg->n && !found; ++t) found = (sg->e[t].id == e);
             if (found) { ++skips; continue; }
-            pair_t c;
-            c.id = e;
-            c.s = orc_sqdist(q, row_f32(base, dtype, e, d, tmp), d);
+            fresh[nf].id = e;
+            fresh[nf].s = orc_sqdist(q, row_f32(base, dtype, e, d, tmp), d);
+            ++nf;
             ++evals;
+        }
+        for (int p = 0; p < nf; ++p) {
+            pair_t c = fresh[p];
+            cseg_t* sg = &C[c.id % m_c];
             if (!(nR < k || c.s < R[nR - 1].s)) continue;
             int inR = 0;
-            for (int t = 0; t < nR && !inR; ++t) inR = (R[t].id == e);
+            for (int t = 0; t < nR && !inR; ++t) inR = (R[t].id == c.id);
             if (inR) continue;
             /* R.push, drop the furthest when over k */
             int pos = nR;

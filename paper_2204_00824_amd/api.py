@@ -57,13 +57,14 @@ def load_library():
     L.ann_search.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     L.ann_search_ex.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
     L.ann_search_multi.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
+    L.ann_search_alg2.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
     L.ann_graph_export.argtypes = [vp, vp, vp, vp]
     L.ann_graph_import.argtypes = [vp, vp, i64, i32, i32, vp, C.POINTER(vp)]
     L.ann_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
     L.ann_graph_free.argtypes = [vp]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_graph_export", "ann_graph_import", "ann_graph_info"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -225,6 +226,33 @@ def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k:
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
     _check(lib.ann_search_multi(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(),
                                 st.data_ptr() if st is not None else None))
+    if want_stats:
+        return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
+    return ids, s
+
+
+def ann_search_alg2(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, delta: float, *, m_c: int = 16,
+                    m_v: int = 16, lambda_visit: int = 0, seed: int = 0, max_hops: int = 0, qi_offset: int = 0,
+                    stream=None, want_stats: bool = False, out=None):
+    """Search with the paper's own R / C / V structures (Alg. 2)."""
+    lib = load_library()
+    p, dt = _base_ptr(base)
+    q = _dev(queries, torch.float32, "queries")
+    nq = queries.shape[0]
+    if out is None:
+        ids = torch.empty((nq, k), dtype=torch.int32, device=base.device)
+        s = torch.empty((nq, k), dtype=torch.float32, device=base.device)
+    else:
+        ids, s = out
+        _dev(ids, torch.int32, "out ids")
+        _dev(s, torch.float32, "out dists")
+    prm = _SearchParams()
+    lib.ann_search_params_default(C.byref(prm))
+    prm.dtype, prm.lambda_visit, prm.seed, prm.max_hops = dt, lambda_visit, seed, max_hops
+    prm.qi_offset, prm.stream = qi_offset, _stream_ptr(stream)
+    st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
+    _check(lib.ann_search_alg2(graph.ptr, p, q, nq, k, C.c_float(delta), m_c, m_v, C.byref(prm), ids.data_ptr(),
+                               s.data_ptr(), st.data_ptr() if st is not None else None))
     if want_stats:
         return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
     return ids, s

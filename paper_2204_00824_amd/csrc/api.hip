@@ -457,6 +457,52 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
     return launch_search_multi(s);
 }
 
+ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void* queries, int nq, int k,
+                           float delta, int m_c, int m_v, const ann_search_params* params, int32_t* out_ids,
+                           float* out_dists, ann_query_stats* stats)
+{
+    g_err[0] = 0;
+    ann_search_params p;
+    ann_search_params_default(&p);
+    if (params) p = *params;
+    if (!graph) { set_error("ann_search_alg2: null graph"); return ANN_EINVAL; }
+    const ann_graph_impl* g = reinterpret_cast<const ann_graph_impl*>(graph);
+    if (nq < 0) { set_error("ann_search_alg2: negative nq"); return ANN_EINVAL; }
+    if (k < 1 || k > 64) { set_error("ann_search_alg2: need 1 <= k <= 64 (k=%d)", k); return ANN_EINVAL; }
+    if (m_c < 1 || m_c > 64 || m_v < 1 || m_v > 64) { set_error("ann_search_alg2: m_c and m_v must be in 1..64"); return ANN_EINVAL; }
+    if (!(delta >= 0.0f)) { set_error("ann_search_alg2: delta must be >= 0"); return ANN_EINVAL; }
+    if (p.max_hops < 0 || p.lambda_visit < 0) { set_error("ann_search_alg2: negative max_hops / lambda_visit"); return ANN_EINVAL; }
+    if (nq == 0) return ANN_OK;
+    if (!queries || !out_ids || !out_dists) { set_error("ann_search_alg2: null pointer"); return ANN_EINVAL; }
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_alg2");
+    if (rc != ANN_OK) return rc;
+    if (!aligned16(queries)) { set_error("ann_search_alg2: query rows must be 16-byte aligned"); return ANN_EINVAL; }
+    Alg2Launch s;
+    s.packed = g->packed;
+    s.N = g->N;
+    s.K = g->K;
+    s.base = base;
+    s.dtype = p.dtype;
+    s.d = g->d;
+    s.queries = static_cast<const float*>(queries);
+    s.nq = nq;
+    s.k = k;
+    s.m_c = m_c;
+    s.m_v = m_v;
+    int lv = p.lambda_visit == 0 ? 5 : p.lambda_visit;   // large-batch prefix (Sec. 5.4)
+    if (lv > 31) lv = 32;
+    s.lambda_visit = lv;
+    s.max_hops = p.max_hops;
+    s.delta = delta;
+    s.seed = p.seed;
+    s.qi_offset = p.qi_offset;
+    s.out_ids = out_ids;
+    s.out_dists = out_dists;
+    s.stats = stats;
+    s.stream = static_cast<hipStream_t>(p.stream);
+    return launch_search_alg2(s);
+}
+
 ann_status ann_search(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int L,
                       int32_t* out_ids, float* out_dists)
 {

@@ -89,6 +89,25 @@ struct MultiLaunch {
 };
 ann_status launch_search_multi(const MultiLaunch& a);
 
+struct Alg2Launch {
+    const uint32_t* packed;
+    int64_t N;
+    int K;
+    const void* base;
+    ann_dtype dtype;
+    int d;
+    const float* queries;
+    int nq, k, m_c, m_v, lambda_visit, max_hops;
+    float delta;
+    uint64_t seed;
+    int64_t qi_offset;
+    int32_t* out_ids;
+    float* out_dists;
+    ann_query_stats* stats;
+    hipStream_t stream;
+};
+ann_status launch_search_alg2(const Alg2Launch& a);
+
 ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries,
                      int64_t nq, int k, bool exclude_self, hipStream_t stream, int32_t* out_ids,
                      float* out_s);

@@ -31,14 +31,17 @@ def py_alg2(adj, lam, base, q, k, m_c, m_v, delta, T, lv, seeds):
             break
         V[u[1] % m_v][vpos[u[1] % m_v]] = u[1]
         vpos[u[1] % m_v] = (vpos[u[1] % m_v] + 1) % 32
+        fresh = []
         for p in range(adj.shape[1]):
             e = int(adj[u[1], p])
             if e < 0 or lam[u[1], p] >= lv:
                 break
             if e in V[e % m_v] or any(i == e for _, i in C[e % m_c]):
                 continue
-            c = (s_of(e), e)
-            evals += 1
+            fresh.append((s_of(e), e))          # all look-ups of the hop precede its pushes
+        evals += len(fresh)
+        for c in fresh:
+            e = c[1]
             if not (len(R) < k or c[0] < R[-1][0]):
                 continue
             if any(i == e for _, i in R):
