@@ -33,6 +33,11 @@ template <typename T, int G, int C> struct RowDist {
     using chunk_t = typename Elem<T>::chunk_t;
 
     float q[C * PC];  // this lane's slices of the query
+    // uint8 rows with an integer-valued query in [0,255]: the same slices as packed bytes, their
+    // sum of squares, and the flag that selects the integer path (wave-uniform)
+    uint32_t qbytes[(sizeof(T) == 1) ? C * 4 : 1];
+    uint32_t qq;
+    bool q_int;
     int g;            // lane within group
     int v;            // group within wave
     int nchunks;      // d / PC
@@ -63,6 +68,7 @@ template <typename T, int G, int C> struct RowDist {
                 q[c * PC + e + 3] = x.w;
             }
         }
+        pack_query();
     }
     // query is itself a base row (build passes)
     __device__ __forceinline__ void load_query_row(const T* __restrict__ base, uint32_t row)
@@ -72,6 +78,29 @@ template <typename T, int G, int C> struct RowDist {
             chunk_t x = {};
             if (has(c)) x = load(base, row, c);
             unpack(x, &q[c * PC]);
+        }
+        pack_query();
+    }
+
+    // uint8 rows only: decide whether every query element is an integer in [0,255] (all lanes of
+    // the wave vote, so the branch is uniform) and keep the packed bytes and their square sum
+    __device__ __forceinline__ void pack_query()
+    {
+        q_int = false;
+        qq = 0u;
+        if constexpr (sizeof(T) == 1) {
+            bool ok = true;
+#pragma unroll
+            for (int i = 0; i < C * PC; ++i) ok = ok && q[i] >= 0.f && q[i] <= 255.f && q[i] == rintf(q[i]);
+            q_int = ballot64(!ok) == 0ull;
+#pragma unroll
+            for (int w = 0; w < C * 4; ++w) {
+                uint32_t b = 0u;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) b |= ((uint32_t)q[w * 4 + e] & 0xFFu) << (8 * e);
+                qbytes[w] = b;
+                qq = __builtin_amdgcn_udot4(b, b, qq, false);
+            }
         }
     }
 
@@ -113,6 +142,52 @@ template <typename T, int G, int C> struct RowDist {
             }
         }
         return acc;
+    }
+
+    // The squared distance between the query and the row whose chunks are in buf, as the fp32
+    // canonical value; every lane of the group gets it.  uint8 rows with an integer query take
+    // the exact integer route sum q^2 + sum x^2 - 2 sum q x on v_dot4_u32_u8 (8 instructions per
+    // 16 elements): the integer total converts to the same fp32 as the fp64 sum of squares.
+    __device__ __forceinline__ float distance(const chunk_t (&buf)[C]) const
+    {
+        if constexpr (sizeof(T) == 1) {
+            if (q_int) {
+                uint32_t xx = 0u, qx = 0u;
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    if (has(c)) {
+                        const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            xx = __builtin_amdgcn_udot4(w[i], w[i], xx, false);
+                            qx = __builtin_amdgcn_udot4(qbytes[c * 4 + i], w[i], qx, false);
+                        }
+                    }
+                }
+                // this lane's share of sum (q-x)^2 (non-negative); chunks the lane does not own
+                // contribute neither q^2 nor x^2
+                uint32_t part = xx - 2u * qx;
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (has(c))
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            part = __builtin_amdgcn_udot4(qbytes[c * 4 + i], qbytes[c * 4 + i], part, false);
+                return (float)group_sum_u32(part);
+            }
+        }
+        return (float)group_sum(partial(buf));
+    }
+
+    static __device__ __forceinline__ uint32_t group_sum_u32(uint32_t a)
+    {
+        a += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0xB1, 0xF, 0xF, false);
+        a += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x4E, 0xF, 0xF, false);
+        if constexpr (G >= 8) a += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x141, 0xF, 0xF, false);
+        if constexpr (G >= 16) a += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x140, 0xF, 0xF, false);
+        if constexpr (G >= 32) a += (uint32_t)__shfl_xor((int)a, 16, 64);
+        if constexpr (G >= 64) a += (uint32_t)__shfl_xor((int)a, 32, 64);
+        return a;
     }
 
     // sum over the G lanes of a group; every lane of the group gets the total.  Butterfly over

@@ -47,8 +47,8 @@ __device__ __forceinline__ void pairwise(RD& rd, const T* __restrict__ base, con
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int j = p0 + u * VP + rd.v;
-                const double tot = RD::group_sum(rd.partial(buf[u]));
-                if (ok[u] && rd.g == 0) P[i * stride + j] = (float)tot;
+                const float tot = rd.distance(buf[u]);
+                if (ok[u] && rd.g == 0) P[i * stride + j] = tot;
             }
         }
     }

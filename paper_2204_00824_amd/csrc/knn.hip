@@ -777,8 +777,8 @@ __global__ __launch_bounds__(64) void refine_kernel(RefineArgs a)
                 buf[cc] = chunk_t{};
                 if (ok && rd.has(cc)) buf[cc] = rd.load(X, e, cc);
             }
-            const double tot = RD::group_sum(rd.partial(buf));
-            if (ok && rd.g == 0) ckey[c] = make_key((float)tot, e);
+            const float tot = rd.distance(buf);
+            if (ok && rd.g == 0) ckey[c] = make_key(tot, e);
         }
         __syncthreads();
         const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
@@ -845,9 +845,9 @@ __global__ __launch_bounds__(64) void scan_kernel(RefineArgs a, int64_t N, int64
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int c = p0 + u * VP + rd.v;
-                const double tot = RD::group_sum(rd.partial(buf[u]));
+                const float tot = rd.distance(buf[u]);
                 if (ok[u] && rd.g == 0)
-                    ckey[c] = (b0 + c == self) ? kKeyEmpty : make_key((float)tot, (uint32_t)(b0 + c));
+                    ckey[c] = (b0 + c == self) ? kKeyEmpty : make_key(tot, (uint32_t)(b0 + c));
             }
         }
         __syncthreads();

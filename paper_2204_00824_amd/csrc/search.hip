@@ -114,8 +114,8 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const double tot = RD::group_sum(rd.partial(buf[u]));
-                if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key((float)tot, e[u]);
+                const float tot = rd.distance(buf[u]);
+                if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
             }
         }
         __syncthreads();

@@ -98,6 +98,14 @@ def test_uint8_rows(gpu, orc):
         (ids, s, st), ref = run_both(gpu, orc, case, 10, 32, 10, mode)
         assert_bitwise(ids, ref[0], "u8 ids")
         assert_bitwise(s, ref[1], "u8 dists")
+    # queries that are not integers take the general path on the same uint8 rows; a batch that mixes
+    # both kinds exercises the per-query choice
+    mixed = case[1].copy()
+    mixed[::2] += np.float32(0.375)
+    mixed[1, 0] = 300.0                                   # integer but outside the byte range
+    (ids, s, st), ref = run_both(gpu, orc, (case[0], mixed, case[2], case[3]), 10, 32, 10, 1)
+    assert_bitwise(ids, ref[0], "u8 mixed ids")
+    assert_bitwise(s, ref[1], "u8 mixed dists")
 
 
 def test_degenerate_graphs_and_padding(gpu, orc):
