@@ -376,13 +376,18 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                uint32_t mask = 0;
+                // common case first: the smallest of the 16 values against the threshold
+                // (16 fma + 8 three-way minima + 1 compare), nothing else when no lane passes
+                float um[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float u = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
-                    mask |= (u < tq[j]) ? (1u << r) : 0u;
-                }
-                if (ballot64(mask != 0u)) {
+                for (int r = 0; r < 16; ++r) um[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
+                float lo = __builtin_fminf(um[0], um[1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, um[r]), um[r + 1]);
+                if (ballot64(lo < tq[j])) {
+                    uint32_t mask = 0;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mask |= (um[r] < tq[j]) ? (1u << r) : 0u;
                     // rare: walk the set bits; the accumulator is picked by a select chain so
                     // that the loop needs no indexed register access
 #pragma unroll 1
@@ -610,13 +615,16 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
                 const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
                 xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
             }
-            uint32_t mask = 0;
+            float um[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float u = __builtin_fmaf(-2.f, acc[i][r], xv[r]);
-                mask |= (u < tq) ? (1u << r) : 0u;
-            }
-            if (ballot64(mask != 0u)) {
+            for (int r = 0; r < 16; ++r) um[r] = __builtin_fmaf(-2.f, acc[i][r], xv[r]);
+            float lo = __builtin_fminf(um[0], um[1]);
+#pragma unroll
+            for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, um[r]), um[r + 1]);
+            if (ballot64(lo < tq)) {
+                uint32_t mask = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mask |= (um[r] < tq) ? (1u << r) : 0u;
 #pragma unroll 1
                 while (ballot64(mask != 0u)) {
                     const int rr = mask ? (int)__builtin_ctz(mask) : 16;
