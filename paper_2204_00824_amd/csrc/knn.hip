@@ -39,7 +39,7 @@ constexpr float kInf = __builtin_inff();
 // info[0] = 1 if some element is not an integer in [0,255]; info[1] = max norm (fp32 bits)
 template <typename T>
 __global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int64_t n, int d,
-                                                    float* __restrict__ norms, unsigned* __restrict__ info)
+                                                    float* __restrict__ norms, unsigned* info)
 {
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = lane_id();
@@ -54,11 +54,13 @@ __global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
     const float nf = (float)acc;
+    // one atomic per row on a single address would serialise a million rows: look first (the
+    // values only grow, so a stale read can only cause a harmless extra atomic)
     if (lane == 0) {
         norms[row] = nf;
-        atomicMax(&info[1], __float_as_uint(nf));
+        if (__float_as_uint(nf) > info[1]) atomicMax(&info[1], __float_as_uint(nf));
     }
-    if (ballot64(nonint) && lane == 0) atomicOr(&info[0], 1u);
+    if (ballot64(nonint) && lane == 0 && info[0] == 0u) atomicOr(&info[0], 1u);
 }
 
 // ---------------------------------------------------------------- tile loads
@@ -473,7 +475,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
                                                          const float* __restrict__ mean, uint16_t* __restrict__ xh,
                                                          uint16_t* __restrict__ xl, float* __restrict__ norms,
-                                                         unsigned* __restrict__ maxnorm)
+                                                         unsigned* maxnorm)
 {
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = lane_id();
@@ -493,7 +495,7 @@ __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x
     if (lane == 0) {
         const float nf = (float)acc;
         norms[row] = nf;
-        atomicMax(maxnorm, __float_as_uint(nf));
+        if (__float_as_uint(nf) > *maxnorm) atomicMax(maxnorm, __float_as_uint(nf));
     }
 }
 
