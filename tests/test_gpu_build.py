@@ -89,7 +89,7 @@ def test_knn_uint8(gpu, orc):
     assert_bitwise(s.cpu().numpy(), ref[1], "u8 knn dists")
 
 
-@pytest.mark.parametrize("d", [8, 96, 960])
+@pytest.mark.parametrize("d", [8, 96, 128, 960])
 def test_knn_real_valued_shapes(gpu, orc, d):
     step(f"ann_knn gaussian d={d}")
     base = workloads.single_gaussian(3000 if d < 900 else 1500, d, seed=100 + d)
