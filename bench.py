@@ -209,6 +209,54 @@ def main():
         "sweep": sweep,
         "build": build,
     }
+    result["roofline"]["kernel_ms_min_max"] = [round(min(kern_ms), 4), round(max(kern_ms), 4)]
+
+    # queries/s at recall exactly `target`, by log-linear interpolation between the bracketing L values
+    for lo_, hi_ in zip(sweep, sweep[1:]):
+        if lo_["recall@10"] < args.target_recall <= hi_["recall@10"]:
+            f = (args.target_recall - lo_["recall@10"]) / (hi_["recall@10"] - lo_["recall@10"])
+            result["qps_interpolated_at_target_recall"] = round(
+                float(np.exp(np.log(lo_["qps"]) + f * (np.log(hi_["qps"]) - np.log(lo_["qps"])))))
+
+    # ---- what this GPU reaches on the same access shape without the search around it: a streaming copy,
+    # and plain gathers of whole rows at random ids (the base itself, partly cache-resident at 512 MB,
+    # and a 4 GiB table that is not)
+    if not args.skip_small:
+        ceil = {}
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e-3
+
+        ceil["copy_1GiB_read_plus_write_GBps"] = round(2 * src.numel() * 4 / timed(lambda: dst.copy_(src)) / 1e9, 1)
+        del src, dst
+        big = torch.zeros(1 << 32, dtype=torch.uint8, device=dev)                # 4 GiB
+        gen = torch.Generator(device=dev).manual_seed(7)
+        n_rows = 1 << 23
+        pout = torch.empty(n_rows, dtype=torch.int32, device=dev)
+        pid = torch.randint(0, args.n, (n_rows,), generator=gen, device=dev, dtype=torch.int32)
+        ceil["gather_base_512B_rows_GBps"] = round(
+            n_rows * d * 4 / timed(lambda: P.ann_probe_gather(base, pid, out=pout)) / 1e9, 1)
+        for rb in (128, 384, 512, 3840):
+            rows_t = (1 << 32) // rb
+            tab = big[: rows_t * rb].view(rows_t, rb)
+            n_g = min(n_rows, (1 << 32) // rb)
+            tid = torch.randint(0, rows_t, (n_g,), generator=gen, device=dev, dtype=torch.int32)
+            ceil[f"gather_4GiB_table_{rb}B_rows_GBps"] = round(
+                n_g * rb / timed(lambda: P.ann_probe_gather(tab, tid, out=pout[:n_g])) / 1e9, 1)
+        del big, pid, pout
+        result["measured_ceilings"] = ceil
+        result["roofline"]["frac_of_measured_gather_512B"] = round(achieved / ceil["gather_base_512B_rows_GBps"], 4)
+        log(f"ceilings: {ceil}")
 
     # ---- small-batch regime (batch 1 / 16 / 100; lambda_visit 10, one workgroup per query):
     # median latency of single calls (launch included) and recall, per L

@@ -179,6 +179,14 @@ ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, i
 ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d);
 void ann_graph_free(ann_graph* graph);
 
+/* Measurement probe, not a step of the method: gathers n rows of row_bytes bytes (a multiple of 16,
+ * at most 8192) from base[N rows] (device, 16-byte aligned) at ids[n] (device; an id >= N reads row
+ * N-1) with the access shape of search step S5 (Alg. 2's distance step) and writes one xor-folded
+ * word per row to out[n] (device).  Asynchronous on `stream`.  Timing it gives the random-row
+ * bandwidth this GPU reaches with no search logic around the loads. */
+ann_status ann_probe_gather(const void* base, int64_t N, int row_bytes, const uint32_t* ids, int64_t n,
+                            uint32_t* out, void* stream);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* ann_last_error(void);
 

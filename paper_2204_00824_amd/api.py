@@ -62,9 +62,10 @@ def load_library():
     L.ann_graph_import.argtypes = [vp, vp, i64, i32, i32, vp, C.POINTER(vp)]
     L.ann_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
     L.ann_graph_free.argtypes = [vp]
+    L.ann_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -280,6 +281,19 @@ def ann_graph_info(graph: Graph):
     N, K, d = C.c_int64(), C.c_int(), C.c_int()
     _check(load_library().ann_graph_info(graph.ptr, C.byref(N), C.byref(K), C.byref(d)))
     return N.value, K.value, d.value
+
+
+def ann_probe_gather(base: torch.Tensor, ids: torch.Tensor, out: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """Measurement probe: gathers base[ids] row by row and returns one xor-folded word per row."""
+    if not (base.is_cuda and base.is_contiguous() and base.dim() == 2):
+        raise ValueError("base must be a contiguous [N,d] device tensor")
+    row_bytes = base.shape[1] * base.element_size()
+    i = _dev(ids, torch.int32, "ids")
+    if out is None:
+        out = torch.empty(ids.numel(), dtype=torch.int32, device=base.device)
+    _check(load_library().ann_probe_gather(base.data_ptr(), base.shape[0], row_bytes, i, ids.numel(),
+                                           _dev(out, torch.int32, "out"), _stream_ptr(stream)))
+    return out
 
 
 def ann_graph_free(graph: Graph) -> None:

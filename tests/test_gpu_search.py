@@ -162,3 +162,21 @@ def test_argument_errors(gpu, orc):
     ids, s = gpu.ann_search(g, b, q, 10, 32)
     ref = orc.search(adj, lam, base, queries, 10, 32, 10)            # 100 queries -> small batch -> lambda < 10
     assert_bitwise(ids.cpu().numpy(), ref[0], "defaults")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("row_bytes", [16, 128, 384, 512, 1040, 3840, 8192])
+def test_probe_gather_reads_the_rows_it_is_given(gpu, row_bytes):
+    """The gather probe's one word per row is the xor of the row's 32-bit words (ids past the end read the last row)."""
+    import torch
+    P = gpu
+    g = torch.Generator().manual_seed(row_bytes)
+    N, n = 3001, 10_007
+    tab = torch.randint(0, 256, (N, row_bytes), generator=g, dtype=torch.uint8)
+    ids = torch.randint(0, N, (n,), generator=g, dtype=torch.int32)
+    ids[5] = N + 17
+    step(f"probe gather row_bytes={row_bytes}")
+    got = P.ann_probe_gather(tab.cuda(), ids.cuda()).cpu().numpy().view(np.uint32)
+    words = tab.numpy().view(np.uint32)
+    want = np.bitwise_xor.reduce(words[np.minimum(ids.numpy(), N - 1)], axis=1)
+    assert np.array_equal(got, want)
