@@ -35,31 +35,47 @@ constexpr int kTile = 128;        // queries and candidates per workgroup tile
 constexpr int kTilesPerBlock = 8; // candidate tiles a workgroup sweeps
 constexpr float kInf = __builtin_inff();
 
+__device__ __forceinline__ float4 load4(const float* p);
+__device__ __forceinline__ float4 load4(const uint8_t* p);
+
 // ---------------------------------------------------------------- row norms, integer test
 // info[0] = 1 if some element is not an integer in [0,255]; info[1] = max norm (fp32 bits)
 template <typename T>
 __global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int64_t n, int d,
                                                     float* __restrict__ norms, unsigned* info)
 {
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = lane_id();
-    if (row >= n) return;
+    // 8 lanes per row, 4 elements per lane and step (128 contiguous bytes per group for fp32)
+    const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int g = (int)(threadIdx.x & 7);
     double acc = 0.0;
     bool nonint = false;
-    for (int j = lane; j < d; j += 64) {
-        const float v = (float)x[row * d + j];
-        acc += (double)v * (double)v;
-        nonint |= !(v >= 0.f && v <= 255.f && v == rintf(v));
+    if (row < n) {
+        const T* xr = x + row * d;
+        for (int j = 4 * g; j < d; j += 32) {
+            const float4 v = load4(xr + j);
+            acc += (double)v.x * (double)v.x;
+            acc += (double)v.y * (double)v.y;
+            acc += (double)v.z * (double)v.z;
+            acc += (double)v.w * (double)v.w;
+            if constexpr (sizeof(T) != 1) {
+                nonint |= !(v.x >= 0.f && v.x <= 255.f && v.x == rintf(v.x));
+                nonint |= !(v.y >= 0.f && v.y <= 255.f && v.y == rintf(v.y));
+                nonint |= !(v.z >= 0.f && v.z <= 255.f && v.z == rintf(v.z));
+                nonint |= !(v.w >= 0.f && v.w <= 255.f && v.w == rintf(v.w));
+            }
+        }
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    for (int o = 4; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
     const float nf = (float)acc;
-    // one atomic per row on a single address would serialise a million rows: look first (the
-    // values only grow, so a stale read can only cause a harmless extra atomic)
-    if (lane == 0) {
-        norms[row] = nf;
-        if (__float_as_uint(nf) > info[1]) atomicMax(&info[1], __float_as_uint(nf));
-    }
+    if (row < n && g == 0) norms[row] = nf;
+    // the wave's largest norm, then at most one atomic per wave, and only when the value read
+    // first is smaller (the maximum only grows, so a stale read costs a harmless extra atomic)
+    unsigned m = row < n ? __float_as_uint(nf) : 0u;
+#pragma unroll
+    for (int o = 32; o >= 8; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o, 64));
+    const int lane = lane_id();
+    if (lane == 0 && m > info[1]) atomicMax(&info[1], m);
     if (ballot64(nonint) && lane == 0 && info[0] == 0u) atomicOr(&info[0], 1u);
 }
 
@@ -258,6 +274,14 @@ __global__ __launch_bounds__(256) void to_bf16_kernel(const T* __restrict__ src,
     *reinterpret_cast<uint2*>(dst + r * dp + c) = make_uint2(lo, hi);
 }
 
+// two packed bf16 values, each multiplied by -2 (exact; zero stays zero)
+__device__ __forceinline__ uint32_t bf16x2_times_minus2(uint32_t w)
+{
+    const float lo = -2.f * __uint_as_float(w << 16);
+    const float hi = -2.f * __uint_as_float(w & 0xFFFF0000u);
+    return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
+}
+
 struct FastArgs {
     const uint16_t* qb;   // [nq, DP] bf16 query rows (row 0 = first query of this sweep)
     const uint16_t* xb;   // [N, DP] bf16 base rows
@@ -276,7 +300,7 @@ constexpr int kFastRows = 64;  // candidate rows per LDS tile
 constexpr int kQueue = 1024;    // survivor queue entries per workgroup
 
 template <int KS>
-__global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void filter_bf16_kernel(FastArgs a)
 {
     constexpr int DP = KS * 16;
     constexpr int XS = DP + 8;                       // LDS row stride (elements): 16-B aligned, staggers banks
@@ -306,6 +330,10 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
         for (int ks = 0; ks < KS; ++ks) {
             uint4 w = make_uint4(0u, 0u, 0u, 0u);
             if (ok) w = *reinterpret_cast<const uint4*>(a.qb + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
+            // the query enters as -2q (exact: a power of two), so that with |x|^2 as the
+            // accumulator's start value the contraction itself yields |x|^2 - 2 q.x
+            w.x = bf16x2_times_minus2(w.x); w.y = bf16x2_times_minus2(w.y);
+            w.z = bf16x2_times_minus2(w.z); w.w = bf16x2_times_minus2(w.w);
             qf[j][ks] = __builtin_bit_cast(bf16x8, w);
         }
     }
@@ -315,43 +343,61 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
     if (span0 >= span1) return;
     const int ntiles = (int)((span1 - span0 + kFastRows - 1) / kFastRows);
 
-    uint4 stage[PER_THREAD];
-    float stage_n = 0.f;
-    auto fetch = [&](int t) {       // global -> registers
-        const int64_t c0 = span0 + (int64_t)t * kFastRows;
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            const int ch = (int)threadIdx.x + i * 256;
-            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
-            stage[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (ch < CHUNKS && c0 + r < span1)
-                stage[i] = *reinterpret_cast<const uint4*>(a.xb + (c0 + r) * DP + c8 * 8);
-        }
-        if (threadIdx.x < kFastRows) stage_n = c0 + threadIdx.x < span1 ? a.xnorm[c0 + threadIdx.x] : 0.f;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
+    struct Stage {
+        u32x4 x[PER_THREAD];
+        float n;
     };
-    auto commit = [&](int b) {      // registers -> LDS buffer b
+    // A tile is one contiguous block of kFastRows * DP elements and this thread's chunks sit at
+    // fixed offsets inside it.  No branch: a chunk index past the span's end is clamped to the
+    // span's last chunk (rows read twice that way carry ids >= span1 and are dropped by the filter).
+    const uint16_t* xspan = a.xb + span0 * DP;
+    const int last_chunk = (int)(span1 - span0) * (DP / 8) - 1;
+    const int last_row = (int)(span1 - span0) - 1;
+    auto fetch = [&](int t, Stage& st) __attribute__((always_inline)) {       // global -> registers
+#pragma unroll
+        for (int i = 0; i < PER_THREAD; ++i) {
+            const int ch = min((int)threadIdx.x + i * 256, CHUNKS - 1);
+            st.x[i] = *reinterpret_cast<const u32x4*>(xspan + (int64_t)min(t * CHUNKS + ch, last_chunk) * 8);
+        }
+        st.n = 0.f;
+        if (threadIdx.x < kFastRows) st.n = a.xnorm[span0 + min(t * kFastRows + (int)threadIdx.x, last_row)];
+    };
+    auto commit = [&](int b, const Stage& st) __attribute__((always_inline)) {      // registers -> LDS buffer b
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int ch = (int)threadIdx.x + i * 256;
             const int r = ch / (DP / 8), c8 = ch % (DP / 8);
-            if (ch < CHUNKS) *reinterpret_cast<uint4*>(&Xs[b][r * XS + c8 * 8]) = stage[i];
+            if (ch < CHUNKS) *reinterpret_cast<u32x4*>(&Xs[b][r * XS + c8 * 8]) = st.x[i];
         }
-        if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = stage_n;
+        if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = st.n;
     };
 
-    fetch(0);
-    commit(0);
+    // Two tiles of loads are in flight while one is multiplied: tile t sits in LDS buffer t & 1,
+    // tile t+1 waits in the registers of one stage, and the loads of tile t+2 go to the other
+    // stage.  Fetches past the last tile are clamped re-reads that nobody uses.
+    Stage sa, sb;
+    fetch(0, sa);
+    commit(0, sa);
+    fetch(1, sa);
     __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const int cur = t & 1;
-        if (t + 1 < ntiles) fetch(t + 1);
+    auto step = [&](int t, int cur, Stage& far, const Stage& near) __attribute__((always_inline)) {
+        fetch(t + 2, far);
+        // the accumulators start at |x|^2 of their rows (lane l, register r holds row
+        // 8*(r/4) + 4*(l/32) + r%4 of the 32-row block), and the query fragments hold -2q
         floatx16 acc[2][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                for (int j = 0; j < 2; ++j) {
+                    acc[i][j][4 * r4 + 0] = v.x; acc[i][j][4 * r4 + 1] = v.y;
+                    acc[i][j][4 * r4 + 2] = v.z; acc[i][j][4 * r4 + 3] = v.w;
+                }
+            }
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             bf16x8 xa[2];
@@ -365,47 +411,33 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qf[j][ks], acc[i][j], 0, 0, 0);
         }
         const int64_t c0 = span0 + (int64_t)t * kFastRows;
-        // filter: u = |x|^2 - 2 q.x (exact: integers < 2^24); survivors have u < tau - |q|^2.
-        // Branch-free pass mask first; the rare survivors go to a queue in LDS that is flushed
-        // to the per-query global buffers by the whole workgroup.
+        // filter: u = |x|^2 - 2 q.x (exact: integers < 2^24, whatever the order of the sums);
+        // survivors have u < tau - |q|^2.  The smallest of a lane's 16 values is compared first
+        // (8 minima + 1 compare); the rare survivors go to a queue in LDS that is flushed to the
+        // per-query global buffers by the whole workgroup.
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            float xv[16];
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
-            }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                // common case first: the smallest of the 16 values against the threshold
-                // (16 fma + 8 three-way minima + 1 compare), nothing else when no lane passes
-                float um[16];
+                float lo = __builtin_fminf(acc[i][j][0], acc[i][j][1]);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) um[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
-                float lo = __builtin_fminf(um[0], um[1]);
-#pragma unroll
-                for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, um[r]), um[r + 1]);
+                for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, acc[i][j][r]), acc[i][j][r + 1]);
                 if (ballot64(lo < tq[j])) {
                     uint32_t mask = 0;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mask |= (um[r] < tq[j]) ? (1u << r) : 0u;
+                    for (int r = 0; r < 16; ++r) mask |= (acc[i][j][r] < tq[j]) ? (1u << r) : 0u;
                     // rare: walk the set bits; the accumulator is picked by a select chain so
                     // that the loop needs no indexed register access
 #pragma unroll 1
                     while (ballot64(mask != 0u)) {
                         const int rr = mask ? (int)__builtin_ctz(mask) : 16;
                         mask &= mask - 1u;
-                        float av = 0.f, xr = 0.f;
+                        float u = 0.f;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            av = rr == r ? acc[i][j][r] : av;
-                            xr = rr == r ? xv[r] : xr;
-                        }
+                        for (int r = 0; r < 16; ++r) u = rr == r ? acc[i][j][r] : u;
                         const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                         const int64_t c = c0 + m;
                         if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
-                            const float u = __builtin_fmaf(-2.f, av, xr);
                             const uint64_t key =
                                 ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
                             const unsigned slot = atomicAdd(&q_cnt, 1u);
@@ -421,7 +453,7 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
                 }
             }
         }
-        if (t + 1 < ntiles) commit(cur ^ 1);
+        if (t + 1 < ntiles) commit(cur ^ 1, near);
         __syncthreads();
         const unsigned queued = q_cnt;
         if (queued >= (unsigned)kQueue / 2 || (t + 1 == ntiles && queued > 0)) {
@@ -435,8 +467,14 @@ __global__ __launch_bounds__(256, 2) void filter_bf16_kernel(FastArgs a)
             if (threadIdx.x == 0) q_cnt = 0u;
             __syncthreads();
         }
+    };
+    for (int t = 0; t < ntiles; t += 2) {
+        step(t, 0, sb, sa);
+        if (t + 1 >= ntiles) break;
+        step(t + 1, 1, sa, sb);
     }
 }
+
 
 // ---------------------------------------------------------------- bf16 split path (real-valued rows, d <= 128)
 // A real-valued row is centred (global mean removed: distances do not change, norms shrink) and
@@ -909,21 +947,21 @@ template <typename TQ, typename TB>
 ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ* queries, int64_t nq, int k,
                      bool self, hipStream_t stream, int32_t* out_ids, float* out_s)
 {
-    const int kprime = std::min(2 * k, k + 64);
-    const int cap = kprime + 192 <= 256 ? 256 : 512;
+    int kprime = std::min(2 * k, k + 64);
+    int cap = kprime + 192 <= 256 ? 256 : 512;
     const int64_t row_block = 1ll << 21;  // query rows per sweep (bounds the candidate buffers: 4-8 GB)
 
     DevBuf xnorm, qnorm, info, tau, cnt, kept, ovf, buf, redo_cnt, redo_rows;
     TSDG_HIP(xnorm.alloc((size_t)N * 4));
     TSDG_HIP(info.alloc(4 * sizeof(unsigned)));
     TSDG_HIP(hipMemsetAsync(info.p, 0, 4 * sizeof(unsigned), stream));
-    hipLaunchKernelGGL((norms_kernel<TB>), dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, base, N, d,
+    hipLaunchKernelGGL((norms_kernel<TB>), dim3((unsigned)((N + 31) / 32)), dim3(256), 0, stream, base, N, d,
                        xnorm.as<float>(), info.as<unsigned>());
     TSDG_HIP(hipGetLastError());
     float* qn = xnorm.as<float>();
     if (!self) {
         TSDG_HIP(qnorm.alloc((size_t)nq * 4));
-        hipLaunchKernelGGL((norms_kernel<TQ>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, stream, queries, nq, d,
+        hipLaunchKernelGGL((norms_kernel<TQ>), dim3((unsigned)((nq + 31) / 32)), dim3(256), 0, stream, queries, nq, d,
                            qnorm.as<float>(), info.as<unsigned>() + 2);
         TSDG_HIP(hipGetLastError());
         qn = qnorm.as<float>();
@@ -937,6 +975,10 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // exact when every product and partial sum is an integer below 2^24
     const bool exact = integer_data && (double)d * 255.0 * 255.0 < 16777216.0;
     const float err_scale = exact ? 0.f : (float)((d + 8) * 5.9604645e-8 * 1.01);
+    // With an exact filter the threshold needs no margin for rounding, only for ties: a row is
+    // accepted when its k-th distance lies strictly below the kprime-th, so a few extra entries
+    // suffice, and every chunk then passes about kprime survivors per row instead of 2k.
+    if (exact && d <= 128) kprime = std::min(kprime, k + std::max(8, k / 4));
 
     // bf16 fast path: integer rows with d <= 128 are rewritten once as padded bf16
     const bool fast = exact && d <= 128;
@@ -1057,7 +1099,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 fa.self_offset = f.self_offset;
                 fa.cap = cap;
                 const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
-                fa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
+                // long column spans per workgroup once there are enough workgroups to fill the chip
+                fa.tiles_per_block = (int)std::min<int64_t>((nr + 255) / 256 >= 2048 ? 128 : 32, ftiles);
                 dim3 fgrid((unsigned)((nr + 255) / 256), (unsigned)((ftiles + fa.tiles_per_block - 1) / fa.tiles_per_block));
                 switch (ks) {
 #define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_bf16_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
