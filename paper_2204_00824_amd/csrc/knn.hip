@@ -711,11 +711,11 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
 }
 
 // ---------------------------------------------------------------- per-row compaction
-// Sorts the row's buffer (bitonic, in LDS), keeps the kprime smallest, sets tau to the
-// kprime-th approximate distance.  cnt > cap means entries were lost: the row is flagged.
+// Keeps the kprime entries of the row's buffer with the smallest approximate distances (in any
+// order) and sets tau to the kprime-th smallest.  cnt > cap means entries were lost: the row is flagged.
 struct CompactArgs {
     unsigned* cnt;
-    unsigned* kept;    // entries that were already sorted by the previous pass
+    unsigned* kept;    // entries left by the previous pass
     uint64_t* buf;
     float* tau;
     unsigned* overflow;
@@ -723,10 +723,51 @@ struct CompactArgs {
     int cap, kprime;
 };
 
-__global__ __launch_bounds__(64) void compact_kernel(CompactArgs a)
+// One wavefront cuts a row's unsorted candidate buffer (more than kprime entries, R = capacity / 64 per
+// lane, already loaded into e[], unused slots holding the empty key) down to kprime entries with the smallest distances and returns
+// the kprime-th smallest distance D, the row's new threshold.  D is found by bisection on the
+// distance's bit pattern (non-negative floats order like unsigned integers) with wave-wide counts;
+// entries below D all stay and of those equal to D as many as still fit (the dropped ones are not
+// below the new threshold, which is all the filter's invariant asks for).  No sorting, no LDS.
+template <int R>
+__device__ __forceinline__ float keep_smallest(uint64_t* __restrict__ g, const uint64_t (&e)[R], int kprime, int lane)
 {
-    extern __shared__ uint64_t sbuf[];  // [cap]
-    const int64_t row = blockIdx.x;
+    uint32_t dist[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) dist[r] = (uint32_t)(e[r] >> 32);
+    uint32_t lo = 0u, hi = 0x7F800000u;  // count(dist <= hi) >= kprime holds: real entries are finite
+    while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo) / 2u;
+        int c = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) c += popc64(ballot64(dist[r] <= mid));
+        if (c >= kprime) hi = mid;
+        else lo = mid + 1u;
+    }
+    const uint32_t D = lo;
+    int below = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) below += popc64(ballot64(dist[r] < D));
+    const int need = kprime - below;  // >= 1 entries equal to D are kept
+    int base = 0, ties = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool lt = dist[r] < D, eq = dist[r] == D;
+        const uint64_t meq = ballot64(eq);
+        const bool keep = lt || (eq && ties + popc64(meq & lanes_below(lane)) < need);
+        const uint64_t mk = ballot64(keep);
+        if (keep) g[base + popc64(mk & lanes_below(lane))] = e[r];
+        base += popc64(mk);
+        ties += popc64(meq);
+    }
+    return __uint_as_float(D);
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
+{
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // one wavefront per row
+    if (row >= a.nq) return;
     const int lane = lane_id();
     unsigned n = a.cnt[row];
     if (n > (unsigned)a.cap) {
@@ -735,31 +776,18 @@ __global__ __launch_bounds__(64) void compact_kernel(CompactArgs a)
     }
     if (n == a.kept[row]) return;  // nothing new since the last pass
     uint64_t* g = a.buf + row * a.cap;
-    int p2 = 64;
-    while (p2 < (int)n) p2 <<= 1;
-    for (int i = lane; i < p2; i += 64) sbuf[i] = i < (int)n ? g[i] : kKeyEmpty;
-    __syncthreads();
-    for (int size = 2; size <= p2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int t = lane; t < p2 / 2; t += 64) {
-                const int lo = 2 * t - (t & (stride - 1));  // index with bit `stride` clear
-                const int hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint64_t x = sbuf[lo], y = sbuf[hi];
-                if ((x > y) == up) {
-                    sbuf[lo] = y;
-                    sbuf[hi] = x;
-                }
-            }
-            __syncthreads();
-        }
+    if ((int)n <= a.kprime) {      // not yet full: everything stays, no threshold
+        if (lane == 0) a.kept[row] = n;
+        return;
     }
-    const int keep = min((int)n, a.kprime);
-    for (int i = lane; i < keep; i += 64) g[i] = sbuf[i];
+    uint64_t e[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) e[r] = lane + 64 * r < (int)n ? g[lane + 64 * r] : kKeyEmpty;
+    const float D = keep_smallest<R>(g, e, a.kprime, lane);
     if (lane == 0) {
-        a.cnt[row] = (unsigned)keep;
-        a.kept[row] = (unsigned)keep;
-        a.tau[row] = keep == a.kprime ? __uint_as_float((uint32_t)(sbuf[a.kprime - 1] >> 32)) : kInf;
+        a.cnt[row] = (unsigned)a.kprime;
+        a.kept[row] = (unsigned)a.kprime;
+        a.tau[row] = D;
     }
 }
 
@@ -1136,7 +1164,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             else
                 hipLaunchKernelGGL((filter_kernel<false, TQ, TB>), grid, dim3(256), 0, stream, f);
             TSDG_HIP(hipGetLastError());
-            hipLaunchKernelGGL(compact_kernel, dim3((unsigned)nr), dim3(64), (size_t)cap * 8, stream, c);
+            if (cap <= 256) hipLaunchKernelGGL(compact_kernel<4>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
+            else hipLaunchKernelGGL(compact_kernel<8>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
             TSDG_HIP(hipGetLastError());
             cb = ce;
             // next chunk as wide as everything seen so far, up to 2M columns per launch
