@@ -126,12 +126,12 @@ template <typename T, int G, int C> struct RowDist {
     }
 
     // this lane's share of sum (q_j - x_j)^2 over its chunks
-    __device__ __forceinline__ double partial(const chunk_t (&buf)[C]) const
+    template <bool FULL = false> __device__ __forceinline__ double partial(const chunk_t (&buf)[C]) const
     {
         double acc = 0.0;
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            if (has(c)) {
+            if (FULL || has(c)) {
                 float x[PC];
                 unpack(buf[c], x);
 #pragma unroll
@@ -148,14 +148,15 @@ template <typename T, int G, int C> struct RowDist {
     // canonical value; every lane of the group gets it.  uint8 rows with an integer query take
     // the exact integer route sum q^2 + sum x^2 - 2 sum q x on v_dot4_u32_u8 (8 instructions per
     // 16 elements): the integer total converts to the same fp32 as the fp64 sum of squares.
-    __device__ __forceinline__ float distance(const chunk_t (&buf)[C]) const
+    // FULL: the row fills all G*C chunks (d = G*C*PC), so no lane has a chunk to skip.
+    template <bool FULL = false> __device__ __forceinline__ float distance(const chunk_t (&buf)[C]) const
     {
         if constexpr (sizeof(T) == 1) {
             if (q_int) {
                 uint32_t xx = 0u, qx = 0u;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
-                    if (has(c)) {
+                    if (FULL || has(c)) {
                         const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
@@ -169,14 +170,14 @@ template <typename T, int G, int C> struct RowDist {
                 uint32_t part = xx - 2u * qx;
 #pragma unroll
                 for (int c = 0; c < C; ++c)
-                    if (has(c))
+                    if (FULL || has(c))
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
                             part = __builtin_amdgcn_udot4(qbytes[c * 4 + i], qbytes[c * 4 + i], part, false);
                 return (float)group_sum_u32(part);
             }
         }
-        return (float)group_sum(partial(buf));
+        return (float)group_sum(partial<FULL>(buf));
     }
 
     static __device__ __forceinline__ uint32_t group_sum_u32(uint32_t a)

@@ -81,6 +81,8 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
 
     uint32_t hops = 0, evals = 0, dedup = 0;
     ListSync<WAVES> lsync;
+    // byte rows only (the fp32 kernels would pay for the second loop with a wave of occupancy)
+    const bool full_rows = sizeof(T) == 1 && rd.nchunks == G * C;  // wave-uniform
 
     // Scores the hop's candidates (ids in `id`, one per lane of wave 0) and merges them.
     auto process = [&](uint32_t id, bool valid) {
@@ -97,25 +99,46 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
         if (m == 0) return;
         evals += (uint32_t)m;
         // S5: gather + distance.  Batch = U passes of VP rows; waves take batches in turn.
-        for (int b0 = wave * U * VP; b0 < m; b0 += WAVES * U * VP) {
-            chunk_t buf[U][C];
-            uint32_t e[U];
-            bool ok[U];
+        if (full_rows) {
+            // every lane owns all its C chunks: no per-chunk test, and a slot past the last
+            // candidate re-reads the last one (its result is dropped) instead of being predicated
+            for (int b0 = wave * U * VP; b0 < m; b0 += WAVES * U * VP) {
+                chunk_t buf[U][C];
+                uint32_t e[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = b0 + u * VP + rd.v;
-                ok[u] = c < m;
-                e[u] = ok[u] ? cid[c] : 0u;
+                for (int u = 0; u < U; ++u) {
+                    e[u] = cid[min(b0 + u * VP + rd.v, m - 1)];
 #pragma unroll
-                for (int cc = 0; cc < C; ++cc) {
-                    buf[u][cc] = chunk_t{};
-                    if (ok[u] && rd.has(cc)) buf[u][cc] = rd.load(base, e[u], cc);
+                    for (int cc = 0; cc < C; ++cc) buf[u][cc] = rd.load(base, e[u], cc);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float tot = rd.template distance<true>(buf[u]);
+                    const int c = b0 + u * VP + rd.v;
+                    if (c < m && rd.g == 0) ckey[c] = make_key(tot, e[u]);
                 }
             }
+        } else {
+            for (int b0 = wave * U * VP; b0 < m; b0 += WAVES * U * VP) {
+                chunk_t buf[U][C];
+                uint32_t e[U];
+                bool ok[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const float tot = rd.distance(buf[u]);
-                if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
+                for (int u = 0; u < U; ++u) {
+                    const int c = b0 + u * VP + rd.v;
+                    ok[u] = c < m;
+                    e[u] = ok[u] ? cid[c] : 0u;
+#pragma unroll
+                    for (int cc = 0; cc < C; ++cc) {
+                        buf[u][cc] = chunk_t{};
+                        if (ok[u] && rd.has(cc)) buf[u][cc] = rd.load(base, e[u], cc);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const float tot = rd.distance(buf[u]);
+                    if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
+                }
             }
         }
         __syncthreads();
