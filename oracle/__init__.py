@@ -95,7 +95,18 @@ def knn(base, K, threads=0):
     return ids, s
 
 
-def stage1(base, knn_id, knn_s, alpha, threads=0):
+METRICS = {"l2": 0, "cosine": 1}
+
+
+def normalize_rows(x):
+    """Unit rows for the cosine metric (fp64 sum of squares, norm and quotient rounded to fp32)."""
+    x = _c(x, np.float32)
+    out = np.empty_like(x)
+    _check(lib().orc_normalize_rows(_p(x), C.c_int64(x.shape[0]), x.shape[1], _p(out)), "normalize_rows")
+    return out
+
+
+def stage1(base, knn_id, knn_s, alpha, threads=0, metric="l2"):
     base = _c(base)
     knn_id = _c(knn_id, np.int32)
     knn_s = _c(knn_s, np.float32)
@@ -104,8 +115,8 @@ def stage1(base, knn_id, knn_s, alpha, threads=0):
     g1_id = np.empty((N, K), np.int32)
     g1_s = np.empty((N, K), np.float32)
     g1_deg = np.empty((N,), np.int32)
-    rc = lib().orc_stage1(_p(base), _dtype_code(base), C.c_int64(N), d, K, _p(knn_id), _p(knn_s),
-                          C.c_float(alpha), _p(g1_id), _p(g1_s), _p(g1_deg), threads)
+    rc = lib().orc_stage1_m(_p(base), _dtype_code(base), C.c_int64(N), d, K, _p(knn_id), _p(knn_s),
+                            C.c_float(alpha), METRICS[metric], _p(g1_id), _p(g1_s), _p(g1_deg), threads)
     _check(rc, "stage1")
     return g1_id, g1_s, g1_deg
 
@@ -140,9 +151,10 @@ def stage2(base, g2_id, g2_s, g2_deg, lambda0, K, threads=0):
     return adj, lam
 
 
-def build_graph(base, K, alpha=1.2, lambda0=9, rev_cap=None, threads=0, stages=False):
+def build_graph(base, K, alpha=1.2, lambda0=9, rev_cap=None, threads=0, stages=False, metric="l2"):
     """Exact k-NN -> stage 1 -> reverse edges -> stage 2.  Returns (adj, lam),
-    plus a dict of the intermediate arrays when stages=True."""
+    plus a dict of the intermediate arrays when stages=True.  metric="cosine" expects unit rows
+    (normalize_rows) and applies Eq. 2 to m = 1 - cos = s/2; the distances in `stages` stay s."""
     base = _c(base)
     N, d = base.shape
     if rev_cap is None:
@@ -158,15 +170,17 @@ def build_graph(base, K, alpha=1.2, lambda0=9, rev_cap=None, threads=0, stages=F
                   g2_deg=np.empty((N,), np.int32))
         args = [st["knn_id"], st["knn_s"], st["g1_id"], st["g1_deg"], st["g2_id"], st["g2_s"],
                 st["g2_deg"]]
-    rc = lib().orc_build(_p(base), _dtype_code(base), C.c_int64(N), d, K, C.c_float(alpha), lambda0,
-                         rev_cap, _p(adj), _p(lam), *[_p(a) for a in args], threads)
+    rc = lib().orc_build_m(_p(base), _dtype_code(base), C.c_int64(N), d, K, C.c_float(alpha), METRICS[metric],
+                           lambda0, rev_cap, _p(adj), _p(lam), *[_p(a) for a in args], threads)
     _check(rc, "build")
     return (adj, lam, st) if stages else (adj, lam)
 
 
 def search(adj, lam, base, queries, k, L, lambda_visit, n_seeds=32, seed=0, max_hops=0,
            visited_cap=0, reverse_hop=False, qi_offset=0, threads=0, want_stats=False,
-           trace_cap=0):
+           trace_cap=0, metric="l2"):
+    """metric="cosine": base rows and queries are unit vectors; the walk is the same (m = s/2 orders
+    like s) and the distances returned are m = 1 - cos = s/2 (halving is exact in fp32)."""
     adj = _c(adj, np.int32)
     lam = _c(lam, np.uint8)
     base = _c(base)
@@ -185,6 +199,8 @@ def search(adj, lam, base, queries, k, L, lambda_visit, n_seeds=32, seed=0, max_
                           C.c_int64(qi_offset), _p(ids), _p(s), _p(stats), _p(trace), trace_cap,
                           threads)
     _check(rc, "search")
+    if METRICS[metric] == 1:
+        s = s * np.float32(0.5)
     out = [ids, s]
     if want_stats:
         out.append(stats)

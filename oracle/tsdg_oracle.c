@@ -184,14 +184,19 @@ int orc_knn(const void* base, int dtype, int64_t N, int d, int K,
  * distance m; squaring both sides gives alpha^2 on squared distances) and
  * each product one fp32 multiply.  Output g1_* is [N,K], kept edges first in
  * their original order, padded with -1 / +inf; g1_deg[N] = number kept.
+ *
+ * Cosine metric (Sec. 5, Table 1: m = Cos): rows are unit vectors (see
+ * orc_normalize_rows) and m(a,b) = 1 - cos(a,b) = s(a,b)/2.  Eq. 2 is stated
+ * on m itself, alpha*m(..) < m(..), and m is proportional to s, so the factor
+ * on the squared distances is alpha, not alpha^2.  metric: 0 = L2, 1 = cosine.
  * ---------------------------------------------------------------------- */
-int orc_stage1(const void* base, int dtype, int64_t N, int d, int K,
-               const int32_t* knn_id, const float* knn_s, float alpha,
-               int32_t* g1_id, float* g1_s, int32_t* g1_deg, int threads)
+int orc_stage1_m(const void* base, int dtype, int64_t N, int d, int K,
+                 const int32_t* knn_id, const float* knn_s, float alpha, int metric,
+                 int32_t* g1_id, float* g1_s, int32_t* g1_deg, int threads)
 {
-    if (!base || !knn_id || !knn_s || N <= 0 || K <= 0) return 1;
+    if (!base || !knn_id || !knn_s || N <= 0 || K <= 0 || (metric != 0 && metric != 1)) return 1;
     threads = use_threads(threads);
-    const float alpha2 = alpha * alpha;
+    const float alpha2 = metric == 1 ? alpha : alpha * alpha;
 #pragma omp parallel num_threads(threads)
     {
         float* ti = (float*)malloc(sizeof(float) * (size_t)d);
@@ -228,6 +233,31 @@ int orc_stage1(const void* base, int dtype, int64_t N, int d, int K,
         }
         free(ti);
         free(tj);
+    }
+    return 0;
+}
+
+int orc_stage1(const void* base, int dtype, int64_t N, int d, int K,
+               const int32_t* knn_id, const float* knn_s, float alpha,
+               int32_t* g1_id, float* g1_s, int32_t* g1_deg, int threads)
+{
+    return orc_stage1_m(base, dtype, N, d, K, knn_id, knn_s, alpha, 0, g1_id, g1_s, g1_deg, threads);
+}
+
+/* ------------------------------------------------------------------------
+ * Unit rows for the cosine metric.  norm = fl32( sqrt( sum (double)x_j^2 ) )
+ * (the sum in fp64, in index order), out_j = fl32( (double)x_j / (double)norm );
+ * a zero row stays zero.  With unit rows, 1 - cos(a,b) = s(a,b) / 2.
+ * ---------------------------------------------------------------------- */
+int orc_normalize_rows(const float* src, int64_t n, int d, float* dst)
+{
+    if (!src || !dst || n < 0 || d <= 0) return 1;
+    for (int64_t i = 0; i < n; ++i) {
+        double ss = 0.0;
+        for (int j = 0; j < d; ++j) ss += (double)src[i * d + j] * (double)src[i * d + j];
+        const float norm = (float)sqrt(ss);
+        for (int j = 0; j < d; ++j)
+            dst[i * d + j] = norm > 0.0f ? (float)((double)src[i * d + j] / (double)norm) : 0.0f;
     }
     return 0;
 }
@@ -374,10 +404,10 @@ int orc_stage2(const void* base, int dtype, int64_t N, int d, int rev_cap,
 /* Whole build: exact k-NN -> stage 1 -> reverse edges -> stage 2.
  * Optional outputs (may be NULL): knn_id/knn_s [N,K] and g1_id [N,K],
  * g1_deg [N], g2_id/g2_s [N,rev_cap], g2_deg [N] for per-stage parity. */
-int orc_build(const void* base, int dtype, int64_t N, int d, int K, float alpha,
-              int lambda0, int rev_cap, int32_t* adj, uint8_t* lam,
-              int32_t* knn_id_out, float* knn_s_out, int32_t* g1_id_out, int32_t* g1_deg_out,
-              int32_t* g2_id_out, float* g2_s_out, int32_t* g2_deg_out, int threads)
+int orc_build_m(const void* base, int dtype, int64_t N, int d, int K, float alpha, int metric,
+                int lambda0, int rev_cap, int32_t* adj, uint8_t* lam,
+                int32_t* knn_id_out, float* knn_s_out, int32_t* g1_id_out, int32_t* g1_deg_out,
+                int32_t* g2_id_out, float* g2_s_out, int32_t* g2_deg_out, int threads)
 {
     if (!base || !adj || !lam || N <= K || K <= 0 || rev_cap <= 0) return 1;
     size_t nk = (size_t)N * (size_t)K, nr = (size_t)N * (size_t)rev_cap;
@@ -392,7 +422,7 @@ int orc_build(const void* base, int dtype, int64_t N, int d, int K, float alpha,
     int rc = 2;
     if (knn_id && knn_s && g1_id && g1_s && g1_deg && g2_id && g2_s && g2_deg) {
         rc = orc_knn(base, dtype, N, d, K, knn_id, knn_s, threads);
-        if (!rc) rc = orc_stage1(base, dtype, N, d, K, knn_id, knn_s, alpha, g1_id, g1_s, g1_deg, threads);
+        if (!rc) rc = orc_stage1_m(base, dtype, N, d, K, knn_id, knn_s, alpha, metric, g1_id, g1_s, g1_deg, threads);
         if (!rc) rc = orc_reverse(base, dtype, N, d, K, g1_id, g1_deg, rev_cap, g2_id, g2_s, g2_deg, threads);
         if (!rc) rc = orc_stage2(base, dtype, N, d, rev_cap, g2_id, g2_s, g2_deg, lambda0, K, adj, lam, threads);
         if (!rc) {
@@ -408,6 +438,15 @@ int orc_build(const void* base, int dtype, int64_t N, int d, int K, float alpha,
     free(knn_id); free(knn_s); free(g1_id); free(g1_s); free(g1_deg);
     free(g2_id); free(g2_s); free(g2_deg);
     return rc;
+}
+
+int orc_build(const void* base, int dtype, int64_t N, int d, int K, float alpha,
+              int lambda0, int rev_cap, int32_t* adj, uint8_t* lam,
+              int32_t* knn_id_out, float* knn_s_out, int32_t* g1_id_out, int32_t* g1_deg_out,
+              int32_t* g2_id_out, float* g2_s_out, int32_t* g2_deg_out, int threads)
+{
+    return orc_build_m(base, dtype, N, d, K, alpha, 0, lambda0, rev_cap, adj, lam, knn_id_out, knn_s_out,
+                       g1_id_out, g1_deg_out, g2_id_out, g2_s_out, g2_deg_out, threads);
 }
 
 /* ------------------------------------------------------------------------

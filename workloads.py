@@ -139,6 +139,22 @@ def deep_like(N: int = 10_000_000, nq: int = 10_000, d: int = 96,
     return unit(mix.draw(N, 1)), unit(mix.draw(nq, 2))
 
 
+def glove_like(N: int = 1_000_000, nq: int = 10_000, d: int = 100,
+               components: int = 512, seed: int = 100100):
+    """Real-valued fp32 word-vector-like rows for the cosine metric (d = 100): a
+    512-component mixture over a shared 32-dimensional latent space, every row then
+    stretched by a log-normal factor (sigma 0.5), so that lengths vary by an order of
+    magnitude and carry no information about direction.  NOT normalised: the
+    caller of a cosine index normalises.  Returns (base, queries)."""
+    mix = _LatentMixture(d, 32, components, seed, mu=0.0, col_norm=(0.5, 1.5), centre_scale=1.0, noise=0.08)
+
+    def stretch(x, stream):
+        g = _rng(seed, stream)
+        return (x * np.exp(0.5 * g.standard_normal((x.shape[0], 1))).astype(np.float32)).astype(np.float32)
+
+    return stretch(mix.draw(N, 1), 11), stretch(mix.draw(nq, 2), 12)
+
+
 def scale_u8_chunks(N: int = 100_000_000, d: int = 128, components: int = 4096,
                     seed: int = 100, chunk: int = 4_000_000):
     """Yields (offset, uint8[chunk_n, d]) blocks of the 1e8-point set; chunk c
