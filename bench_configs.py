@@ -1,6 +1,6 @@
 #!/usr/bin/env python3
 """Measurements on the other workload shapes (one MI355X): gist-like 1M x 960,
-deep-like 10M x 96, and the 100M x 128 uint8 set.  bench.py stays the headline
+deep-like 10M x 96, glove-like 1M x 100 under the cosine metric, and the 100M x 128 uint8 set.  bench.py stays the headline
 (sift-like 1M x 128); this script prints one JSON line per run with the same
 kind of fields.  Long builds print progress (TSDG_PROGRESS=1 is set here).
 
@@ -46,7 +46,7 @@ def timed_search(fn, reps=3):
     return e0.elapsed_time(e1) / reps
 
 
-def run_single_graph(args, name, base_h, queries_h, ks, Ls):
+def run_single_graph(args, name, base_h, queries_h, ks, Ls, metric="l2"):
     import torch
     import paper_2204_00824_amd as P
     K = 32
@@ -54,15 +54,18 @@ def run_single_graph(args, name, base_h, queries_h, ks, Ls):
     queries = torch.from_numpy(queries_h).cuda()
     N, d = base.shape
     nq = queries.shape[0]
+    if metric == "cosine":      # unit rows, once; ground truth by squared L2 of unit rows = the 1 - cos order
+        P.ann_normalize_rows(base, out=base)
+        P.ann_normalize_rows(queries, out=queries)
     t0 = time.time()
-    graph = P.ann_build_graph_ex(base, K)
+    graph = P.ann_build_graph_ex(base, K, metric=metric)
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"{name}: build {build_s:.1f}s")
     adj, _ = P.ann_graph_export(graph)
     deg = (adj >= 0).sum(dim=1).float().mean().item()
     del adj
-    out = {"workload": name, "N": N, "d": d, "nq": nq, "K": K, "build_seconds": round(build_s, 2),
+    out = {"workload": name, "metric": metric, "N": N, "d": d, "nq": nq, "K": K, "build_seconds": round(build_s, 2),
            "knn_tflops": round(2.0 * N * N * d / build_s / 1e12, 1), "avg_degree": round(deg, 2), "curves": {}}
     for k in ks:
         gt, _ = P.ann_bruteforce(base, queries, k)
@@ -72,8 +75,8 @@ def run_single_graph(args, name, base_h, queries_h, ks, Ls):
             for L in Ls:
                 if L < k:
                     continue
-                ids, s, st = P.ann_search_ex(graph, base, queries, k, L, mode=mode, lambda_visit=lv, want_stats=True)
-                ms = timed_search(lambda: P.ann_search_ex(graph, base, queries, k, L, mode=mode, lambda_visit=lv, out=(ids, s)))
+                ids, s, st = P.ann_search_ex(graph, base, queries, k, L, mode=mode, lambda_visit=lv, want_stats=True, metric=metric)
+                ms = timed_search(lambda: P.ann_search_ex(graph, base, queries, k, L, mode=mode, lambda_visit=lv, out=(ids, s), metric=metric))
                 ev = st.dist_evals.double().mean().item()
                 hp = st.hops.double().mean().item()
                 alg = (ev * d * base.element_size() + hp * K * 4) * nq
@@ -156,7 +159,7 @@ def run_sharded_u8(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m"])
+    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "glove1m"])
     ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
     args = ap.parse_args()
     import workloads
@@ -166,6 +169,9 @@ def main():
     elif args.workload == "deep10m":
         base, q = workloads.deep_like(N=args.n or 10_000_000)
         run_single_graph(args, "deep-like", base, q, (10, 100), (64, 128, 256, 512))
+    elif args.workload == "glove1m":
+        base, q = workloads.glove_like(N=args.n or 1_000_000)
+        run_single_graph(args, "glove-like, cosine", base, q, (10,), (32, 64, 128, 256, 512), metric="cosine")
     else:
         run_sharded_u8(args)
 

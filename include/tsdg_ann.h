@@ -53,6 +53,15 @@ typedef enum {
 
 typedef enum { ANN_F32 = 0, ANN_U8 = 1 } ann_dtype; /* element type of base rows */
 
+/* Dissimilarity m(.,.) of Sec. 2 / Table 1.
+ *   ANN_L2:     squared Euclidean distance s (what every call returns); Eq. 2's alpha acts on
+ *               the distance, i.e. alpha^2 on s.
+ *   ANN_COSINE: m = 1 - cos.  Base rows and queries must be UNIT vectors in fp32 (the caller
+ *               normalises once, e.g. with ann_normalize_rows; this is not checked).  Then
+ *               m = s/2: the k-NN graph and every walk are those of s, Eq. 2's alpha acts on m
+ *               (alpha on s), and the distances returned are m = s/2. */
+typedef enum { ANN_L2 = 0, ANN_COSINE = 1 } ann_metric;
+
 /* Build parameters.  Defaults (ann_build_params_default): fp32 rows,
  * alpha = 1.2 (Sec. 3.2: "usually greater than 1.1"), lambda0 = 9 (so that the
  * paper's "lambda < 10" prefix of Sec. 5.4 means every stored edge),
@@ -64,6 +73,7 @@ typedef struct {
     int lambda0;
     int rev_cap;
     void* stream;
+    ann_metric metric; /* default ANN_L2 */
 } ann_build_params;
 
 /* Search parameters.  Defaults (ann_search_params_default): fp32 rows, mode 0
@@ -92,6 +102,7 @@ typedef struct {
     int waves_per_query;
     int64_t qi_offset;
     void* stream;
+    ann_metric metric; /* default ANN_L2; must be the metric the graph was built with */
 } ann_search_params;
 
 /* Optional per-query counters written by ann_search_ex ([nq] on the device). */
@@ -178,6 +189,12 @@ ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, i
                             void* stream, ann_graph** out);
 ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d);
 void ann_graph_free(ann_graph* graph);
+
+/* Unit rows for ANN_COSINE (Table 1, m = Cos): dst[i,:] = src[i,:] / |src[i,:]| for n rows of d
+ * fp32 elements (d a multiple of 4, at most 2048; both device, 16-byte aligned, may be the same
+ * buffer).  The norm is fl32(sqrt(sum of squares in fp64)), each quotient is formed in fp64 and
+ * rounded once; a zero row stays zero.  Asynchronous on `stream`. */
+ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, void* stream);
 
 /* Measurement probe, not a step of the method: gathers n rows of row_bytes bytes (a multiple of 16,
  * at most 8192) from base[N rows] (device, 16-byte aligned) at ids[n] (device; an id >= N reads row

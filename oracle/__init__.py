@@ -210,8 +210,9 @@ def search(adj, lam, base, queries, k, L, lambda_visit, n_seeds=32, seed=0, max_
 
 
 def search_multi(adj, lam, base, queries, k, t0, max_hops=16, lambda_visit=10, seed=0, qi_offset=0, threads=0,
-                 want_stats=False):
-    """Small-batch multi-search (Alg. 1): t0 greedy searches per query, merged."""
+                 want_stats=False, metric="l2"):
+    """Small-batch multi-search (Alg. 1): t0 greedy searches per query, merged.  metric="cosine":
+    unit rows, distances returned as m = s/2."""
     adj = _c(adj, np.int32)
     lam = _c(lam, np.uint8)
     base = _c(base)
@@ -226,12 +227,18 @@ def search_multi(adj, lam, base, queries, k, t0, max_hops=16, lambda_visit=10, s
                                 C.c_int64(nq), k, t0, max_hops, lambda_visit, C.c_uint64(seed),
                                 C.c_int64(qi_offset), _p(ids), _p(s), _p(stats), threads)
     _check(rc, "search_multi")
+    if METRICS[metric] == 1:
+        s = s * np.float32(0.5)
     return (ids, s, stats) if want_stats else (ids, s)
 
 
 def search_alg2(adj, lam, base, queries, k, delta, m_c=16, m_v=16, max_hops=0, lambda_visit=5, seed=0, qi_offset=0,
-                threads=0, want_stats=False):
-    """Large-batch search with the paper's own R / C / V structures and the Delta stop (Alg. 2)."""
+                threads=0, want_stats=False, metric="l2"):
+    """Large-batch search with the paper's own R / C / V structures and the Delta stop (Alg. 2).
+    metric="cosine": unit rows; delta is given in units of m = 1 - cos, the walk compares s = 2m,
+    so it runs with 2*delta, and the distances returned are m = s/2."""
+    if METRICS[metric] == 1:
+        delta = float(np.float32(2.0) * np.float32(delta))
     adj = _c(adj, np.int32)
     lam = _c(lam, np.uint8)
     base = _c(base)
@@ -246,6 +253,8 @@ def search_alg2(adj, lam, base, queries, k, delta, m_c=16, m_v=16, max_hops=0, l
                                C.c_int64(nq), k, m_c, m_v, C.c_float(delta), max_hops, lambda_visit,
                                C.c_uint64(seed), C.c_int64(qi_offset), _p(ids), _p(s), _p(stats), threads)
     _check(rc, "search_alg2")
+    if METRICS[metric] == 1:
+        s = s * np.float32(0.5)
     return (ids, s, stats) if want_stats else (ids, s)
 
 

@@ -24,13 +24,18 @@ class AnnError(RuntimeError):
 
 class _BuildParams(C.Structure):
     _fields_ = [("dtype", C.c_int), ("alpha", C.c_float), ("lambda0", C.c_int), ("rev_cap", C.c_int),
-                ("stream", C.c_void_p)]
+                ("stream", C.c_void_p), ("metric", C.c_int)]
 
 
 class _SearchParams(C.Structure):
     _fields_ = [("dtype", C.c_int), ("mode", C.c_int), ("lambda_visit", C.c_int), ("n_seeds", C.c_int),
                 ("seed", C.c_uint64), ("max_hops", C.c_int), ("visited_slots", C.c_int),
-                ("waves_per_query", C.c_int), ("qi_offset", C.c_int64), ("stream", C.c_void_p)]
+                ("waves_per_query", C.c_int), ("qi_offset", C.c_int64), ("stream", C.c_void_p),
+                ("metric", C.c_int)]
+
+
+ANN_L2, ANN_COSINE = 0, 1
+_METRICS = {"l2": ANN_L2, "cosine": ANN_COSINE, ANN_L2: ANN_L2, ANN_COSINE: ANN_COSINE}
 
 
 def library_path() -> str:
@@ -63,9 +68,10 @@ def load_library():
     L.ann_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
     L.ann_graph_free.argtypes = [vp]
     L.ann_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
+    L.ann_normalize_rows.argtypes = [vp, i64, i32, vp, vp]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_normalize_rows"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -131,12 +137,13 @@ def ann_build_graph(base: torch.Tensor, K: int) -> Graph:
 
 
 def ann_build_graph_ex(base: torch.Tensor, K: int, alpha: float = 1.2, lambda0: int = 9, rev_cap: int = 0,
-                       stream=None) -> Graph:
+                       stream=None, metric="l2") -> Graph:
     L = load_library()
     p, dt = _base_ptr(base)
     prm = _BuildParams()
     L.ann_build_params_default(C.byref(prm))
     prm.dtype, prm.alpha, prm.lambda0, prm.rev_cap, prm.stream = dt, alpha, lambda0, rev_cap, _stream_ptr(stream)
+    prm.metric = _METRICS[metric]
     out = C.c_void_p()
     _check(L.ann_build_graph_ex(p, base.shape[0], base.shape[1], K, C.byref(prm), C.byref(out)))
     return Graph(out.value)
@@ -179,7 +186,7 @@ def ann_search(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, 
 def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, L: int, *, mode: int = 0,
                   lambda_visit: int = 0, n_seeds: int = 32, seed: int = 0, max_hops: int = 0,
                   visited_slots: int = 0, waves_per_query: int = 0, qi_offset: int = 0, stream=None,
-                  want_stats: bool = False, out=None):
+                  want_stats: bool = False, out=None, metric="l2"):
     """Returns (ids, dists) or (ids, dists, QueryStats).  `out=(ids, dists)` reuses output tensors."""
     lib = load_library()
     p, dt = _base_ptr(base)
@@ -196,7 +203,7 @@ def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: in
     lib.ann_search_params_default(C.byref(prm))
     prm.dtype, prm.mode, prm.lambda_visit, prm.n_seeds, prm.seed = dt, mode, lambda_visit, n_seeds, seed
     prm.max_hops, prm.visited_slots, prm.waves_per_query = max_hops, visited_slots, waves_per_query
-    prm.qi_offset, prm.stream = qi_offset, _stream_ptr(stream)
+    prm.qi_offset, prm.stream, prm.metric = qi_offset, _stream_ptr(stream), _METRICS[metric]
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
     _check(lib.ann_search_ex(graph.ptr, p, q, nq, k, L, C.byref(prm), ids.data_ptr(), s.data_ptr(),
                              st.data_ptr() if st is not None else None))
@@ -207,7 +214,7 @@ def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: in
 
 def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, t0: int, *,
                      lambda_visit: int = 0, seed: int = 0, max_hops: int = 0, qi_offset: int = 0, stream=None,
-                     want_stats: bool = False, out=None):
+                     want_stats: bool = False, out=None, metric="l2"):
     """Small-batch multi-search (Alg. 1).  Returns (ids, dists) or (ids, dists, QueryStats)."""
     lib = load_library()
     p, dt = _base_ptr(base)
@@ -223,7 +230,7 @@ def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k:
     prm = _SearchParams()
     lib.ann_search_params_default(C.byref(prm))
     prm.dtype, prm.lambda_visit, prm.seed, prm.max_hops = dt, lambda_visit, seed, max_hops
-    prm.qi_offset, prm.stream = qi_offset, _stream_ptr(stream)
+    prm.qi_offset, prm.stream, prm.metric = qi_offset, _stream_ptr(stream), _METRICS[metric]
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
     _check(lib.ann_search_multi(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(),
                                 st.data_ptr() if st is not None else None))
@@ -234,7 +241,7 @@ def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k:
 
 def ann_search_alg2(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, delta: float, *, m_c: int = 16,
                     m_v: int = 16, lambda_visit: int = 0, seed: int = 0, max_hops: int = 0, qi_offset: int = 0,
-                    stream=None, want_stats: bool = False, out=None):
+                    stream=None, want_stats: bool = False, out=None, metric="l2"):
     """Search with the paper's own R / C / V structures (Alg. 2)."""
     lib = load_library()
     p, dt = _base_ptr(base)
@@ -250,7 +257,7 @@ def ann_search_alg2(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: 
     prm = _SearchParams()
     lib.ann_search_params_default(C.byref(prm))
     prm.dtype, prm.lambda_visit, prm.seed, prm.max_hops = dt, lambda_visit, seed, max_hops
-    prm.qi_offset, prm.stream = qi_offset, _stream_ptr(stream)
+    prm.qi_offset, prm.stream, prm.metric = qi_offset, _stream_ptr(stream), _METRICS[metric]
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
     _check(lib.ann_search_alg2(graph.ptr, p, q, nq, k, C.c_float(delta), m_c, m_v, C.byref(prm), ids.data_ptr(),
                                s.data_ptr(), st.data_ptr() if st is not None else None))
@@ -281,6 +288,16 @@ def ann_graph_info(graph: Graph):
     N, K, d = C.c_int64(), C.c_int(), C.c_int()
     _check(load_library().ann_graph_info(graph.ptr, C.byref(N), C.byref(K), C.byref(d)))
     return N.value, K.value, d.value
+
+
+def ann_normalize_rows(x: torch.Tensor, out: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """Unit rows for the cosine metric; `out` may be `x` itself."""
+    src = _dev(x, torch.float32, "x")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(load_library().ann_normalize_rows(src, x.shape[0], x.shape[1], _dev(out, torch.float32, "out"),
+                                             _stream_ptr(stream)))
+    return out
 
 
 def ann_probe_gather(base: torch.Tensor, ids: torch.Tensor, out: torch.Tensor = None, stream=None) -> torch.Tensor:

@@ -119,6 +119,64 @@ static ann_status check_rows(const void* base, int64_t N, int d, ann_dtype dtype
     return ANN_OK;
 }
 
+static ann_status check_metric(ann_metric metric, ann_dtype dtype, const char* what)
+{
+    if (metric != ANN_L2 && metric != ANN_COSINE) { set_error("%s: unknown metric %d", what, (int)metric); return ANN_EINVAL; }
+    if (metric == ANN_COSINE && dtype != ANN_F32) {
+        set_error("%s: the cosine metric needs unit rows, hence fp32 storage", what);
+        return ANN_EUNSUPPORTED;
+    }
+    return ANN_OK;
+}
+
+// Distances of a cosine search are reported as m = 1 - cos = s/2 (exact halving; +inf stays +inf).
+__global__ __launch_bounds__(256) void halve_kernel(float* __restrict__ v, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) v[i] *= 0.5f;
+}
+
+static ann_status report_metric(ann_metric metric, float* out_dists, int64_t n, hipStream_t stream)
+{
+    if (metric != ANN_COSINE || n == 0) return ANN_OK;
+    hipLaunchKernelGGL(halve_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, out_dists, n);
+    TSDG_HIP(hipGetLastError());
+    return ANN_OK;
+}
+
+// One group of 8 lanes per row: sum of squares in fp64, norm rounded to fp32, quotients formed in
+// fp64 and rounded once.
+__global__ __launch_bounds__(256) void normalize_kernel(const float* __restrict__ src, int64_t n, int d,
+                                                        float* __restrict__ dst)
+{
+    const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int g = (int)(threadIdx.x & 7);
+    double acc = 0.0;
+    if (row < n)
+        for (int j = 4 * g; j < d; j += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(src + row * d + j);
+            acc += (double)v.x * (double)v.x;
+            acc += (double)v.y * (double)v.y;
+            acc += (double)v.z * (double)v.z;
+            acc += (double)v.w * (double)v.w;
+        }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    const float norm = (float)sqrt(acc);
+    if (row < n)
+        for (int j = 4 * g; j < d; j += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(src + row * d + j);
+            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (norm > 0.f) {
+                o.x = (float)((double)v.x / (double)norm);
+                o.y = (float)((double)v.y / (double)norm);
+                o.z = (float)((double)v.z / (double)norm);
+                o.w = (float)((double)v.w / (double)norm);
+            }
+            *reinterpret_cast<float4*>(dst + row * d + j) = o;
+        }
+}
+
 // Batch size from which one wavefront per query fills the GPU (256 CUs x 32 wave slots).
 constexpr int kLargeBatchThreshold = 2048;
 
@@ -145,6 +203,7 @@ void ann_build_params_default(ann_build_params* p)
     p->lambda0 = 9;
     p->rev_cap = 0;
     p->stream = nullptr;
+    p->metric = ANN_L2;
 }
 
 void ann_search_params_default(ann_search_params* p)
@@ -160,6 +219,7 @@ void ann_search_params_default(ann_search_params* p)
     p->waves_per_query = 0;
     p->qi_offset = 0;
     p->stream = nullptr;
+    p->metric = ANN_L2;
 }
 
 static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
@@ -281,6 +341,10 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
         return ANN_EINVAL;
     }
     if (!(p.alpha >= 1.0f) || p.alpha > 16.0f) { set_error("ann_build_graph: alpha must be in [1,16]"); return ANN_EINVAL; }
+    rc = check_metric(p.metric, p.dtype, "ann_build_graph");
+    if (rc != ANN_OK) return rc;
+    // Eq. 2 compares alpha*m with m.  m = L2 distance: alpha^2 on the squared distances; m = 1 - cos = s/2: alpha.
+    const float alpha_on_s = p.metric == ANN_COSINE ? p.alpha : p.alpha * p.alpha;
     if (p.lambda0 < 0 || p.lambda0 > kMaxLambda) { set_error("ann_build_graph: lambda0 must be in 0..30"); return ANN_EINVAL; }
     int rev_cap = p.rev_cap == 0 ? 2 * K : p.rev_cap;
     if (rev_cap < K || rev_cap > 2 * kMaxK) { set_error("ann_build_graph: rev_cap must be in K..128"); return ANN_EINVAL; }
@@ -299,7 +363,7 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
     rc = knn_exact(base, N, d, p.dtype, nullptr, N, K, true, stream, knn_id, knn_s);
     if (rc == ANN_OK) rc = new_graph(N, K, d, &g);
     if (rc == ANN_OK)
-        rc = diversify(base, N, d, p.dtype, K, knn_id, knn_s, p.alpha, p.lambda0, rev_cap, stream, g->packed,
+        rc = diversify(base, N, d, p.dtype, K, knn_id, knn_s, alpha_on_s, p.lambda0, rev_cap, stream, g->packed,
                        &g->max_lambda);
     (void)hipFree(knn_id);
     (void)hipFree(knn_s);
@@ -314,6 +378,19 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
 ann_status ann_build_graph(const void* base, int64_t N, int d, int K, ann_graph** out)
 {
     return ann_build_graph_ex(base, N, d, K, nullptr, out);
+}
+
+ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, void* stream)
+{
+    g_err[0] = 0;
+    if (n == 0) return ANN_OK;
+    ann_status rc = check_rows(src, n, d, ANN_F32, "ann_normalize_rows");
+    if (rc != ANN_OK) return rc;
+    if (!dst || !aligned16(dst)) { set_error("ann_normalize_rows: dst must be a 16-byte aligned device pointer"); return ANN_EINVAL; }
+    hipLaunchKernelGGL(normalize_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       src, n, d, dst);
+    TSDG_HIP(hipGetLastError());
+    return ANN_OK;
 }
 
 ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int L,
@@ -336,6 +413,8 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     if (nq == 0) return ANN_OK;
     if (!queries || !out_ids || !out_dists) { set_error("ann_search: null pointer"); return ANN_EINVAL; }
     ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search");
+    if (rc != ANN_OK) return rc;
+    rc = check_metric(p.metric, p.dtype, "ann_search");
     if (rc != ANN_OK) return rc;
     if (!aligned16(queries)) { set_error("ann_search: query rows must be 16-byte aligned"); return ANN_EINVAL; }
 
@@ -397,7 +476,9 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
         return ANN_EINVAL;
     }
     s.visited_slots = slots;
-    return launch_search(s);
+    rc = launch_search(s);
+    if (rc != ANN_OK) return rc;
+    return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
 }
 
 ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k, int t0,
@@ -417,6 +498,8 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
     if (nq == 0) return ANN_OK;
     if (!queries || !out_ids || !out_dists) { set_error("ann_search_multi: null pointer"); return ANN_EINVAL; }
     ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_multi");
+    if (rc != ANN_OK) return rc;
+    rc = check_metric(p.metric, p.dtype, "ann_search_multi");
     if (rc != ANN_OK) return rc;
     if (!aligned16(queries)) { set_error("ann_search_multi: query rows must be 16-byte aligned"); return ANN_EINVAL; }
     if ((int64_t)nq * t0 > 65535ll * 1024) { set_error("ann_search_multi: nq * t0 too large"); return ANN_EUNSUPPORTED; }
@@ -454,7 +537,9 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
     s.out_dists = out_dists;
     s.stats = stats;
     s.stream = static_cast<hipStream_t>(p.stream);
-    return launch_search_multi(s);
+    rc = launch_search_multi(s);
+    if (rc != ANN_OK) return rc;
+    return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
 }
 
 ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void* queries, int nq, int k,
@@ -476,6 +561,8 @@ ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void*
     if (!queries || !out_ids || !out_dists) { set_error("ann_search_alg2: null pointer"); return ANN_EINVAL; }
     ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_alg2");
     if (rc != ANN_OK) return rc;
+    rc = check_metric(p.metric, p.dtype, "ann_search_alg2");
+    if (rc != ANN_OK) return rc;
     if (!aligned16(queries)) { set_error("ann_search_alg2: query rows must be 16-byte aligned"); return ANN_EINVAL; }
     Alg2Launch s;
     s.packed = g->packed;
@@ -493,14 +580,16 @@ ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void*
     if (lv > 31) lv = 32;
     s.lambda_visit = lv;
     s.max_hops = p.max_hops;
-    s.delta = delta;
+    s.delta = p.metric == ANN_COSINE ? 2.0f * delta : delta;  // delta is in units of m; the walk compares s = 2m
     s.seed = p.seed;
     s.qi_offset = p.qi_offset;
     s.out_ids = out_ids;
     s.out_dists = out_dists;
     s.stats = stats;
     s.stream = static_cast<hipStream_t>(p.stream);
-    return launch_search_alg2(s);
+    rc = launch_search_alg2(s);
+    if (rc != ANN_OK) return rc;
+    return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
 }
 
 ann_status ann_search(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int L,

@@ -113,7 +113,7 @@ ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const 
                      float* out_s);
 
 ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
-                     const float* knn_s, float alpha, int lambda0, int rev_cap, hipStream_t stream,
+                     const float* knn_s, float alpha_on_s, int lambda0, int rev_cap, hipStream_t stream,
                      uint32_t* packed, int* max_lambda);
 
 ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, hipStream_t stream,

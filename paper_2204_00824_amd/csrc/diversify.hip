@@ -360,7 +360,7 @@ struct Stage2Launch {
 }  // namespace
 
 ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
-                     const float* knn_s, float alpha, int lambda0, int rev_cap, hipStream_t stream, uint32_t* packed,
+                     const float* knn_s, float alpha_on_s, int lambda0, int rev_cap, hipStream_t stream, uint32_t* packed,
                      int* max_lambda)
 {
     DevBuf g1_id, g1_s, g1_deg, indeg, cursor, start, bsums, rev_src, rev_s, g2_id, g2_s, g2_deg, mlam;
@@ -390,7 +390,7 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s1.a.N = N;
     s1.a.d = d;
     s1.a.K = K;
-    s1.a.alpha2 = alpha * alpha;
+    s1.a.alpha2 = alpha_on_s;
     s1.stream = stream;
     if (!dispatch_row_shape(dtype, d, s1)) {
         set_error("unsupported row shape d=%d", d);

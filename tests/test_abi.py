@@ -37,10 +37,10 @@ def test_defaults_and_host_side_validation(lib):
     import paper_2204_00824_amd.api as api
     bp = api._BuildParams()
     lib.ann_build_params_default(C.byref(bp))
-    assert (bp.dtype, bp.lambda0, bp.rev_cap) == (0, 9, 0) and abs(bp.alpha - 1.2) < 1e-6
+    assert (bp.dtype, bp.lambda0, bp.rev_cap, bp.metric) == (0, 9, 0, 0) and abs(bp.alpha - 1.2) < 1e-6
     sp = api._SearchParams()
     lib.ann_search_params_default(C.byref(sp))
-    assert (sp.mode, sp.lambda_visit, sp.n_seeds, sp.seed, sp.max_hops) == (0, 0, 32, 0, 0)
+    assert (sp.mode, sp.lambda_visit, sp.n_seeds, sp.seed, sp.max_hops, sp.metric) == (0, 0, 32, 0, 0, 0)
     # argument errors are caught before any device work
     assert lib.ann_graph_info(None, None, None, None) == 1
     assert b"null graph" in lib.ann_last_error()
