@@ -20,6 +20,9 @@ namespace tsdg {
 constexpr float kInfD = __builtin_inff();
 
 // P[i*stride + j] = s(x_ids[i], x_ids[j]) for i < j < m (canonical distance), one wavefront.
+// Four rows i at a time sit in registers as "queries", so that every row j fetched from the
+// caches serves four distances (a row would otherwise be fetched once per pair: m^2/2 fetches
+// of d elements per node, which is what bounds these kernels).
 template <typename RD, typename T>
 __device__ __forceinline__ void pairwise(RD& rd, const T* __restrict__ base, const int32_t* ids, int m, float* P,
                                          int stride)
@@ -27,28 +30,27 @@ __device__ __forceinline__ void pairwise(RD& rd, const T* __restrict__ base, con
     using chunk_t = typename RD::chunk_t;
     constexpr int VP = RD::VP;
     constexpr int C = RD::NC;
-    constexpr int U = (C >= 3) ? 2 : 4;
-    for (int i = 0; i + 1 < m; ++i) {
-        rd.load_query_row(base, (uint32_t)ids[i]);
-        for (int p0 = i + 1; p0 < m; p0 += U * VP) {
-            chunk_t buf[U][C];
-            bool ok[U];
+    constexpr int QB = 4;
+    RD q[QB];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int j = p0 + u * VP + rd.v;
-                ok[u] = j < m;
-                const uint32_t e = ok[u] ? (uint32_t)ids[j] : 0u;
+    for (int b = 0; b < QB; ++b) q[b] = rd;  // lane geometry
+    for (int i0 = 0; i0 + 1 < m; i0 += QB) {
 #pragma unroll
-                for (int cc = 0; cc < C; ++cc) {
-                    buf[u][cc] = chunk_t{};
-                    if (ok[u] && rd.has(cc)) buf[u][cc] = rd.load(base, e, cc);
-                }
+        for (int b = 0; b < QB; ++b) q[b].load_query_row(base, (uint32_t)ids[min(i0 + b, m - 1)]);
+        for (int p0 = i0 + 1; p0 < m; p0 += VP) {
+            const int j = p0 + rd.v;
+            const bool ok = j < m;
+            const uint32_t e = (uint32_t)ids[ok ? j : m - 1];
+            chunk_t buf[C];
+#pragma unroll
+            for (int cc = 0; cc < C; ++cc) {
+                buf[cc] = chunk_t{};
+                if (rd.has(cc)) buf[cc] = rd.load(base, e, cc);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int j = p0 + u * VP + rd.v;
-                const float tot = rd.distance(buf[u]);
-                if (ok[u] && rd.g == 0) P[i * stride + j] = tot;
+            for (int b = 0; b < QB; ++b) {
+                const float tot = q[b].distance(buf);
+                if (ok && rd.g == 0 && i0 + b < j) P[(i0 + b) * stride + j] = tot;
             }
         }
     }
