@@ -258,6 +258,22 @@ def search_alg2(adj, lam, base, queries, k, delta, m_c=16, m_v=16, max_hops=0, l
     return (ids, s, stats) if want_stats else (ids, s)
 
 
+def knn_descent(base, K, S=8, max_iters=10, delta=0.001, seed=0, init_ids=None, threads=0):
+    """Approximate k-NN lists by neighbourhood propagation (pull form, deterministic).
+    Returns (ids [N,K], s [N,K], iterations done, entries changed per iteration)."""
+    base = _c(base)
+    N, d = base.shape
+    ids = np.empty((N, K), np.int32)
+    s = np.empty((N, K), np.float32)
+    done = C.c_int32(0)
+    changed = np.zeros((max(max_iters, 1),), np.int64)
+    init = _c(init_ids, np.int32) if init_ids is not None else None
+    rc = lib().orc_knn_descent(_p(base), _dtype_code(base), C.c_int64(N), d, K, S, max_iters, C.c_float(delta),
+                               C.c_uint64(seed), _p(init), _p(ids), _p(s), C.byref(done), _p(changed), threads)
+    _check(rc, "knn_descent")
+    return ids, s, done.value, changed[:done.value]
+
+
 def recall(found, truth) -> float:
     found = _c(found, np.int32)
     truth = _c(truth, np.int32)

@@ -911,6 +911,219 @@ int orc_search_alg2(const int32_t* adj, const uint8_t* lam, int64_t N, int K, co
 }
 
 /* Recall@k (Eq. 3): found[nq,k] against truth[nq,k]; -1 entries never match. */
+/* ------------------------------------------------------------------------
+ * Approximate k-NN graph by neighbourhood propagation.
+ *
+ * Sec. 3 (opening) starts from an approximate k-NN graph and names no builder.
+ * This one follows the published NN-descent idea -- a neighbour of a neighbour
+ * is likely a neighbour; only edges that are new since they were last looked
+ * at need looking at again; both directions of an edge count -- in a form in
+ * which every node PULLS its candidates from the lists as they stood before
+ * the iteration, so that the result does not depend on any order of execution.
+ *
+ * State: list B[v] of K entries (s, id, new-flag), sorted by (s,id), ids
+ * distinct and != v.  S (a power of two, 2..16) is the sample size.
+ *
+ * Start: draw c_j = seed_id(seed, v, j), j = 0..2K-1 (the generator of the
+ * search's seeds), drop v itself and repeats, keep the first K in draw order;
+ * score, sort, flag all as new.  (Or the caller's lists, all flagged new.)
+ *
+ * One iteration, everything read from the lists B of the previous iteration:
+ *   newF[v] = the first S entries of B[v], in list order, that are flagged new;
+ *   oldF[v] = the first S that are not.
+ *   Reverse samples: tables Rnew[w][0..S), Rold[w][0..S), empty at first.  For
+ *   every u and every w in newF[u]:  slot = (uint32(u) * 2654435761) >> (32 - log2 S);
+ *   Rnew[w][slot] keeps the smallest key (s(u,w), u) offered to it.  Rold
+ *   likewise from oldF.  (A fixed-size sample of the reverse edges that does
+ *   not depend on the order in which they are offered.)
+ *   Node a: L = B[a] with the entries of newF[a] now flagged old (they have
+ *   been sampled).  Sources, in this order: newF[a] (edge new), oldF[a] (edge
+ *   old), the ids in Rnew[a] by slot (edge new), the ids in Rold[a] (edge old).
+ *   From source v the candidates are newF[v], the ids in Rnew[v], and, when the
+ *   edge a-v is new, also oldF[v] and the ids in Rold[v]  (a pair is looked at
+ *   when at least one of its two edges to the common neighbour is new).  Every
+ *   candidate b != a is scored with the canonical distance and put into L
+ *   (bounded K, order (s,id), an id already in L is left as it is), flagged new.
+ *   B'[a] = L;  changed += entries of B'[a] that were not in B[a].
+ * Stop after max_iters iterations or when changed <= delta * N * K.
+ *
+ * The final list is the K smallest of B[a] united with the scored candidates,
+ * whatever the order, so a parallel implementation reproduces it exactly.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    float s;
+    int32_t id;
+    int32_t is_new;
+} dnode_t;
+
+static int dnode_less(float s, int32_t id, const dnode_t* b)
+{
+    if (s != b->s) return s < b->s;
+    return id < b->id;
+}
+
+/* insert (s,id) flagged new into the sorted list l[0..*m) of capacity K; returns 1 if it went in */
+static int dlist_insert(dnode_t* l, int* m, int K, float s, int32_t id)
+{
+    for (int t = 0; t < *m; ++t)
+        if (l[t].id == id) return 0;
+    if (*m == K && !dnode_less(s, id, &l[K - 1])) return 0;
+    int pos = *m < K ? *m : K - 1;
+    while (pos > 0 && dnode_less(s, id, &l[pos - 1])) {
+        l[pos] = l[pos - 1];
+        --pos;
+    }
+    l[pos].s = s;
+    l[pos].id = id;
+    l[pos].is_new = 1;
+    if (*m < K) ++*m;
+    return 1;
+}
+
+int orc_knn_descent(const void* base, int dtype, int64_t N, int d, int K, int S, int max_iters, float delta,
+                    uint64_t seed, const int32_t* init_ids, int32_t* knn_id, float* knn_s,
+                    int32_t* iters_done, int64_t* changed_per_iter, int threads)
+{
+    if (!base || !knn_id || !knn_s || N <= K || K <= 0 || d <= 0 || max_iters < 0) return 1;
+    if (S < 2 || S > 16 || (S & (S - 1)) != 0) return 1;
+    threads = use_threads(threads);
+    int log2s = 0;
+    while ((1 << log2s) < S) ++log2s;
+    const size_t nk = (size_t)N * (size_t)K, ns = (size_t)N * (size_t)S;
+    dnode_t* B = (dnode_t*)malloc(sizeof(dnode_t) * nk);
+    dnode_t* B2 = (dnode_t*)malloc(sizeof(dnode_t) * nk);
+    int32_t* cnt = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t* cnt2 = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    pair_t* Rnew = (pair_t*)malloc(sizeof(pair_t) * ns);
+    pair_t* Rold = (pair_t*)malloc(sizeof(pair_t) * ns);
+    if (!B || !B2 || !cnt || !cnt2 || !Rnew || !Rold) {
+        free(B); free(B2); free(cnt); free(cnt2); free(Rnew); free(Rold);
+        return 2;
+    }
+    /* ---- start lists */
+#pragma omp parallel num_threads(threads)
+    {
+        float* ta = (float*)malloc(sizeof(float) * (size_t)d);
+        float* tb = (float*)malloc(sizeof(float) * (size_t)d);
+#pragma omp for schedule(dynamic, 256)
+        for (int64_t v = 0; v < N; ++v) {
+            dnode_t* l = B + v * K;
+            int m = 0;
+            if (init_ids) {
+                for (int t = 0; t < K; ++t) {
+                    int32_t c = init_ids[v * K + t];
+                    if (c >= 0 && c != v) dlist_insert(l, &m, K, sqdist_rows(base, dtype, d, v, c, ta, tb), c);
+                }
+            } else {
+                int32_t picked[128];
+                int np = 0;
+                for (int j = 0; j < 2 * K && np < K; ++j) {
+                    int32_t c = (int32_t)orc_seed_id(seed, (uint64_t)v, (uint64_t)j, N);
+                    int seen = c == v;
+                    for (int t = 0; t < np && !seen; ++t) seen = picked[t] == c;
+                    if (!seen) picked[np++] = c;
+                }
+                for (int t = 0; t < np; ++t)
+                    dlist_insert(l, &m, K, sqdist_rows(base, dtype, d, v, picked[t], ta, tb), picked[t]);
+            }
+            cnt[v] = m;
+        }
+        free(ta);
+        free(tb);
+    }
+    int it = 0;
+    for (; it < max_iters; ++it) {
+        /* ---- reverse samples from the forward samples of the lists as they stand */
+        for (size_t i = 0; i < ns; ++i) {
+            Rnew[i].id = -1; Rnew[i].s = INFINITY;
+            Rold[i].id = -1; Rold[i].s = INFINITY;
+        }
+        for (int64_t u = 0; u < N; ++u) {
+            const uint32_t slot = ((uint32_t)u * 2654435761u) >> (32 - log2s);
+            int nn = 0, no = 0;
+            for (int t = 0; t < cnt[u]; ++t) {
+                const dnode_t* e = &B[u * K + t];
+                pair_t k;
+                k.s = e->s;
+                k.id = (int32_t)u;
+                pair_t* tab = NULL;
+                if (e->is_new && nn < S) { tab = Rnew; ++nn; }
+                else if (!e->is_new && no < S) { tab = Rold; ++no; }
+                if (!tab) continue;
+                pair_t* cell = &tab[(size_t)e->id * S + slot];
+                if (cell->id < 0 || pair_less(k, *cell)) *cell = k;
+            }
+        }
+        /* ---- every node pulls */
+        int64_t changed = 0;
+#pragma omp parallel num_threads(threads) reduction(+ : changed)
+        {
+            float* ta = (float*)malloc(sizeof(float) * (size_t)d);
+            float* tb = (float*)malloc(sizeof(float) * (size_t)d);
+#pragma omp for schedule(dynamic, 64)
+            for (int64_t a = 0; a < N; ++a) {
+                dnode_t* L = B2 + a * K;
+                int m = cnt[a];
+                int32_t src[64];
+                int src_new[64];
+                int nsrc = 0, nn = 0, no = 0;
+                for (int t = 0; t < m; ++t) L[t] = B[a * K + t];
+                for (int t = 0; t < m; ++t)       /* newF[a], sampled now: flagged old in L */
+                    if (B[a * K + t].is_new && nn < S) { src[nsrc] = B[a * K + t].id; src_new[nsrc++] = 1; L[t].is_new = 0; ++nn; }
+                for (int t = 0; t < m; ++t)
+                    if (!B[a * K + t].is_new && no < S) { src[nsrc] = B[a * K + t].id; src_new[nsrc++] = 0; ++no; }
+                for (int t = 0; t < S; ++t)
+                    if (Rnew[(size_t)a * S + t].id >= 0) { src[nsrc] = Rnew[(size_t)a * S + t].id; src_new[nsrc++] = 1; }
+                for (int t = 0; t < S; ++t)
+                    if (Rold[(size_t)a * S + t].id >= 0) { src[nsrc] = Rold[(size_t)a * S + t].id; src_new[nsrc++] = 0; }
+                for (int q = 0; q < nsrc; ++q) {
+                    const int64_t v = src[q];
+                    int32_t cand[64];
+                    int nc = 0, vn = 0, vo = 0;
+                    for (int t = 0; t < cnt[v]; ++t) {
+                        const dnode_t* e = &B[v * K + t];
+                        if (e->is_new && vn < S) { cand[nc++] = e->id; ++vn; }
+                        else if (!e->is_new && vo < S) { if (src_new[q]) cand[nc++] = e->id; ++vo; }
+                    }
+                    for (int t = 0; t < S; ++t)
+                        if (Rnew[(size_t)v * S + t].id >= 0) cand[nc++] = Rnew[(size_t)v * S + t].id;
+                    if (src_new[q])
+                        for (int t = 0; t < S; ++t)
+                            if (Rold[(size_t)v * S + t].id >= 0) cand[nc++] = Rold[(size_t)v * S + t].id;
+                    for (int t = 0; t < nc; ++t) {
+                        if (cand[t] == a) continue;
+                        int present = 0;
+                        for (int z = 0; z < m && !present; ++z) present = L[z].id == cand[t];
+                        if (present) continue;
+                        float s = sqdist_rows(base, dtype, d, a, cand[t], ta, tb);
+                        dlist_insert(L, &m, K, s, cand[t]);
+                    }
+                }
+                cnt2[a] = m;
+                for (int t = 0; t < m; ++t) {
+                    int was = 0;
+                    for (int z = 0; z < cnt[a] && !was; ++z) was = B[a * K + z].id == L[t].id;
+                    changed += !was;
+                }
+            }
+            free(ta);
+            free(tb);
+        }
+        { dnode_t* tmp = B; B = B2; B2 = tmp; }
+        { int32_t* tmp = cnt; cnt = cnt2; cnt2 = tmp; }
+        if (changed_per_iter) changed_per_iter[it] = changed;
+        if ((double)changed <= (double)delta * (double)N * (double)K) { ++it; break; }
+    }
+    if (iters_done) *iters_done = it;
+    for (int64_t v = 0; v < N; ++v)
+        for (int t = 0; t < K; ++t) {
+            knn_id[v * K + t] = t < cnt[v] ? B[v * K + t].id : -1;
+            knn_s[v * K + t] = t < cnt[v] ? B[v * K + t].s : INFINITY;
+        }
+    free(B); free(B2); free(cnt); free(cnt2); free(Rnew); free(Rold);
+    return 0;
+}
+
 double orc_recall(const int32_t* found, const int32_t* truth, int64_t nq, int k)
 {
     int64_t hit = 0;
