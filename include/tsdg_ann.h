@@ -74,6 +74,15 @@ typedef struct {
     int rev_cap;
     void* stream;
     ann_metric metric; /* default ANN_L2 */
+    /* Which k-NN graph the diversification starts from (Sec. 3 opening: "an approximate k-NN
+     * graph"; the default here is the exact one).  knn_mode 0 = exact (MFMA contraction);
+     * 1 = neighbourhood propagation, see ann_knn_descent, with the four parameters below
+     * (0 = defaults: S = largest power of two <= min(16, K/2), 12 iterations, delta 0.001, seed 0). */
+    int knn_mode;
+    int descent_S;
+    int descent_iters;
+    float descent_delta;
+    uint64_t descent_seed;
 } ann_build_params;
 
 /* Search parameters.  Defaults (ann_search_params_default): fp32 rows, mode 0
@@ -189,6 +198,20 @@ ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, i
                             void* stream, ann_graph** out);
 ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d);
 void ann_graph_free(ann_graph* graph);
+
+/* Approximate k-NN lists by neighbourhood propagation (the published NN-descent idea in a form
+ * where every node pulls its candidates from the previous iteration's lists, so the result does
+ * not depend on execution order; the paper starts from "an approximate k-NN graph", Sec. 3, and
+ * names no builder).  base[N,d] device rows of `dtype`; K in 1..64, K < N; S = sample size, a
+ * power of two in 2..16; at most max_iters iterations, stopping early once an iteration changes
+ * no more than delta*N*K list entries; `seed` draws the start lists (2K draws per node from the
+ * generator of the search's seeds), or init_ids[N,K] (device, may be NULL; -1 = none) gives them.
+ * Outputs knn_ids[N,K] int32 / knn_dists[N,K] fp32 (device) in (s,id) order, padded -1 / +inf;
+ * iters_done and last_changed (host, may be NULL).  Work per iteration is O(N * S^2) distance
+ * evaluations instead of the exact build's N^2.  Synchronises `stream` once per iteration. */
+ann_status ann_knn_descent(const void* base, int64_t N, int d, int K, ann_dtype dtype, int S, int max_iters,
+                           float delta, uint64_t seed, const int32_t* init_ids, void* stream, int32_t* knn_ids,
+                           float* knn_dists, int* iters_done, int64_t* last_changed);
 
 /* Unit rows for ANN_COSINE (Table 1, m = Cos): dst[i,:] = src[i,:] / |src[i,:]| for n rows of d
  * fp32 elements (d a multiple of 4, at most 2048; both device, 16-byte aligned, may be the same

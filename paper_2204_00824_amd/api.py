@@ -24,7 +24,8 @@ class AnnError(RuntimeError):
 
 class _BuildParams(C.Structure):
     _fields_ = [("dtype", C.c_int), ("alpha", C.c_float), ("lambda0", C.c_int), ("rev_cap", C.c_int),
-                ("stream", C.c_void_p), ("metric", C.c_int)]
+                ("stream", C.c_void_p), ("metric", C.c_int), ("knn_mode", C.c_int), ("descent_S", C.c_int),
+                ("descent_iters", C.c_int), ("descent_delta", C.c_float), ("descent_seed", C.c_uint64)]
 
 
 class _SearchParams(C.Structure):
@@ -69,9 +70,11 @@ def load_library():
     L.ann_graph_free.argtypes = [vp]
     L.ann_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
     L.ann_normalize_rows.argtypes = [vp, i64, i32, vp, vp]
+    L.ann_knn_descent.argtypes = [vp, i64, i32, i32, i32, i32, i32, C.c_float, u64, vp, vp, vp, vp,
+                                  C.POINTER(i32), C.POINTER(i64)]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_normalize_rows"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_normalize_rows", "ann_knn_descent"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -137,13 +140,16 @@ def ann_build_graph(base: torch.Tensor, K: int) -> Graph:
 
 
 def ann_build_graph_ex(base: torch.Tensor, K: int, alpha: float = 1.2, lambda0: int = 9, rev_cap: int = 0,
-                       stream=None, metric="l2") -> Graph:
+                       stream=None, metric="l2", knn_mode: int = 0, descent_S: int = 0, descent_iters: int = 0,
+                       descent_delta: float = 0.0, descent_seed: int = 0) -> Graph:
     L = load_library()
     p, dt = _base_ptr(base)
     prm = _BuildParams()
     L.ann_build_params_default(C.byref(prm))
     prm.dtype, prm.alpha, prm.lambda0, prm.rev_cap, prm.stream = dt, alpha, lambda0, rev_cap, _stream_ptr(stream)
     prm.metric = _METRICS[metric]
+    prm.knn_mode, prm.descent_S, prm.descent_iters = knn_mode, descent_S, descent_iters
+    prm.descent_delta, prm.descent_seed = descent_delta, descent_seed
     out = C.c_void_p()
     _check(L.ann_build_graph_ex(p, base.shape[0], base.shape[1], K, C.byref(prm), C.byref(out)))
     return Graph(out.value)
@@ -156,6 +162,21 @@ def ann_knn(base: torch.Tensor, K: int, stream=None):
     s = torch.empty((N, K), dtype=torch.float32, device=base.device)
     _check(load_library().ann_knn(p, N, d, K, dt, _stream_ptr(stream), ids.data_ptr(), s.data_ptr()))
     return ids, s
+
+
+def ann_knn_descent(base: torch.Tensor, K: int, S: int = 8, max_iters: int = 12, delta: float = 0.001, seed: int = 0,
+                    init_ids: torch.Tensor = None, stream=None):
+    """Approximate k-NN lists by neighbourhood propagation.  Returns (ids, dists, iterations, last_changed)."""
+    p, dt = _base_ptr(base)
+    N, d = base.shape
+    ids = torch.empty((N, K), dtype=torch.int32, device=base.device)
+    s = torch.empty((N, K), dtype=torch.float32, device=base.device)
+    done, changed = C.c_int(0), C.c_int64(0)
+    init = _dev(init_ids, torch.int32, "init_ids") if init_ids is not None else None
+    _check(load_library().ann_knn_descent(p, N, d, K, dt, S, max_iters, C.c_float(delta), C.c_uint64(seed), init,
+                                          _stream_ptr(stream), ids.data_ptr(), s.data_ptr(), C.byref(done),
+                                          C.byref(changed)))
+    return ids, s, done.value, changed.value
 
 
 def ann_bruteforce(base: torch.Tensor, queries: torch.Tensor, k: int, stream=None):

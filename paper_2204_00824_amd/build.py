@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libtsdg_ann.so")
-SOURCES = ["api.hip", "search.hip", "multi.hip", "alg2.hip", "knn.hip", "diversify.hip", "probe.hip"]
+SOURCES = ["api.hip", "search.hip", "multi.hip", "alg2.hip", "knn.hip", "diversify.hip", "probe.hip", "descent.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

@@ -1,6 +1,7 @@
 // extern "C" entry points (include/tsdg_ann.h): argument validation, the graph
 // object, import/export.  Every step of the path runs in the kernels of
 // search.hip, knn.hip and diversify.hip; nothing here computes on the host.
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -129,6 +130,14 @@ static ann_status check_metric(ann_metric metric, ann_dtype dtype, const char* w
     return ANN_OK;
 }
 
+static ann_status check_descent(int64_t N, int K, int S, int max_iters, float delta, const char* what)
+{
+    if (K < 1 || K > kMaxK || N <= K || N >= (1ll << kIdBits)) { set_error("%s: need 1 <= K <= 64 and K < N < 2^27", what); return ANN_EINVAL; }
+    if (S < 2 || S > 16 || (S & (S - 1)) != 0) { set_error("%s: the sample size S must be 2, 4, 8 or 16 (S=%d)", what, S); return ANN_EINVAL; }
+    if (max_iters < 0 || !(delta >= 0.f)) { set_error("%s: negative iteration count or delta", what); return ANN_EINVAL; }
+    return ANN_OK;
+}
+
 // Distances of a cosine search are reported as m = 1 - cos = s/2 (exact halving; +inf stays +inf).
 __global__ __launch_bounds__(256) void halve_kernel(float* __restrict__ v, int64_t n)
 {
@@ -204,6 +213,11 @@ void ann_build_params_default(ann_build_params* p)
     p->rev_cap = 0;
     p->stream = nullptr;
     p->metric = ANN_L2;
+    p->knn_mode = 0;
+    p->descent_S = 0;
+    p->descent_iters = 0;
+    p->descent_delta = 0.f;
+    p->descent_seed = 0;
 }
 
 void ann_search_params_default(ann_search_params* p)
@@ -346,6 +360,7 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
     // Eq. 2 compares alpha*m with m.  m = L2 distance: alpha^2 on the squared distances; m = 1 - cos = s/2: alpha.
     const float alpha_on_s = p.metric == ANN_COSINE ? p.alpha : p.alpha * p.alpha;
     if (p.lambda0 < 0 || p.lambda0 > kMaxLambda) { set_error("ann_build_graph: lambda0 must be in 0..30"); return ANN_EINVAL; }
+    if (p.knn_mode != 0 && p.knn_mode != 1) { set_error("ann_build_graph: knn_mode must be 0 or 1"); return ANN_EINVAL; }
     int rev_cap = p.rev_cap == 0 ? 2 * K : p.rev_cap;
     if (rev_cap < K || rev_cap > 2 * kMaxK) { set_error("ann_build_graph: rev_cap must be in K..128"); return ANN_EINVAL; }
     hipStream_t stream = static_cast<hipStream_t>(p.stream);
@@ -360,7 +375,20 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
         return ANN_ENOMEM;
     }
     ann_graph_impl* g = nullptr;
-    rc = knn_exact(base, N, d, p.dtype, nullptr, N, K, true, stream, knn_id, knn_s);
+    if (p.knn_mode == 1) {
+        int S = p.descent_S;
+        if (S == 0) {
+            S = 2;
+            while (S * 2 <= std::min(16, K / 2)) S *= 2;
+        }
+        rc = check_descent(N, K, S, p.descent_iters, p.descent_delta, "ann_build_graph");
+        if (rc == ANN_OK)
+            rc = knn_descent(base, N, d, p.dtype, K, S, p.descent_iters == 0 ? 12 : p.descent_iters,
+                             p.descent_delta == 0.f ? 0.001f : p.descent_delta, p.descent_seed, nullptr, stream, knn_id,
+                             knn_s, nullptr, nullptr);
+    } else {
+        rc = knn_exact(base, N, d, p.dtype, nullptr, N, K, true, stream, knn_id, knn_s);
+    }
     if (rc == ANN_OK) rc = new_graph(N, K, d, &g);
     if (rc == ANN_OK)
         rc = diversify(base, N, d, p.dtype, K, knn_id, knn_s, alpha_on_s, p.lambda0, rev_cap, stream, g->packed,
@@ -378,6 +406,20 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
 ann_status ann_build_graph(const void* base, int64_t N, int d, int K, ann_graph** out)
 {
     return ann_build_graph_ex(base, N, d, K, nullptr, out);
+}
+
+ann_status ann_knn_descent(const void* base, int64_t N, int d, int K, ann_dtype dtype, int S, int max_iters,
+                           float delta, uint64_t seed, const int32_t* init_ids, void* stream, int32_t* knn_ids,
+                           float* knn_dists, int* iters_done, int64_t* last_changed)
+{
+    g_err[0] = 0;
+    ann_status rc = check_rows(base, N, d, dtype, "ann_knn_descent");
+    if (rc != ANN_OK) return rc;
+    rc = check_descent(N, K, S, max_iters, delta, "ann_knn_descent");
+    if (rc != ANN_OK) return rc;
+    if (!knn_ids || !knn_dists) { set_error("ann_knn_descent: null output"); return ANN_EINVAL; }
+    return knn_descent(base, N, d, dtype, K, S, max_iters, delta, seed, init_ids, static_cast<hipStream_t>(stream),
+                       knn_ids, knn_dists, iters_done, last_changed);
 }
 
 ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, void* stream)

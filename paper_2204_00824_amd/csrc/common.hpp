@@ -112,6 +112,11 @@ ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const 
                      int64_t nq, int k, bool exclude_self, hipStream_t stream, int32_t* out_ids,
                      float* out_s);
 
+// Approximate k-NN lists by neighbourhood propagation (descent.hip); lists in (s,id) order, -1 / +inf padded.
+ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int K, int S, int max_iters, float delta,
+                       uint64_t seed, const int32_t* init_ids, hipStream_t stream, int32_t* out_ids, float* out_s,
+                       int* iters_done, int64_t* last_changed);
+
 ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
                      const float* knn_s, float alpha_on_s, int lambda0, int rev_cap, hipStream_t stream,
                      uint32_t* packed, int* max_lambda);

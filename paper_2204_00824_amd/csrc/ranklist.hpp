@@ -36,7 +36,9 @@ __device__ __forceinline__ int list_first_unexpanded(const uint64_t* list, int L
 // a time with v_readlane (their lane index is wave-uniform) and every lane compares its own
 // list entries against them, so a rank is one ballot + popcount and needs no dependent LDS
 // reads.  `sync` must order LDS accesses among the calling lanes.
-template <typename Sync>
+// DISTINCT = false: the lanes may hold the same candidate more than once; only the first lane's
+// copy is merged (costs one more pass over the candidates).
+template <bool DISTINCT = true, typename Sync>
 __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, int lane, Sync sync)
 {
     const uint64_t worst = list[L - 1] | 1ull;
@@ -44,6 +46,15 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
     bool valid = kk < worst;
     uint64_t vm = ballot64(valid);
     if (!vm) return;
+    if constexpr (!DISTINCT) {
+        bool again = false;
+        for (uint64_t m = vm; m; m &= m - 1) {
+            const int j = ctz64(m);
+            again = again || (j < lane && readlane64(kk, j) == kk);
+        }
+        valid = valid && !again;
+        vm = ballot64(valid);
+    }
 
     const int top = ((L - 1) / 64) * 64;
     int r = 0;
