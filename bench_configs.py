@@ -157,9 +157,71 @@ def run_sharded_u8(args):
     print(json.dumps(out), flush=True)
 
 
+def run_whole_u8(args):
+    """The 100M x 128 uint8 set as ONE graph: k-NN lists by neighbourhood propagation (O(N) work per
+    iteration instead of the exact build's N^2), then the same two-stage diversification."""
+    import torch
+    import workloads
+    import paper_2204_00824_amd as P
+    N, d, K, k = args.n or 100_000_000, 128, 32, 10
+    nq = 10_000
+    _, queries = next(workloads.scale_u8_torch(N=N, nq=nq))
+    base = torch.empty((N, d), dtype=torch.uint8, device="cuda")
+    for lo, x in workloads.scale_u8_torch(N=N, chunk=4_000_000):
+        base[lo:lo + x.shape[0]] = x
+    torch.cuda.synchronize()
+    log(f"generated {N} rows")
+    t0 = time.time()
+    ids, _, done, last = P.ann_knn_descent(base, K, S=16, max_iters=12, delta=0.001, seed=0)
+    torch.cuda.synchronize()
+    knn_s = time.time() - t0
+    log(f"neighbourhood propagation alone: {done} iterations, {last} entries changed in the last, {knn_s:.1f}s")
+    # quality of the lists on a sample of rows against the exact lists
+    sample = torch.arange(0, N, max(1, N // 2000), device="cuda")[:2000]
+    ex, _ = P.ann_bruteforce(base, base[sample].to(torch.float32), K + 1)
+    ex = ex[:, 1:]                                            # the row itself comes first
+    list_recall = (ids[sample.long()].unsqueeze(2) == ex.unsqueeze(1)).any(dim=2).float().mean().item()
+    del ids, ex
+    t0 = time.time()
+    graph = P.ann_build_graph_ex(base, K, knn_mode=1)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    log(f"whole build (propagation + diversification): {build_s:.1f}s; list recall on 2000 rows {list_recall:.4f}")
+    gt, _ = P.ann_bruteforce(base, queries, k)
+    gt_h = gt.cpu().numpy()
+    log("ground truth done")
+    out = {"workload": f"scale N={N} d={d} uint8, one graph from neighbourhood propagation (S=16)", "nq": nq, "K": K,
+           "knn_seconds": round(knn_s, 1), "knn_iterations": done, "knn_list_recall_on_2000_rows": round(list_recall, 4),
+           "build_seconds": round(build_s, 1), "curves": {}}
+    rows = []
+    for L in (16, 32, 64, 128, 256):
+        ids, s, st = P.ann_search_ex(graph, base, queries, k, L, mode=1, lambda_visit=5, want_stats=True)
+        ms = timed_search(lambda: P.ann_search_ex(graph, base, queries, k, L, mode=1, lambda_visit=5, out=(ids, s)))
+        ev, hp = st.dist_evals.double().mean().item(), st.hops.double().mean().item()
+        rows.append({"L": L, "recall@10": round(recall(ids.cpu().numpy(), gt_h), 4), "qps": round(nq / ms * 1e3),
+                     "ms": round(ms, 3), "dist_evals": round(ev, 1), "alg_TBps": round((ev * d + hp * K * 4) * nq / ms / 1e9, 2)})
+        log(f"large batch: {rows[-1]}")
+    out["curves"]["large_batch_lambda5"] = rows
+    rows = []
+    for t0_ in (32, 64):
+        lat, hit = [], 0
+        for c in range(50):
+            q = queries[c:c + 1].contiguous()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            ids, _ = P.ann_search_multi(graph, base, q, k, t0_, max_hops=8, qi_offset=c)
+            torch.cuda.synchronize()
+            lat.append(time.perf_counter() - t1)
+            hit += recall(ids.cpu().numpy(), gt_h[c:c + 1])
+        rows.append({"t0": t0_, "T": 8, "recall@10": round(hit / 50, 4), "median_latency_ms": round(float(np.median(lat)) * 1e3, 3)})
+        log(f"batch 1 multi-search: {rows[-1]}")
+    out["curves"]["batch1_multi_search"] = rows
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "glove1m"])
+    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m"])
     ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
     args = ap.parse_args()
     import workloads
@@ -172,6 +234,8 @@ def main():
     elif args.workload == "glove1m":
         base, q = workloads.glove_like(N=args.n or 1_000_000)
         run_single_graph(args, "glove-like, cosine", base, q, (10,), (32, 64, 128, 256, 512), metric="cosine")
+    elif args.workload == "scale100m_one_graph":
+        run_whole_u8(args)
     else:
         run_sharded_u8(args)
 

@@ -30,7 +30,8 @@
  *     are untouched when argument validation fails; ann_last_error() gives a
  *     thread-local message for the last failing call.
  *   - Limits: 1 <= K <= 64, N > K, N < 2^27, 1 <= k <= L <= 512,
- *     d <= 2048 (fp32) / d <= 1024 (uint8), 0 <= lambda0 <= 30.
+ *     d <= 2048 (fp32) / d <= 1024 (uint8), 0 <= lambda0 <= 30, at most 2^22
+ *     queries per search call.
  */
 #ifndef TSDG_ANN_H
 #define TSDG_ANN_H

@@ -26,7 +26,7 @@ void set_error(const char* fmt, ...)
 __global__ void pack_kernel(const int32_t* __restrict__ adj, const uint8_t* __restrict__ lam, int64_t N,
                             int K, uint32_t* __restrict__ packed, int* __restrict__ flags)
 {
-    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);
+    const int64_t row = linear_block() * (blockDim.x / 64) + (threadIdx.x >> 6);
     const int lane = lane_id();
     if (row >= N) return;
     int32_t id = -1;
@@ -55,7 +55,7 @@ __global__ void pack_kernel(const int32_t* __restrict__ adj, const uint8_t* __re
 __global__ void unpack_kernel(const uint32_t* __restrict__ packed, int64_t total, int32_t* __restrict__ adj,
                               uint8_t* __restrict__ lam)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = linear_block() * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const uint32_t w = packed[i];
     adj[i] = w == kPackPad ? -1 : (int32_t)(w & kIdMask);
@@ -70,8 +70,7 @@ ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, 
     hipError_t e = hipMemsetAsync(flags, 0, 2 * sizeof(int), stream);
     if (e == hipSuccess) {
         const int rows_per_block = 4;
-        const unsigned grid = (unsigned)((N + rows_per_block - 1) / rows_per_block);
-        hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(64 * rows_per_block), 0, stream, adj, lam, N, K, packed,
+        hipLaunchKernelGGL(pack_kernel, folded_grid((N + rows_per_block - 1) / rows_per_block), dim3(64 * rows_per_block), 0, stream, adj, lam, N, K, packed,
                            flags);
         e = hipGetLastError();
     }
@@ -96,8 +95,7 @@ ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, 
 ann_status unpack_graph(const uint32_t* packed, int64_t N, int K, hipStream_t stream, int32_t* adj, uint8_t* lam)
 {
     const int64_t total = N * K;
-    const unsigned grid = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(unpack_kernel, dim3(grid), dim3(256), 0, stream, packed, total, adj, lam);
+    hipLaunchKernelGGL(unpack_kernel, folded_grid((total + 255) / 256), dim3(256), 0, stream, packed, total, adj, lam);
     TSDG_HIP(hipGetLastError());
     TSDG_HIP(hipStreamSynchronize(stream));
     return ANN_OK;
@@ -141,14 +139,14 @@ static ann_status check_descent(int64_t N, int K, int S, int max_iters, float de
 // Distances of a cosine search are reported as m = 1 - cos = s/2 (exact halving; +inf stays +inf).
 __global__ __launch_bounds__(256) void halve_kernel(float* __restrict__ v, int64_t n)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = linear_block() * 256 + threadIdx.x;
     if (i < n) v[i] *= 0.5f;
 }
 
 static ann_status report_metric(ann_metric metric, float* out_dists, int64_t n, hipStream_t stream)
 {
     if (metric != ANN_COSINE || n == 0) return ANN_OK;
-    hipLaunchKernelGGL(halve_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, out_dists, n);
+    hipLaunchKernelGGL(halve_kernel, folded_grid((n + 255) / 256), dim3(256), 0, stream, out_dists, n);
     TSDG_HIP(hipGetLastError());
     return ANN_OK;
 }
@@ -158,7 +156,7 @@ static ann_status report_metric(ann_metric metric, float* out_dists, int64_t n, 
 __global__ __launch_bounds__(256) void normalize_kernel(const float* __restrict__ src, int64_t n, int d,
                                                         float* __restrict__ dst)
 {
-    const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
     const int g = (int)(threadIdx.x & 7);
     double acc = 0.0;
     if (row < n)
@@ -429,7 +427,7 @@ ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, vo
     ann_status rc = check_rows(src, n, d, ANN_F32, "ann_normalize_rows");
     if (rc != ANN_OK) return rc;
     if (!dst || !aligned16(dst)) { set_error("ann_normalize_rows: dst must be a 16-byte aligned device pointer"); return ANN_EINVAL; }
-    hipLaunchKernelGGL(normalize_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, static_cast<hipStream_t>(stream),
+    hipLaunchKernelGGL(normalize_kernel, folded_grid((n + 31) / 32), dim3(256), 0, static_cast<hipStream_t>(stream),
                        src, n, d, dst);
     TSDG_HIP(hipGetLastError());
     return ANN_OK;
@@ -446,6 +444,7 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     if (!graph) { set_error("ann_search: null graph"); return ANN_EINVAL; }
     const ann_graph_impl* g = reinterpret_cast<const ann_graph_impl*>(graph);
     if (nq < 0) { set_error("ann_search: negative nq"); return ANN_EINVAL; }
+    if (nq > (1 << 22)) { set_error("ann_search: at most 4,194,304 queries per call (nq=%d)", nq); return ANN_EUNSUPPORTED; }
     if (k < 1 || L < k || L > kMaxL) { set_error("ann_search: need 1 <= k <= L <= 512 (k=%d, L=%d)", k, L); return ANN_EINVAL; }
     if (p.n_seeds < 1) { set_error("ann_search: n_seeds must be positive"); return ANN_EINVAL; }
     if (p.max_hops < 0 || p.mode < 0 || p.mode > 2 || p.lambda_visit < 0) {
@@ -595,6 +594,7 @@ ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void*
     if (!graph) { set_error("ann_search_alg2: null graph"); return ANN_EINVAL; }
     const ann_graph_impl* g = reinterpret_cast<const ann_graph_impl*>(graph);
     if (nq < 0) { set_error("ann_search_alg2: negative nq"); return ANN_EINVAL; }
+    if (nq > (1 << 22)) { set_error("ann_search_alg2: at most 4,194,304 queries per call (nq=%d)", nq); return ANN_EUNSUPPORTED; }
     if (k < 1 || k > 64) { set_error("ann_search_alg2: need 1 <= k <= 64 (k=%d)", k); return ANN_EINVAL; }
     if (m_c < 1 || m_c > 64 || m_v < 1 || m_v > 64) { set_error("ann_search_alg2: m_c and m_v must be in 1..64"); return ANN_EINVAL; }
     if (!(delta >= 0.0f)) { set_error("ann_search_alg2: delta must be >= 0"); return ANN_EINVAL; }

@@ -1,6 +1,7 @@
 // Shared host/device definitions of the HIP library (gfx950, wave64).
 // Nothing here is shared with the CPU oracle.
 #pragma once
+#include <algorithm>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -32,6 +33,21 @@ struct ann_graph_impl {
     void* ws;          // grow-only scratch of the multi-search (rankings of the t0 searches)
     size_t ws_bytes;
 };
+
+// ---- grids that grow with the number of base rows
+// A dispatch counts the work-items of each grid dimension in 32 bits, so a 1-D grid of B
+// workgroups of T threads needs B*T < 2^32 -- which 64 threads per base row break beyond 67M
+// rows.  Such grids are folded into two dimensions; the kernel takes its linear workgroup index
+// from linear_block() and leaves when that is past its work.
+constexpr unsigned kGridFold = 1u << 16;  // small enough that sets of a few 10^5 rows already take the folded path
+inline dim3 folded_grid(int64_t blocks)
+{
+    if (blocks <= (int64_t)kGridFold) return dim3((unsigned)std::max<int64_t>(blocks, 1));
+    return dim3(kGridFold, (unsigned)((blocks + kGridFold - 1) / kGridFold));
+}
+#ifdef __HIPCC__
+__device__ __forceinline__ int64_t linear_block() { return (int64_t)blockIdx.y * (int64_t)gridDim.x + (int64_t)blockIdx.x; }
+#endif
 
 // ---- error plumbing (host)
 void set_error(const char* fmt, ...);

@@ -53,7 +53,7 @@ struct DescentArgs {
 
 __global__ __launch_bounds__(256) void fill_u64_kernel(uint64_t* p, int64_t n, uint64_t v)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = linear_block() * 256 + threadIdx.x;
     if (i < n) p[i] = v;
 }
 
@@ -105,7 +105,8 @@ __global__ __launch_bounds__(64) void descent_init_kernel(DescentArgs a)
     __shared__ uint32_t cid[64];
     __shared__ uint32_t table[kDescentSlots];
     const int lane = lane_id();
-    const uint64_t v = blockIdx.x;
+    const uint64_t v = (uint64_t)linear_block();
+    if (v >= a.N) return;  // folded grid: past the last node
     const T* __restrict__ base = static_cast<const T*>(a.base);
     list[lane] = kKeyEmpty;
     for (int i = lane; i < kDescentSlots; i += 64) table[i] = kHashEmpty;
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(64) void descent_init_kernel(DescentArgs a)
 // Reverse samples: every node offers itself to the nodes in its forward samples.
 __global__ __launch_bounds__(256) void descent_reverse_kernel(DescentArgs a)
 {
-    const uint64_t u = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint64_t u = (uint64_t)linear_block() * 4 + (threadIdx.x >> 6);
     if (u >= a.N) return;
     const int lane = lane_id();
     const uint64_t key = lane < a.K ? a.cur[u * a.K + lane] : kKeyEmpty;
@@ -187,7 +188,8 @@ __global__ __launch_bounds__(64) void descent_join_kernel(DescentArgs a)
     __shared__ uint32_t src[64];       // source id << 1 | edge-is-new
     __shared__ uint32_t table[kDescentSlots];
     const int lane = lane_id();
-    const uint64_t v0 = blockIdx.x;
+    const uint64_t v0 = (uint64_t)linear_block();
+    if (v0 >= a.N) return;  // folded grid: past the last node
     const T* __restrict__ base = static_cast<const T*>(a.base);
     const int K = a.K, S = a.S;
     for (int i = lane; i < kDescentSlots; i += 64) table[i] = kHashEmpty;
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(64) void descent_join_kernel(DescentArgs a)
 __global__ __launch_bounds__(256) void descent_export_kernel(const uint64_t* __restrict__ keys, int64_t n,
                                                              int32_t* __restrict__ ids, float* __restrict__ s)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = linear_block() * 256 + threadIdx.x;
     if (i >= n) return;
     const uint64_t k = keys[i];
     ids[i] = k != kKeyEmpty ? (int32_t)key_id(k) : -1;
@@ -286,8 +288,8 @@ struct DescentLaunch {
     bool init;
     template <typename T, int G, int C> void operator()()
     {
-        if (init) hipLaunchKernelGGL((descent_init_kernel<T, G, C>), dim3((unsigned)a.N), dim3(64), 0, stream, a);
-        else hipLaunchKernelGGL((descent_join_kernel<T, G, C>), dim3((unsigned)a.N), dim3(64), 0, stream, a);
+        if (init) hipLaunchKernelGGL((descent_init_kernel<T, G, C>), folded_grid((int64_t)a.N), dim3(64), 0, stream, a);
+        else hipLaunchKernelGGL((descent_join_kernel<T, G, C>), folded_grid((int64_t)a.N), dim3(64), 0, stream, a);
     }
 };
 }  // namespace
@@ -341,13 +343,13 @@ ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int 
     const char* prog_env = getenv("TSDG_PROGRESS");
     const bool progress = prog_env && prog_env[0] == '1';
     for (; it < max_iters; ++it) {
-        hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, stream, rnew, (int64_t)ns, kRevEmpty);
-        hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, stream, rold, (int64_t)ns, kRevEmpty);
+        hipLaunchKernelGGL(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rnew, (int64_t)ns, kRevEmpty);
+        hipLaunchKernelGGL(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rold, (int64_t)ns, kRevEmpty);
         hipLaunchKernelGGL(fill_u64_kernel, dim3((kChangedBins + 255) / 256), dim3(256), 0, stream,
                            reinterpret_cast<uint64_t*>(changed), (int64_t)kChangedBins, 0ull);
         L.a.cur = cur;
         L.a.next = nxt;
-        hipLaunchKernelGGL(descent_reverse_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, L.a);
+        hipLaunchKernelGGL(descent_reverse_kernel, folded_grid((N + 3) / 4), dim3(256), 0, stream, L.a);
         dispatch_row_shape(dtype, d, L);
         unsigned long long h[kChangedBins];
         hipError_t ce = hipMemcpyAsync(h, changed, sizeof(h), hipMemcpyDeviceToHost, stream);
@@ -363,7 +365,7 @@ ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int 
         }
         if ((double)ch <= (double)delta * (double)N * (double)K) { ++it; break; }
     }
-    hipLaunchKernelGGL(descent_export_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, stream, cur, (int64_t)nk,
+    hipLaunchKernelGGL(descent_export_kernel, folded_grid((int64_t)((nk + 255) / 256)), dim3(256), 0, stream, cur, (int64_t)nk,
                        out_ids, out_s);
     hipError_t fe = hipStreamSynchronize(stream);
     if (fe == hipSuccess) fe = hipGetLastError();

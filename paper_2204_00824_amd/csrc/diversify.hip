@@ -79,7 +79,8 @@ __global__ __launch_bounds__(64) void stage1_kernel(Stage1Args a)
     float* P = sm;                                         // [K*K]
     float* s0 = P + K * K;                                 // [K]
     int32_t* ids = reinterpret_cast<int32_t*>(s0 + K);     // [K]
-    const int64_t x0 = blockIdx.x;
+    const int64_t x0 = linear_block();
+    if (x0 >= a.N) return;  // folded grid: past the last node
     const int lane = lane_id();
     const T* __restrict__ base = static_cast<const T*>(a.base);
 
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(const int32_t* __restrict_
                                                       unsigned* __restrict__ cursor, int32_t* __restrict__ rev_src,
                                                       float* __restrict__ rev_s)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = linear_block() * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const int32_t tgt = g1_id[i];
     if (tgt < 0) return;
@@ -225,7 +226,8 @@ struct MergeArgs {
 __global__ __launch_bounds__(64) void merge_kernel(MergeArgs a)
 {
     extern __shared__ uint64_t list[];  // [rev_cap rounded to 64]
-    const int64_t x0 = blockIdx.x;
+    const int64_t x0 = linear_block();
+    if (x0 >= a.N) return;  // folded grid: past the last node
     const int lane = lane_id();
     const int Lp = (a.rev_cap + 63) & ~63;
     for (int i = lane; i < Lp; i += 64) list[i] = kKeyEmpty;
@@ -277,7 +279,8 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     float* s0 = P + R * R;                                 // [R]
     int32_t* ids = reinterpret_cast<int32_t*>(s0 + R);     // [R]
     int* lam = reinterpret_cast<int*>(ids + R);            // [R]
-    const int64_t x0 = blockIdx.x;
+    const int64_t x0 = linear_block();
+    if (x0 >= a.N) return;  // folded grid: past the last node
     const int lane = lane_id();
     const T* __restrict__ base = static_cast<const T*>(a.base);
     const int m = a.g2_deg[x0];
@@ -343,7 +346,7 @@ struct Stage1Launch {
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage1_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((stage1_kernel<T, G, C>), dim3((unsigned)a.N), dim3(64), lds, stream, a);
+        hipLaunchKernelGGL((stage1_kernel<T, G, C>), folded_grid(a.N), dim3(64), lds, stream, a);
     }
 };
 struct Stage2Launch {
@@ -356,7 +359,7 @@ struct Stage2Launch {
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage2_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((stage2_kernel<T, G, C>), dim3((unsigned)a.N), dim3(64), lds, stream, a);
+        hipLaunchKernelGGL((stage2_kernel<T, G, C>), folded_grid(a.N), dim3(64), lds, stream, a);
     }
 };
 }  // namespace
@@ -413,7 +416,7 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     TSDG_HIP(hipStreamSynchronize(stream));
     TSDG_HIP(rev_src.alloc((size_t)total * 4));
     TSDG_HIP(rev_s.alloc((size_t)total * 4));
-    hipLaunchKernelGGL(scatter_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, stream, g1_id.as<int32_t>(),
+    hipLaunchKernelGGL(scatter_kernel, folded_grid((int64_t)((nk + 255) / 256)), dim3(256), 0, stream, g1_id.as<int32_t>(),
                        g1_s.as<float>(), (int64_t)nk, K, start.as<uint64_t>(), cursor.as<unsigned>(),
                        rev_src.as<int32_t>(), rev_s.as<float>());
     TSDG_HIP(hipGetLastError());
@@ -435,7 +438,7 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     m.N = N;
     m.K = K;
     m.rev_cap = rev_cap;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)N), dim3(64), (size_t)((rev_cap + 63) & ~63) * 8, stream, m);
+    hipLaunchKernelGGL(merge_kernel, folded_grid(N), dim3(64), (size_t)((rev_cap + 63) & ~63) * 8, stream, m);
     TSDG_HIP(hipGetLastError());
 
     // stage 2

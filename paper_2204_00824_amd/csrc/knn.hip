@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int
                                                     float* __restrict__ norms, unsigned* info)
 {
     // 8 lanes per row, 4 elements per lane and step (128 contiguous bytes per group for fp32)
-    const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
     const int g = (int)(threadIdx.x & 7);
     double acc = 0.0;
     bool nonint = false;
@@ -262,7 +262,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void to_bf16_kernel(const T* __restrict__ src, int64_t n, int d, int dp,
                                                       uint16_t* __restrict__ dst)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 4-element group
+    const int64_t i = linear_block() * blockDim.x + threadIdx.x;  // one 4-element group
     const int groups = dp / 4;
     if (i >= n * groups) return;
     const int64_t r = i / groups;
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x
                                                          uint16_t* __restrict__ xl, float* __restrict__ norms,
                                                          unsigned* maxnorm)
 {
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t row = linear_block() * 4 + (threadIdx.x >> 6);
     const int lane = lane_id();
     if (row >= n) return;
     double acc = 0.0;
@@ -983,13 +983,13 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     TSDG_HIP(xnorm.alloc((size_t)N * 4));
     TSDG_HIP(info.alloc(4 * sizeof(unsigned)));
     TSDG_HIP(hipMemsetAsync(info.p, 0, 4 * sizeof(unsigned), stream));
-    hipLaunchKernelGGL((norms_kernel<TB>), dim3((unsigned)((N + 31) / 32)), dim3(256), 0, stream, base, N, d,
+    hipLaunchKernelGGL((norms_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d,
                        xnorm.as<float>(), info.as<unsigned>());
     TSDG_HIP(hipGetLastError());
     float* qn = xnorm.as<float>();
     if (!self) {
         TSDG_HIP(qnorm.alloc((size_t)nq * 4));
-        hipLaunchKernelGGL((norms_kernel<TQ>), dim3((unsigned)((nq + 31) / 32)), dim3(256), 0, stream, queries, nq, d,
+        hipLaunchKernelGGL((norms_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
                            qnorm.as<float>(), info.as<unsigned>() + 2);
         TSDG_HIP(hipGetLastError());
         qn = qnorm.as<float>();
@@ -1014,11 +1014,11 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     DevBuf xb, qb;
     if (fast) {
         TSDG_HIP(xb.alloc((size_t)N * dp * 2));
-        hipLaunchKernelGGL((to_bf16_kernel<TB>), dim3((unsigned)((N * (dp / 4) + 255) / 256)), dim3(256), 0, stream,
+        hipLaunchKernelGGL((to_bf16_kernel<TB>), folded_grid((N * (dp / 4) + 255) / 256), dim3(256), 0, stream,
                            base, N, d, dp, xb.as<uint16_t>());
         if (!self) {
             TSDG_HIP(qb.alloc((size_t)nq * dp * 2));
-            hipLaunchKernelGGL((to_bf16_kernel<TQ>), dim3((unsigned)((nq * (dp / 4) + 255) / 256)), dim3(256), 0,
+            hipLaunchKernelGGL((to_bf16_kernel<TQ>), folded_grid((nq * (dp / 4) + 255) / 256), dim3(256), 0,
                                stream, queries, nq, d, dp, qb.as<uint16_t>());
         }
         TSDG_HIP(hipGetLastError());
@@ -1041,7 +1041,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                            csum.as<double>());
         hipLaunchKernelGGL(mean_kernel, dim3((unsigned)((d + 63) / 64)), dim3(64), 0, stream, csum.as<double>(), d, N,
                            cmean.as<float>());
-        hipLaunchKernelGGL((split_prep_kernel<TB>), dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, base, N, d, dp,
+        hipLaunchKernelGGL((split_prep_kernel<TB>), folded_grid((N + 3) / 4), dim3(256), 0, stream, base, N, d, dp,
                            cmean.as<float>(), xh.as<uint16_t>(), xl.as<uint16_t>(), cxnorm.as<float>(),
                            cinfo.as<unsigned>());
         unsigned h_max = 0;
@@ -1050,7 +1050,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             TSDG_HIP(qh.alloc((size_t)nq * dp * 2));
             TSDG_HIP(ql.alloc((size_t)nq * dp * 2));
             TSDG_HIP(cqnorm.alloc((size_t)nq * 4));
-            hipLaunchKernelGGL((split_prep_kernel<TQ>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, stream, queries, nq,
+            hipLaunchKernelGGL((split_prep_kernel<TQ>), folded_grid((nq + 3) / 4), dim3(256), 0, stream, queries, nq,
                                d, dp, cmean.as<float>(), qh.as<uint16_t>(), ql.as<uint16_t>(), cqnorm.as<float>(),
                                cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
         }
