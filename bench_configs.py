@@ -172,7 +172,7 @@ def run_whole_u8(args):
     torch.cuda.synchronize()
     log(f"generated {N} rows")
     t0 = time.time()
-    ids, _, done, last = P.ann_knn_descent(base, K, S=16, max_iters=12, delta=0.001, seed=0)
+    ids, _, done, last = P.ann_knn_descent(base, K, S=16, max_iters=args.iters, delta=0.001, seed=0)
     torch.cuda.synchronize()
     knn_s = time.time() - t0
     log(f"neighbourhood propagation alone: {done} iterations, {last} entries changed in the last, {knn_s:.1f}s")
@@ -182,8 +182,9 @@ def run_whole_u8(args):
     ex = ex[:, 1:]                                            # the row itself comes first
     list_recall = (ids[sample.long()].unsqueeze(2) == ex.unsqueeze(1)).any(dim=2).float().mean().item()
     del ids, ex
+    torch.cuda.empty_cache()                                  # the library allocates outside torch's cache
     t0 = time.time()
-    graph = P.ann_build_graph_ex(base, K, knn_mode=1)
+    graph = P.ann_build_graph_ex(base, K, knn_mode=1, descent_iters=args.iters)
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"whole build (propagation + diversification): {build_s:.1f}s; list recall on 2000 rows {list_recall:.4f}")
@@ -223,6 +224,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m"])
     ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
+    ap.add_argument("--iters", type=int, default=20, help="scale100m_one_graph: most iterations of the propagation")
     args = ap.parse_args()
     import workloads
     if args.workload == "gist1m":
