@@ -52,7 +52,10 @@ typedef enum {
     ANN_EUNSUPPORTED = 4 /* valid request outside the limits above */
 } ann_status;
 
-typedef enum { ANN_F32 = 0, ANN_U8 = 1 } ann_dtype; /* element type of base rows */
+/* Element type of base rows.  ANN_F16 (IEEE binary16, d a multiple of 8) is a STORAGE type for the
+ * search entry points only: distances are the canonical ones of the stored values (each converts
+ * exactly to fp32); the graph is built from fp32 or uint8 rows. */
+typedef enum { ANN_F32 = 0, ANN_U8 = 1, ANN_F16 = 2 } ann_dtype;
 
 /* Dissimilarity m(.,.) of Sec. 2 / Table 1.
  *   ANN_L2:     squared Euclidean distance s (what every call returns); Eq. 2's alpha acts on

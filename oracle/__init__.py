@@ -15,7 +15,7 @@ import numpy as np
 
 from . import build as _build
 
-F32, U8 = 0, 1
+F32, U8, F16 = 0, 1, 2
 _lib = None
 
 
@@ -40,7 +40,9 @@ def _dtype_code(base: np.ndarray) -> int:
         return F32
     if base.dtype == np.uint8:
         return U8
-    raise TypeError("base must be float32 or uint8")
+    if base.dtype == np.float16:
+        return F16
+    raise TypeError("base must be float32, float16 or uint8")
 
 
 def _c(a: np.ndarray, dt=None) -> np.ndarray:

@@ -46,6 +46,7 @@
 
 #define ORC_F32 0
 #define ORC_U8 1
+#define ORC_F16 2 /* rows stored as IEEE binary16; every value converts exactly to fp32 */
 
 typedef struct {
     float s;
@@ -68,10 +69,27 @@ static int pair_cmp(const void* pa, const void* pb)
     return 0;
 }
 
-/* Row i of the base set as fp32 (uint8 converts exactly). */
+/* IEEE binary16 bit pattern -> fp32 (exact): sign, 5 exponent bits (bias 15), 10 fraction bits;
+ * exponent 0 = zero / subnormal (fraction * 2^-24), exponent 31 = infinity / NaN. */
+float orc_half_to_float(uint16_t h)
+{
+    const int sign = (h >> 15) & 1, e = (h >> 10) & 31, f = h & 1023;
+    float v;
+    if (e == 0) v = ldexpf((float)f, -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexpf((float)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
+
+/* Row i of the base set as fp32 (uint8 and binary16 convert exactly). */
 static const float* row_f32(const void* base, int dtype, int64_t i, int d, float* tmp)
 {
     if (dtype == ORC_F32) return (const float*)base + i * (int64_t)d;
+    if (dtype == ORC_F16) {
+        const uint16_t* r = (const uint16_t*)base + i * (int64_t)d;
+        for (int j = 0; j < d; ++j) tmp[j] = orc_half_to_float(r[j]);
+        return tmp;
+    }
     const uint8_t* r = (const uint8_t*)base + i * (int64_t)d;
     for (int j = 0; j < d; ++j) tmp[j] = (float)r[j];
     return tmp;

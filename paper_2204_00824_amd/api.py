@@ -8,7 +8,7 @@ from dataclasses import dataclass
 
 import torch
 
-ANN_F32, ANN_U8 = 0, 1
+ANN_F32, ANN_U8, ANN_F16 = 0, 1, 2
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libtsdg_ann.so")
 _lib = None
@@ -107,7 +107,9 @@ def _base_ptr(base: torch.Tensor):
         return _dev(base, torch.float32, "base"), ANN_F32
     if base.dtype == torch.uint8:
         return _dev(base, torch.uint8, "base"), ANN_U8
-    raise TypeError("base: float32 or uint8 rows")
+    if base.dtype == torch.float16:      # storage type of the search calls
+        return _dev(base, torch.float16, "base"), ANN_F16
+    raise TypeError("base: float32, float16 or uint8 rows")
 
 
 class Graph:

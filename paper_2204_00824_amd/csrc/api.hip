@@ -103,13 +103,19 @@ ann_status unpack_graph(const uint32_t* packed, int64_t N, int K, hipStream_t st
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static ann_status check_rows(const void* base, int64_t N, int d, ann_dtype dtype, const char* what)
+// storage_types: the call also takes rows that are only a storage format (binary16)
+static ann_status check_rows(const void* base, int64_t N, int d, ann_dtype dtype, const char* what,
+                             bool storage_types = false)
 {
     if (!base) { set_error("%s: null pointer", what); return ANN_EINVAL; }
-    if (dtype != ANN_F32 && dtype != ANN_U8) { set_error("%s: unknown dtype %d", what, (int)dtype); return ANN_EINVAL; }
+    if (dtype == ANN_F16 && !storage_types) {
+        set_error("%s: binary16 rows are a storage type of the search calls only", what);
+        return ANN_EUNSUPPORTED;
+    }
+    if (dtype != ANN_F32 && dtype != ANN_U8 && dtype != ANN_F16) { set_error("%s: unknown dtype %d", what, (int)dtype); return ANN_EINVAL; }
     if (N <= 0 || d <= 0) { set_error("%s: N and d must be positive", what); return ANN_EINVAL; }
     if (!aligned16(base)) { set_error("%s: rows must be 16-byte aligned", what); return ANN_EINVAL; }
-    const int pc = dtype == ANN_U8 ? 16 : 4;
+    const int pc = dtype == ANN_U8 ? 16 : (dtype == ANN_F16 ? 8 : 4);
     const int dmax = dtype == ANN_U8 ? 1024 : 2048;
     if (d % pc != 0 || d > dmax) {
         set_error("%s: d=%d unsupported (must be a multiple of %d and at most %d)", what, d, pc, dmax);
@@ -453,7 +459,7 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     }
     if (nq == 0) return ANN_OK;
     if (!queries || !out_ids || !out_dists) { set_error("ann_search: null pointer"); return ANN_EINVAL; }
-    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search");
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search", true);
     if (rc != ANN_OK) return rc;
     rc = check_metric(p.metric, p.dtype, "ann_search");
     if (rc != ANN_OK) return rc;
@@ -480,7 +486,7 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     s.stream = static_cast<hipStream_t>(p.stream);
 
     // batch regime (Sec. 4): below the threshold a query gets a whole workgroup
-    const int row_bytes = g->d * (p.dtype == ANN_U8 ? 1 : 4);
+    const int row_bytes = g->d * (p.dtype == ANN_U8 ? 1 : (p.dtype == ANN_F16 ? 2 : 4));
     int mode = p.mode;
     if (mode == 0) mode = nq >= kLargeBatchThreshold ? 1 : 2;
     int waves = 1;
@@ -538,7 +544,7 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
     if (p.max_hops < 0 || p.lambda_visit < 0) { set_error("ann_search_multi: negative max_hops / lambda_visit"); return ANN_EINVAL; }
     if (nq == 0) return ANN_OK;
     if (!queries || !out_ids || !out_dists) { set_error("ann_search_multi: null pointer"); return ANN_EINVAL; }
-    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_multi");
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_multi", true);
     if (rc != ANN_OK) return rc;
     rc = check_metric(p.metric, p.dtype, "ann_search_multi");
     if (rc != ANN_OK) return rc;
@@ -601,7 +607,7 @@ ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void*
     if (p.max_hops < 0 || p.lambda_visit < 0) { set_error("ann_search_alg2: negative max_hops / lambda_visit"); return ANN_EINVAL; }
     if (nq == 0) return ANN_OK;
     if (!queries || !out_ids || !out_dists) { set_error("ann_search_alg2: null pointer"); return ANN_EINVAL; }
-    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_alg2");
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_alg2", true);
     if (rc != ANN_OK) return rc;
     rc = check_metric(p.metric, p.dtype, "ann_search_alg2");
     if (rc != ANN_OK) return rc;

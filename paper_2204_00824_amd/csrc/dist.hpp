@@ -25,6 +25,10 @@ template <> struct Elem<uint8_t> {
     static constexpr int kPerChunk = 16;
     using chunk_t = uint4;
 };
+template <> struct Elem<_Float16> {  // IEEE binary16 storage; every value converts exactly to fp32
+    static constexpr int kPerChunk = 8;
+    using chunk_t = uint4;
+};
 
 template <typename T, int G, int C> struct RowDist {
     static constexpr int PC = Elem<T>::kPerChunk;
@@ -109,19 +113,26 @@ template <typename T, int G, int C> struct RowDist {
         return *reinterpret_cast<const chunk_t*>(base + (size_t)row * (size_t)d + (size_t)(g + G * c) * PC);
     }
 
-    static __device__ __forceinline__ void unpack(const float4& x, float* out)
+    static __device__ __forceinline__ void unpack(const chunk_t& x, float* out)
     {
-        out[0] = x.x; out[1] = x.y; out[2] = x.z; out[3] = x.w;
-    }
-    static __device__ __forceinline__ void unpack(const uint4& x, float* out)
-    {
-        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+        if constexpr (sizeof(T) == 4) {
+            out[0] = x.x; out[1] = x.y; out[2] = x.z; out[3] = x.w;
+        } else if constexpr (sizeof(T) == 2) {
+            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            out[4 * i + 0] = (float)(w[i] & 0xFFu);
-            out[4 * i + 1] = (float)((w[i] >> 8) & 0xFFu);
-            out[4 * i + 2] = (float)((w[i] >> 16) & 0xFFu);
-            out[4 * i + 3] = (float)(w[i] >> 24);
+            for (int i = 0; i < 4; ++i) {
+                out[2 * i + 0] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[i] & 0xFFFFu));
+                out[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[i] >> 16));
+            }
+        } else {
+            const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                out[4 * i + 0] = (float)(w[i] & 0xFFu);
+                out[4 * i + 1] = (float)((w[i] >> 8) & 0xFFu);
+                out[4 * i + 2] = (float)((w[i] >> 16) & 0xFFu);
+                out[4 * i + 3] = (float)(w[i] >> 24);
+            }
         }
     }
 
@@ -237,6 +248,21 @@ template <typename F> inline bool dispatch_row_shape(ann_dtype dtype, int d, F&&
         TSDG_CASE(uint8_t, 8, 1) TSDG_CASE(uint8_t, 8, 2) TSDG_CASE(uint8_t, 8, 3) TSDG_CASE(uint8_t, 8, 4)
         TSDG_CASE(uint8_t, 16, 4)
     }
+#undef TSDG_CASE
+    return false;
+}
+
+// The search entry points also take rows stored as binary16 (8 elements per chunk); the build
+// kernels do not, so they keep dispatch_row_shape.
+template <typename F> inline bool dispatch_search_row_shape(ann_dtype dtype, int d, F&& f)
+{
+    if (dtype != ANN_F16) return dispatch_row_shape(dtype, d, f);
+    if (d <= 0 || d % 8 != 0) return false;
+    int G, C;
+    if (!pick_group(d / 8, &G, &C)) return false;
+#define TSDG_CASE(GG, CC) \
+    if (G == GG && C == CC) { f.template operator()<_Float16, GG, CC>(); return true; }
+    TSDG_CASE(8, 1) TSDG_CASE(8, 2) TSDG_CASE(8, 3) TSDG_CASE(8, 4) TSDG_CASE(16, 4) TSDG_CASE(32, 4) TSDG_CASE(64, 4)
 #undef TSDG_CASE
     return false;
 }

@@ -358,7 +358,7 @@ ann_status launch_search_multi(const MultiLaunch& s)
     disp.a.lambda_visit = s.lambda_visit;
     disp.nq = s.nq;
     disp.stream = s.stream;
-    if (!dispatch_row_shape(s.dtype, s.d, disp)) {
+    if (!dispatch_search_row_shape(s.dtype, s.d, disp)) {
         set_error("unsupported row shape: d=%d dtype=%d", s.d, (int)s.dtype);
         return ANN_EUNSUPPORTED;
     }

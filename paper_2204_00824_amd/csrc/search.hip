@@ -270,7 +270,7 @@ ann_status launch_search(const SearchLaunch& s)
 {
     if (s.nq == 0) return ANN_OK;
     SearchDispatch disp{s};
-    if (!dispatch_row_shape(s.dtype, s.d, disp)) {
+    if (!dispatch_search_row_shape(s.dtype, s.d, disp)) {
         set_error("unsupported row shape: d=%d dtype=%d (d must be a multiple of %d and at most %d)", s.d,
                   (int)s.dtype, s.dtype == ANN_U8 ? 16 : 4, s.dtype == ANN_U8 ? 1024 : 2048);
         return ANN_EUNSUPPORTED;

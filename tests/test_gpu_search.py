@@ -180,3 +180,32 @@ def test_probe_gather_reads_the_rows_it_is_given(gpu, row_bytes):
     words = tab.numpy().view(np.uint32)
     want = np.bitwise_xor.reduce(words[np.minimum(ids.numpy(), N - 1)], axis=1)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d", [8, 96, 128, 960])
+def test_binary16_storage(gpu, orc, d):
+    """Rows stored as binary16 (a storage type of the search calls): distances are the canonical ones
+    of the stored values, so every search agrees with the oracle run on the same binary16 rows."""
+    step(f"binary16 rows d={d}")
+    def make():
+        base, queries = workloads.single_gaussian(3000, d, seed=300 + d, nq=64)
+        h = base.astype(np.float16)
+        adj, lam = orc.build_graph(h, 16)
+        return h, queries, adj, lam
+    h, queries, adj, lam = cached(f"f16_{d}", make)
+    g = gpu.ann_graph_import(dev(adj), dev(lam), d)
+    hb = torch.from_numpy(h).cuda()
+    for mode in (1, 2):
+        ids, s = gpu.ann_search_ex(g, hb, dev(queries), 10, 40, mode=mode, lambda_visit=10)
+        ref = orc.search(adj, lam, h, queries, 10, 40, 10)
+        assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"f16 d={d} mode={mode}") == 0
+        assert_bitwise(s.cpu().numpy(), ref[1], f"f16 dists d={d}")
+    ids, s = gpu.ann_search_multi(g, hb, dev(queries[:16]), 10, 4, max_hops=5)
+    ref = orc.search_multi(adj, lam, h, queries[:16], 10, 4, max_hops=5)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "f16 multi") == 0
+    ids, s = gpu.ann_search_alg2(g, hb, dev(queries[:16]), 16, 0.0)
+    ref = orc.search_alg2(adj, lam, h, queries[:16], 16, 0.0)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "f16 alg2") == 0
+    with pytest.raises(gpu.AnnError):      # not a type the build takes
+        gpu.ann_build_graph_ex(hb, 8)

@@ -159,3 +159,23 @@ def test_recall_definition(orc):
     found = np.array([[4, 3, 9, -1], [8, 7, 6, 5]], np.int32)
     assert orc.recall(found, truth) == (2 + 4) / 8.0          # Eq. 3
     assert orc.recall(truth, truth) == 1.0
+
+
+def test_binary16_rows_convert_exactly_and_serve_as_base(orc):
+    """Rows stored as IEEE binary16: all 65,536 bit patterns convert like numpy's routine, and a base
+    set given in binary16 behaves exactly like the same values given in fp32."""
+    import ctypes as C
+    lib = orc.lib()
+    lib.orc_half_to_float.restype = C.c_float
+    lib.orc_half_to_float.argtypes = [C.c_uint16]
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float32)
+    got = np.array([lib.orc_half_to_float(int(b)) for b in bits], np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    base = workloads.single_gaussian(400, 16, seed=77).astype(np.float16)
+    q = workloads.single_gaussian(20, 16, seed=78)
+    a16 = orc.bruteforce(base, q, 7)
+    a32 = orc.bruteforce(base.astype(np.float32), q, 7)
+    assert np.array_equal(a16[0], a32[0]) and np.array_equal(a16[1], a32[1])
+    assert np.array_equal(orc.build_graph(base, 8)[0], orc.build_graph(base.astype(np.float32), 8)[0])
