@@ -45,7 +45,7 @@ struct DescentArgs {
     uint64_t* rnew;        // [N,S]
     uint64_t* rold;        // [N,S]
     const int32_t* init_ids;  // optional [N,K] start lists
-    unsigned long long* changed;  // [kChangedBins]
+    unsigned long long* changed;  // [2 * kChangedBins]: list entries changed, then rows scored
     uint64_t N;
     uint64_t seed;
     int d, K, S, log2s;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void fill_u64_kernel(uint64_t* p, int64_t n, u
 // Scores the ids in `id` (one per lane, `valid` lanes only), skipping those the hash has seen,
 // and merges them into list[0..K).  cid/ckey: 64 entries each.
 template <typename RD, typename T>
-__device__ __forceinline__ void score_and_merge(RD& rd, const T* __restrict__ base, uint32_t id, bool valid,
+__device__ __forceinline__ int score_and_merge(RD& rd, const T* __restrict__ base, uint32_t id, bool valid,
                                                 uint64_t* list, int K, uint64_t* ckey, uint32_t* cid,
                                                 uint32_t* table, int lane)
 {
@@ -71,7 +71,7 @@ __device__ __forceinline__ void score_and_merge(RD& rd, const T* __restrict__ ba
     if (valid) seen = visited_test_and_set(table, kDescentSlots, id);
     const uint64_t nm = ballot64(valid && !seen);
     const int m = popc64(nm);
-    if (m == 0) return;
+    if (m == 0) return 0;
     if (valid && !seen) cid[popc64(nm & lanes_below(lane))] = id;
     __syncthreads();
     for (int b0 = 0; b0 < m; b0 += VP) {
@@ -92,6 +92,7 @@ __device__ __forceinline__ void score_and_merge(RD& rd, const T* __restrict__ ba
     // the hash may have forgotten an id, so one call can carry the same candidate twice
     list_merge<false>(list, K, key, lane, [] { __syncthreads(); });
     __syncthreads();
+    return m;
 }
 
 // Start lists: 2K draws of the seed generator, self and repeats dropped, the first K kept, or
@@ -224,6 +225,7 @@ __global__ __launch_bounds__(64) void descent_join_kernel(DescentArgs a)
     __syncthreads();
 
     const bool one_pass = K + 2 * S <= 64;
+    int scored = 0;
     for (int q = 0; q < nsrc; ++q) {
         const uint32_t sv = src[q];
         const uint64_t v = sv >> 1;
@@ -248,12 +250,12 @@ __global__ __launch_bounds__(64) void descent_join_kernel(DescentArgs a)
                 id = (uint32_t)rr;
             }
             valid = valid && (uint64_t)id != v0;
-            score_and_merge(rd, base, id, valid, list, K, ckey, cid, table, lane);
+            scored += score_and_merge(rd, base, id, valid, list, K, ckey, cid, table, lane);
         } else {
             valid = valid && (uint64_t)id != v0;
-            score_and_merge(rd, base, id, valid, list, K, ckey, cid, table, lane);
+            scored += score_and_merge(rd, base, id, valid, list, K, ckey, cid, table, lane);
             const uint32_t id2 = (uint32_t)rr;
-            score_and_merge(rd, base, id2, rr != kRevEmpty && (uint64_t)id2 != v0, list, K, ckey, cid, table, lane);
+            scored += score_and_merge(rd, base, id2, rr != kRevEmpty && (uint64_t)id2 != v0, list, K, ckey, cid, table, lane);
         }
     }
 
@@ -269,6 +271,7 @@ __global__ __launch_bounds__(64) void descent_join_kernel(DescentArgs a)
         const int changed = nfin - stayed;
         if (lane == 0 && changed > 0) atomicAdd(&a.changed[v0 % kChangedBins], (unsigned long long)changed);
     }
+    if (lane == 0 && scored > 0) atomicAdd(&a.changed[kChangedBins + v0 % kChangedBins], (unsigned long long)scored);
 }
 
 __global__ __launch_bounds__(256) void descent_export_kernel(const uint64_t* __restrict__ keys, int64_t n,
@@ -310,7 +313,7 @@ ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int 
     if (e == hipSuccess) e = hipMalloc(&b1, nk * 8);
     if (e == hipSuccess) e = hipMalloc(&rnew, ns * 8);
     if (e == hipSuccess) e = hipMalloc(&rold, ns * 8);
-    if (e == hipSuccess) e = hipMalloc(&changed, kChangedBins * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMalloc(&changed, 2 * kChangedBins * sizeof(unsigned long long));
     if (e != hipSuccess) {
         release();
         set_error("hipMalloc of the neighbourhood-propagation buffers failed: %s", hipGetErrorString(e));
@@ -345,22 +348,27 @@ ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int 
     for (; it < max_iters; ++it) {
         hipLaunchKernelGGL(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rnew, (int64_t)ns, kRevEmpty);
         hipLaunchKernelGGL(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rold, (int64_t)ns, kRevEmpty);
-        hipLaunchKernelGGL(fill_u64_kernel, dim3((kChangedBins + 255) / 256), dim3(256), 0, stream,
-                           reinterpret_cast<uint64_t*>(changed), (int64_t)kChangedBins, 0ull);
+        hipLaunchKernelGGL(fill_u64_kernel, dim3((2 * kChangedBins + 255) / 256), dim3(256), 0, stream,
+                           reinterpret_cast<uint64_t*>(changed), (int64_t)(2 * kChangedBins), 0ull);
         L.a.cur = cur;
         L.a.next = nxt;
         hipLaunchKernelGGL(descent_reverse_kernel, folded_grid((N + 3) / 4), dim3(256), 0, stream, L.a);
         dispatch_row_shape(dtype, d, L);
-        unsigned long long h[kChangedBins];
+        unsigned long long h[2 * kChangedBins];
         hipError_t ce = hipMemcpyAsync(h, changed, sizeof(h), hipMemcpyDeviceToHost, stream);
         if (ce == hipSuccess) ce = hipStreamSynchronize(stream);
         if (ce == hipSuccess) ce = hipGetLastError();
         if (ce != hipSuccess) { set_error("neighbourhood propagation failed on the device: %s", hipGetErrorString(ce)); return fail(ANN_EDEVICE); }
         ch = 0;
-        for (int i = 0; i < kChangedBins; ++i) ch += (int64_t)h[i];
+        int64_t scored = 0;
+        for (int i = 0; i < kChangedBins; ++i) {
+            ch += (int64_t)h[i];
+            scored += (int64_t)h[kChangedBins + i];
+        }
         std::swap(cur, nxt);
         if (progress) {
-            fprintf(stderr, "[tsdg] neighbourhood propagation: iteration %d, %lld list entries changed\n", it + 1, (long long)ch);
+            fprintf(stderr, "[tsdg] neighbourhood propagation: iteration %d, %lld rows scored, %lld list entries changed\n",
+                    it + 1, (long long)scored, (long long)ch);
             fflush(stderr);
         }
         if ((double)ch <= (double)delta * (double)N * (double)K) { ++it; break; }
