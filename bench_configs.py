@@ -237,9 +237,32 @@ def run_whole_u8(args):
     print(json.dumps(out), flush=True)
 
 
+def run_descent_1m(args):
+    """The neighbourhood-propagation builder alone on the headline set (fp32 rows and the same rows as uint8)."""
+    import torch
+    import workloads
+    import paper_2204_00824_amd as P
+    N, K = args.n or 1_000_000, 32
+    base = torch.from_numpy(workloads.sift_like(N=N, nq=16)[0]).cuda()
+    exact = P.ann_knn(base, K)[0][:20000]
+    out = {"workload": f"sift-like N={N} d=128, K={K}, S=16, delta=0.001", "runs": []}
+    for x, name in ((base, "fp32"), (base.to(torch.uint8), "uint8")):
+        for rep in range(2):
+            torch.cuda.synchronize()
+            t0 = time.time()
+            ids, _, done, last = P.ann_knn_descent(x, K, S=16, max_iters=12, delta=0.001, seed=1)
+            torch.cuda.synchronize()
+            dt = time.time() - t0
+        rec = (ids[:20000].unsqueeze(2) == exact.unsqueeze(1)).any(dim=2).float().mean().item()
+        out["runs"].append({"rows": name, "seconds": round(dt, 3), "iterations": done, "last_changed": last,
+                            "list_recall_on_20000_rows": round(rec, 4)})
+        log(str(out["runs"][-1]))
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m"])
+    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m", "descent1m"])
     ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
     ap.add_argument("--iters", type=int, default=20, help="scale100m_one_graph: most iterations of the propagation")
     args = ap.parse_args()
@@ -255,6 +278,8 @@ def main():
         run_single_graph(args, "glove-like, cosine", base, q, (10,), (32, 64, 128, 256, 512), metric="cosine")
     elif args.workload == "scale100m_one_graph":
         run_whole_u8(args)
+    elif args.workload == "descent1m":
+        run_descent_1m(args)
     else:
         run_sharded_u8(args)
 
