@@ -3,14 +3,17 @@
 //
 // The squared distance is expanded as |q|^2 + |x|^2 - 2 q.x and the cross term is
 // a dense contraction on the matrix cores:
-//   * data that are integers in [0,255] (uint8 rows, SIFT-like fp32 rows) go
-//     through bf16 MFMA (v_mfma_f32_32x32x16_bf16): every product and every
-//     partial sum is an integer below 2^24, so the fp32 result is exact;
+//   * rows that are integers in [0,255] with d <= 128 (uint8 rows, SIFT-like fp32 rows) are
+//     centred to int8 and go through the integer matrix cores (v_mfma_i32_32x32x32_i8), exact;
+//     such rows with 128 < d <= 258 go through bf16 MFMA with both operands staged in LDS
+//     (every product and partial sum is an integer below 2^24, so that is exact too);
+//   * real-valued rows with d <= 128 are centred and split into bf16 hi + lo parts, three
+//     v_mfma_f32_32x32x16_bf16 per k-step, with an error near that of fp32 accumulation;
 //   * anything else goes through fp32 MFMA (v_mfma_f32_32x32x2_f32).
 // The contraction only SELECTS candidates: each query row keeps the K' = 2k
-// smallest approximate distances through a threshold filter fused into the tile
-// epilogue.  The base columns are swept in chunks of doubling size; after each
-// chunk a per-row pass sorts the row's buffer, keeps K' and lowers the row's
+// smallest approximate distances (K' = k + max(8, k/4) where the filter is exact) through a
+// threshold filter fused into the tile epilogue.  The base columns are swept in chunks of doubling
+// size; after each chunk a per-row pass keeps the K' smallest of the row's buffer and lowers the row's
 // threshold, so the expected number of survivors per chunk stays near K' ln 2.
 // The kept candidates are then re-scored with the canonical distance, sorted by
 // (s, id) and cut to k.  A row is accepted only if its k-th canonical distance
@@ -252,41 +255,50 @@ __global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
 }
 
 
-// ---------------------------------------------------------------- bf16 fast path (integer rows, d <= 128)
-// Rows are first rewritten as bf16 (exact for integers up to 255), padded to KS*16 elements.
-// One workgroup = 4 waves x 64 queries; each wave keeps the fragments of its 64 queries in
-// registers for the whole sweep, so only the candidate tile (64 rows) goes through LDS, double
-// buffered: the global loads of tile t+1 are in flight while tile t is multiplied.  Per tile and
-// wave: 2 candidate blocks x 2 query blocks x KS MFMAs (32x32x16), then the threshold filter.
+constexpr int kFastRows = 64;  // candidate rows per LDS tile
+constexpr int kQueue = 1024;    // survivor queue entries per workgroup
+
+// ---------------------------------------------------------------- int8 path (integer rows in [0,255], d <= 128)
+// The same sweep on the integer matrix cores (v_mfma_i32_32x32x32_i8: twice the rate of bf16 and
+// half the bytes per element in LDS).  Rows are rewritten once as x' = x - 128 (int8, padded with
+// zeros to 32-element steps); ||q - x||^2 = |q'|^2 + |x'|^2 - 2 q'.x' holds for the centred rows,
+// and all of it is exact in int32.  -2q' does not fit a byte, so the accumulators start at
+// -(|x'|^2 >> 1) and end as  a = q'.x' - (|x'|^2 >> 1), i.e.  u = |x'|^2 - 2 q'.x' = (|x'|^2 & 1) - 2a.
+// The hot test "some a above floor((|q'|^2 - tau) / 2)" lets every survivor through (it ignores
+// the parity bit); the rare path then tests u < tau - |q'|^2 exactly.
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+
+// 8 lanes per row: x' = x - 128 as packed bytes (zero beyond d), and |x'|^2
 template <typename T>
-__global__ __launch_bounds__(256) void to_bf16_kernel(const T* __restrict__ src, int64_t n, int d, int dp,
-                                                      uint16_t* __restrict__ dst)
+__global__ __launch_bounds__(256) void i8_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
+                                                      uint8_t* __restrict__ xc, int* __restrict__ norms)
 {
-    const int64_t i = linear_block() * blockDim.x + threadIdx.x;  // one 4-element group
-    const int groups = dp / 4;
-    if (i >= n * groups) return;
-    const int64_t r = i / groups;
-    const int c = (int)(i % groups) * 4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (c < d) v = load4(src + r * d + c);
-    const uint32_t lo = (uint32_t)bf16_bits(v.x) | ((uint32_t)bf16_bits(v.y) << 16);
-    const uint32_t hi = (uint32_t)bf16_bits(v.z) | ((uint32_t)bf16_bits(v.w) << 16);
-    *reinterpret_cast<uint2*>(dst + r * dp + c) = make_uint2(lo, hi);
+    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
+    const int g = (int)(threadIdx.x & 7);
+    int acc = 0;
+    if (row < n)
+        for (int j = 4 * g; j < dp; j += 32) {
+            uint32_t w = 0u;
+            if (j < d) {
+                const float4 v = load4(x + row * d + j);
+                const int c0 = (int)v.x - 128, c1 = (int)v.y - 128, c2 = (int)v.z - 128, c3 = (int)v.w - 128;
+                acc += c0 * c0 + c1 * c1 + c2 * c2 + c3 * c3;
+                w = (uint32_t)(c0 & 0xFF) | ((uint32_t)(c1 & 0xFF) << 8) | ((uint32_t)(c2 & 0xFF) << 16) |
+                    ((uint32_t)(c3 & 0xFF) << 24);
+            }
+            *reinterpret_cast<uint32_t*>(xc + row * dp + j) = w;
+        }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (row < n && g == 0) norms[row] = acc;
 }
 
-// two packed bf16 values, each multiplied by -2 (exact; zero stays zero)
-__device__ __forceinline__ uint32_t bf16x2_times_minus2(uint32_t w)
-{
-    const float lo = -2.f * __uint_as_float(w << 16);
-    const float hi = -2.f * __uint_as_float(w & 0xFFFF0000u);
-    return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
-}
-
-struct FastArgs {
-    const uint16_t* qb;   // [nq, DP] bf16 query rows (row 0 = first query of this sweep)
-    const uint16_t* xb;   // [N, DP] bf16 base rows
-    const float* qnorm;
-    const float* xnorm;
+struct I8Args {
+    const uint8_t* qc;    // [nq, DP] centred int8 query rows (row 0 = first query of this sweep)
+    const uint8_t* xc;    // [N, DP] centred int8 base rows
+    const int* qnorm;     // |q'|^2
+    const int* xnorm;     // |x'|^2
     const float* tau;
     unsigned* cnt;
     uint64_t* buf;
@@ -296,18 +308,16 @@ struct FastArgs {
     int cap, tiles_per_block;
 };
 
-constexpr int kFastRows = 64;  // candidate rows per LDS tile
-constexpr int kQueue = 1024;    // survivor queue entries per workgroup
-
 template <int KS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void filter_bf16_kernel(FastArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void filter_i8_kernel(I8Args a)
 {
-    constexpr int DP = KS * 16;
-    constexpr int XS = DP + 8;                       // LDS row stride (elements): 16-B aligned, staggers banks
-    constexpr int CHUNKS = kFastRows * DP / 8;       // 16-byte chunks per tile
+    constexpr int DP = KS * 32;                      // bytes per row
+    constexpr int XS = DP + 16;                      // LDS row stride (bytes): 16-B aligned, staggers banks
+    constexpr int CHUNKS = kFastRows * DP / 16;      // 16-byte chunks per tile
     constexpr int PER_THREAD = (CHUNKS + 255) / 256;
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][kFastRows * XS];
-    __shared__ __attribute__((aligned(16))) float xn[2][kFastRows];
+    __shared__ __attribute__((aligned(16))) uint8_t Xs[2][kFastRows * XS];
+    __shared__ __attribute__((aligned(16))) int xstart[2][kFastRows];   // -(|x'|^2 >> 1)
+    __shared__ int xpar[2][kFastRows];                                  // |x'|^2 & 1
     __shared__ uint64_t q_key[kQueue];
     __shared__ uint16_t q_row[kQueue];
     __shared__ unsigned q_cnt;
@@ -317,24 +327,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int64_t q0 = (int64_t)blockIdx.x * 256 + wave * 64;
     if (threadIdx.x == 0) q_cnt = 0u;
 
-    bf16x8 qf[2][KS];
+    intx4 qf[2][KS];
     int64_t qg[2];
-    float qn[2], tq[2];
+    int qn[2], tq[2], thr[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         qg[j] = q0 + j * 32 + (lane & 31);
         const bool ok = qg[j] < a.nq;
-        qn[j] = ok ? a.qnorm[qg[j]] : 0.f;
-        tq[j] = ok ? a.tau[qg[j]] - qn[j] : -kInf;   // survivors satisfy |x|^2 - 2 q.x < tau - |q|^2
+        qn[j] = ok ? a.qnorm[qg[j]] : 0;
+        // survivors satisfy u < tau - |q'|^2; tau is an integer-valued float or +inf
+        const float tf = ok ? a.tau[qg[j]] : -1.f;
+        tq[j] = ok ? (tf < 1.0e9f ? (int)tf - qn[j] : (1 << 30)) : -(1 << 30);
+        thr[j] = (-tq[j]) >> 1;                      // floor((|q'|^2 - tau) / 2)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            uint4 w = make_uint4(0u, 0u, 0u, 0u);
-            if (ok) w = *reinterpret_cast<const uint4*>(a.qb + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
-            // the query enters as -2q (exact: a power of two), so that with |x|^2 as the
-            // accumulator's start value the contraction itself yields |x|^2 - 2 q.x
-            w.x = bf16x2_times_minus2(w.x); w.y = bf16x2_times_minus2(w.y);
-            w.z = bf16x2_times_minus2(w.z); w.w = bf16x2_times_minus2(w.w);
-            qf[j][ks] = __builtin_bit_cast(bf16x8, w);
+            intx4 w = {0, 0, 0, 0};
+            if (ok) w = *reinterpret_cast<const intx4*>(a.qc + qg[j] * DP + ks * 32 + 16 * (lane >> 5));
+            qf[j][ks] = w;
         }
     }
 
@@ -346,31 +355,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
     struct Stage {
         u32x4 x[PER_THREAD];
-        float n;
+        int n;
     };
-    // A tile is one contiguous block of kFastRows * DP elements and this thread's chunks sit at
-    // fixed offsets inside it.  No branch: a chunk index past the span's end is clamped to the
-    // span's last chunk (rows read twice that way carry ids >= span1 and are dropped by the filter).
-    const uint16_t* xspan = a.xb + span0 * DP;
-    const int last_chunk = (int)(span1 - span0) * (DP / 8) - 1;
+    // A tile is one contiguous block of kFastRows * DP bytes and this thread's chunks sit at fixed
+    // offsets inside it.  No branch: a chunk index past the span's end is clamped to the span's
+    // last chunk (rows read twice that way carry ids >= span1 and are dropped by the filter).
+    const uint8_t* xspan = a.xc + span0 * DP;
+    const int last_chunk = (int)(span1 - span0) * (DP / 16) - 1;
     const int last_row = (int)(span1 - span0) - 1;
     auto fetch = [&](int t, Stage& st) __attribute__((always_inline)) {       // global -> registers
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int ch = min((int)threadIdx.x + i * 256, CHUNKS - 1);
-            st.x[i] = *reinterpret_cast<const u32x4*>(xspan + (int64_t)min(t * CHUNKS + ch, last_chunk) * 8);
+            st.x[i] = *reinterpret_cast<const u32x4*>(xspan + (int64_t)min(t * CHUNKS + ch, last_chunk) * 16);
         }
-        st.n = 0.f;
+        st.n = 0;
         if (threadIdx.x < kFastRows) st.n = a.xnorm[span0 + min(t * kFastRows + (int)threadIdx.x, last_row)];
     };
     auto commit = [&](int b, const Stage& st) __attribute__((always_inline)) {      // registers -> LDS buffer b
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int ch = (int)threadIdx.x + i * 256;
-            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
-            if (ch < CHUNKS) *reinterpret_cast<u32x4*>(&Xs[b][r * XS + c8 * 8]) = st.x[i];
+            const int r = ch / (DP / 16), c16 = ch % (DP / 16);
+            if (ch < CHUNKS) *reinterpret_cast<u32x4*>(&Xs[b][r * XS + c16 * 16]) = st.x[i];
         }
-        if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = st.n;
+        if (threadIdx.x < kFastRows) {
+            xstart[b][threadIdx.x] = -(st.n >> 1);
+            xpar[b][threadIdx.x] = st.n & 1;
+        }
     };
 
     // Two tiles of loads are in flight while one is multiplied: tile t sits in LDS buffer t & 1,
@@ -383,14 +395,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
     auto step = [&](int t, int cur, Stage& far, const Stage& near) __attribute__((always_inline)) {
         fetch(t + 2, far);
-        // the accumulators start at |x|^2 of their rows (lane l, register r holds row
-        // 8*(r/4) + 4*(l/32) + r%4 of the 32-row block), and the query fragments hold -2q
-        floatx16 acc[2][2];
+        // lane l, register r of a 32x32 block holds candidate row 8*(r/4) + 4*(l/32) + r%4
+        intx16 acc[2][2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                const intx4 v = *reinterpret_cast<const intx4*>(&xstart[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     acc[i][j][4 * r4 + 0] = v.x; acc[i][j][4 * r4 + 1] = v.y;
@@ -400,46 +411,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 xa[2];
+            intx4 xa[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                xa[i] = *reinterpret_cast<const bf16x8*>(&Xs[cur][(i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5)]);
+                xa[i] = *reinterpret_cast<const intx4*>(&Xs[cur][(i * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5)]);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qf[j][ks], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa[i], qf[j][ks], acc[i][j], 0, 0, 0);
         }
         const int64_t c0 = span0 + (int64_t)t * kFastRows;
-        // filter: u = |x|^2 - 2 q.x (exact: integers < 2^24, whatever the order of the sums);
-        // survivors have u < tau - |q|^2.  The smallest of a lane's 16 values is compared first
-        // (8 minima + 1 compare); the rare survivors go to a queue in LDS that is flushed to the
-        // per-query global buffers by the whole workgroup.
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                float lo = __builtin_fminf(acc[i][j][0], acc[i][j][1]);
+                int hi = max(acc[i][j][0], acc[i][j][1]);
 #pragma unroll
-                for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, acc[i][j][r]), acc[i][j][r + 1]);
-                if (ballot64(lo < tq[j])) {
+                for (int r = 2; r < 16; r += 2) hi = max(max(hi, acc[i][j][r]), acc[i][j][r + 1]);
+                if (ballot64(hi > thr[j])) {
                     uint32_t mask = 0;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mask |= (acc[i][j][r] < tq[j]) ? (1u << r) : 0u;
+                    for (int r = 0; r < 16; ++r) mask |= (acc[i][j][r] > thr[j]) ? (1u << r) : 0u;
                     // rare: walk the set bits; the accumulator is picked by a select chain so
                     // that the loop needs no indexed register access
 #pragma unroll 1
                     while (ballot64(mask != 0u)) {
                         const int rr = mask ? (int)__builtin_ctz(mask) : 16;
                         mask &= mask - 1u;
-                        float u = 0.f;
+                        int av = 0;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) u = rr == r ? acc[i][j][r] : u;
+                        for (int r = 0; r < 16; ++r) av = rr == r ? acc[i][j][r] : av;
                         const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                         const int64_t c = c0 + m;
-                        if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
+                        const int u = xpar[cur][m & (kFastRows - 1)] - 2 * av;   // |x'|^2 - 2 q'.x', exact
+                        if (rr < 16 && u < tq[j] && c < span1 && c != a.self_offset + qg[j]) {
                             const uint64_t key =
-                                ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                                ((uint64_t)__float_as_uint((float)max(u + qn[j], 0)) << 32) | (uint64_t)(uint32_t)c;
                             const unsigned slot = atomicAdd(&q_cnt, 1u);
                             if (slot < (unsigned)kQueue) {
                                 q_key[slot] = key;
@@ -474,7 +482,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         step(t + 1, 1, sa, sb);
     }
 }
-
 
 // ---------------------------------------------------------------- bf16 split path (real-valued rows, d <= 128)
 // A real-valued row is centred (global mean removed: distances do not change, norms shrink) and
@@ -1008,18 +1015,21 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // suffice, and every chunk then passes about kprime survivors per row instead of 2k.
     if (exact && d <= 128) kprime = std::min(kprime, k + std::max(8, k / 4));
 
-    // bf16 fast path: integer rows with d <= 128 are rewritten once as padded bf16
+    // int8 fast path: integer rows with d <= 128 are rewritten once as centred, padded int8
     const bool fast = exact && d <= 128;
-    const int ks = (d + 15) / 16, dp = ks * 16;
-    DevBuf xb, qb;
+    const int ks = (d + 15) / 16, dp = ks * 16;   // bf16 k-steps of the split path below
+    const int ks8 = (d + 31) / 32, dp8 = ks8 * 32;
+    DevBuf xc8, qc8, xn8, qn8;
     if (fast) {
-        TSDG_HIP(xb.alloc((size_t)N * dp * 2));
-        hipLaunchKernelGGL((to_bf16_kernel<TB>), folded_grid((N * (dp / 4) + 255) / 256), dim3(256), 0, stream,
-                           base, N, d, dp, xb.as<uint16_t>());
+        TSDG_HIP(xc8.alloc((size_t)N * dp8));
+        TSDG_HIP(xn8.alloc((size_t)N * 4));
+        hipLaunchKernelGGL((i8_prep_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dp8,
+                           xc8.as<uint8_t>(), xn8.as<int>());
         if (!self) {
-            TSDG_HIP(qb.alloc((size_t)nq * dp * 2));
-            hipLaunchKernelGGL((to_bf16_kernel<TQ>), folded_grid((nq * (dp / 4) + 255) / 256), dim3(256), 0,
-                               stream, queries, nq, d, dp, qb.as<uint16_t>());
+            TSDG_HIP(qc8.alloc((size_t)nq * dp8));
+            TSDG_HIP(qn8.alloc((size_t)nq * 4));
+            hipLaunchKernelGGL((i8_prep_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
+                               dp8, qc8.as<uint8_t>(), qn8.as<int>());
         }
         TSDG_HIP(hipGetLastError());
     }
@@ -1113,11 +1123,11 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             const int64_t tiles = (ce - cb + kTile - 1) / kTile;
             dim3 grid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((tiles + kTilesPerBlock - 1) / kTilesPerBlock));
             if (fast) {
-                FastArgs fa;
-                fa.qb = (self ? xb.as<uint16_t>() : qb.as<uint16_t>()) + r0 * dp;
-                fa.xb = xb.as<uint16_t>();
-                fa.qnorm = f.qnorm;
-                fa.xnorm = f.xnorm;
+                I8Args fa;
+                fa.qc = (self ? xc8.as<uint8_t>() : qc8.as<uint8_t>()) + r0 * dp8;
+                fa.xc = xc8.as<uint8_t>();
+                fa.qnorm = (self ? xn8.as<int>() : qn8.as<int>()) + r0;
+                fa.xnorm = xn8.as<int>();
                 fa.tau = f.tau;
                 fa.cnt = f.cnt;
                 fa.buf = f.buf;
@@ -1130,9 +1140,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 // long column spans per workgroup once there are enough workgroups to fill the chip
                 fa.tiles_per_block = (int)std::min<int64_t>((nr + 255) / 256 >= 2048 ? 128 : 32, ftiles);
                 dim3 fgrid((unsigned)((nr + 255) / 256), (unsigned)((ftiles + fa.tiles_per_block - 1) / fa.tiles_per_block));
-                switch (ks) {
-#define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_bf16_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
-                    TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
+                switch (ks8) {
+#define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_i8_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
+                    TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4)
 #undef TSDG_KS
                 }
             } else if (split) {
