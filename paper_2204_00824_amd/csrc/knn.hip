@@ -488,7 +488,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // written as x = hi + lo with hi = bf16(x), lo = bf16(x - hi), both round-to-nearest; what is
 // left is below 2^-16 |x|.  q.x is taken as hi.hi + hi.lo + lo.hi on the bf16 matrix cores
 // (three MFMAs per k-step, products exact in fp32), which is 16/3 times the fp32-MFMA rate at
-// nearly the same accuracy: |error of q.x| <= (3*2^-16 + 3d*2^-24) sum|q_j||x_j|.  The
+// nearly the same accuracy: |error of q.x| <= (3*2^-16 + 3d*2^-24) sum|q_j||x_j|; the
+// accumulators also carry |x|^2 from the start, which doubles the accumulation term.  The
 // result only SELECTS candidates; the acceptance test of the re-scoring pass carries the
 // bound.  One wave owns 32 queries (hi and lo fragments in registers), four waves share a
 // 64-row candidate tile (hi and lo) in LDS, double buffered.
@@ -544,6 +545,14 @@ __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x
     }
 }
 
+// two packed bf16 values, each multiplied by -2 (exact; zero stays zero)
+__device__ __forceinline__ uint32_t bf16x2_times_minus2(uint32_t w)
+{
+    const float lo = -2.f * __uint_as_float(w << 16);
+    const float hi = -2.f * __uint_as_float(w & 0xFFFF0000u);
+    return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
+}
+
 struct SplitArgs {
     const uint16_t* qh;   // [nq, DP] hi / lo parts of the centred query rows
     const uint16_t* ql;
@@ -591,6 +600,12 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
             wh = *reinterpret_cast<const uint4*>(a.qh + qg * DP + ks * 16 + 8 * (lane >> 5));
             wl = *reinterpret_cast<const uint4*>(a.ql + qg * DP + ks * 16 + 8 * (lane >> 5));
         }
+        // both parts of the query enter as -2q (exact), so that with |x|^2 as the accumulators'
+        // start value the contraction itself yields |x|^2 - 2 q.x
+        wh.x = bf16x2_times_minus2(wh.x); wh.y = bf16x2_times_minus2(wh.y);
+        wh.z = bf16x2_times_minus2(wh.z); wh.w = bf16x2_times_minus2(wh.w);
+        wl.x = bf16x2_times_minus2(wl.x); wl.y = bf16x2_times_minus2(wl.y);
+        wl.z = bf16x2_times_minus2(wl.z); wl.w = bf16x2_times_minus2(wl.w);
         qfh[ks] = __builtin_bit_cast(bf16x8, wh);
         qfl[ks] = __builtin_bit_cast(bf16x8, wl);
     }
@@ -600,31 +615,34 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     if (span0 >= span1) return;
     const int ntiles = (int)((span1 - span0 + kFastRows - 1) / kFastRows);
 
-    uint4 stage[2][PER_THREAD];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
+    u32x4 stage[2][PER_THREAD];
     float stage_n = 0.f;
-    auto fetch = [&](int t) {
-        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+    // A tile part is one contiguous block of kFastRows * DP elements; a chunk index past the span's
+    // end is clamped to the span's last chunk (rows read twice that way carry ids >= span1 and are
+    // dropped by the filter), so the loads need no branch.
+    const int last_chunk = (int)(span1 - span0) * (DP / 8) - 1;
+    const int last_row = (int)(span1 - span0) - 1;
+    const uint16_t* xh_span = a.xh + span0 * DP;
+    const uint16_t* xl_span = a.xl + span0 * DP;
+    auto fetch = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
-            const int ch = (int)threadIdx.x + i * 256;
-            const int r = ch / (DP / 8), c8 = ch % (DP / 8);
-            stage[0][i] = make_uint4(0u, 0u, 0u, 0u);
-            stage[1][i] = stage[0][i];
-            if (ch < CHUNKS && c0 + r < span1) {
-                stage[0][i] = *reinterpret_cast<const uint4*>(a.xh + (c0 + r) * DP + c8 * 8);
-                stage[1][i] = *reinterpret_cast<const uint4*>(a.xl + (c0 + r) * DP + c8 * 8);
-            }
+            const int ch = min((int)threadIdx.x + i * 256, CHUNKS - 1);
+            const int64_t off = (int64_t)min(t * CHUNKS + ch, last_chunk) * 8;
+            stage[0][i] = *reinterpret_cast<const u32x4*>(xh_span + off);
+            stage[1][i] = *reinterpret_cast<const u32x4*>(xl_span + off);
         }
-        if (threadIdx.x < kFastRows) stage_n = c0 + threadIdx.x < span1 ? a.xnorm[c0 + threadIdx.x] : 0.f;
+        if (threadIdx.x < kFastRows) stage_n = a.xnorm[span0 + min(t * kFastRows + (int)threadIdx.x, last_row)];
     };
-    auto commit = [&](int b) {
+    auto commit = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int ch = (int)threadIdx.x + i * 256;
             const int r = ch / (DP / 8), c8 = ch % (DP / 8);
             if (ch < CHUNKS) {
-                *reinterpret_cast<uint4*>(&Xs[b][0][r * XS + c8 * 8]) = stage[0][i];
-                *reinterpret_cast<uint4*>(&Xs[b][1][r * XS + c8 * 8]) = stage[1][i];
+                *reinterpret_cast<u32x4*>(&Xs[b][0][r * XS + c8 * 8]) = stage[0][i];
+                *reinterpret_cast<u32x4*>(&Xs[b][1][r * XS + c8 * 8]) = stage[1][i];
             }
         }
         if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = stage_n;
@@ -635,12 +653,17 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const int cur = t & 1;
-        if (t + 1 < ntiles) fetch(t + 1);
+        fetch(t + 1);  // clamped: past the last tile it re-reads the span's end, unused
+        // the accumulators start at |x|^2 of their rows (lane l, register r: row 8*(r/4) + 4*(l/32) + r%4)
         floatx16 acc[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                acc[i][4 * r4 + 0] = v.x; acc[i][4 * r4 + 1] = v.y; acc[i][4 * r4 + 2] = v.z; acc[i][4 * r4 + 3] = v.w;
+            }
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
@@ -656,36 +679,23 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
         const int64_t c0 = span0 + (int64_t)t * kFastRows;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            float xv[16];
+            float lo = __builtin_fminf(acc[i][0], acc[i][1]);
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
-            }
-            float um[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) um[r] = __builtin_fmaf(-2.f, acc[i][r], xv[r]);
-            float lo = __builtin_fminf(um[0], um[1]);
-#pragma unroll
-            for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, um[r]), um[r + 1]);
+            for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, acc[i][r]), acc[i][r + 1]);
             if (ballot64(lo < tq)) {
                 uint32_t mask = 0;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mask |= (um[r] < tq) ? (1u << r) : 0u;
+                for (int r = 0; r < 16; ++r) mask |= (acc[i][r] < tq) ? (1u << r) : 0u;
 #pragma unroll 1
                 while (ballot64(mask != 0u)) {
                     const int rr = mask ? (int)__builtin_ctz(mask) : 16;
                     mask &= mask - 1u;
-                    float av = 0.f, xr = 0.f;
+                    float u = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        av = rr == r ? acc[i][r] : av;
-                        xr = rr == r ? xv[r] : xr;
-                    }
+                    for (int r = 0; r < 16; ++r) u = rr == r ? acc[i][r] : u;
                     const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                     const int64_t c = c0 + m;
                     if (rr < 16 && c < span1 && c != a.self_offset + qg) {
-                        const float u = __builtin_fmaf(-2.f, av, xr);
                         const uint64_t key =
                             ((uint64_t)__float_as_uint(fmaxf(u + qn, 0.f)) << 32) | (uint64_t)(uint32_t)c;
                         const unsigned slot = atomicAdd(&q_cnt, 1u);
@@ -1070,7 +1080,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     }
     // rounding-error bound of the split expansion, as a multiple of (|q|^2 + max|x|^2) of the centred rows:
     // dropped terms 3*2^-16, fp32 accumulation over 3*dp products, norms and centring a few 2^-24
-    const float split_err = (float)(1.05 * (3.0 / 65536.0 + (3.0 * dp + 32.0) * 5.9604645e-8));
+    // (the accumulation term is doubled because the accumulators also carry |x|^2 from the start)
+    const float split_err = (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
 
     const char* prog_env = getenv("TSDG_PROGRESS");
     const bool progress = prog_env && prog_env[0] == '1';
