@@ -108,6 +108,16 @@ def normalize_rows(x):
     return out
 
 
+def ip_augment_rows(x, M=0.0, is_query=False):
+    """Rows for the inner-product measure by its reduction to L2: [x, sqrt(M^2 - |x|^2), 0, 0, 0] for
+    base rows (M >= every base norm), [q, 0, 0, 0, 0] for queries."""
+    x = _c(x, np.float32)
+    out = np.empty((x.shape[0], x.shape[1] + 4), np.float32)
+    _check(lib().orc_ip_augment_rows(_p(x), C.c_int64(x.shape[0]), x.shape[1], C.c_float(M), int(bool(is_query)),
+                                     _p(out)), "ip_augment_rows")
+    return out
+
+
 def stage1(base, knn_id, knn_s, alpha, threads=0, metric="l2"):
     base = _c(base)
     knn_id = _c(knn_id, np.int32)

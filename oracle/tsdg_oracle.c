@@ -281,6 +281,33 @@ int orc_normalize_rows(const float* src, int64_t n, int d, float* dst)
 }
 
 /* ------------------------------------------------------------------------
+ * Inner product (Table 1 lists m = IP for one dataset; the paper says no more).
+ * Reading: the standard reduction of maximum-inner-product search to L2.  With
+ * M >= every base norm, a base row x becomes [x, sqrt(M^2 - |x|^2), 0, 0, 0]
+ * and a query q becomes [q, 0, 0, 0, 0] (d + 4 columns, so rows stay 16-byte
+ * multiples); then  s(q~, x~) = |q|^2 + M^2 - 2 <q,x>,  which orders the base
+ * rows of one query exactly as -<q,x> does, and the graph is the L2 graph of
+ * the augmented rows.  extra = fl32( sqrt( max(0, (double)M*M - sum (double)x_j^2) ) ).
+ * ---------------------------------------------------------------------- */
+int orc_ip_augment_rows(const float* src, int64_t n, int d, float M, int is_query, float* dst)
+{
+    if (!src || !dst || n < 0 || d <= 0 || (!is_query && !(M > 0.0f))) return 1;
+    const int dp = d + 4;
+    for (int64_t i = 0; i < n; ++i) {
+        double ss = 0.0;
+        for (int j = 0; j < d; ++j) {
+            dst[i * dp + j] = src[i * d + j];
+            ss += (double)src[i * d + j] * (double)src[i * d + j];
+        }
+        double rest = (double)M * (double)M - ss;
+        if (rest < 0.0) rest = 0.0;
+        dst[i * dp + d] = is_query ? 0.0f : (float)sqrt(rest);
+        dst[i * dp + d + 1] = dst[i * dp + d + 2] = dst[i * dp + d + 3] = 0.0f;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
  * Reverse edges (Sec. 3.3, second sentence): list(x0) = kept(x0) united with
  * { y : x0 in kept(y) }.  Reading where the paper is silent: duplicates are
  * removed by id, the list is sorted by (s,id) with s = s(x0,y) computed

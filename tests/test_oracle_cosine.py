@@ -91,3 +91,26 @@ def test_stage1_is_eq2_on_one_minus_cos(orc, alpha):
     if alpha > 1.0:   # the factor is alpha, not alpha^2: the L2 rule on the same unit rows keeps more
         l2_deg = orc.stage1(base, knn_id, knn_s, alpha, metric="l2")[2]
         assert l2_deg.sum() > g1_deg.sum()
+
+
+def test_inner_product_by_its_reduction_to_l2(orc):
+    """Table 1's m = IP: on the augmented rows the L2 order of the base rows of a query is the order of
+    -<q,x> computed in fp64 from the raw rows, and the inner product is recovered from the distance."""
+    base, q = workloads.glove_like(N=700, nq=30, d=20, components=1, seed=8)
+    M = np.float32(np.sqrt((base.astype(np.float64) ** 2).sum(1).max()) * 1.0001)
+    ab, aq = orc.ip_augment_rows(base, M), orc.ip_augment_rows(q, is_query=True)
+    assert ab.shape == (700, 24) and np.array_equal(ab[:, :20], base) and (ab[:, 21:] == 0).all() and (aq[:, 20:] == 0).all()
+    assert np.abs((ab.astype(np.float64) ** 2).sum(1) - float(M) ** 2).max() < 1e-4 * float(M) ** 2   # all on the sphere of radius M
+    ids, s = orc.bruteforce(ab, aq, 10)
+    ip = q.astype(np.float64) @ base.astype(np.float64).T
+    scale = np.abs(ip).max()
+    for i in range(q.shape[0]):
+        order = np.argsort(-ip[i], kind="stable")[:10]
+        got_ip = ((q[i].astype(np.float64) ** 2).sum() + float(M) ** 2 - s[i].astype(np.float64)) / 2
+        assert np.abs(got_ip - ip[i][ids[i]]).max() < 2e-6 * (float(M) ** 2 + scale)
+        if not np.array_equal(ids[i], order):
+            assert np.abs(ip[i][ids[i]] - ip[i][order]).max() < 2e-6 * (float(M) ** 2 + scale)
+    # a row as long as M gets no extra coordinate; a longer one is clamped, not NaN
+    two = np.array([[3.0, 4.0, 0.0, 0.0], [6.0, 8.0, 0.0, 0.0]], np.float32)
+    out = orc.ip_augment_rows(two, 5.0)
+    assert out[0, 4] == 0.0 and out[1, 4] == 0.0 and not np.isnan(out).any()
