@@ -203,6 +203,17 @@ ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, i
 ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d);
 void ann_graph_free(ann_graph* graph);
 
+/* Inner product (Table 1, m = IP) by the standard reduction of maximum-inner-product search to L2:
+ * with M >= every base norm a base row x becomes [x, sqrt(M^2 - |x|^2), 0, 0, 0] and a query q
+ * becomes [q, 0, 0, 0, 0]; on these rows of d + 4 columns s = |q|^2 + M^2 - 2<q,x>, so every build
+ * and search call with ANN_L2 ranks by -<q,x>, and <q,x> = (|q|^2 + M^2 - s) / 2.
+ * ann_max_row_norm writes the largest row norm fl32(sqrt(sum x^2 in fp64)) of src[n,d] to *M (host;
+ * the call synchronises `stream`).  ann_ip_augment_rows writes dst[n, d+4] (device, 16-byte aligned;
+ * not in place); is_query = 0 needs M > 0, and a row longer than M gets 0 as its extra coordinate.
+ * src: device fp32 rows, d a multiple of 4, d + 4 <= 2048. */
+ann_status ann_max_row_norm(const float* src, int64_t n, int d, void* stream, float* M);
+ann_status ann_ip_augment_rows(const float* src, int64_t n, int d, float M, int is_query, float* dst, void* stream);
+
 /* Approximate k-NN lists by neighbourhood propagation (the published NN-descent idea in a form
  * where every node pulls its candidates from the previous iteration's lists, so the result does
  * not depend on execution order; the paper starts from "an approximate k-NN graph", Sec. 3, and

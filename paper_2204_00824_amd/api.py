@@ -70,11 +70,13 @@ def load_library():
     L.ann_graph_free.argtypes = [vp]
     L.ann_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
     L.ann_normalize_rows.argtypes = [vp, i64, i32, vp, vp]
+    L.ann_max_row_norm.argtypes = [vp, i64, i32, vp, C.POINTER(C.c_float)]
+    L.ann_ip_augment_rows.argtypes = [vp, i64, i32, C.c_float, i32, vp, vp]
     L.ann_knn_descent.argtypes = [vp, i64, i32, i32, i32, i32, i32, C.c_float, u64, vp, vp, vp, vp,
                                   C.POINTER(i32), C.POINTER(i64)]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_normalize_rows", "ann_knn_descent"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_normalize_rows", "ann_knn_descent", "ann_max_row_norm", "ann_ip_augment_rows"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -320,6 +322,21 @@ def ann_normalize_rows(x: torch.Tensor, out: torch.Tensor = None, stream=None) -
         out = torch.empty_like(x)
     _check(load_library().ann_normalize_rows(src, x.shape[0], x.shape[1], _dev(out, torch.float32, "out"),
                                              _stream_ptr(stream)))
+    return out
+
+
+def ann_max_row_norm(x: torch.Tensor, stream=None) -> float:
+    M = C.c_float(0.0)
+    _check(load_library().ann_max_row_norm(_dev(x, torch.float32, "x"), x.shape[0], x.shape[1], _stream_ptr(stream),
+                                           C.byref(M)))
+    return M.value
+
+
+def ann_ip_augment_rows(x: torch.Tensor, M: float = 0.0, is_query: bool = False, stream=None) -> torch.Tensor:
+    """Rows for the inner-product measure by its reduction to L2 (d + 4 columns)."""
+    out = torch.empty((x.shape[0], x.shape[1] + 4), dtype=torch.float32, device=x.device)
+    _check(load_library().ann_ip_augment_rows(_dev(x, torch.float32, "x"), x.shape[0], x.shape[1], C.c_float(M),
+                                              int(bool(is_query)), out.data_ptr(), _stream_ptr(stream)))
     return out
 
 

@@ -190,6 +190,39 @@ __global__ __launch_bounds__(256) void normalize_kernel(const float* __restrict_
         }
 }
 
+// Inner product by its reduction to L2: 8 lanes per row copy the row and append
+// sqrt(max(0, M^2 - |x|^2)) (0 for queries) and three zeros; maxbits (optional) collects the
+// largest squared norm as fp32 bits (non-negative floats order like unsigned integers).
+__global__ __launch_bounds__(256) void ip_augment_kernel(const float* __restrict__ src, int64_t n, int d, float M,
+                                                         int is_query, float* __restrict__ dst, unsigned* maxbits)
+{
+    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
+    const int g = (int)(threadIdx.x & 7);
+    double acc = 0.0;
+    if (row < n)
+        for (int j = 4 * g; j < d; j += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(src + row * d + j);
+            acc += (double)v.x * (double)v.x;
+            acc += (double)v.y * (double)v.y;
+            acc += (double)v.z * (double)v.z;
+            acc += (double)v.w * (double)v.w;
+            if (dst) *reinterpret_cast<float4*>(dst + row * (d + 4) + j) = v;
+        }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    if (row < n && g == 0) {
+        if (dst) {
+            const double rest = (double)M * (double)M - acc;
+            const float extra = is_query ? 0.f : (float)sqrt(rest > 0.0 ? rest : 0.0);
+            *reinterpret_cast<float4*>(dst + row * (d + 4) + d) = make_float4(extra, 0.f, 0.f, 0.f);
+        }
+        if (maxbits) {
+            const unsigned b = __float_as_uint((float)sqrt(acc));
+            if (b > *maxbits) atomicMax(maxbits, b);
+        }
+    }
+}
+
 // Batch size from which one wavefront per query fills the GPU (256 CUs x 32 wave slots).
 constexpr int kLargeBatchThreshold = 2048;
 
@@ -424,6 +457,45 @@ ann_status ann_knn_descent(const void* base, int64_t N, int d, int K, ann_dtype 
     if (!knn_ids || !knn_dists) { set_error("ann_knn_descent: null output"); return ANN_EINVAL; }
     return knn_descent(base, N, d, dtype, K, S, max_iters, delta, seed, init_ids, static_cast<hipStream_t>(stream),
                        knn_ids, knn_dists, iters_done, last_changed);
+}
+
+ann_status ann_max_row_norm(const float* src, int64_t n, int d, void* stream, float* M)
+{
+    g_err[0] = 0;
+    if (!M) { set_error("ann_max_row_norm: null output"); return ANN_EINVAL; }
+    ann_status rc = check_rows(src, n, d, ANN_F32, "ann_max_row_norm");
+    if (rc != ANN_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned* bits = nullptr;
+    TSDG_HIP(hipMalloc(&bits, sizeof(unsigned)));
+    hipError_t e = hipMemsetAsync(bits, 0, sizeof(unsigned), st);
+    unsigned h = 0;
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(ip_augment_kernel, folded_grid((n + 31) / 32), dim3(256), 0, st, src, n, d, 0.f, 1,
+                           static_cast<float*>(nullptr), bits);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, bits, sizeof(h), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(bits);
+    if (e != hipSuccess) { set_error("ann_max_row_norm failed on the device: %s", hipGetErrorString(e)); return ANN_EDEVICE; }
+    std::memcpy(M, &h, sizeof(float));
+    return ANN_OK;
+}
+
+ann_status ann_ip_augment_rows(const float* src, int64_t n, int d, float M, int is_query, float* dst, void* stream)
+{
+    g_err[0] = 0;
+    if (n == 0) return ANN_OK;
+    ann_status rc = check_rows(src, n, d, ANN_F32, "ann_ip_augment_rows");
+    if (rc != ANN_OK) return rc;
+    if (d + 4 > 2048) { set_error("ann_ip_augment_rows: d + 4 must not exceed 2048"); return ANN_EUNSUPPORTED; }
+    if (!dst || !aligned16(dst) || dst == src) { set_error("ann_ip_augment_rows: dst must be another 16-byte aligned device buffer"); return ANN_EINVAL; }
+    if (!is_query && !(M > 0.f)) { set_error("ann_ip_augment_rows: base rows need M > 0"); return ANN_EINVAL; }
+    hipLaunchKernelGGL(ip_augment_kernel, folded_grid((n + 31) / 32), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       src, n, d, M, is_query ? 1 : 0, dst, static_cast<unsigned*>(nullptr));
+    TSDG_HIP(hipGetLastError());
+    return ANN_OK;
 }
 
 ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, void* stream)

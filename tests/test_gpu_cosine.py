@@ -95,3 +95,32 @@ def test_cosine_needs_fp32_rows(gpu):
     base = torch.randint(0, 255, (512, 32), dtype=torch.uint8, device="cuda")
     with pytest.raises(gpu.AnnError):
         gpu.ann_build_graph_ex(base, 8, metric="cosine")
+
+
+def test_inner_product_by_reduction_to_l2(gpu, orc):
+    step("inner product: augmented rows, build + search on them, ranking by <q,x>")
+    base, q = workloads.glove_like(N=3000, nq=100, d=100, components=24, seed=32)
+    M = gpu.ann_max_row_norm(dev(base))
+    assert M == np.float32(np.sqrt((base.astype(np.float64) ** 2).sum(1).max()))
+    ab = gpu.ann_ip_augment_rows(dev(base), M)
+    aq = gpu.ann_ip_augment_rows(dev(q), is_query=True)
+    ab_o, aq_o = orc.ip_augment_rows(base, M), orc.ip_augment_rows(q, is_query=True)
+    assert np.array_equal(aq.cpu().numpy(), aq_o)
+    assert np.abs(ab.cpu().numpy().astype(np.float64) - ab_o).max() <= 1e-6 * M      # the fp64 sum is formed in another order
+    assert (ab.cpu().numpy() != ab_o).any(axis=1).sum() <= 3
+    # from here on both sides work on the oracle's rows
+    adj_o, lam_o = orc.build_graph(ab_o, 16)
+    g = gpu.ann_build_graph_ex(dev(ab_o), 16)
+    adj, lam = gpu.ann_graph_export(g)
+    assert (adj.cpu().numpy() != adj_o).any(axis=1).sum() <= 0.01 * 3000
+    g = gpu.ann_graph_import(dev(adj_o), dev(lam_o), 104)
+    ids, s = gpu.ann_search_ex(g, dev(ab_o), dev(aq_o), 10, 64, mode=1, lambda_visit=10)
+    ref = orc.search(adj_o, lam_o, ab_o, aq_o, 10, 64, 10)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "ip search") == 0
+    ip = q.astype(np.float64) @ base.astype(np.float64).T
+    truth = np.argsort(-ip, axis=1)[:, :10].astype(np.int32)
+    assert orc.recall(ids.cpu().numpy(), truth) > 0.9
+    got_ip = ((q.astype(np.float64) ** 2).sum(1)[:, None] + float(M) ** 2 - s.cpu().numpy().astype(np.float64)) / 2
+    assert np.abs(got_ip - np.take_along_axis(ip, ids.cpu().numpy().astype(np.int64), 1)).max() < 1e-5 * float(M) ** 2
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_ip_augment_rows(dev(base))            # base rows need M
