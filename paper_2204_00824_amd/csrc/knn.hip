@@ -308,16 +308,18 @@ struct I8Args {
     int cap, tiles_per_block;
 };
 
+constexpr int kI8Rows = 128;  // candidate rows per LDS tile of the int8 kernel (two 64-row halves per barrier)
+
 template <int KS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void filter_i8_kernel(I8Args a)
 {
     constexpr int DP = KS * 32;                      // bytes per row
     constexpr int XS = DP + 16;                      // LDS row stride (bytes): 16-B aligned, staggers banks
-    constexpr int CHUNKS = kFastRows * DP / 16;      // 16-byte chunks per tile
+    constexpr int CHUNKS = kI8Rows * DP / 16;      // 16-byte chunks per tile
     constexpr int PER_THREAD = (CHUNKS + 255) / 256;
-    __shared__ __attribute__((aligned(16))) uint8_t Xs[2][kFastRows * XS];
-    __shared__ __attribute__((aligned(16))) int xstart[2][kFastRows];   // -(|x'|^2 >> 1)
-    __shared__ int xpar[2][kFastRows];                                  // |x'|^2 & 1
+    __shared__ __attribute__((aligned(16))) uint8_t Xs[2][kI8Rows * XS];
+    __shared__ __attribute__((aligned(16))) int xstart[2][kI8Rows];   // -(|x'|^2 >> 1)
+    __shared__ int xpar[2][kI8Rows];                                  // |x'|^2 & 1
     __shared__ uint64_t q_key[kQueue];
     __shared__ uint16_t q_row[kQueue];
     __shared__ unsigned q_cnt;
@@ -347,17 +349,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
     }
 
-    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kFastRows;
-    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kFastRows);
+    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kI8Rows;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kI8Rows);
     if (span0 >= span1) return;
-    const int ntiles = (int)((span1 - span0 + kFastRows - 1) / kFastRows);
+    const int ntiles = (int)((span1 - span0 + kI8Rows - 1) / kI8Rows);
 
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
     struct Stage {
         u32x4 x[PER_THREAD];
         int n;
     };
-    // A tile is one contiguous block of kFastRows * DP bytes and this thread's chunks sit at fixed
+    // A tile is one contiguous block of kI8Rows * DP bytes and this thread's chunks sit at fixed
     // offsets inside it.  No branch: a chunk index past the span's end is clamped to the span's
     // last chunk (rows read twice that way carry ids >= span1 and are dropped by the filter).
     const uint8_t* xspan = a.xc + span0 * DP;
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             st.x[i] = *reinterpret_cast<const u32x4*>(xspan + (int64_t)min(t * CHUNKS + ch, last_chunk) * 16);
         }
         st.n = 0;
-        if (threadIdx.x < kFastRows) st.n = a.xnorm[span0 + min(t * kFastRows + (int)threadIdx.x, last_row)];
+        if (threadIdx.x < kI8Rows) st.n = a.xnorm[span0 + min(t * kI8Rows + (int)threadIdx.x, last_row)];
     };
     auto commit = [&](int b, const Stage& st) __attribute__((always_inline)) {      // registers -> LDS buffer b
 #pragma unroll
@@ -379,89 +381,91 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             const int r = ch / (DP / 16), c16 = ch % (DP / 16);
             if (ch < CHUNKS) *reinterpret_cast<u32x4*>(&Xs[b][r * XS + c16 * 16]) = st.x[i];
         }
-        if (threadIdx.x < kFastRows) {
+        if (threadIdx.x < kI8Rows) {
             xstart[b][threadIdx.x] = -(st.n >> 1);
             xpar[b][threadIdx.x] = st.n & 1;
         }
     };
 
-    // Two tiles of loads are in flight while one is multiplied: tile t sits in LDS buffer t & 1,
-    // tile t+1 waits in the registers of one stage, and the loads of tile t+2 go to the other
-    // stage.  Fetches past the last tile are clamped re-reads that nobody uses.
-    Stage sa, sb;
-    fetch(0, sa);
-    commit(0, sa);
-    fetch(1, sa);
+    // The loads of tile t+1 are in flight while tile t (in LDS buffer t & 1) is multiplied.
+    // Fetches past the last tile are clamped re-reads that nobody uses.
+    Stage st;
+    fetch(0, st);
+    commit(0, st);
     __syncthreads();
-    auto step = [&](int t, int cur, Stage& far, const Stage& near) __attribute__((always_inline)) {
-        fetch(t + 2, far);
-        // lane l, register r of a 32x32 block holds candidate row 8*(r/4) + 4*(l/32) + r%4
-        intx16 acc[2][2];
+    for (int t = 0; t < ntiles; ++t) {
+        const int cur = t & 1;
+        fetch(t + 1, st);
+        for (int h = 0; h < kI8Rows / 64; ++h) {   // the tile's 64-row halves, one after the other
+            // lane l, register r of a 32x32 block holds candidate row 8*(r/4) + 4*(l/32) + r%4
+            intx16 acc[2][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const intx4 v = *reinterpret_cast<const intx4*>(&xstart[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const intx4 v = *reinterpret_cast<const intx4*>(&xstart[cur][h * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc[i][j][4 * r4 + 0] = v.x; acc[i][j][4 * r4 + 1] = v.y;
-                    acc[i][j][4 * r4 + 2] = v.z; acc[i][j][4 * r4 + 3] = v.w;
+                    for (int j = 0; j < 2; ++j) {
+                        acc[i][j][4 * r4 + 0] = v.x; acc[i][j][4 * r4 + 1] = v.y;
+                        acc[i][j][4 * r4 + 2] = v.z; acc[i][j][4 * r4 + 3] = v.w;
+                    }
                 }
             }
-        }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            intx4 xa[2];
+            for (int ks = 0; ks < KS; ++ks) {
+                intx4 xa[2];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                xa[i] = *reinterpret_cast<const intx4*>(&Xs[cur][(i * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5)]);
+                for (int i = 0; i < 2; ++i)
+                    xa[i] = *reinterpret_cast<const intx4*>(
+                        &Xs[cur][(h * 64 + i * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5)]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa[i], qf[j][ks], acc[i][j], 0, 0, 0);
-        }
-        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xa[i], qf[j][ks], acc[i][j], 0, 0, 0);
+            }
+            const int64_t c0 = span0 + (int64_t)t * kI8Rows + h * 64;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                int hi = max(acc[i][j][0], acc[i][j][1]);
+                for (int j = 0; j < 2; ++j) {
+                    int hi = max(acc[i][j][0], acc[i][j][1]);
 #pragma unroll
-                for (int r = 2; r < 16; r += 2) hi = max(max(hi, acc[i][j][r]), acc[i][j][r + 1]);
-                if (ballot64(hi > thr[j])) {
-                    uint32_t mask = 0;
+                    for (int r = 2; r < 16; r += 2) hi = max(max(hi, acc[i][j][r]), acc[i][j][r + 1]);
+                    if (ballot64(hi > thr[j])) {
+                        uint32_t mask = 0;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mask |= (acc[i][j][r] > thr[j]) ? (1u << r) : 0u;
-                    // rare: walk the set bits; the accumulator is picked by a select chain so
-                    // that the loop needs no indexed register access
+                        for (int r = 0; r < 16; ++r) mask |= (acc[i][j][r] > thr[j]) ? (1u << r) : 0u;
+                        // rare: walk the set bits; the accumulator is picked by a select chain so
+                        // that the loop needs no indexed register access
 #pragma unroll 1
-                    while (ballot64(mask != 0u)) {
-                        const int rr = mask ? (int)__builtin_ctz(mask) : 16;
-                        mask &= mask - 1u;
-                        int av = 0;
+                        while (ballot64(mask != 0u)) {
+                            const int rr = mask ? (int)__builtin_ctz(mask) : 16;
+                            mask &= mask - 1u;
+                            int av = 0;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) av = rr == r ? acc[i][j][r] : av;
-                        const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
-                        const int64_t c = c0 + m;
-                        const int u = xpar[cur][m & (kFastRows - 1)] - 2 * av;   // |x'|^2 - 2 q'.x', exact
-                        if (rr < 16 && u < tq[j] && c < span1 && c != a.self_offset + qg[j]) {
-                            const uint64_t key =
-                                ((uint64_t)__float_as_uint((float)max(u + qn[j], 0)) << 32) | (uint64_t)(uint32_t)c;
-                            const unsigned slot = atomicAdd(&q_cnt, 1u);
-                            if (slot < (unsigned)kQueue) {
-                                q_key[slot] = key;
-                                q_row[slot] = (uint16_t)(wave * 64 + j * 32 + (lane & 31));
-                            } else {  // queue full: straight to the global buffer
-                                const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
-                                if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
+                            for (int r = 0; r < 16; ++r) av = rr == r ? acc[i][j][r] : av;
+                            const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
+                            const int64_t c = c0 + m;
+                            const int u = xpar[cur][(h * 64 + m) & (kI8Rows - 1)] - 2 * av;   // |x'|^2 - 2 q'.x', exact
+                            if (rr < 16 && u < tq[j] && c < span1 && c != a.self_offset + qg[j]) {
+                                const uint64_t key =
+                                    ((uint64_t)__float_as_uint((float)max(u + qn[j], 0)) << 32) | (uint64_t)(uint32_t)c;
+                                const unsigned slot = atomicAdd(&q_cnt, 1u);
+                                if (slot < (unsigned)kQueue) {
+                                    q_key[slot] = key;
+                                    q_row[slot] = (uint16_t)(wave * 64 + j * 32 + (lane & 31));
+                                } else {  // queue full: straight to the global buffer
+                                    const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
+                                    if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
+                                }
                             }
                         }
                     }
                 }
             }
         }
-        if (t + 1 < ntiles) commit(cur ^ 1, near);
+        if (t + 1 < ntiles) commit(cur ^ 1, st);
         __syncthreads();
         const unsigned queued = q_cnt;
         if (queued >= (unsigned)kQueue / 2 || (t + 1 == ntiles && queued > 0)) {
@@ -475,11 +479,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             if (threadIdx.x == 0) q_cnt = 0u;
             __syncthreads();
         }
-    };
-    for (int t = 0; t < ntiles; t += 2) {
-        step(t, 0, sb, sa);
-        if (t + 1 >= ntiles) break;
-        step(t + 1, 1, sa, sb);
     }
 }
 
@@ -741,7 +740,8 @@ struct CompactArgs {
 };
 
 // One wavefront cuts a row's unsorted candidate buffer (more than kprime entries, R = capacity / 64 per
-// lane, already loaded into e[], unused slots holding the empty key) down to kprime entries with the smallest distances and returns
+// lane, already loaded into e[], unused slots holding the empty key) down to kprime entries with
+// the smallest distances and returns
 // the kprime-th smallest distance D, the row's new threshold.  D is found by bisection on the
 // distance's bit pattern (non-negative floats order like unsigned integers) with wave-wide counts;
 // entries below D all stay and of those equal to D as many as still fit (the dropped ones are not
@@ -1147,9 +1147,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 fa.c_end = ce;
                 fa.self_offset = f.self_offset;
                 fa.cap = cap;
-                const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
+                const int64_t ftiles = (ce - cb + kI8Rows - 1) / kI8Rows;
                 // long column spans per workgroup once there are enough workgroups to fill the chip
-                fa.tiles_per_block = (int)std::min<int64_t>((nr + 255) / 256 >= 2048 ? 128 : 32, ftiles);
+                fa.tiles_per_block = (int)std::min<int64_t>((nr + 255) / 256 >= 2048 ? 64 : 16, ftiles);
                 dim3 fgrid((unsigned)((nr + 255) / 256), (unsigned)((ftiles + fa.tiles_per_block - 1) / fa.tiles_per_block));
                 switch (ks8) {
 #define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_i8_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
