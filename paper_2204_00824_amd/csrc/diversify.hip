@@ -13,6 +13,7 @@
 #include <algorithm>
 
 #include "dist.hpp"
+#include "i8rows.hpp"
 #include "ranklist.hpp"
 
 namespace tsdg {
@@ -56,6 +57,50 @@ __device__ __forceinline__ void pairwise(RD& rd, const T* __restrict__ base, con
     }
 }
 
+// The same matrix for rows that are integers in [0,255], m <= 64: the list's rows (centred int8) are
+// gathered into LDS once and their Gram matrix comes from the integer matrix cores; s(x_i, x_j) =
+// |x_i'|^2 + |x_j'|^2 - 2 x_i'.x_j' is exact in int32, and its conversion to fp32 is the canonical
+// value (an exact sum rounded once).  rows: [64][dp8 + 16] bytes, nrm: [64]; one wavefront.
+struct I8Rows {
+    const uint8_t* xc8;   // [N, dp8] centred rows, or null: use the general routine
+    const int* xn8;       // [N] |x'|^2
+    int dp8;
+};
+__device__ __forceinline__ void pairwise_i8(const I8Rows& x, const int32_t* ids, int m, float* P, int stride,
+                                            uint8_t* rows, int* nrm, int lane)
+{
+    const int XS = x.dp8 + 16;
+    const int cpr = x.dp8 / 16;  // 16-byte chunks per row
+    for (int c = lane; c < 64 * cpr; c += 64) {
+        const int r = c / cpr, k = c % cpr;
+        intx4 v = {0, 0, 0, 0};
+        if (r < m) v = *reinterpret_cast<const intx4*>(x.xc8 + (size_t)ids[r] * x.dp8 + k * 16);
+        *reinterpret_cast<intx4*>(rows + r * XS + k * 16) = v;
+    }
+    nrm[lane] = lane < m ? x.xn8[ids[lane]] : 0;
+    __syncthreads();
+    for (int blk = 0; blk < 3; ++blk) {  // 32x32 blocks (0,0), (0,1), (1,1) of the upper triangle
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+        if (bj * 32 >= m) continue;
+        intx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0;
+        for (int ks = 0; ks < x.dp8 / 32; ++ks) {
+            const intx4 A = *reinterpret_cast<const intx4*>(rows + (bi * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5));
+            const intx4 B = *reinterpret_cast<const intx4*>(rows + (bj * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5));
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A, B, acc, 0, 0, 0);
+        }
+        // lane l, register r: row i = 8*(r/4) + 4*(l/32) + r%4 of block bi, column j = l%32 of block bj
+        const int j = bj * 32 + (lane & 31);
+        const int nj = nrm[j];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = bi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (i < j && j < m) P[i * stride + j] = (float)(nrm[i] + nj - 2 * acc[r]);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ stage 1
 struct Stage1Args {
     const void* base;
@@ -68,6 +113,7 @@ struct Stage1Args {
     int64_t N;
     int d, K;
     float alpha2;
+    I8Rows i8;
 };
 
 template <typename T, int G, int C>
@@ -95,9 +141,15 @@ __global__ __launch_bounds__(64) void stage1_kernel(Stage1Args a)
     const uint64_t used = ballot64(id >= 0);
     const int m = used ? 64 - __builtin_clzll(used) : 0;   // lists are prefixes
     __syncthreads();
-    RD rd;
-    rd.init(a.d, lane);
-    pairwise(rd, base, ids, m, P, K);
+    if (a.i8.xc8) {
+        int* nrm = reinterpret_cast<int*>(ids + K);
+        uint8_t* rows = reinterpret_cast<uint8_t*>(sm) + ((((size_t)K * K + 2 * (size_t)K + 64) * 4 + 15) & ~(size_t)15);
+        pairwise_i8(a.i8, ids, m, P, K, rows, nrm, lane);
+    } else {
+        RD rd;
+        rd.init(a.d, lane);
+        pairwise(rd, base, ids, m, P, K);
+    }
     __syncthreads();
 
     // sequential scan: lane i answers "does kept edge i occlude edge j"
@@ -267,6 +319,7 @@ struct Stage2Args {
     int* max_lambda;
     int64_t N;
     int d, K, rev_cap, lambda0;
+    I8Rows i8;
 };
 
 template <typename T, int G, int C>
@@ -290,9 +343,15 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     }
     for (int i = lane; i < a.K; i += 64) a.packed[x0 * a.K + i] = kPackPad;
     __syncthreads();
-    RD rd;
-    rd.init(a.d, lane);
-    pairwise(rd, base, ids, m, P, R);
+    if (a.i8.xc8) {
+        int* nrm = lam + R;
+        uint8_t* rows = reinterpret_cast<uint8_t*>(sm) + ((((size_t)R * R + 3 * (size_t)R + 64) * 4 + 15) & ~(size_t)15);
+        pairwise_i8(a.i8, ids, m, P, R, rows, nrm, lane);
+    } else {
+        RD rd;
+        rd.init(a.d, lane);
+        pairwise(rd, base, ids, m, P, R);
+    }
     __syncthreads();
 
     // lambda_j (Eq. 1, counted over the whole list, strict comparisons)
@@ -342,7 +401,8 @@ struct Stage1Launch {
     hipError_t err = hipSuccess;
     template <typename T, int G, int C> void operator()()
     {
-        const size_t lds = (size_t)a.K * a.K * 4 + (size_t)a.K * 8;
+        size_t lds = (size_t)a.K * a.K * 4 + (size_t)a.K * 8;
+        if (a.i8.xc8) lds = ((lds + 64 * 4 + 15) & ~(size_t)15) + 64 * (size_t)(a.i8.dp8 + 16);
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage1_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -355,7 +415,8 @@ struct Stage2Launch {
     hipError_t err = hipSuccess;
     template <typename T, int G, int C> void operator()()
     {
-        const size_t lds = (size_t)a.rev_cap * a.rev_cap * 4 + (size_t)a.rev_cap * 12;
+        size_t lds = (size_t)a.rev_cap * a.rev_cap * 4 + (size_t)a.rev_cap * 12;
+        if (a.i8.xc8) lds = ((lds + 64 * 4 + 15) & ~(size_t)15) + 64 * (size_t)(a.i8.dp8 + 16);
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage2_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -383,6 +444,31 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     TSDG_HIP(hipMemsetAsync(cursor.p, 0, (size_t)N * 4, stream));
     TSDG_HIP(hipMemsetAsync(mlam.p, 0, 4, stream));
 
+    // Rows that are integers in [0,255] (uint8 storage, or fp32 that passes the test) with lists of at
+    // most 64 entries take their pairwise distances from the int8 matrix cores.
+    DevBuf xc8, xn8, notint;
+    I8Rows i8{nullptr, nullptr, 0};
+    const int dp8 = (d + 31) / 32 * 32;
+    if (K <= 64 && rev_cap <= 64 && dp8 <= 256) {
+        TSDG_HIP(xc8.alloc((size_t)N * dp8));
+        TSDG_HIP(xn8.alloc((size_t)N * 4));
+        TSDG_HIP(notint.alloc(4));
+        TSDG_HIP(hipMemsetAsync(notint.p, 0, 4, stream));
+        if (dtype == ANN_U8)
+            hipLaunchKernelGGL((i8_prep_kernel<uint8_t>), folded_grid((N + 31) / 32), dim3(256), 0, stream,
+                               static_cast<const uint8_t*>(base), N, d, dp8, xc8.as<uint8_t>(), xn8.as<int>(),
+                               notint.as<unsigned>());
+        else
+            hipLaunchKernelGGL((i8_prep_kernel<float>), folded_grid((N + 31) / 32), dim3(256), 0, stream,
+                               static_cast<const float*>(base), N, d, dp8, xc8.as<uint8_t>(), xn8.as<int>(),
+                               notint.as<unsigned>());
+        TSDG_HIP(hipGetLastError());
+        unsigned h_notint = 1;
+        TSDG_HIP(hipMemcpyAsync(&h_notint, notint.p, 4, hipMemcpyDeviceToHost, stream));
+        TSDG_HIP(hipStreamSynchronize(stream));
+        if (h_notint == 0) i8 = I8Rows{xc8.as<uint8_t>(), xn8.as<int>(), dp8};
+    }
+
     // stage 1
     Stage1Launch s1;
     s1.a.base = base;
@@ -396,6 +482,7 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s1.a.d = d;
     s1.a.K = K;
     s1.a.alpha2 = alpha_on_s;
+    s1.a.i8 = i8;
     s1.stream = stream;
     if (!dispatch_row_shape(dtype, d, s1)) {
         set_error("unsupported row shape d=%d", d);
@@ -454,6 +541,7 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s2.a.K = K;
     s2.a.rev_cap = rev_cap;
     s2.a.lambda0 = lambda0;
+    s2.a.i8 = i8;
     s2.stream = stream;
     dispatch_row_shape(dtype, d, s2);
     TSDG_HIP(s2.err);

@@ -27,6 +27,7 @@
 #include <cstring>
 
 #include "dist.hpp"
+#include "i8rows.hpp"
 #include "ranklist.hpp"
 
 namespace tsdg {
@@ -266,34 +267,6 @@ constexpr int kQueue = 1024;    // survivor queue entries per workgroup
 // -(|x'|^2 >> 1) and end as  a = q'.x' - (|x'|^2 >> 1), i.e.  u = |x'|^2 - 2 q'.x' = (|x'|^2 & 1) - 2a.
 // The hot test "some a above floor((|q'|^2 - tau) / 2)" lets every survivor through (it ignores
 // the parity bit); the rare path then tests u < tau - |q'|^2 exactly.
-typedef int intx4 __attribute__((ext_vector_type(4)));
-typedef int intx16 __attribute__((ext_vector_type(16)));
-
-// 8 lanes per row: x' = x - 128 as packed bytes (zero beyond d), and |x'|^2
-template <typename T>
-__global__ __launch_bounds__(256) void i8_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
-                                                      uint8_t* __restrict__ xc, int* __restrict__ norms)
-{
-    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
-    const int g = (int)(threadIdx.x & 7);
-    int acc = 0;
-    if (row < n)
-        for (int j = 4 * g; j < dp; j += 32) {
-            uint32_t w = 0u;
-            if (j < d) {
-                const float4 v = load4(x + row * d + j);
-                const int c0 = (int)v.x - 128, c1 = (int)v.y - 128, c2 = (int)v.z - 128, c3 = (int)v.w - 128;
-                acc += c0 * c0 + c1 * c1 + c2 * c2 + c3 * c3;
-                w = (uint32_t)(c0 & 0xFF) | ((uint32_t)(c1 & 0xFF) << 8) | ((uint32_t)(c2 & 0xFF) << 16) |
-                    ((uint32_t)(c3 & 0xFF) << 24);
-            }
-            *reinterpret_cast<uint32_t*>(xc + row * dp + j) = w;
-        }
-#pragma unroll
-    for (int o = 4; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (row < n && g == 0) norms[row] = acc;
-}
-
 struct I8Args {
     const uint8_t* qc;    // [nq, DP] centred int8 query rows (row 0 = first query of this sweep)
     const uint8_t* xc;    // [N, DP] centred int8 base rows
@@ -1034,12 +1007,12 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(xc8.alloc((size_t)N * dp8));
         TSDG_HIP(xn8.alloc((size_t)N * 4));
         hipLaunchKernelGGL((i8_prep_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dp8,
-                           xc8.as<uint8_t>(), xn8.as<int>());
+                           xc8.as<uint8_t>(), xn8.as<int>(), static_cast<unsigned*>(nullptr));
         if (!self) {
             TSDG_HIP(qc8.alloc((size_t)nq * dp8));
             TSDG_HIP(qn8.alloc((size_t)nq * 4));
             hipLaunchKernelGGL((i8_prep_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
-                               dp8, qc8.as<uint8_t>(), qn8.as<int>());
+                               dp8, qc8.as<uint8_t>(), qn8.as<int>(), static_cast<unsigned*>(nullptr));
         }
         TSDG_HIP(hipGetLastError());
     }
