@@ -176,15 +176,9 @@ template <typename T, int G, int C> struct RowDist {
                         }
                     }
                 }
-                // this lane's share of sum (q-x)^2 (non-negative); chunks the lane does not own
-                // contribute neither q^2 nor x^2
-                uint32_t part = xx - 2u * qx;
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (FULL || has(c))
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            part = __builtin_amdgcn_udot4(qbytes[c * 4 + i], qbytes[c * 4 + i], part, false);
+                // this lane's share of sum (q-x)^2 (non-negative).  qq is the lane's sum of q^2 kept since
+                // pack_query: slices of chunks the lane does not own are zero there, as they are in xx and qx
+                const uint32_t part = xx - 2u * qx + qq;
                 return (float)group_sum_u32(part);
             }
         }
