@@ -56,6 +56,37 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
         vm = ballot64(valid);
     }
 
+    if (L <= 64) {
+        // One block: a single pass over the candidates yields everything.  Candidate j is broadcast;
+        // the list entries below it give r_j, the candidates below it give t_j (lane j keeps their sum,
+        // its position in the merged list), and every lane counts the candidates above its own entry,
+        // which leaves u = (candidates) - (that count) places to move up.  A candidate already in the
+        // list is rare and sends the call down the general path below, which has touched nothing yet.
+        const uint64_t a = lane < L ? list[lane] : kKeyEmpty;
+        const uint64_t am1 = a | 1ull;
+        int pos = 0, above = 0, n = 0;
+        bool present = false;
+        for (uint64_t m = vm; m; m &= m - 1) {
+            const int j = ctz64(m);
+            const uint64_t kj = readlane64(kk, j);
+            const bool lt = am1 < kj;
+            const uint64_t lt_m = ballot64(lt);
+            present = present || ballot64(am1 == kj) != 0ull;
+            const uint64_t tb_m = ballot64(valid && kk < kj);
+            above += lt ? 1 : 0;
+            pos = lane == j ? popc64(lt_m) + popc64(tb_m) : pos;
+            ++n;
+        }
+        if (!present) {
+            const int u = n - above;
+            sync();
+            if (lane < L && u > 0 && lane + u < L) list[lane + u] = a;
+            if (valid && pos < L) list[pos] = key;
+            sync();
+            return;
+        }
+    }
+
     const int top = ((L - 1) / 64) * 64;
     int r = 0;
     bool dup = false;
