@@ -579,11 +579,14 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
 
     // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds,
     // and 1,024 slots measured fastest for every L (a smaller set re-scores more rows, a larger
-    // one lowers occupancy); a workgroup per query has LDS to spare.
+    // one lowers occupancy); a workgroup per query has LDS to spare, and a batch that leaves
+    // most CUs with one workgroup takes the largest set that still pays (fewer rows scored twice).
     int slots = p.visited_slots;
     if (slots == 0) {
         if (mode == 1) {
             slots = 1024;
+        } else if (nq <= 512) {
+            slots = 8192;
         } else {
             slots = pow2_at_least(16 * L);
             if (slots < 1024) slots = 1024;
