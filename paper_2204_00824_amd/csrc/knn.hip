@@ -5,11 +5,11 @@
 // a dense contraction on the matrix cores:
 //   * rows that are integers in [0,255] with d <= 128 (uint8 rows, SIFT-like fp32 rows) are
 //     centred to int8 and go through the integer matrix cores (v_mfma_i32_32x32x32_i8), exact;
-//     such rows with 128 < d <= 258 go through bf16 MFMA with both operands staged in LDS
-//     (every product and partial sum is an integer below 2^24, so that is exact too);
-//   * real-valued rows with d <= 128 are centred and split into bf16 hi + lo parts, three
-//     v_mfma_f32_32x32x16_bf16 per k-step, with an error near that of fp32 accumulation;
-//   * anything else goes through fp32 MFMA (v_mfma_f32_32x32x2_f32).
+//     such rows with d > 128 go through bf16 MFMA with both operands staged in LDS (the values are
+//     exact in bf16 and up to d = 258 so is every partial sum; beyond, fp32 accumulation rounds);
+//   * real-valued rows are centred and split into bf16 hi + lo parts, three
+//     v_mfma_f32_32x32x16_bf16 per k-step, with an error near that of fp32 accumulation: with the
+//     query fragments in registers up to d = 128, with both operands staged through LDS beyond.
 // The contraction only SELECTS candidates: each query row keeps the K' = 2k
 // smallest approximate distances (K' = k + max(8, k/4) where the filter is exact) through a
 // threshold filter fused into the tile epilogue.  The base columns are swept in chunks of doubling
@@ -93,37 +93,26 @@ __device__ __forceinline__ float4 load4(const uint8_t* p)
 // exact for values representable in bf16 (integers up to 255 are)
 __device__ __forceinline__ uint16_t bf16_bits(float v) { return (uint16_t)(__float_as_uint(v) >> 16); }
 
-template <bool BF16> struct TileCfg;
-template <> struct TileCfg<true> {
+struct TileCfg {
     static constexpr int DK = 64;            // k extent of a staged tile
     static constexpr int STRIDE = DK + 8;    // in elements (144 B rows, 16-B aligned fragments)
     using elem_t = uint16_t;
 };
-template <> struct TileCfg<false> {
-    static constexpr int DK = 16;
-    static constexpr int STRIDE = DK + 1;    // 17 floats: fragment reads hit distinct banks
-    using elem_t = float;
-};
 
 // Stages rows [r0, r0+128) x columns [k0, k0+DK) of src (zero beyond nrows / d) into LDS.
-template <bool BF16, typename T>
-__device__ __forceinline__ void stage_tile(typename TileCfg<BF16>::elem_t* lds, const T* __restrict__ src,
+template <typename T>
+__device__ __forceinline__ void stage_tile(TileCfg::elem_t* lds, const T* __restrict__ src,
                                            int64_t r0, int64_t nrows, int d, int k0)
 {
-    using Cfg = TileCfg<BF16>;
+    using Cfg = TileCfg;
     constexpr int CH = Cfg::DK / 4;  // 4-element chunks per row
     for (int ch = (int)threadIdx.x; ch < kTile * CH; ch += 256) {
         const int r = ch / CH, c4 = (ch % CH) * 4;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (r0 + r < nrows && k0 + c4 < d) v = load4(src + (r0 + r) * (int64_t)d + k0 + c4);
-        typename Cfg::elem_t* out = lds + r * Cfg::STRIDE + c4;
-        if constexpr (BF16) {
-            const uint32_t lo = (uint32_t)bf16_bits(v.x) | ((uint32_t)bf16_bits(v.y) << 16);
-            const uint32_t hi = (uint32_t)bf16_bits(v.z) | ((uint32_t)bf16_bits(v.w) << 16);
-            *reinterpret_cast<uint2*>(out) = make_uint2(lo, hi);
-        } else {
-            out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
-        }
+        const uint32_t lo = (uint32_t)bf16_bits(v.x) | ((uint32_t)bf16_bits(v.y) << 16);
+        const uint32_t hi = (uint32_t)bf16_bits(v.z) | ((uint32_t)bf16_bits(v.w) << 16);
+        *reinterpret_cast<uint2*>(lds + r * Cfg::STRIDE + c4) = make_uint2(lo, hi);
     }
 }
 
@@ -146,11 +135,11 @@ struct FilterArgs {
 // fragment is the A operand and the query fragment the B operand, so that the 16
 // accumulators a lane holds per block all belong to ONE query (column lane%32) and the
 // query's threshold and norm sit in that lane's registers.
-template <bool BF16, typename TQ, typename TB>
+template <typename TQ, typename TB>
 __global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
 {
-    using Cfg = TileCfg<BF16>;
-    using elem_t = typename Cfg::elem_t;
+    using Cfg = TileCfg;
+    using elem_t = Cfg::elem_t;
     __shared__ __attribute__((aligned(16))) elem_t Qs[kTile * Cfg::STRIDE];
     __shared__ __attribute__((aligned(16))) elem_t Xs[kTile * Cfg::STRIDE];
     __shared__ float xn[kTile];
@@ -186,45 +175,27 @@ __global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
 
         for (int k0 = 0; k0 < a.d; k0 += Cfg::DK) {
             __syncthreads();
-            stage_tile<BF16, TQ>(Qs, Q, q0, a.nq, a.d, k0);
-            stage_tile<BF16, TB>(Xs, X, c0, a.c_end, a.d, k0);
+            stage_tile<TQ>(Qs, Q, q0, a.nq, a.d, k0);
+            stage_tile<TB>(Xs, X, c0, a.c_end, a.d, k0);
             if (k0 == 0 && threadIdx.x < kTile) {
                 const int64_t c = c0 + threadIdx.x;
                 xn[threadIdx.x] = c < a.c_end ? a.xnorm[c] : 0.f;
             }
             __syncthreads();
-            if constexpr (BF16) {
 #pragma unroll
-                for (int ks = 0; ks < Cfg::DK / 16; ++ks) {
-                    const int ko = ks * 16 + 8 * (lane >> 5);
-                    bf16x8 xa[2], qb[2];
+            for (int ks = 0; ks < Cfg::DK / 16; ++ks) {
+                const int ko = ks * 16 + 8 * (lane >> 5);
+                bf16x8 xa[2], qb[2];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        xa[i] = *reinterpret_cast<const bf16x8*>(&Xs[(wc * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
-                        qb[i] = *reinterpret_cast<const bf16x8*>(&Qs[(wq * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
-                    }
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qb[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < 2; ++i) {
+                    xa[i] = *reinterpret_cast<const bf16x8*>(&Xs[(wc * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
+                    qb[i] = *reinterpret_cast<const bf16x8*>(&Qs[(wq * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
                 }
-            } else {
 #pragma unroll
-                for (int ks = 0; ks < Cfg::DK / 2; ++ks) {
-                    const int ko = ks * 2 + (lane >> 5);
-                    float xa[2], qb[2];
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        xa[i] = Xs[(wc * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko];
-                        qb[i] = Qs[(wq * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko];
-                    }
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], qb[j], acc[i][j], 0, 0, 0);
-                }
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qb[j], acc[i][j], 0, 0, 0);
             }
         }
 
@@ -699,6 +670,216 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     }
 }
 
+// ---------------------------------------------------------------- bf16 split path, d > 128
+// The same hi + lo contraction when a query's fragments no longer fit the registers: both
+// operands go through LDS in slabs of 32 elements of the k dimension, double buffered, with
+// the loads of slab g+1 in flight during the MFMAs of slab g.  One workgroup owns a tile of
+// 128 queries x 128 candidates (4 waves, 64 x 64 each = 2 x 2 blocks of 32 x 32, 12 MFMAs per
+// 16 elements of k); the filter runs once per tile, after the last slab, so it is amortised
+// over d / 16 k-steps and needs none of the tricks of the register kernels: u = |x|^2 - 2 q.x
+// is formed from the finished accumulators.
+// LDS rows are 64 bytes with no padding; the 16-byte chunk c of row r is stored at chunk
+// c ^ ((r >> 2) & 3), which spreads the 16 rows a fragment read touches per cycle over all banks.
+// Workgroups are numbered so that those resident together form a block of q_group query tiles
+// times a few candidate spans: the slabs they stream are then shared through the L2 caches
+// instead of each being fetched from memory once per workgroup.
+constexpr int kWideDK = 32;
+
+struct WideArgs {
+    SplitArgs s;
+    int dp;            // padded row length (multiple of kWideDK)
+    int q_tiles, ny;   // query tiles of 128 rows; candidate spans of tiles_per_block tiles
+    int q_group;       // query tiles per group of the block numbering
+};
+
+__device__ __forceinline__ int wide_lds_offset(int row, int chunk)
+{
+    return row * kWideDK + ((chunk ^ ((row >> 2) & 3)) << 3);
+}
+
+__global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
+{
+    const SplitArgs& a = w.s;
+    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][4][128 * kWideDK]: qh, ql, xh, xl
+    __shared__ __attribute__((aligned(16))) float xn[2][kTile];
+    __shared__ uint64_t q_key[kSplitQueue];
+    __shared__ uint16_t q_row[kSplitQueue];
+    __shared__ unsigned q_cnt;
+    constexpr int PART = kTile * kWideDK;   // elements of one operand part of a slab
+
+    // block numbering: groups of q_group query tiles, inside a group the query tile varies fastest
+    const int64_t b = linear_block();
+    if (b >= (int64_t)w.q_tiles * w.ny) return;
+    const int64_t per_group = (int64_t)w.q_group * w.ny;
+    const int64_t grp = b / per_group, within = b - grp * per_group;
+    const int gq = (int)min((int64_t)w.q_group, (int64_t)w.q_tiles - grp * w.q_group);
+    const int64_t q0 = (grp * w.q_group + within % gq) * kTile;
+    const int64_t y = within / gq;
+
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int wq = wave >> 1, wc = wave & 1;
+    if (threadIdx.x == 0) q_cnt = 0u;
+
+    int64_t qg[2];
+    float qn[2], tq[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        qg[j] = q0 + wq * 64 + j * 32 + (lane & 31);
+        const bool ok = qg[j] < a.nq;
+        qn[j] = ok ? a.qnorm[qg[j]] : 0.f;
+        tq[j] = ok ? a.tau[qg[j]] - qn[j] : -kInf;
+    }
+
+    const int64_t span0 = a.c_begin + y * a.tiles_per_block * kTile;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kTile);
+    if (span0 >= span1) return;
+    const int ntiles = (int)((span1 - span0 + kTile - 1) / kTile);
+    const int nstage = w.dp / kWideDK;
+    const int G = ntiles * nstage;
+
+    // this thread's share of a slab: chunk (threadIdx & 3) of rows r and r + 64 of all four parts
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int fr = (int)(threadIdx.x >> 2), fc = (int)(threadIdx.x & 3);
+    const int64_t qrow[2] = {min(q0 + fr, a.nq - 1), min(q0 + fr + 64, a.nq - 1)};   // clamped: rows past the end are
+    const int last_row = (int)(span1 - span0) - 1;                                   // re-reads whose results are dropped
+    u32x4 st[4][2];
+    float st_n = 0.f;
+    auto fetch = [&](int t, int sg) __attribute__((always_inline)) {
+        const int ko = sg * kWideDK + fc * 8;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int64_t xr = span0 + min(t * kTile + fr + h * 64, last_row);
+            st[0][h] = *reinterpret_cast<const u32x4*>(a.qh + qrow[h] * w.dp + ko);
+            st[1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
+            st[2][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
+            st[3][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
+        }
+        if (threadIdx.x < kTile) st_n = a.xnorm[span0 + min(t * kTile + (int)threadIdx.x, last_row)];
+    };
+    auto commit = [&](int buf, int t, int sg) __attribute__((always_inline)) {
+        uint16_t* slab = wide_slabs + buf * 4 * PART;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                *reinterpret_cast<u32x4*>(slab + p * PART + wide_lds_offset(fr + h * 64, fc)) = st[p][h];
+        if (sg == 0 && threadIdx.x < kTile) xn[t & 1][threadIdx.x] = st_n;
+    };
+
+    floatx16 acc[2][2];
+    int t = 0, sg = 0;       // slab being multiplied
+    int tn = 0, sn = 0;      // slab being fetched
+    fetch(0, 0);
+    commit(0, 0, 0);
+    __syncthreads();
+    for (int g = 0; g < G; ++g) {
+        const int cur = g & 1;
+        const bool more = g + 1 < G;
+        if (more && ++sn == nstage) { sn = 0; ++tn; }
+        fetch(tn, sn);   // past the last slab this re-reads it, unused
+        if (sg == 0) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        }
+        const uint16_t* slab = wide_slabs + cur * 4 * PART;
+#pragma unroll
+        for (int k16 = 0; k16 < kWideDK / 16; ++k16) {
+            const int chunk = k16 * 2 + (lane >> 5);
+            bf16x8 qh[2], ql[2], xh[2], xl[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int qo = wide_lds_offset(wq * 64 + i * 32 + (lane & 31), chunk);
+                const int xo = wide_lds_offset(wc * 64 + i * 32 + (lane & 31), chunk);
+                qh[i] = *reinterpret_cast<const bf16x8*>(slab + 0 * PART + qo);
+                ql[i] = *reinterpret_cast<const bf16x8*>(slab + 1 * PART + qo);
+                xh[i] = *reinterpret_cast<const bf16x8*>(slab + 2 * PART + xo);
+                xl[i] = *reinterpret_cast<const bf16x8*>(slab + 3 * PART + xo);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[j], acc[i][j], 0, 0, 0);
+                }
+        }
+        const bool tile_done = sg == nstage - 1;
+        if (tile_done) {
+            // lane l, register r of block (i, j): candidate row 8*(r/4) + 4*(l/32) + r%4 of block i, query l%32 of block j
+            const int64_t c0 = span0 + (int64_t)t * kTile + wc * 64;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                float xv[16];
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                    xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    floatx16 u;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
+                    float lo = __builtin_fminf(u[0], u[1]);
+#pragma unroll
+                    for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, u[r]), u[r + 1]);
+                    if (ballot64(lo < tq[j])) {
+                        uint32_t mask = 0;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) mask |= (u[r] < tq[j]) ? (1u << r) : 0u;
+#pragma unroll 1
+                        while (ballot64(mask != 0u)) {
+                            const int rr = mask ? (int)__builtin_ctz(mask) : 16;
+                            mask &= mask - 1u;
+                            float uv = 0.f;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) uv = rr == r ? u[r] : uv;
+                            const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
+                            const int64_t c = c0 + m;
+                            if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
+                                const uint64_t key =
+                                    ((uint64_t)__float_as_uint(fmaxf(uv + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                                const unsigned slot = atomicAdd(&q_cnt, 1u);
+                                if (slot < (unsigned)kSplitQueue) {
+                                    q_key[slot] = key;
+                                    q_row[slot] = (uint16_t)(wq * 64 + j * 32 + (lane & 31));
+                                } else {
+                                    const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
+                                    if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (more) commit(cur ^ 1, tn, sn);
+        __syncthreads();
+        if (tile_done) {
+            const unsigned queued = q_cnt;
+            if (queued >= (unsigned)kSplitQueue / 2 || (!more && queued > 0)) {
+                const unsigned n = min(queued, (unsigned)kSplitQueue);
+                for (unsigned e = threadIdx.x; e < n; e += 256) {
+                    const int64_t row = q0 + q_row[e];
+                    const unsigned pos = atomicAdd(&a.cnt[row], 1u);
+                    if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
+                }
+                __syncthreads();
+                if (threadIdx.x == 0) q_cnt = 0u;
+                __syncthreads();
+            }
+        }
+        t = tn;
+        sg = sn;
+    }
+}
+
 // ---------------------------------------------------------------- per-row compaction
 // Keeps the kprime entries of the row's buffer with the smallest approximate distances (in any
 // order) and sets tau to the kprime-th smallest.  cnt > cap means entries were lost: the row is flagged.
@@ -1000,7 +1181,12 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 
     // int8 fast path: integer rows with d <= 128 are rewritten once as centred, padded int8
     const bool fast = exact && d <= 128;
-    const int ks = (d + 15) / 16, dp = ks * 16;   // bf16 k-steps of the split path below
+    // bf16 split path: real-valued rows are centred and written as hi + lo; up to d = 128 the query
+    // fragments stay in registers (k-steps of 16), wider rows are staged through LDS in slabs of 32
+    const bool split = !integer_data;
+    const bool wide = split && d > 128;
+    const int ks = (d + 15) / 16;
+    const int dp = wide ? (d + kWideDK - 1) / kWideDK * kWideDK : ks * 16;
     const int ks8 = (d + 31) / 32, dp8 = ks8 * 32;
     DevBuf xc8, qc8, xn8, qn8;
     if (fast) {
@@ -1017,8 +1203,6 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(hipGetLastError());
     }
 
-    // bf16 split path: real-valued rows with d <= 128 are centred and written as hi + lo
-    const bool split = !integer_data && d <= 128;
     DevBuf xh, xl, qh, ql, csum, cmean, cxnorm, cqnorm, cinfo;
     float split_xmax = 0.f;
     if (split) {
@@ -1055,6 +1239,16 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // dropped terms 3*2^-16, fp32 accumulation over 3*dp products, norms and centring a few 2^-24
     // (the accumulation term is doubled because the accumulators also carry |x|^2 from the start)
     const float split_err = (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
+
+    constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);   // dynamic part: the slabs
+    if (wide) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&filter_wide_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLds);
+        if (e != hipSuccess) {
+            set_error("hipFuncSetAttribute(%zu bytes of LDS) failed: %s", kWideLds, hipGetErrorString(e));
+            return ANN_EDEVICE;
+        }
+    }
 
     const char* prog_env = getenv("TSDG_PROGRESS");
     const bool progress = prog_env && prog_env[0] == '1';
@@ -1130,7 +1324,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 #undef TSDG_KS
                 }
             } else if (split) {
-                SplitArgs sa;
+                WideArgs wa;
+                SplitArgs& sa = wa.s;
                 sa.qh = (self ? xh.as<uint16_t>() : qh.as<uint16_t>()) + r0 * dp;
                 sa.ql = (self ? xl.as<uint16_t>() : ql.as<uint16_t>()) + r0 * dp;
                 sa.xh = xh.as<uint16_t>();
@@ -1145,18 +1340,27 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 sa.c_end = ce;
                 sa.self_offset = f.self_offset;
                 sa.cap = cap;
-                const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
-                sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
-                dim3 sgrid((unsigned)((nr + 127) / 128), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
-                switch (ks) {
+                if (wide) {
+                    sa.tiles_per_block = (int)std::min<int64_t>(4, tiles);
+                    wa.dp = dp;
+                    wa.q_tiles = (int)((nr + kTile - 1) / kTile);
+                    wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
+                    wa.q_group = 64;
+                    hipLaunchKernelGGL(filter_wide_kernel, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                                       kWideLds, stream, wa);
+                } else {
+                    const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
+                    sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
+                    dim3 sgrid((unsigned)((nr + 127) / 128), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
+                    switch (ks) {
 #define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_split_kernel<n>), sgrid, dim3(256), 0, stream, sa); break;
-                    TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
+                        TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
 #undef TSDG_KS
+                    }
                 }
-            } else if (integer_data)
-                hipLaunchKernelGGL((filter_kernel<true, TQ, TB>), grid, dim3(256), 0, stream, f);
-            else
-                hipLaunchKernelGGL((filter_kernel<false, TQ, TB>), grid, dim3(256), 0, stream, f);
+            } else {  // integer rows wider than 128 elements
+                hipLaunchKernelGGL((filter_kernel<TQ, TB>), grid, dim3(256), 0, stream, f);
+            }
             TSDG_HIP(hipGetLastError());
             if (cap <= 256) hipLaunchKernelGGL(compact_kernel<4>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
             else hipLaunchKernelGGL(compact_kernel<8>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);

@@ -39,7 +39,7 @@ def check_graph(gpu, orc, base, K, what, ref=None, **kw):
 
 
 def test_knn_tiny_fp32(gpu, orc):
-    step("ann_knn tiny (fp32 MFMA path)")
+    step("ann_knn tiny (real-valued rows: bf16 split path)")
     base, _, _, _, st = tiny_case(orc)
     ref = (st["knn_id"], st["knn_s"])
     ids, s = gpu.ann_knn(dev(base), 16)
@@ -48,7 +48,7 @@ def test_knn_tiny_fp32(gpu, orc):
 
 
 def test_knn_integer_bf16(gpu, orc):
-    step("ann_knn sift-like 20k (bf16 MFMA path, exact)")
+    step("ann_knn sift-like 20k (integer rows: int8 MFMA path, exact)")
     base, _, _, _, st = sift_case(orc)
     ref = (st["knn_id"], st["knn_s"])
     ids, s = gpu.ann_knn(dev(base), 32)
@@ -96,6 +96,35 @@ def test_knn_real_valued_shapes(gpu, orc, d):
     ref = orc.knn(base, 16)
     ids, s = gpu.ann_knn(dev(base), 16)
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"knn d={d}") == 0
+
+
+@pytest.mark.parametrize("d,N", [(132, 1237), (200, 2100), (516, 1500), (2048, 700)])
+def test_knn_real_valued_wide_rows(gpu, orc, d, N):
+    """Real-valued rows wider than 128 elements (operands staged through LDS in slabs): N not a multiple
+    of the tile, d not a multiple of the slab, rows far from the origin, and separate query rows."""
+    step(f"ann_knn wide rows d={d} N={N}")
+    g = np.random.default_rng(500 + d)
+    base = (g.standard_normal((N, d)) * g.uniform(0.2, 2.0, size=d) + 3.0).astype(np.float32)
+    ref = orc.knn(base, 16)
+    ids, s = gpu.ann_knn(dev(base), 16)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"wide knn d={d}") == 0
+    q = (base[:70] + g.standard_normal((70, d)) * 0.3).astype(np.float32)
+    ref = orc.bruteforce(base, q, 10)
+    ids, s = gpu.ann_bruteforce(dev(base), dev(q), 10)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"wide bf d={d}") == 0
+
+
+@pytest.mark.parametrize("d", [200, 320])
+def test_knn_integer_wide_rows(gpu, orc, d):
+    """Integer rows in [0,255] wider than 128 elements: bf16 operands are exact, and up to d = 258 so
+    is the fp32 accumulation; beyond it the acceptance margin covers the rounding."""
+    step(f"ann_knn integer rows d={d}")
+    g = np.random.default_rng(700 + d)
+    base = np.clip(np.rint(g.normal(120, 40, size=(1300, d))), 0, 255).astype(np.float32)
+    ref = orc.knn(base, 16)
+    ids, s = gpu.ann_knn(dev(base), 16)
+    assert_bitwise(ids.cpu().numpy(), ref[0], f"integer wide ids d={d}")
+    assert_bitwise(s.cpu().numpy(), ref[1], f"integer wide dists d={d}")
 
 
 def test_bruteforce(gpu, orc):
