@@ -255,6 +255,14 @@ def main():
             ceil[f"gather_4GiB_table_{rb}B_rows_GBps"] = round(
                 n_g * rb / timed(lambda: P.ann_probe_gather(tab, tid, out=pout[:n_g])) / 1e9, 1)
         del big, pid, pout
+        # matrix cores alone: MFMAs on register operands, 3 workgroups of 4 waves per compute unit
+        mblocks, miters = 256 * 3, 50000
+        mout = torch.empty(4 * mblocks, dtype=torch.float32, device=dev)
+        for kind, name, ops in ((0, "mfma_int8_registers_only_TOPS", 65536), (1, "mfma_bf16_registers_only_TFLOPS", 32768)):
+            t = timed(lambda: P.ann_probe_mfma(kind, mblocks, miters, out=mout))
+            ceil[name] = round(mblocks * 4 * miters * 4 * ops / t / 1e12, 1)
+        result["build"]["knn_mfma_frac_of_registers_only_loop"] = round(
+            result["build"]["knn_mfma_tops"] / ceil["mfma_int8_registers_only_TOPS"], 4)
         result["measured_ceilings"] = ceil
         result["roofline"]["frac_of_measured_gather_512B"] = round(achieved / ceil["gather_base_512B_rows_GBps"], 4)
         log(f"ceilings: {ceil}")

@@ -69,6 +69,7 @@ def load_library():
     L.ann_graph_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
     L.ann_graph_free.argtypes = [vp]
     L.ann_probe_gather.argtypes = [vp, i64, i32, vp, i64, vp, vp]
+    L.ann_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
     L.ann_normalize_rows.argtypes = [vp, i64, i32, vp, vp]
     L.ann_max_row_norm.argtypes = [vp, i64, i32, vp, C.POINTER(C.c_float)]
     L.ann_ip_augment_rows.argtypes = [vp, i64, i32, C.c_float, i32, vp, vp]
@@ -76,7 +77,7 @@ def load_library():
                                   C.POINTER(i32), C.POINTER(i64)]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_normalize_rows", "ann_knn_descent", "ann_max_row_norm", "ann_ip_augment_rows"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_probe_mfma", "ann_normalize_rows", "ann_knn_descent", "ann_max_row_norm", "ann_ip_augment_rows"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -350,6 +351,18 @@ def ann_probe_gather(base: torch.Tensor, ids: torch.Tensor, out: torch.Tensor = 
         out = torch.empty(ids.numel(), dtype=torch.int32, device=base.device)
     _check(load_library().ann_probe_gather(base.data_ptr(), base.shape[0], row_bytes, i, ids.numel(),
                                            _dev(out, torch.int32, "out"), _stream_ptr(stream)))
+    return out
+
+
+def ann_probe_mfma(kind: int, blocks: int, iters: int, out: torch.Tensor = None, stream=None) -> torch.Tensor:
+    """Measurement probe: 4 * iters matrix-core instructions per wavefront on register operands
+    (kind 0 int8 32x32x32, kind 1 bf16 32x32x16); returns one float per wavefront."""
+    if out is None:
+        out = torch.empty(4 * blocks, dtype=torch.float32, device="cuda")
+    if out.numel() < 4 * blocks:
+        raise ValueError("out must hold 4 * blocks floats")
+    _check(load_library().ann_probe_mfma(int(kind), int(blocks), int(iters), _dev(out, torch.float32, "out"),
+                                         _stream_ptr(stream)))
     return out
 
 

@@ -1,5 +1,6 @@
-// Measurement probe: how fast can this GPU gather whole rows at random?
+// Measurement probes (not steps of the method).
 //
+// How fast can this GPU gather whole rows at random?
 // The search's step S5 reads rows of d*e bytes at ids nobody can predict; its
 // roofline is priced against the published HBM peak, and this kernel shows how
 // much of that peak a plain gather of the same shape reaches, with none of the
@@ -48,7 +49,65 @@ __global__ __launch_bounds__(256) void probe_gather_kernel(const uint4* __restri
     }
 }
 
+// How fast do the matrix cores run with nothing around them?  Every wave keeps four independent
+// 32x32 accumulator blocks in registers and issues MFMAs on constant fragments (all ones), no
+// memory access in the loop; the k-NN contraction's fraction of the published peak is read
+// against what this loop reaches.  KIND 0: v_mfma_i32_32x32x32_i8, 1: v_mfma_f32_32x32x16_bf16.
+typedef int probe_i4 __attribute__((ext_vector_type(4)));
+typedef int probe_i16 __attribute__((ext_vector_type(16)));
+typedef __bf16 probe_bf8 __attribute__((ext_vector_type(8)));
+typedef float probe_f16 __attribute__((ext_vector_type(16)));
+
+template <int KIND>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __restrict__ out)
+{
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    float result = 0.f;
+    if constexpr (KIND == 0) {
+        const probe_i4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        probe_i16 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0;
+        for (int it = 0; it < iters; ++it)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, ones, acc[b], 0, 0, 0);
+        result = (float)(acc[0][0] + acc[1][5] + acc[2][10] + acc[3][15]);
+    } else {
+        const uint32_t w = 0x3F803F80u;  // two bf16 ones
+        const uint4 u = make_uint4(w, w, w, w);
+        const probe_bf8 ones = __builtin_bit_cast(probe_bf8, u);
+        probe_f16 acc[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+        for (int it = 0; it < iters; ++it)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, ones, acc[b], 0, 0, 0);
+        result = acc[0][0] + acc[1][5] + acc[2][10] + acc[3][15];
+    }
+    if (lane_id() == 0) out[wave] = result;  // 4 * iters * (32 or 16): every MFMA is accounted for
+}
+
 }  // namespace tsdg
+
+extern "C" ann_status ann_probe_mfma(int kind, int blocks, int iters, float* out, void* stream)
+{
+    using namespace tsdg;
+    if (!out) { set_error("ann_probe_mfma: null pointer"); return ANN_EINVAL; }
+    if (kind != 0 && kind != 1) { set_error("ann_probe_mfma: kind must be 0 (int8) or 1 (bf16)"); return ANN_EINVAL; }
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > 100000) {
+        set_error("ann_probe_mfma: need 1 <= blocks <= 2^20 and 1 <= iters <= 100000");
+        return ANN_EINVAL;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (kind == 0) probe_mfma_kernel<0><<<blocks, 256, 0, st>>>(iters, out);
+    else probe_mfma_kernel<1><<<blocks, 256, 0, st>>>(iters, out);
+    TSDG_HIP(hipGetLastError());
+    return ANN_OK;
+}
 
 extern "C" ann_status ann_probe_gather(const void* base, int64_t N, int row_bytes, const uint32_t* ids, int64_t n,
                                        uint32_t* out, void* stream)

@@ -183,6 +183,17 @@ def test_probe_gather_reads_the_rows_it_is_given(gpu, row_bytes):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("kind,per_mfma", [(0, 32), (1, 16)])
+def test_probe_mfma_counts_every_instruction(gpu, kind, per_mfma):
+    """The matrix-core probe's operands are all ones, so each wavefront's word is 4 blocks x iters x k."""
+    step(f"probe mfma kind={kind}")
+    out = gpu.ann_probe_mfma(kind, 37, 1000).cpu().numpy()
+    assert out.shape == (4 * 37,) and np.all(out == 4 * 1000 * per_mfma)
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_probe_mfma(2, 1, 1)
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("d", [8, 96, 128, 960])
 def test_binary16_storage(gpu, orc, d):
     """Rows stored as binary16 (a storage type of the search calls): distances are the canonical ones
