@@ -38,6 +38,50 @@ __device__ __forceinline__ int list_first_unexpanded(const uint64_t* list, int L
 // reads.  `sync` must order LDS accesses among the calling lanes.
 // DISTINCT = false: the lanes may hold the same candidate more than once; only the first lane's
 // copy is merged (costs one more pass over the candidates).
+// The single-pass merge of list_merge (see there) for lists of at most 64 * B entries, B entries per
+// lane; returns false (list untouched) when some candidate is already in the list.
+template <int B, typename Sync>
+__device__ __forceinline__ bool merge_single_pass(uint64_t* list, int L, uint64_t key, uint64_t kk, bool valid,
+                                                  uint64_t vm, int lane, Sync sync)
+{
+    uint64_t a[B], am1[B];
+    int above[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        const int i = b * 64 + lane;
+        a[b] = i < L ? list[i] : kKeyEmpty;
+        am1[b] = a[b] | 1ull;
+        above[b] = 0;
+    }
+    int pos = 0, n = 0;
+    bool present = false;
+    for (uint64_t m = vm; m; m &= m - 1) {
+        const int j = ctz64(m);
+        const uint64_t kj = readlane64(kk, j);
+        int below = popc64(ballot64(valid && kk < kj));
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const bool lt = am1[b] < kj;
+            below += popc64(ballot64(lt));
+            present = present || ballot64(am1[b] == kj) != 0ull;
+            above[b] += lt ? 1 : 0;
+        }
+        pos = lane == j ? below : pos;
+        ++n;
+    }
+    if (present) return false;
+    sync();
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        const int i = b * 64 + lane;
+        const int u = n - above[b];
+        if (i < L && u > 0 && i + u < L) list[i + u] = a[b];
+    }
+    if (valid && pos < L) list[pos] = key;
+    sync();
+    return true;
+}
+
 template <bool DISTINCT = true, typename Sync>
 __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, int lane, Sync sync)
 {
@@ -56,12 +100,13 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
         vm = ballot64(valid);
     }
 
+    // Short lists: a single pass over the candidates yields everything.  Candidate j is broadcast;
+    // the list entries below it give r_j, the candidates below it give t_j (lane j keeps their sum,
+    // its position in the merged list), and every lane counts the candidates above each of its own
+    // entries (one per block of 64), which leaves u = (candidates) - (that count) places to move up.
+    // A candidate already in the list is rare and sends the call down the general path below,
+    // which has touched nothing yet.
     if (L <= 64) {
-        // One block: a single pass over the candidates yields everything.  Candidate j is broadcast;
-        // the list entries below it give r_j, the candidates below it give t_j (lane j keeps their sum,
-        // its position in the merged list), and every lane counts the candidates above its own entry,
-        // which leaves u = (candidates) - (that count) places to move up.  A candidate already in the
-        // list is rare and sends the call down the general path below, which has touched nothing yet.
         const uint64_t a = lane < L ? list[lane] : kKeyEmpty;
         const uint64_t am1 = a | 1ull;
         int pos = 0, above = 0, n = 0;
@@ -85,6 +130,8 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
             sync();
             return;
         }
+    } else if (L <= 128) {  // the same with two entries per lane
+        if (merge_single_pass<2>(list, L, key, kk, valid, vm, lane, sync)) return;
     }
 
     const int top = ((L - 1) / 64) * 64;
