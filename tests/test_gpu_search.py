@@ -40,7 +40,8 @@ def test_tiny_matches_oracle(gpu, orc, mode, waves, lv):
     assert np.all(st.dist_evals.cpu().numpy() >= ref[2][:, 1])
 
 
-@pytest.mark.parametrize("L,k,mode", [(16, 10, 1), (64, 10, 1), (200, 100, 1), (512, 10, 1), (64, 10, 2), (1, 1, 1)])
+@pytest.mark.parametrize("L,k,mode", [(16, 10, 1), (64, 10, 1), (65, 10, 1), (100, 10, 1), (128, 100, 1), (128, 10, 2),
+                                      (200, 100, 1), (512, 10, 1), (64, 10, 2), (1, 1, 1)])
 def test_integer_data_matches_oracle_exactly(gpu, orc, L, k, mode):
     """d=128 integer-valued rows: every distance is an exact integer, so parity is zero-tolerance."""
     step(f"sift20k search L={L} k={k} mode={mode}")
@@ -59,6 +60,10 @@ def test_result_independent_of_visited_capacity(gpu, orc):
         assert_bitwise(ids, ref[0], f"slots={slots}")
         outs.append(int(st.dist_evals.sum()))
     assert outs[0] >= outs[1] >= outs[2] >= int(ref[2][:, 1].sum())   # a smaller set only costs evaluations
+    # a list of two entries per lane with a set that forgets: re-scored ids meet their copies in the list
+    (ids, s, st), ref = run_both(gpu, orc, case, 10, 100, 10, 1, visited_slots=64)
+    assert_bitwise(ids, ref[0], "L=100 slots=64")
+    assert int(st.dist_evals.sum()) > int(ref[2][:, 1].sum())
 
 
 @pytest.mark.parametrize("kw", [dict(n_seeds=1), dict(n_seeds=100), dict(n_seeds=32, seed=12345),
