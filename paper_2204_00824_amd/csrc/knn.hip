@@ -434,8 +434,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // nearly the same accuracy: |error of q.x| <= (3*2^-16 + 3d*2^-24) sum|q_j||x_j|; the
 // accumulators also carry |x|^2 from the start, which doubles the accumulation term.  The
 // result only SELECTS candidates; the acceptance test of the re-scoring pass carries the
-// bound.  One wave owns 32 queries (hi and lo fragments in registers), four waves share a
-// 64-row candidate tile (hi and lo) in LDS, double buffered.
+// bound.  One wave owns 64 queries (hi and lo fragments in registers: every candidate fragment
+// read from LDS feeds six MFMAs), four waves share a 64-row candidate tile (hi and lo) in LDS,
+// double buffered.
 __device__ __forceinline__ uint16_t bf16_rne(float v)
 {
     const uint32_t b = __float_as_uint(v);
@@ -513,10 +514,12 @@ struct SplitArgs {
 };
 
 constexpr int kSplitQueue = 512;
+constexpr int kSplitQB = 2;   // blocks of 32 queries per wave
 
 template <int KS>
 __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
 {
+    constexpr int QB = kSplitQB;
     constexpr int DP = KS * 16;
     constexpr int XS = DP + 8;
     constexpr int CHUNKS = kFastRows * DP / 8;       // 16-byte chunks per part of a tile
@@ -529,28 +532,34 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    const int64_t qg = (int64_t)blockIdx.x * 128 + wave * 32 + (lane & 31);
     if (threadIdx.x == 0) q_cnt = 0u;
 
-    bf16x8 qfh[KS], qfl[KS];
-    const bool qok = qg < a.nq;
-    const float qn = qok ? a.qnorm[qg] : 0.f;
-    const float tq = qok ? a.tau[qg] - qn : -kInf;
+    // QB blocks of 32 queries per wave
+    bf16x8 qfh[QB][KS], qfl[QB][KS];
+    int64_t qg[QB];
+    float qn[QB], tq[QB];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 wh = make_uint4(0u, 0u, 0u, 0u), wl = wh;
-        if (qok) {
-            wh = *reinterpret_cast<const uint4*>(a.qh + qg * DP + ks * 16 + 8 * (lane >> 5));
-            wl = *reinterpret_cast<const uint4*>(a.ql + qg * DP + ks * 16 + 8 * (lane >> 5));
+    for (int j = 0; j < QB; ++j) {
+        qg[j] = (int64_t)blockIdx.x * (128 * QB) + wave * (32 * QB) + j * 32 + (lane & 31);
+        const bool qok = qg[j] < a.nq;
+        qn[j] = qok ? a.qnorm[qg[j]] : 0.f;
+        tq[j] = qok ? a.tau[qg[j]] - qn[j] : -kInf;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint4 wh = make_uint4(0u, 0u, 0u, 0u), wl = wh;
+            if (qok) {
+                wh = *reinterpret_cast<const uint4*>(a.qh + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
+                wl = *reinterpret_cast<const uint4*>(a.ql + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
+            }
+            // both parts of the query enter as -2q (exact), so that with |x|^2 as the accumulators'
+            // start value the contraction itself yields |x|^2 - 2 q.x
+            wh.x = bf16x2_times_minus2(wh.x); wh.y = bf16x2_times_minus2(wh.y);
+            wh.z = bf16x2_times_minus2(wh.z); wh.w = bf16x2_times_minus2(wh.w);
+            wl.x = bf16x2_times_minus2(wl.x); wl.y = bf16x2_times_minus2(wl.y);
+            wl.z = bf16x2_times_minus2(wl.z); wl.w = bf16x2_times_minus2(wl.w);
+            qfh[j][ks] = __builtin_bit_cast(bf16x8, wh);
+            qfl[j][ks] = __builtin_bit_cast(bf16x8, wl);
         }
-        // both parts of the query enter as -2q (exact), so that with |x|^2 as the accumulators'
-        // start value the contraction itself yields |x|^2 - 2 q.x
-        wh.x = bf16x2_times_minus2(wh.x); wh.y = bf16x2_times_minus2(wh.y);
-        wh.z = bf16x2_times_minus2(wh.z); wh.w = bf16x2_times_minus2(wh.w);
-        wl.x = bf16x2_times_minus2(wl.x); wl.y = bf16x2_times_minus2(wl.y);
-        wl.z = bf16x2_times_minus2(wl.z); wl.w = bf16x2_times_minus2(wl.w);
-        qfh[ks] = __builtin_bit_cast(bf16x8, wh);
-        qfl[ks] = __builtin_bit_cast(bf16x8, wl);
     }
 
     const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kFastRows;
@@ -598,13 +607,17 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
         const int cur = t & 1;
         fetch(t + 1);  // clamped: past the last tile it re-reads the span's end, unused
         // the accumulators start at |x|^2 of their rows (lane l, register r: row 8*(r/4) + 4*(l/32) + r%4)
-        floatx16 acc[2];
+        floatx16 acc[2][QB];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                acc[i][4 * r4 + 0] = v.x; acc[i][4 * r4 + 1] = v.y; acc[i][4 * r4 + 2] = v.z; acc[i][4 * r4 + 3] = v.w;
+#pragma unroll
+                for (int j = 0; j < QB; ++j) {
+                    acc[i][j][4 * r4 + 0] = v.x; acc[i][j][4 * r4 + 1] = v.y;
+                    acc[i][j][4 * r4 + 2] = v.z; acc[i][j][4 * r4 + 3] = v.w;
+                }
             }
         }
 #pragma unroll
@@ -614,40 +627,46 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
                 const int off = (i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
                 const bf16x8 xh = *reinterpret_cast<const bf16x8*>(&Xs[cur][0][off]);
                 const bf16x8 xl = *reinterpret_cast<const bf16x8*>(&Xs[cur][1][off]);
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[ks], acc[i], 0, 0, 0);
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[ks], acc[i], 0, 0, 0);
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[ks], acc[i], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < QB; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[j][ks], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[j][ks], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
+                }
             }
         }
         const int64_t c0 = span0 + (int64_t)t * kFastRows;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            float lo = __builtin_fminf(acc[i][0], acc[i][1]);
 #pragma unroll
-            for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, acc[i][r]), acc[i][r + 1]);
-            if (ballot64(lo < tq)) {
-                uint32_t mask = 0;
+            for (int j = 0; j < QB; ++j) {
+                float lo = __builtin_fminf(acc[i][j][0], acc[i][j][1]);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mask |= (acc[i][r] < tq) ? (1u << r) : 0u;
+                for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, acc[i][j][r]), acc[i][j][r + 1]);
+                if (ballot64(lo < tq[j])) {
+                    uint32_t mask = 0;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mask |= (acc[i][j][r] < tq[j]) ? (1u << r) : 0u;
 #pragma unroll 1
-                while (ballot64(mask != 0u)) {
-                    const int rr = mask ? (int)__builtin_ctz(mask) : 16;
-                    mask &= mask - 1u;
-                    float u = 0.f;
+                    while (ballot64(mask != 0u)) {
+                        const int rr = mask ? (int)__builtin_ctz(mask) : 16;
+                        mask &= mask - 1u;
+                        float u = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) u = rr == r ? acc[i][r] : u;
-                    const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
-                    const int64_t c = c0 + m;
-                    if (rr < 16 && c < span1 && c != a.self_offset + qg) {
-                        const uint64_t key =
-                            ((uint64_t)__float_as_uint(fmaxf(u + qn, 0.f)) << 32) | (uint64_t)(uint32_t)c;
-                        const unsigned slot = atomicAdd(&q_cnt, 1u);
-                        if (slot < (unsigned)kSplitQueue) {
-                            q_key[slot] = key;
-                            q_row[slot] = (uint16_t)(wave * 32 + (lane & 31));
-                        } else {
-                            const unsigned pos = atomicAdd(&a.cnt[qg], 1u);
-                            if (pos < (unsigned)a.cap) a.buf[qg * a.cap + pos] = key;
+                        for (int r = 0; r < 16; ++r) u = rr == r ? acc[i][j][r] : u;
+                        const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
+                        const int64_t c = c0 + m;
+                        if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
+                            const uint64_t key =
+                                ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                            const unsigned slot = atomicAdd(&q_cnt, 1u);
+                            if (slot < (unsigned)kSplitQueue) {
+                                q_key[slot] = key;
+                                q_row[slot] = (uint16_t)(wave * (32 * QB) + j * 32 + (lane & 31));
+                            } else {
+                                const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
+                                if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
+                            }
                         }
                     }
                 }
@@ -659,7 +678,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
         if (queued >= (unsigned)kSplitQueue / 2 || (t + 1 == ntiles && queued > 0)) {
             const unsigned n = min(queued, (unsigned)kSplitQueue);
             for (unsigned e = threadIdx.x; e < n; e += 256) {
-                const int64_t row = (int64_t)blockIdx.x * 128 + q_row[e];
+                const int64_t row = (int64_t)blockIdx.x * (128 * QB) + q_row[e];
                 const unsigned pos = atomicAdd(&a.cnt[row], 1u);
                 if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
             }
@@ -1351,7 +1370,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 } else {
                     const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
                     sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
-                    dim3 sgrid((unsigned)((nr + 127) / 128), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
+                    constexpr int qpb = 128 * kSplitQB;   // queries per workgroup
+                    dim3 sgrid((unsigned)((nr + qpb - 1) / qpb), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
                     switch (ks) {
 #define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_split_kernel<n>), sgrid, dim3(256), 0, stream, sa); break;
                         TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
