@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
 }
 
 
-constexpr int kFastRows = 64;  // candidate rows per LDS tile
+constexpr int kSplitRows = 64;  // candidate rows per LDS tile of the bf16 split kernel
 constexpr int kQueue = 1024;    // survivor queue entries per workgroup
 
 // ---------------------------------------------------------------- int8 path (integer rows in [0,255], d <= 128)
@@ -522,10 +522,10 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     constexpr int QB = kSplitQB;
     constexpr int DP = KS * 16;
     constexpr int XS = DP + 8;
-    constexpr int CHUNKS = kFastRows * DP / 8;       // 16-byte chunks per part of a tile
+    constexpr int CHUNKS = kSplitRows * DP / 8;       // 16-byte chunks per part of a tile
     constexpr int PER_THREAD = (CHUNKS + 255) / 256;
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][kFastRows * XS];   // [buffer][hi|lo]
-    __shared__ __attribute__((aligned(16))) float xn[2][kFastRows];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][kSplitRows * XS];   // [buffer][hi|lo]
+    __shared__ __attribute__((aligned(16))) float xn[2][kSplitRows];
     __shared__ uint64_t q_key[kSplitQueue];
     __shared__ uint16_t q_row[kSplitQueue];
     __shared__ unsigned q_cnt;
@@ -562,15 +562,15 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
         }
     }
 
-    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kFastRows;
-    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kFastRows);
+    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kSplitRows;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kSplitRows);
     if (span0 >= span1) return;
-    const int ntiles = (int)((span1 - span0 + kFastRows - 1) / kFastRows);
+    const int ntiles = (int)((span1 - span0 + kSplitRows - 1) / kSplitRows);
 
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
     u32x4 stage[2][PER_THREAD];
     float stage_n = 0.f;
-    // A tile part is one contiguous block of kFastRows * DP elements; a chunk index past the span's
+    // A tile part is one contiguous block of kSplitRows * DP elements; a chunk index past the span's
     // end is clamped to the span's last chunk (rows read twice that way carry ids >= span1 and are
     // dropped by the filter), so the loads need no branch.
     const int last_chunk = (int)(span1 - span0) * (DP / 8) - 1;
@@ -585,7 +585,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
             stage[0][i] = *reinterpret_cast<const u32x4*>(xh_span + off);
             stage[1][i] = *reinterpret_cast<const u32x4*>(xl_span + off);
         }
-        if (threadIdx.x < kFastRows) stage_n = a.xnorm[span0 + min(t * kFastRows + (int)threadIdx.x, last_row)];
+        if (threadIdx.x < kSplitRows) stage_n = a.xnorm[span0 + min(t * kSplitRows + (int)threadIdx.x, last_row)];
     };
     auto commit = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
@@ -597,7 +597,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
                 *reinterpret_cast<u32x4*>(&Xs[b][1][r * XS + c8 * 8]) = stage[1][i];
             }
         }
-        if (threadIdx.x < kFastRows) xn[b][threadIdx.x] = stage_n;
+        if (threadIdx.x < kSplitRows) xn[b][threadIdx.x] = stage_n;
     };
 
     fetch(0);
@@ -635,7 +635,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
                 }
             }
         }
-        const int64_t c0 = span0 + (int64_t)t * kFastRows;
+        const int64_t c0 = span0 + (int64_t)t * kSplitRows;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -1368,7 +1368,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     hipLaunchKernelGGL(filter_wide_kernel, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                        kWideLds, stream, wa);
                 } else {
-                    const int64_t ftiles = (ce - cb + kFastRows - 1) / kFastRows;
+                    const int64_t ftiles = (ce - cb + kSplitRows - 1) / kSplitRows;
                     sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
                     constexpr int qpb = 128 * kSplitQB;   // queries per workgroup
                     dim3 sgrid((unsigned)((nr + qpb - 1) / qpb), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
