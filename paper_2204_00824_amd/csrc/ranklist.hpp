@@ -32,10 +32,11 @@ __device__ __forceinline__ int list_first_unexpanded(const uint64_t* list, int L
 // list (same distance, same id) is dropped.
 // Positions: with r_j = #{a in list : a < c_j} and t_j = #{c_i < c_j}, candidate j lands at
 // r_j + t_j and list entry i at i + #{j : r_j <= i}; together these are the positions of the
-// merged sequence, and everything at L or beyond falls off.  Candidates are broadcast one at
-// a time with v_readlane (their lane index is wave-uniform) and every lane compares its own
-// list entries against them, so a rank is one ballot + popcount and needs no dependent LDS
-// reads.  `sync` must order LDS accesses among the calling lanes.
+// merged sequence, and everything at L or beyond falls off.  Lists of up to 128 entries sit in
+// registers (one or two entries per lane) while the candidates are broadcast one at a time with
+// v_readlane, so that a rank is one ballot + popcount; longer lists are searched in LDS (a
+// binary search per candidate, all candidates at once) and moved block by block from the end.
+// `sync` must order LDS accesses among the calling lanes.
 // DISTINCT = false: the lanes may hold the same candidate more than once; only the first lane's
 // copy is merged (costs one more pass over the candidates).
 // The single-pass merge of list_merge (see there) for lists of at most 64 * B entries, B entries per
@@ -134,25 +135,23 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
         if (merge_single_pass<2>(list, L, key, kk, valid, vm, lane, sync)) return;
     }
 
+    // Longer lists.  r_j by a binary search of the list (one LDS read per step, all candidates at once);
+    // a candidate that meets its own key there is already present.
     const int top = ((L - 1) / 64) * 64;
     int r = 0;
     bool dup = false;
-    for (int i0 = 0; i0 <= top; i0 += 64) {
-        const int i = i0 + lane;
-        const uint64_t am = (i < L ? list[i] : kKeyEmpty) | 1ull;
-        bool more = false;  // some candidate lies beyond this whole block
-        for (uint64_t m = vm; m; m &= m - 1) {
-            const int j = ctz64(m);
-            const uint64_t kj = readlane64(kk, j);
-            const uint64_t lt = ballot64(am < kj);
-            const uint64_t eq = ballot64(am == kj);
-            if (lane == j) {
-                r += popc64(lt);
-                dup = dup || eq != 0ull;
-            }
-            more = more || lt == ~0ull;
+    {
+        int lo = 0, hi = L;
+        const int steps = 32 - __builtin_clz((unsigned)L);  // 2^steps > L
+        for (int step = 0; step < steps; ++step) {
+            const int mid = (lo + hi) >> 1;
+            const bool open = lo < hi;
+            const bool below = (list[min(mid, L - 1)] | 1ull) < kk;
+            lo = open && below ? mid + 1 : lo;
+            hi = open && !below ? mid : hi;
         }
-        if (!more) break;
+        r = lo;
+        dup = r < L && (list[min(r, L - 1)] | 1ull) == kk;
     }
     valid = valid && !dup;  // already present
     vm = ballot64(valid);
@@ -171,11 +170,10 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
     for (int i0 = top; i0 >= (rmin & ~63); i0 -= 64) {
         const int i = i0 + lane;
         const uint64_t a = i < L ? list[i] : kKeyEmpty;
-        int u = 0;
-        for (uint64_t m = vm; m; m &= m - 1) {
-            const int j = ctz64(m);
-            u += ((int)readlane32((uint32_t)r, j) <= i) ? 1 : 0;
-        }
+        // candidates that land before this block all count; those inside it are compared one by one
+        int u = popc64(ballot64(valid && r < i0));
+        for (uint64_t m = ballot64(valid && r >= i0 && r < i0 + 64); m; m &= m - 1)
+            u += ((int)readlane32((uint32_t)r, ctz64(m)) <= i) ? 1 : 0;
         sync();
         if (i < L && u > 0 && i + u < L) list[i + u] = a;
         sync();

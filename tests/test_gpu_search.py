@@ -41,7 +41,8 @@ def test_tiny_matches_oracle(gpu, orc, mode, waves, lv):
 
 
 @pytest.mark.parametrize("L,k,mode", [(16, 10, 1), (64, 10, 1), (65, 10, 1), (100, 10, 1), (128, 100, 1), (128, 10, 2),
-                                      (200, 100, 1), (512, 10, 1), (64, 10, 2), (1, 1, 1)])
+                                      (129, 10, 1), (200, 100, 1), (257, 10, 2), (512, 10, 1), (512, 100, 2), (64, 10, 2),
+                                      (1, 1, 1)])
 def test_integer_data_matches_oracle_exactly(gpu, orc, L, k, mode):
     """d=128 integer-valued rows: every distance is an exact integer, so parity is zero-tolerance."""
     step(f"sift20k search L={L} k={k} mode={mode}")
@@ -64,6 +65,10 @@ def test_result_independent_of_visited_capacity(gpu, orc):
     (ids, s, st), ref = run_both(gpu, orc, case, 10, 100, 10, 1, visited_slots=64)
     assert_bitwise(ids, ref[0], "L=100 slots=64")
     assert int(st.dist_evals.sum()) > int(ref[2][:, 1].sum())
+    # and a list searched in LDS (more than 128 entries)
+    (ids, s, st), ref = run_both(gpu, orc, case, 100, 300, 10, 1, visited_slots=64)
+    assert_bitwise(ids, ref[0], "L=300 slots=64")
+    assert_bitwise(s, ref[1], "L=300 slots=64 dists")
 
 
 @pytest.mark.parametrize("kw", [dict(n_seeds=1), dict(n_seeds=100), dict(n_seeds=32, seed=12345),
