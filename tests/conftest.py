@@ -21,14 +21,16 @@ def orc():
 
 
 def step(msg: str) -> None:
-    """Names the GPU case about to run: printed unbuffered and appended to a
-    steps.log in the run's output folder, so that a run that dies still says
-    where it was."""
+    """Names the GPU case about to run: printed unbuffered and, when TSDG_STEP_LOG names a
+    file, appended to it, so that a run that dies still says where it was."""
     line = f"[step] {msg}"
     print(line, file=sys.stderr, flush=True)
+    path = os.environ.get("TSDG_STEP_LOG")
+    if not path:
+        return
     try:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "steps.log"), "a") as f:
+        os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
+        with open(path, "a") as f:
             f.write(line + "\n")
             f.flush()
             os.fsync(f.fileno())
