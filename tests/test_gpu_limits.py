@@ -85,3 +85,26 @@ def test_smallest_set(gpu, orc):
     assert gpu.ann_search_ex(g, dev(base), e, 3, 8)[0].shape == (0, 3)
     assert gpu.ann_search_multi(g, dev(base), e, 3, 2)[0].shape == (0, 3)
     assert gpu.ann_search_alg2(g, dev(base), e, 3, 0.0)[0].shape == (0, 3)
+
+
+def test_largest_batch(gpu, orc):
+    """2^22 queries in one call (the grid is one workgroup per query); one more is refused.  Sampled
+    queries of the big call against the oracle (the seeds depend on the query's index in the batch)."""
+    step("2^22 queries in one search call")
+    from conftest import tiny_case
+    base, _, adj, lam, _ = tiny_case(orc)
+    g = gpu.ann_graph_import(dev(adj), dev(lam), base.shape[1])
+    nq = 1 << 22
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    q = torch.randn((nq + 1, base.shape[1]), generator=gen, device="cuda") * 3.0
+    b = dev(base)
+    ids, s = gpu.ann_search_ex(g, b, q[:nq], 10, 16, mode=1, lambda_visit=5)
+    torch.cuda.synchronize()
+    for lo in (0, 123_457, nq - 40):
+        qs = q[lo:lo + 40].cpu().numpy()
+        ref = orc.search(adj, lam, base, qs, 10, 16, 5, qi_offset=lo)
+        got_i, got_s = ids[lo:lo + 40].cpu().numpy(), s[lo:lo + 40].cpu().numpy()
+        assert compare_topk(got_i, got_s, ref[0], ref[1], f"queries from {lo}") == 0
+    with pytest.raises(gpu.AnnError) as e:
+        gpu.ann_search_ex(g, b, q, 10, 16, mode=1)
+    assert e.value.status == 4
