@@ -220,20 +220,36 @@ def run_whole_u8(args):
                      "ms": round(ms, 3), "dist_evals": round(ev, 1), "alg_TBps": round((ev * d + hp * K * 4) * nq / ms / 1e9, 2)})
         log(f"large batch: {rows[-1]}")
     out["curves"]["large_batch_lambda5"] = rows
-    rows = []
-    for t0_ in (32, 64):
-        lat, hit = [], 0
-        for c in range(50):
-            q = queries[c:c + 1].contiguous()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            ids, _ = P.ann_search_multi(graph, base, q, k, t0_, max_hops=8, qi_offset=c)
-            torch.cuda.synchronize()
-            lat.append(time.perf_counter() - t1)
-            hit += recall(ids.cpu().numpy(), gt_h[c:c + 1])
-        rows.append({"t0": t0_, "T": 8, "recall@10": round(hit / 50, 4), "median_latency_ms": round(float(np.median(lat)) * 1e3, 3)})
-        log(f"batch 1 multi-search: {rows[-1]}")
-    out["curves"]["batch1_multi_search"] = rows
+    # small batches (1 and 16 queries per call): Alg. 1's multi-search and the best-first search
+    for bs in (1, 16):
+        rows = []
+        for t0_ in (32, 64, 128):
+            lat, hit = [], 0
+            for c in range(50):
+                q = queries[c * bs:(c + 1) * bs].contiguous()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                ids, _ = P.ann_search_multi(graph, base, q, k, t0_, max_hops=8, qi_offset=c * bs)
+                torch.cuda.synchronize()
+                lat.append(time.perf_counter() - t1)
+                hit += recall(ids.cpu().numpy(), gt_h[c * bs:(c + 1) * bs])
+            rows.append({"t0": t0_, "T": 8, "recall@10": round(hit / 50, 4), "median_latency_ms": round(float(np.median(lat)) * 1e3, 3)})
+            log(f"batch {bs} multi-search: {rows[-1]}")
+        out["curves"][f"batch{bs}_multi_search"] = rows
+        rows = []
+        for L in (64, 128, 256):
+            lat, hit = [], 0
+            for c in range(50):
+                q = queries[c * bs:(c + 1) * bs].contiguous()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                ids, _ = P.ann_search_ex(graph, base, q, k, L, mode=2, lambda_visit=10, qi_offset=c * bs)
+                torch.cuda.synchronize()
+                lat.append(time.perf_counter() - t1)
+                hit += recall(ids.cpu().numpy(), gt_h[c * bs:(c + 1) * bs])
+            rows.append({"L": L, "recall@10": round(hit / 50, 4), "median_latency_ms": round(float(np.median(lat)) * 1e3, 3)})
+            log(f"batch {bs} best-first: {rows[-1]}")
+        out["curves"][f"batch{bs}_best_first"] = rows
     print(json.dumps(out), flush=True)
 
 
