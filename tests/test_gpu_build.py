@@ -215,3 +215,16 @@ def test_knn_real_valued_with_large_offset_and_near_ties(gpu, orc):
     ref = orc.bruteforce(y, q, 10)
     ids, s = gpu.ann_bruteforce(dev(y), dev(q), 10)
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "near ties bf") == 0
+
+
+@pytest.mark.parametrize("scale", [1e-12, 1e12])
+@pytest.mark.parametrize("d", [16, 200])
+def test_knn_extreme_magnitudes(gpu, orc, scale, d):
+    """Rows whose squares sit far from 1 in fp32 (1e-24 and 1e24 per element): the hi + lo split, the
+    norms and the acceptance margin scale with the data, so the lists still equal the oracle's."""
+    step(f"ann_knn magnitudes scale={scale:g} d={d}")
+    g = np.random.default_rng(900 + d)
+    base = (g.standard_normal((1500, d)) * scale).astype(np.float32)
+    ref = orc.knn(base, 16)
+    ids, s = gpu.ann_knn(dev(base), 16)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"scale {scale:g} d={d}") == 0
