@@ -5,8 +5,9 @@
 // a dense contraction on the matrix cores:
 //   * rows that are integers in [0,255] with d <= 128 (uint8 rows, SIFT-like fp32 rows) are
 //     centred to int8 and go through the integer matrix cores (v_mfma_i32_32x32x32_i8), exact;
-//     such rows with d > 128 go through bf16 MFMA with both operands staged in LDS (the values are
-//     exact in bf16 and up to d = 258 so is every partial sum; beyond, fp32 accumulation rounds);
+//     such rows with d > 128 go through bf16 MFMA with both operands staged in LDS, one MFMA per
+//     k-step (the values are exact in bf16 and up to d = 258 so is every partial sum; beyond, fp32
+//     accumulation rounds and the acceptance test carries the bound);
 //   * real-valued rows are centred and split into bf16 hi + lo parts, three
 //     v_mfma_f32_32x32x16_bf16 per k-step, with an error near that of fp32 accumulation: with the
 //     query fragments in registers up to d = 128, with both operands staged through LDS beyond.
@@ -22,6 +23,7 @@
 // rows that fail, or whose buffer overflowed, are redone by a plain scan of
 // all base rows with the canonical distance.
 #include <algorithm>
+#include <type_traits>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -36,11 +38,14 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 constexpr int kTile = 128;        // queries and candidates per workgroup tile
-constexpr int kTilesPerBlock = 8; // candidate tiles a workgroup sweeps
 constexpr float kInf = __builtin_inff();
 
-__device__ __forceinline__ float4 load4(const float* p);
-__device__ __forceinline__ float4 load4(const uint8_t* p);
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const uint8_t* p)
+{
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
+    return make_float4((float)(w & 0xFFu), (float)((w >> 8) & 0xFFu), (float)((w >> 16) & 0xFFu), (float)(w >> 24));
+}
 
 // ---------------------------------------------------------------- row norms, integer test
 // info[0] = 1 if some element is not an integer in [0,255]; info[1] = max norm (fp32 bits)
@@ -83,39 +88,7 @@ __global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int
     if (ballot64(nonint) && lane == 0 && info[0] == 0u) atomicOr(&info[0], 1u);
 }
 
-// ---------------------------------------------------------------- tile loads
-__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ float4 load4(const uint8_t* p)
-{
-    const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
-    return make_float4((float)(w & 0xFFu), (float)((w >> 8) & 0xFFu), (float)((w >> 16) & 0xFFu), (float)(w >> 24));
-}
-// exact for values representable in bf16 (integers up to 255 are)
-__device__ __forceinline__ uint16_t bf16_bits(float v) { return (uint16_t)(__float_as_uint(v) >> 16); }
-
-struct TileCfg {
-    static constexpr int DK = 64;            // k extent of a staged tile
-    static constexpr int STRIDE = DK + 8;    // in elements (144 B rows, 16-B aligned fragments)
-    using elem_t = uint16_t;
-};
-
-// Stages rows [r0, r0+128) x columns [k0, k0+DK) of src (zero beyond nrows / d) into LDS.
-template <typename T>
-__device__ __forceinline__ void stage_tile(TileCfg::elem_t* lds, const T* __restrict__ src,
-                                           int64_t r0, int64_t nrows, int d, int k0)
-{
-    using Cfg = TileCfg;
-    constexpr int CH = Cfg::DK / 4;  // 4-element chunks per row
-    for (int ch = (int)threadIdx.x; ch < kTile * CH; ch += 256) {
-        const int r = ch / CH, c4 = (ch % CH) * 4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r0 + r < nrows && k0 + c4 < d) v = load4(src + (r0 + r) * (int64_t)d + k0 + c4);
-        const uint32_t lo = (uint32_t)bf16_bits(v.x) | ((uint32_t)bf16_bits(v.y) << 16);
-        const uint32_t hi = (uint32_t)bf16_bits(v.z) | ((uint32_t)bf16_bits(v.w) << 16);
-        *reinterpret_cast<uint2*>(lds + r * Cfg::STRIDE + c4) = make_uint2(lo, hi);
-    }
-}
-
+// what every contraction launch of one row block shares
 struct FilterArgs {
     const void* q;        // [nq, d] query rows (type TQ), row 0 = global query q_begin
     const void* x;        // [N, d] base rows (type TB)
@@ -129,103 +102,6 @@ struct FilterArgs {
     int64_t self_offset;      // global id of query row 0 when queries are base rows, else -1
     int d, cap;
 };
-
-// One workgroup: 128 queries x (kTilesPerBlock x 128) candidates.  4 waves in a 2x2
-// arrangement, each owning a 64x64 sub-tile = 2x2 MFMA blocks of 32x32.  The candidate
-// fragment is the A operand and the query fragment the B operand, so that the 16
-// accumulators a lane holds per block all belong to ONE query (column lane%32) and the
-// query's threshold and norm sit in that lane's registers.
-template <typename TQ, typename TB>
-__global__ __launch_bounds__(256) void filter_kernel(FilterArgs a)
-{
-    using Cfg = TileCfg;
-    using elem_t = Cfg::elem_t;
-    __shared__ __attribute__((aligned(16))) elem_t Qs[kTile * Cfg::STRIDE];
-    __shared__ __attribute__((aligned(16))) elem_t Xs[kTile * Cfg::STRIDE];
-    __shared__ float xn[kTile];
-
-    const int lane = lane_id();
-    const int wave = (int)(threadIdx.x >> 6);
-    const int wq = wave >> 1, wc = wave & 1;
-    const int64_t q0 = (int64_t)blockIdx.x * kTile;
-    const TQ* __restrict__ Q = static_cast<const TQ*>(a.q);
-    const TB* __restrict__ X = static_cast<const TB*>(a.x);
-
-    // this lane's two queries (one per query block)
-    int64_t qg[2];
-    float qn[2], tau[2];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        qg[qb] = q0 + wq * 64 + qb * 32 + (lane & 31);
-        const bool ok = qg[qb] < a.nq;
-        qn[qb] = ok ? a.qnorm[qg[qb]] : 0.f;
-        tau[qb] = ok ? a.tau[qg[qb]] : -kInf;
-    }
-
-    for (int t = 0; t < kTilesPerBlock; ++t) {
-        const int64_t c0 = a.c_begin + ((int64_t)blockIdx.y * kTilesPerBlock + t) * kTile;
-        if (c0 >= a.c_end) break;
-        floatx16 acc[2][2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-        for (int k0 = 0; k0 < a.d; k0 += Cfg::DK) {
-            __syncthreads();
-            stage_tile<TQ>(Qs, Q, q0, a.nq, a.d, k0);
-            stage_tile<TB>(Xs, X, c0, a.c_end, a.d, k0);
-            if (k0 == 0 && threadIdx.x < kTile) {
-                const int64_t c = c0 + threadIdx.x;
-                xn[threadIdx.x] = c < a.c_end ? a.xnorm[c] : 0.f;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int ks = 0; ks < Cfg::DK / 16; ++ks) {
-                const int ko = ks * 16 + 8 * (lane >> 5);
-                bf16x8 xa[2], qb[2];
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    xa[i] = *reinterpret_cast<const bf16x8*>(&Xs[(wc * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
-                    qb[i] = *reinterpret_cast<const bf16x8*>(&Qs[(wq * 64 + i * 32 + (lane & 31)) * Cfg::STRIDE + ko]);
-                }
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], qb[j], acc[i][j], 0, 0, 0);
-            }
-        }
-
-        // epilogue: acc[i][j][r] = x_m . q_n with n = lane%32 (query block j) and
-        // m = 8*(r/4) + 4*(lane/32) + r%4 (candidate block i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (qg[j] >= a.nq) continue;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = wc * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    const float dot = acc[i][j][r];
-                    const float s = (qn[j] - dot) + (xn[m] - dot);
-                    if (s < tau[j]) {
-                        const int64_t c = c0 + m;
-                        if (c < a.c_end && c != a.self_offset + qg[j]) {
-                            const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
-                            if (pos < (unsigned)a.cap)
-                                a.buf[qg[j] * a.cap + pos] =
-                                    ((uint64_t)__float_as_uint(fmaxf(s, 0.f)) << 32) | (uint64_t)(uint32_t)c;
-                        }
-                    }
-                }
-            }
-        }
-    }
-}
-
 
 constexpr int kSplitRows = 64;  // candidate rows per LDS tile of the bf16 split kernel
 constexpr int kQueue = 1024;    // survivor queue entries per workgroup
@@ -489,6 +365,25 @@ __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x
     }
 }
 
+// rows of integers in [0,255], centred (x - 128, exact in bf16) and zero-padded to dp elements, with
+// |x - 128|^2 as an int; 8 lanes per row
+template <typename T>
+__global__ __launch_bounds__(256) void bf16_rows_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
+                                                        uint16_t* __restrict__ xb, int* __restrict__ norms)
+{
+    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
+    int acc = 0;
+    if (row < n)
+        for (int j = (int)(threadIdx.x & 7); j < dp; j += 8) {
+            const int c = j < d ? (int)x[row * d + j] - 128 : 0;
+            acc += c * c;
+            xb[row * dp + j] = (uint16_t)(__float_as_uint((float)c) >> 16);
+        }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (row < n && (threadIdx.x & 7) == 0) norms[row] = acc;
+}
+
 // two packed bf16 values, each multiplied by -2 (exact; zero stays zero)
 __device__ __forceinline__ uint32_t bf16x2_times_minus2(uint32_t w)
 {
@@ -689,8 +584,9 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     }
 }
 
-// ---------------------------------------------------------------- bf16 split path, d > 128
-// The same hi + lo contraction when a query's fragments no longer fit the registers: both
+// ---------------------------------------------------------------- rows wider than 128 elements
+// The same hi + lo contraction when a query's fragments no longer fit the registers (LO = true; integer
+// rows, which are exact in bf16, run it with the hi parts alone, LO = false, one MFMA per k-step): both
 // operands go through LDS in slabs of 32 elements of the k dimension, double buffered, with
 // the loads of slab g+1 in flight during the MFMAs of slab g.  One workgroup owns a tile of
 // 128 queries x 128 candidates (4 waves, 64 x 64 each = 2 x 2 blocks of 32 x 32, 12 MFMAs per
@@ -716,6 +612,7 @@ __device__ __forceinline__ int wide_lds_offset(int row, int chunk)
     return row * kWideDK + ((chunk ^ ((row >> 2) & 3)) << 3);
 }
 
+template <bool LO>
 __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
 {
     const SplitArgs& a = w.s;
@@ -740,14 +637,24 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int wq = wave >> 1, wc = wave & 1;
     if (threadIdx.x == 0) q_cnt = 0u;
 
+    // LO: float arithmetic with a rounding margin downstream.  !LO: the rows are centred integers, every
+    // product and partial sum is an integer below 2^24 in magnitude (d <= 1024), so the accumulators are
+    // exact and the norms, thresholds and the filter are taken in int32 (the norm arrays hold ints).
+    using V = std::conditional_t<LO, float, int>;
     int64_t qg[2];
-    float qn[2], tq[2];
+    V qn[2], tq[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         qg[j] = q0 + wq * 64 + j * 32 + (lane & 31);
         const bool ok = qg[j] < a.nq;
-        qn[j] = ok ? a.qnorm[qg[j]] : 0.f;
-        tq[j] = ok ? a.tau[qg[j]] - qn[j] : -kInf;
+        if constexpr (LO) {
+            qn[j] = ok ? a.qnorm[qg[j]] : 0.f;
+            tq[j] = ok ? a.tau[qg[j]] - qn[j] : -kInf;
+        } else {
+            qn[j] = ok ? reinterpret_cast<const int*>(a.qnorm)[qg[j]] : 0;
+            const float tf = ok ? a.tau[qg[j]] : -1.f;   // an integer-valued float or +inf
+            tq[j] = ok ? (tf < 1.0e9f ? (int)tf - qn[j] : (1 << 30)) : -(1 << 30);
+        }
     }
 
     const int64_t span0 = a.c_begin + y * a.tiles_per_block * kTile;
@@ -770,16 +677,18 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         for (int h = 0; h < 2; ++h) {
             const int64_t xr = span0 + min(t * kTile + fr + h * 64, last_row);
             st[0][h] = *reinterpret_cast<const u32x4*>(a.qh + qrow[h] * w.dp + ko);
-            st[1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
             st[2][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
-            st[3][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
+            if constexpr (LO) {
+                st[1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
+                st[3][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
+            }
         }
         if (threadIdx.x < kTile) st_n = a.xnorm[span0 + min(t * kTile + (int)threadIdx.x, last_row)];
     };
     auto commit = [&](int buf, int t, int sg) __attribute__((always_inline)) {
         uint16_t* slab = wide_slabs + buf * 4 * PART;
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
+        for (int p = 0; p < 4; p += LO ? 1 : 2)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
                 *reinterpret_cast<u32x4*>(slab + p * PART + wide_lds_offset(fr + h * 64, fc)) = st[p][h];
@@ -815,16 +724,20 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                 const int qo = wide_lds_offset(wq * 64 + i * 32 + (lane & 31), chunk);
                 const int xo = wide_lds_offset(wc * 64 + i * 32 + (lane & 31), chunk);
                 qh[i] = *reinterpret_cast<const bf16x8*>(slab + 0 * PART + qo);
-                ql[i] = *reinterpret_cast<const bf16x8*>(slab + 1 * PART + qo);
                 xh[i] = *reinterpret_cast<const bf16x8*>(slab + 2 * PART + xo);
-                xl[i] = *reinterpret_cast<const bf16x8*>(slab + 3 * PART + xo);
+                if constexpr (LO) {
+                    ql[i] = *reinterpret_cast<const bf16x8*>(slab + 1 * PART + qo);
+                    xl[i] = *reinterpret_cast<const bf16x8*>(slab + 3 * PART + xo);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[j], acc[i][j], 0, 0, 0);
+                    if constexpr (LO) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[j], acc[i][j], 0, 0, 0);
+                    }
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[j], acc[i][j], 0, 0, 0);
                 }
         }
@@ -834,20 +747,31 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
             const int64_t c0 = span0 + (int64_t)t * kTile + wc * 64;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                float xv[16];
+                V xv[16];
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                    xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
+                    if constexpr (LO) {
+                        xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
+                    } else {  // the same words, read as the ints they are
+                        xv[4 * r4 + 0] = __float_as_int(v.x); xv[4 * r4 + 1] = __float_as_int(v.y);
+                        xv[4 * r4 + 2] = __float_as_int(v.z); xv[4 * r4 + 3] = __float_as_int(v.w);
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    floatx16 u;
+                    V u[16];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
-                    float lo = __builtin_fminf(u[0], u[1]);
+                    for (int r = 0; r < 16; ++r) {
+                        if constexpr (LO) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
+                        else u[r] = xv[r] - 2 * (int)acc[i][j][r];
+                    }
+                    V lo = u[0] < u[1] ? u[0] : u[1];
 #pragma unroll
-                    for (int r = 2; r < 16; r += 2) lo = __builtin_fminf(__builtin_fminf(lo, u[r]), u[r + 1]);
+                    for (int r = 2; r < 16; r += 2) {
+                        const V p = u[r] < u[r + 1] ? u[r] : u[r + 1];
+                        lo = p < lo ? p : lo;
+                    }
                     if (ballot64(lo < tq[j])) {
                         uint32_t mask = 0;
 #pragma unroll
@@ -856,14 +780,14 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                         while (ballot64(mask != 0u)) {
                             const int rr = mask ? (int)__builtin_ctz(mask) : 16;
                             mask &= mask - 1u;
-                            float uv = 0.f;
+                            V uv = 0;
 #pragma unroll
                             for (int r = 0; r < 16; ++r) uv = rr == r ? u[r] : uv;
                             const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                             const int64_t c = c0 + m;
                             if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
-                                const uint64_t key =
-                                    ((uint64_t)__float_as_uint(fmaxf(uv + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                                const float sf = LO ? fmaxf((float)(uv + qn[j]), 0.f) : (float)max((int)(uv + qn[j]), 0);
+                                const uint64_t key = ((uint64_t)__float_as_uint(sf) << 32) | (uint64_t)(uint32_t)c;
                                 const unsigned slot = atomicAdd(&q_cnt, 1u);
                                 if (slot < (unsigned)kSplitQueue) {
                                     q_key[slot] = key;
@@ -1190,19 +1114,21 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     const bool integer_data = h_info[0] == 0 && (self || h_info[2] == 0);
     float xnorm_max;
     std::memcpy(&xnorm_max, &h_info[1], 4);
-    // exact when every product and partial sum is an integer below 2^24
-    const bool exact = integer_data && (double)d * 255.0 * 255.0 < 16777216.0;
-    const float err_scale = exact ? 0.f : (float)((d + 8) * 5.9604645e-8 * 1.01);
+    // Integer rows are centred to x - 128; their products and partial sums are then integers of at most
+    // d * 2^14 in magnitude: exact in int32 (int8 path) and, up to d = 1024, in the fp32 accumulators
+    // of the bf16 path as well.  Wider integer rows are treated like real-valued ones.
+    const bool exact = integer_data && d <= 1024;
+    const float err_scale = 0.f;  // of the exact paths; the split paths carry split_err
     // With an exact filter the threshold needs no margin for rounding, only for ties: a row is
     // accepted when its k-th distance lies strictly below the kprime-th, so a few extra entries
     // suffice, and every chunk then passes about kprime survivors per row instead of 2k.
-    if (exact && d <= 128) kprime = std::min(kprime, k + std::max(8, k / 4));
+    if (exact) kprime = std::min(kprime, k + std::max(8, k / 4));
 
     // int8 fast path: integer rows with d <= 128 are rewritten once as centred, padded int8
     const bool fast = exact && d <= 128;
     // bf16 split path: real-valued rows are centred and written as hi + lo; up to d = 128 the query
     // fragments stay in registers (k-steps of 16), wider rows are staged through LDS in slabs of 32
-    const bool split = !integer_data;
+    const bool split = !exact;
     const bool wide = split && d > 128;
     const int ks = (d + 15) / 16;
     const int dp = wide ? (d + kWideDK - 1) / kWideDK * kWideDK : ks * 16;
@@ -1218,6 +1144,25 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             TSDG_HIP(qn8.alloc((size_t)nq * 4));
             hipLaunchKernelGGL((i8_prep_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
                                dp8, qc8.as<uint8_t>(), qn8.as<int>(), static_cast<unsigned*>(nullptr));
+        }
+        TSDG_HIP(hipGetLastError());
+    }
+
+    // integer rows of 129..1024 elements: centred, exact in bf16, so the staged kernel runs on one part
+    // per row (one MFMA per k-step) and filters in int32
+    const bool iwide = exact && !fast;
+    const int dpi = (d + kWideDK - 1) / kWideDK * kWideDK;
+    DevBuf xb16, qb16, xn16, qn16;
+    if (iwide) {
+        TSDG_HIP(xb16.alloc((size_t)N * dpi * 2));
+        TSDG_HIP(xn16.alloc((size_t)N * 4));
+        hipLaunchKernelGGL((bf16_rows_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dpi,
+                           xb16.as<uint16_t>(), xn16.as<int>());
+        if (!self) {
+            TSDG_HIP(qb16.alloc((size_t)nq * dpi * 2));
+            TSDG_HIP(qn16.alloc((size_t)nq * 4));
+            hipLaunchKernelGGL((bf16_rows_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
+                               dpi, qb16.as<uint16_t>(), qn16.as<int>());
         }
         TSDG_HIP(hipGetLastError());
     }
@@ -1260,8 +1205,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     const float split_err = (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
 
     constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);   // dynamic part: the slabs
-    if (wide) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&filter_wide_kernel),
+    if (wide || iwide) {
+        hipError_t e = hipFuncSetAttribute(wide ? reinterpret_cast<const void*>(&filter_wide_kernel<true>)
+                                                : reinterpret_cast<const void*>(&filter_wide_kernel<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLds);
         if (e != hipSuccess) {
             set_error("hipFuncSetAttribute(%zu bytes of LDS) failed: %s", kWideLds, hipGetErrorString(e));
@@ -1318,7 +1264,6 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             f.c_begin = cb;
             f.c_end = ce;
             const int64_t tiles = (ce - cb + kTile - 1) / kTile;
-            dim3 grid((unsigned)((nr + kTile - 1) / kTile), (unsigned)((tiles + kTilesPerBlock - 1) / kTilesPerBlock));
             if (fast) {
                 I8Args fa;
                 fa.qc = (self ? xc8.as<uint8_t>() : qc8.as<uint8_t>()) + r0 * dp8;
@@ -1365,7 +1310,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     wa.q_tiles = (int)((nr + kTile - 1) / kTile);
                     wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                     wa.q_group = 64;
-                    hipLaunchKernelGGL(filter_wide_kernel, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                    hipLaunchKernelGGL(filter_wide_kernel<true>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                        kWideLds, stream, wa);
                 } else {
                     const int64_t ftiles = (ce - cb + kSplitRows - 1) / kSplitRows;
@@ -1379,7 +1324,29 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     }
                 }
             } else {  // integer rows wider than 128 elements
-                hipLaunchKernelGGL((filter_kernel<TQ, TB>), grid, dim3(256), 0, stream, f);
+                WideArgs wa;
+                SplitArgs& sa = wa.s;
+                sa.qh = (self ? xb16.as<uint16_t>() : qb16.as<uint16_t>()) + r0 * dpi;
+                sa.ql = nullptr;
+                sa.xh = xb16.as<uint16_t>();
+                sa.xl = nullptr;
+                sa.qnorm = reinterpret_cast<const float*>((self ? xn16.as<int>() : qn16.as<int>()) + r0);  // ints
+                sa.xnorm = reinterpret_cast<const float*>(xn16.as<int>());
+                sa.tau = f.tau;
+                sa.cnt = f.cnt;
+                sa.buf = f.buf;
+                sa.nq = nr;
+                sa.c_begin = cb;
+                sa.c_end = ce;
+                sa.self_offset = f.self_offset;
+                sa.cap = cap;
+                sa.tiles_per_block = (int)std::min<int64_t>(4, tiles);
+                wa.dp = dpi;
+                wa.q_tiles = (int)((nr + kTile - 1) / kTile);
+                wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
+                wa.q_group = 64;
+                hipLaunchKernelGGL(filter_wide_kernel<false>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                                   kWideLds, stream, wa);
             }
             TSDG_HIP(hipGetLastError());
             if (cap <= 256) hipLaunchKernelGGL(compact_kernel<4>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);

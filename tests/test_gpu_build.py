@@ -114,17 +114,35 @@ def test_knn_real_valued_wide_rows(gpu, orc, d, N):
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"wide bf d={d}") == 0
 
 
-@pytest.mark.parametrize("d", [200, 320])
+@pytest.mark.parametrize("d", [208, 320, 1024, 1100])
 def test_knn_integer_wide_rows(gpu, orc, d):
-    """Integer rows in [0,255] wider than 128 elements: bf16 operands are exact, and up to d = 258 so
-    is the fp32 accumulation; beyond it the acceptance margin covers the rounding."""
+    """Integer rows in [0,255] wider than 128 elements: centred they are exact in bf16 and, up to d = 1024,
+    so is every partial sum of the fp32 accumulators (the filter then runs in int32); wider ones go the
+    way of real-valued rows.  fp32 and uint8 storage, and separate query rows (integer and not)."""
     step(f"ann_knn integer rows d={d}")
     g = np.random.default_rng(700 + d)
-    base = np.clip(np.rint(g.normal(120, 40, size=(1300, d))), 0, 255).astype(np.float32)
+    protos = g.integers(0, 256, size=(24, d))
+    base = np.clip(protos[g.integers(0, 24, size=900)] + np.rint(g.normal(0, 25, size=(900, d))), 0, 255).astype(np.float32)
+    base[:3] = 255.0                                        # rows of the largest norm, exact copies of each other
+    base[3:6] = 0.0
     ref = orc.knn(base, 16)
     ids, s = gpu.ann_knn(dev(base), 16)
     assert_bitwise(ids.cpu().numpy(), ref[0], f"integer wide ids d={d}")
     assert_bitwise(s.cpu().numpy(), ref[1], f"integer wide dists d={d}")
+    if d <= 1024:
+        b8 = base.astype(np.uint8)
+        ids, s = gpu.ann_knn(dev(b8), 16)
+        assert_bitwise(ids.cpu().numpy(), ref[0], f"integer wide ids u8 d={d}")
+        q = base[100:140].copy()
+        q[::2] = np.clip(q[::2] + 3.0, 0, 255)
+        refb = orc.bruteforce(b8, q, 10)
+        ids, s = gpu.ann_bruteforce(dev(b8), dev(q), 10)
+        assert_bitwise(ids.cpu().numpy(), refb[0], f"integer wide bf ids d={d}")
+        assert_bitwise(s.cpu().numpy(), refb[1], f"integer wide bf dists d={d}")
+        qr = (q + 0.25).astype(np.float32)                  # queries that are not integers: the split path on uint8 rows
+        refb = orc.bruteforce(b8, qr, 10)
+        ids, s = gpu.ann_bruteforce(dev(b8), dev(qr), 10)
+        assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), refb[0], refb[1], f"integer wide bf real q d={d}") == 0
 
 
 def test_bruteforce(gpu, orc):
