@@ -5,10 +5,10 @@
 // a dense contraction on the matrix cores:
 //   * rows that are integers in [0,255] with d <= 128 (uint8 rows, SIFT-like fp32 rows) are
 //     centred to int8 and go through the integer matrix cores (v_mfma_i32_32x32x32_i8), exact;
-//     such rows with d > 128 go through bf16 MFMA with both operands staged in LDS, one MFMA per
-//     k-step (the values are exact in bf16 and up to d = 258 so is every partial sum; beyond, fp32
-//     accumulation rounds and the acceptance test carries the bound);
-//   * real-valued rows are centred and split into bf16 hi + lo parts, three
+//     such rows of 129..1024 elements go through bf16 MFMA with both operands staged in LDS, one
+//     MFMA per k-step: centred to x - 128 they are exact in bf16 and every partial sum is an integer
+//     of at most 2^24 in magnitude, so the fp32 accumulators are exact and the filter runs in int32;
+//   * real-valued rows (and integer rows wider than 1024) are centred and split into bf16 hi + lo parts, three
 //     v_mfma_f32_32x32x16_bf16 per k-step, with an error near that of fp32 accumulation: with the
 //     query fragments in registers up to d = 128, with both operands staged through LDS beyond.
 // The contraction only SELECTS candidates: each query row keeps the K' = 2k
