@@ -219,6 +219,33 @@ def main():
             result["qps_interpolated_at_target_recall"] = round(
                 float(np.exp(np.log(lo_["qps"]) + f * (np.log(hi_["qps"]) - np.log(lo_["qps"])))))
 
+    # the smallest L (not only of the grid above) that meets the target, by bisection between the
+    # bracketing grid values: a measured point next to the interpolated one
+    if not args.L:
+        for lo_, hi_ in zip(sweep, sweep[1:]):
+            if lo_["recall@10"] < args.target_recall <= hi_["recall@10"]:
+                a_, b_ = lo_["L"], hi_["L"]          # a_ fails, b_ passes
+                best = {"L": b_, "recall@10": hi_["recall@10"], "qps": hi_["qps"], "ms": hi_["ms"]}
+                while b_ - a_ > 1:
+                    m_ = (a_ + b_) // 2
+                    ids_m, s_m = P.ann_search_ex(graph, base, queries, k, m_, mode=1, lambda_visit=lambda_visit)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(5):
+                        P.ann_search_ex(graph, base, queries, k, m_, mode=1, lambda_visit=lambda_visit, out=(ids_m, s_m))
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms_m = e0.elapsed_time(e1) / 5
+                    rec_m = recall_of(ids_m)
+                    if rec_m >= args.target_recall:
+                        b_ = m_
+                        best = {"L": m_, "recall@10": round(rec_m, 4), "qps": round(args.nq / ms_m * 1e3), "ms": round(ms_m, 4)}
+                    else:
+                        a_ = m_
+                result["smallest_L_meeting_target"] = best
+                log(f"smallest L meeting the target: {best}")
+
     # ---- what this GPU reaches on the same access shape without the search around it: a streaming copy,
     # and plain gathers of whole rows at random ids (the base itself, partly cache-resident at 512 MB,
     # and a 4 GiB table that is not)
