@@ -25,7 +25,10 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream).  ann_search* return after enqueueing; ann_build_graph*,
  *     ann_knn, ann_bruteforce, import and export synchronise the stream before
- *     returning because they size or free temporary device memory.
+ *     returning because they size or free temporary device memory (hipFree also
+ *     waits for work on the caller's other streams).  ann_search_ex and
+ *     ann_search_alg2 allocate nothing; ann_search_multi allocates only when the
+ *     graph's scratch buffer has to grow.
  *   - Errors: a status code is returned, never an exception or abort; outputs
  *     are untouched when argument validation fails; ann_last_error() gives a
  *     thread-local message for the last failing call.
