@@ -28,7 +28,8 @@
  *     returning because they size or free temporary device memory (hipFree also
  *     waits for work on the caller's other streams).  ann_search_ex and
  *     ann_search_alg2 allocate nothing; ann_search_multi allocates only when the
- *     graph's scratch buffer has to grow.
+ *     graph's scratch buffer has to grow (it starts large enough for 16 queries x
+ *     128 searches).
  *   - Errors: a status code is returned, never an exception or abort; outputs
  *     are untouched when argument validation fails; ann_last_error() gives a
  *     thread-local message for the last failing call.

@@ -273,6 +273,14 @@ void ann_search_params_default(ann_search_params* p)
     p->metric = ANN_L2;
 }
 
+static void destroy_graph(ann_graph_impl* g)
+{
+    if (!g) return;
+    if (g->packed) (void)hipFree(g->packed);
+    if (g->ws) (void)hipFree(g->ws);
+    delete g;
+}
+
 static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
 {
     ann_graph_impl* g = new (std::nothrow) ann_graph_impl();
@@ -292,6 +300,11 @@ static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
         delete g;
         return ANN_ENOMEM;
     }
+    // scratch of the multi-search for its usual calls (up to 16 queries x 128 searches), so that those never
+    // allocate; larger calls grow it
+    const size_t ws = (size_t)16 * 128 * 33 * sizeof(uint64_t);
+    if (hipMalloc(&g->ws, ws) == hipSuccess) g->ws_bytes = ws;
+    else { g->ws = nullptr; (void)hipGetLastError(); }
     *out = g;
     return ANN_OK;
 }
@@ -309,8 +322,7 @@ ann_status ann_graph_import(const int32_t* adj, const uint8_t* lam, int64_t N, i
     if (rc != ANN_OK) return rc;
     rc = pack_graph(adj, lam, N, K, static_cast<hipStream_t>(stream), g->packed, &g->max_lambda);
     if (rc != ANN_OK) {
-        (void)hipFree(g->packed);
-        delete g;
+        destroy_graph(g);
         return rc;
     }
     *out = reinterpret_cast<ann_graph*>(g);
@@ -338,10 +350,7 @@ ann_status ann_graph_info(const ann_graph* graph, int64_t* N, int* K, int* d)
 void ann_graph_free(ann_graph* graph)
 {
     if (!graph) return;
-    ann_graph_impl* g = reinterpret_cast<ann_graph_impl*>(graph);
-    (void)hipFree(g->packed);
-    if (g->ws) (void)hipFree(g->ws);
-    delete g;
+    destroy_graph(reinterpret_cast<ann_graph_impl*>(graph));
 }
 
 ann_status ann_knn(const void* base, int64_t N, int d, int K, ann_dtype dtype, void* stream, int32_t* knn_ids,
@@ -433,7 +442,7 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
     (void)hipFree(knn_id);
     (void)hipFree(knn_s);
     if (rc != ANN_OK) {
-        if (g) { (void)hipFree(g->packed); delete g; }
+        destroy_graph(g);
         return rc;
     }
     *out = reinterpret_cast<ann_graph*>(g);
