@@ -103,7 +103,7 @@ typedef struct {
  *         2 = small batch (one workgroup of several wavefronts per query).
  *   lambda_visit: edges with lambda < lambda_visit are followed; values above
  *         31 mean every stored edge.  RESULTS DEPEND ON IT.
- *   visited_slots: capacity (power of two, 64..16384) of the per-query hashed
+ *   visited_slots: capacity (a multiple of 64 in 64..16384) of the per-query hashed
  *         visited set.  It is lossy without false positives: results do not
  *         depend on it, only the number of distance evaluations does.
  *   qi_offset: added to the query's index in the seed generator, so that a

@@ -586,14 +586,16 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     if (lv > 31) lv = 32;
     s.lambda_visit = lv;
 
-    // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds,
-    // and 1,024 slots measured fastest for every L (a smaller set re-scores more rows, a larger
-    // one lowers occupancy); a workgroup per query has LDS to spare, and a batch that leaves
+    // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds:
+    // 1,280 slots is the most that keeps 20 workgroups on a CU with room to spare for lists of up
+    // to 128 entries, and measured fastest there (1,024: 1-3 % slower, re-scoring more rows; 1,536 and
+    // 2,048: slower from L = 128 on, by occupancy); longer lists take 1,024.  A workgroup per
+    // query has LDS to spare, and a batch that leaves
     // most CUs with one workgroup takes the largest set that still pays (fewer rows scored twice).
     int slots = p.visited_slots;
     if (slots == 0) {
         if (mode == 1) {
-            slots = 1024;
+            slots = L <= 128 ? 1280 : 1024;
         } else if (nq <= 512) {
             slots = 8192;
         } else {
@@ -602,8 +604,8 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
             if (slots > 8192) slots = 8192;
         }
     }
-    if (slots < 64 || slots > 16384 || (slots & (slots - 1)) != 0) {
-        set_error("ann_search: visited_slots must be a power of two in 64..16384");
+    if (slots < 64 || slots > 16384 || slots % 64 != 0) {
+        set_error("ann_search: visited_slots must be a multiple of 64 in 64..16384");
         return ANN_EINVAL;
     }
     s.visited_slots = slots;

@@ -195,10 +195,11 @@ __device__ __forceinline__ uint32_t hash_id(uint32_t id)
 }
 __device__ __forceinline__ bool visited_test_and_set(uint32_t* table, int slots, uint32_t id)
 {
-    const uint32_t mask = (uint32_t)slots - 1u;
-    const uint32_t h = hash_id(id) & mask;
+    const uint32_t h = __umulhi(hash_id(id), (uint32_t)slots);   // any table size, not only powers of two
     for (int p = 0; p < kProbes; ++p) {
-        const uint32_t old = atomicCAS(&table[(h + p) & mask], kHashEmpty, id);
+        uint32_t j = h + (uint32_t)p;
+        j = j >= (uint32_t)slots ? j - (uint32_t)slots : j;
+        const uint32_t old = atomicCAS(&table[j], kHashEmpty, id);
         if (old == kHashEmpty) return false;
         if (old == id) return true;
     }

@@ -153,7 +153,7 @@ def test_argument_errors(gpu, orc):
             gpu.ann_search_ex(g, b, q, k, L)
         assert e.value.status == 1
     with pytest.raises(gpu.AnnError):
-        gpu.ann_search_ex(g, b, q, 10, 32, visited_slots=100)        # not a power of two
+        gpu.ann_search_ex(g, b, q, 10, 32, visited_slots=100)        # not a multiple of 64
     with pytest.raises(gpu.AnnError):
         gpu.ann_search_ex(g, b, q, 10, 32, waves_per_query=3, mode=2)
     bad = adj.copy()
