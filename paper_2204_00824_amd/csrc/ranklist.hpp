@@ -182,8 +182,8 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
     sync();
 }
 
-// S4: insert-if-absent into an open-addressed table of `slots` (power of two)
-// 32-bit ids.  Returns true when the id was already there.  After kProbes full
+// S4: insert-if-absent into an open-addressed table of `slots` 32-bit ids (any size: the home
+// slot is the high half of hash x slots, and probing wraps round).  Returns true when the id was already there.  After kProbes full
 // slots the home slot is overwritten: the set then forgets an id (a later visit
 // re-scores it, which the merge's duplicate rule makes harmless) but never
 // reports an id it has not seen.
