@@ -285,11 +285,16 @@ def main():
         # matrix cores alone: MFMAs on register operands, 3 workgroups of 4 waves per compute unit
         mblocks, miters = 256 * 3, 50000
         mout = torch.empty(4 * mblocks, dtype=torch.float32, device=dev)
-        for kind, name, ops in ((0, "mfma_int8_registers_only_TOPS", 65536), (1, "mfma_bf16_registers_only_TFLOPS", 32768)):
+        for kind, name, ops in ((0, "mfma_int8_registers_only_TOPS", 65536), (1, "mfma_bf16_registers_only_TFLOPS", 32768),
+                                (2, "mfma_int8_registers_only_random_fragments_TOPS", 65536),
+                                (3, "mfma_bf16_registers_only_random_fragments_TFLOPS", 32768)):
             t = timed(lambda: P.ann_probe_mfma(kind, mblocks, miters, out=mout))
             ceil[name] = round(mblocks * 4 * miters * 4 * ops / t / 1e12, 1)
         result["build"]["knn_mfma_frac_of_registers_only_loop"] = round(
             result["build"]["knn_mfma_tops"] / ceil["mfma_int8_registers_only_TOPS"], 4)
+        # the same loop on pseudo-random fragments draws more power and sustains less: the rate that data allows
+        result["build"]["knn_mfma_frac_of_registers_only_loop_random_fragments"] = round(
+            result["build"]["knn_mfma_tops"] / ceil["mfma_int8_registers_only_random_fragments_TOPS"], 4)
         result["measured_ceilings"] = ceil
         result["roofline"]["frac_of_measured_gather_512B"] = round(achieved / ceil["gather_base_512B_rows_GBps"], 4)
         log(f"ceilings: {ceil}")

@@ -250,10 +250,12 @@ ann_status ann_probe_gather(const void* base, int64_t N, int row_bytes, const ui
  * 4 * iters matrix-core instructions on constant register fragments, with no memory access in
  * the loop (kind 0: v_mfma_i32_32x32x32_i8, 65,536 operations each; kind 1:
  * v_mfma_f32_32x32x16_bf16, 32,768 each), and write one float per wavefront to out[4 * blocks]
- * (device): 4 * iters * 32 (kind 0) or 4 * iters * 16 (kind 1).  Timing it gives the rate the
- * matrix cores sustain on this GPU with nothing else in the way, against which the k-NN
- * contraction of the build (the exact k-NN graph under Sec. 3's diversification) is read.
- * 1 <= blocks <= 2^20, 1 <= iters <= 100000.  Asynchronous on `stream`. */
+ * (device): 4 * iters * 32 (kind 0) or 4 * iters * 16 (kind 1).  Kinds 2 and 3 are kinds 0 and
+ * 1 with pseudo-random fragments instead of ones (the same instructions; more wires toggle, so
+ * more power is drawn and the sustained rate falls; out then holds data-dependent sums).  Timing
+ * it gives the rate the matrix cores sustain on this GPU with nothing else in the way, against
+ * which the k-NN contraction of the build (the exact k-NN graph under Sec. 3's diversification)
+ * is read.  1 <= blocks <= 2^20, 1 <= iters <= 100000.  Asynchronous on `stream`. */
 ann_status ann_probe_mfma(int kind, int blocks, int iters, float* out, void* stream);
 
 /* Message of the last failing call on this thread ("" if none). */

@@ -356,7 +356,8 @@ def ann_probe_gather(base: torch.Tensor, ids: torch.Tensor, out: torch.Tensor = 
 
 def ann_probe_mfma(kind: int, blocks: int, iters: int, out: torch.Tensor = None, stream=None) -> torch.Tensor:
     """Measurement probe: 4 * iters matrix-core instructions per wavefront on register operands
-    (kind 0 int8 32x32x32, kind 1 bf16 32x32x16); returns one float per wavefront."""
+    (kind 0 int8 32x32x32, kind 1 bf16 32x32x16, on fragments of ones; kinds 2 and 3 the same on
+    pseudo-random fragments); returns one float per wavefront."""
     if out is None:
         out = torch.empty(4 * blocks, dtype=torch.float32, device="cuda")
     if out.numel() < 4 * blocks:

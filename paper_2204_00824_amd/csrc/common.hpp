@@ -76,7 +76,7 @@ struct SearchLaunch {
     int n_seeds;
     uint64_t seed;
     int max_hops;
-    int visited_slots;  // power of two
+    int visited_slots;  // a multiple of 64
     int waves;          // 1 = large-batch kernel
     int64_t qi_offset;
     int32_t* out_ids;

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void probe_gather_kernel(const uint4* __restri
 }
 
 // How fast do the matrix cores run with nothing around them?  Every wave keeps four independent
-// 32x32 accumulator blocks in registers and issues MFMAs on constant fragments (all ones), no
+// 32x32 accumulator blocks in registers and issues MFMAs on constant fragments (all ones, or see RANDOM), no
 // memory access in the loop; the k-NN contraction's fraction of the published peak is read
 // against what this loop reaches.  KIND 0: v_mfma_i32_32x32x32_i8, 1: v_mfma_f32_32x32x16_bf16.
 typedef int probe_i4 __attribute__((ext_vector_type(4)));
@@ -58,13 +58,36 @@ typedef int probe_i16 __attribute__((ext_vector_type(16)));
 typedef __bf16 probe_bf8 __attribute__((ext_vector_type(8)));
 typedef float probe_f16 __attribute__((ext_vector_type(16)));
 
-template <int KIND>
+__device__ __forceinline__ uint32_t probe_mix(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    return x;
+}
+
+// RANDOM: the fragments hold pseudo-random values (int8: any byte; bf16: +-[1, 2) with a random
+// mantissa), different in every lane, operand and accumulator block, instead of ones.  The
+// instruction stream is the same; what changes is how many wires toggle, that is the power drawn,
+// and with it the rate the chip sustains.
+template <int KIND, bool RANDOM>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __restrict__ out)
 {
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    uint4 fa[4], fb[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t h = probe_mix((uint32_t)threadIdx.x * 64u + (uint32_t)(b * 8 + i) + 1u);
+            const uint32_t one = KIND == 0 ? 0x01010101u : 0x3F803F80u;
+            // bf16: keep sign and mantissa bits of both halves, fix the exponent at 127
+            w[i] = !RANDOM ? one : KIND == 0 ? h : ((h & 0x807F807Fu) | 0x3F803F80u);
+        }
+        fa[b] = make_uint4(w[0], w[1], w[2], w[3]);
+        fb[b] = make_uint4(w[4], w[5], w[6], w[7]);
+    }
     float result = 0.f;
     if constexpr (KIND == 0) {
-        const probe_i4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
         probe_i16 acc[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b)
@@ -72,12 +95,11 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __res
             for (int r = 0; r < 16; ++r) acc[b][r] = 0;
         for (int it = 0; it < iters; ++it)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, ones, acc[b], 0, 0, 0);
+            for (int b = 0; b < 4; ++b)
+                acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(probe_i4, fa[b]),
+                                                               __builtin_bit_cast(probe_i4, fb[b]), acc[b], 0, 0, 0);
         result = (float)(acc[0][0] + acc[1][5] + acc[2][10] + acc[3][15]);
     } else {
-        const uint32_t w = 0x3F803F80u;  // two bf16 ones
-        const uint4 u = make_uint4(w, w, w, w);
-        const probe_bf8 ones = __builtin_bit_cast(probe_bf8, u);
         probe_f16 acc[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b)
@@ -85,10 +107,12 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __res
             for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
         for (int it = 0; it < iters; ++it)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, ones, acc[b], 0, 0, 0);
+            for (int b = 0; b < 4; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(probe_bf8, fa[b]),
+                                                                 __builtin_bit_cast(probe_bf8, fb[b]), acc[b], 0, 0, 0);
         result = acc[0][0] + acc[1][5] + acc[2][10] + acc[3][15];
     }
-    if (lane_id() == 0) out[wave] = result;  // 4 * iters * (32 or 16): every MFMA is accounted for
+    if (lane_id() == 0) out[wave] = result;  // ones: 4 * iters * (32 or 16), every MFMA is accounted for
 }
 
 }  // namespace tsdg
@@ -97,14 +121,19 @@ extern "C" ann_status ann_probe_mfma(int kind, int blocks, int iters, float* out
 {
     using namespace tsdg;
     if (!out) { set_error("ann_probe_mfma: null pointer"); return ANN_EINVAL; }
-    if (kind != 0 && kind != 1) { set_error("ann_probe_mfma: kind must be 0 (int8) or 1 (bf16)"); return ANN_EINVAL; }
+    if (kind < 0 || kind > 3) {
+        set_error("ann_probe_mfma: kind must be 0 (int8), 1 (bf16), 2 (int8, random fragments) or 3 (bf16, random fragments)");
+        return ANN_EINVAL;
+    }
     if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > 100000) {
         set_error("ann_probe_mfma: need 1 <= blocks <= 2^20 and 1 <= iters <= 100000");
         return ANN_EINVAL;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (kind == 0) probe_mfma_kernel<0><<<blocks, 256, 0, st>>>(iters, out);
-    else probe_mfma_kernel<1><<<blocks, 256, 0, st>>>(iters, out);
+    if (kind == 0) probe_mfma_kernel<0, false><<<blocks, 256, 0, st>>>(iters, out);
+    else if (kind == 1) probe_mfma_kernel<1, false><<<blocks, 256, 0, st>>>(iters, out);
+    else if (kind == 2) probe_mfma_kernel<0, true><<<blocks, 256, 0, st>>>(iters, out);
+    else probe_mfma_kernel<1, true><<<blocks, 256, 0, st>>>(iters, out);
     TSDG_HIP(hipGetLastError());
     return ANN_OK;
 }

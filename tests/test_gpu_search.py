@@ -200,7 +200,49 @@ def test_probe_mfma_counts_every_instruction(gpu, kind, per_mfma):
     out = gpu.ann_probe_mfma(kind, 37, 1000).cpu().numpy()
     assert out.shape == (4 * 37,) and np.all(out == 4 * 1000 * per_mfma)
     with pytest.raises(gpu.AnnError):
-        gpu.ann_probe_mfma(2, 1, 1)
+        gpu.ann_probe_mfma(4, 1, 1)
+
+
+def _probe_fragments(kind):
+    """The probe's pseudo-random register fragments, recomputed: [thread 0..255][block 0..3][A|B][4 words]."""
+    def mix(x):
+        x = x.astype(np.uint64)
+        x ^= x >> 16; x = (x * 0x7FEB352D) & 0xFFFFFFFF
+        x ^= x >> 15; x = (x * 0x846CA68B) & 0xFFFFFFFF
+        x ^= x >> 16
+        return x.astype(np.uint32)
+    t = np.arange(256, dtype=np.uint64)[:, None] * 64 + np.arange(32, dtype=np.uint64)[None, :] + 1
+    h = mix(t & 0xFFFFFFFF)
+    if kind == 3:
+        h = (h & np.uint32(0x807F807F)) | np.uint32(0x3F803F80)
+    return h.reshape(256, 4, 2, 4)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kind", [2, 3])
+def test_probe_mfma_random_fragments(gpu, kind):
+    """Kinds 2 and 3 multiply pseudo-random fragments: the word each wavefront writes is iters x the
+    sum of four entries of A_b B_b^T, recomputed here from the fragments (rows of A and B sit in lanes
+    l % 32, the two halves of the k range in lanes < 32 and >= 32)."""
+    step(f"probe mfma kind={kind}")
+    iters = 3
+    out = gpu.ann_probe_mfma(kind, 5, iters).cpu().numpy().reshape(5, 4)
+    w = _probe_fragments(kind)
+    if kind == 2:
+        v = w.view(np.int8).reshape(256, 4, 2, 16).astype(np.int64)
+    else:
+        v = (w.view(np.uint16).astype(np.uint32) << 16).view(np.float32).reshape(256, 4, 2, 8).astype(np.float64)
+    want = np.zeros(4)
+    for wave in range(4):
+        for b, m in enumerate((0, 9, 18, 27)):      # registers 0, 5, 10, 15 of lane 0: rows 0, 9, 18, 27, column 0
+            for kh in range(2):
+                want[wave] += np.dot(v[wave * 64 + m + 32 * kh, b, 0], v[wave * 64 + 0 + 32 * kh, b, 1])
+    want *= iters
+    for blk in range(5):
+        if kind == 2:
+            assert np.array_equal(out[blk], want.astype(np.float32)), (out[blk], want)
+        else:
+            assert np.allclose(out[blk], want, rtol=1e-5, atol=1e-4), (out[blk], want)
 
 
 @pytest.mark.gpu
