@@ -106,6 +106,45 @@ struct FilterArgs {
 constexpr int kSplitRows = 64;  // candidate rows per LDS tile of the bf16 split kernel
 constexpr int kQueue = 1024;    // survivor queue entries per workgroup
 
+// The survivors of a workgroup's sweep wait in LDS and go to their rows' global buffers in bursts, issued
+// by all 256 threads at once instead of one by one from inside the sweep.
+template <int CAPQ>
+struct SurvivorQueue {
+    uint64_t key[CAPQ];
+    uint16_t row[CAPQ];   // query row, counted from the workgroup's first
+    unsigned count;
+
+    // any lane, any time between two flushes; a full queue sends the entry straight to the global buffer
+    __device__ __forceinline__ void push(uint64_t k, int row_in_group, int64_t global_row, unsigned* cnt, uint64_t* buf, int cap)
+    {
+        const unsigned slot = atomicAdd(&count, 1u);
+        if (slot < (unsigned)CAPQ) {
+            key[slot] = k;
+            row[slot] = (uint16_t)row_in_group;
+        } else {
+            const unsigned pos = atomicAdd(&cnt[global_row], 1u);
+            if (pos < (unsigned)cap) buf[global_row * cap + pos] = k;
+        }
+    }
+    // all 256 threads, after a barrier that follows the last push; empties the queue once it is half full
+    // (or holds anything and `last` is set).  row0 = global row of the workgroup's first query.
+    __device__ __forceinline__ void flush(int64_t row0, unsigned* cnt, uint64_t* buf, int cap, bool last)
+    {
+        const unsigned queued = count;
+        if (queued >= (unsigned)CAPQ / 2 || (last && queued > 0)) {
+            const unsigned n = min(queued, (unsigned)CAPQ);
+            for (unsigned e = threadIdx.x; e < n; e += 256) {
+                const int64_t r = row0 + row[e];
+                const unsigned pos = atomicAdd(&cnt[r], 1u);
+                if (pos < (unsigned)cap) buf[r * cap + pos] = key[e];
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) count = 0u;
+            __syncthreads();
+        }
+    }
+};
+
 // ---------------------------------------------------------------- int8 path (integer rows in [0,255], d <= 128)
 // The same sweep on the integer matrix cores (v_mfma_i32_32x32x32_i8: twice the rate of bf16 and
 // half the bytes per element in LDS).  Rows are rewritten once as x' = x - 128 (int8, padded with
@@ -140,14 +179,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     __shared__ __attribute__((aligned(16))) uint8_t Xs[2][kI8Rows * XS];
     __shared__ __attribute__((aligned(16))) int xstart[2][kI8Rows];   // -(|x'|^2 >> 1)
     __shared__ int xpar[2][kI8Rows];                                  // |x'|^2 & 1
-    __shared__ uint64_t q_key[kQueue];
-    __shared__ uint16_t q_row[kQueue];
-    __shared__ unsigned q_cnt;
+    __shared__ SurvivorQueue<kQueue> queue;
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
     const int64_t q0 = (int64_t)blockIdx.x * 256 + wave * 64;
-    if (threadIdx.x == 0) q_cnt = 0u;
+    if (threadIdx.x == 0) queue.count = 0u;
 
     intx4 qf[2][KS];
     int64_t qg[2];
@@ -271,14 +308,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                             if (rr < 16 && u < tq[j] && c < span1 && c != a.self_offset + qg[j]) {
                                 const uint64_t key =
                                     ((uint64_t)__float_as_uint((float)max(u + qn[j], 0)) << 32) | (uint64_t)(uint32_t)c;
-                                const unsigned slot = atomicAdd(&q_cnt, 1u);
-                                if (slot < (unsigned)kQueue) {
-                                    q_key[slot] = key;
-                                    q_row[slot] = (uint16_t)(wave * 64 + j * 32 + (lane & 31));
-                                } else {  // queue full: straight to the global buffer
-                                    const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
-                                    if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
-                                }
+                                queue.push(key, wave * 64 + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                             }
                         }
                     }
@@ -287,18 +317,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
         if (t + 1 < ntiles) commit(cur ^ 1, st);
         __syncthreads();
-        const unsigned queued = q_cnt;
-        if (queued >= (unsigned)kQueue / 2 || (t + 1 == ntiles && queued > 0)) {
-            const unsigned n = min(queued, (unsigned)kQueue);
-            for (unsigned e = threadIdx.x; e < n; e += 256) {
-                const int64_t row = (int64_t)blockIdx.x * 256 + q_row[e];
-                const unsigned pos = atomicAdd(&a.cnt[row], 1u);
-                if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) q_cnt = 0u;
-            __syncthreads();
-        }
+        queue.flush((int64_t)blockIdx.x * 256, a.cnt, a.buf, a.cap, t + 1 == ntiles);
     }
 }
 
@@ -421,13 +440,11 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     constexpr int PER_THREAD = (CHUNKS + 255) / 256;
     __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][kSplitRows * XS];   // [buffer][hi|lo]
     __shared__ __attribute__((aligned(16))) float xn[2][kSplitRows];
-    __shared__ uint64_t q_key[kSplitQueue];
-    __shared__ uint16_t q_row[kSplitQueue];
-    __shared__ unsigned q_cnt;
+    __shared__ SurvivorQueue<kSplitQueue> queue;
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    if (threadIdx.x == 0) q_cnt = 0u;
+    if (threadIdx.x == 0) queue.count = 0u;
 
     // QB blocks of 32 queries per wave
     bf16x8 qfh[QB][KS], qfl[QB][KS];
@@ -554,14 +571,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
                         if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
                             const uint64_t key =
                                 ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
-                            const unsigned slot = atomicAdd(&q_cnt, 1u);
-                            if (slot < (unsigned)kSplitQueue) {
-                                q_key[slot] = key;
-                                q_row[slot] = (uint16_t)(wave * (32 * QB) + j * 32 + (lane & 31));
-                            } else {
-                                const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
-                                if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
-                            }
+                            queue.push(key, wave * (32 * QB) + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                         }
                     }
                 }
@@ -569,18 +579,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
         }
         if (t + 1 < ntiles) commit(cur ^ 1);
         __syncthreads();
-        const unsigned queued = q_cnt;
-        if (queued >= (unsigned)kSplitQueue / 2 || (t + 1 == ntiles && queued > 0)) {
-            const unsigned n = min(queued, (unsigned)kSplitQueue);
-            for (unsigned e = threadIdx.x; e < n; e += 256) {
-                const int64_t row = (int64_t)blockIdx.x * (128 * QB) + q_row[e];
-                const unsigned pos = atomicAdd(&a.cnt[row], 1u);
-                if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) q_cnt = 0u;
-            __syncthreads();
-        }
+        queue.flush((int64_t)blockIdx.x * (128 * QB), a.cnt, a.buf, a.cap, t + 1 == ntiles);
     }
 }
 
@@ -618,9 +617,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const SplitArgs& a = w.s;
     extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][4][128 * kWideDK]: qh, ql, xh, xl
     __shared__ __attribute__((aligned(16))) float xn[2][kTile];
-    __shared__ uint64_t q_key[kSplitQueue];
-    __shared__ uint16_t q_row[kSplitQueue];
-    __shared__ unsigned q_cnt;
+    __shared__ SurvivorQueue<kSplitQueue> queue;
     constexpr int PART = kTile * kWideDK;   // elements of one operand part of a slab
 
     // block numbering: groups of q_group query tiles, inside a group the query tile varies fastest
@@ -635,7 +632,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
     const int wq = wave >> 1, wc = wave & 1;
-    if (threadIdx.x == 0) q_cnt = 0u;
+    if (threadIdx.x == 0) queue.count = 0u;
 
     // LO: float arithmetic with a rounding margin downstream.  !LO: the rows are centred integers, every
     // product and partial sum is an integer below 2^24 in magnitude (d <= 1024), so the accumulators are
@@ -788,14 +785,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                             if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
                                 const float sf = LO ? fmaxf((float)(uv + qn[j]), 0.f) : (float)max((int)(uv + qn[j]), 0);
                                 const uint64_t key = ((uint64_t)__float_as_uint(sf) << 32) | (uint64_t)(uint32_t)c;
-                                const unsigned slot = atomicAdd(&q_cnt, 1u);
-                                if (slot < (unsigned)kSplitQueue) {
-                                    q_key[slot] = key;
-                                    q_row[slot] = (uint16_t)(wq * 64 + j * 32 + (lane & 31));
-                                } else {
-                                    const unsigned pos = atomicAdd(&a.cnt[qg[j]], 1u);
-                                    if (pos < (unsigned)a.cap) a.buf[qg[j] * a.cap + pos] = key;
-                                }
+                                queue.push(key, wq * 64 + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                             }
                         }
                     }
@@ -805,18 +795,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         if (more) commit(cur ^ 1, tn, sn);
         __syncthreads();
         if (tile_done) {
-            const unsigned queued = q_cnt;
-            if (queued >= (unsigned)kSplitQueue / 2 || (!more && queued > 0)) {
-                const unsigned n = min(queued, (unsigned)kSplitQueue);
-                for (unsigned e = threadIdx.x; e < n; e += 256) {
-                    const int64_t row = q0 + q_row[e];
-                    const unsigned pos = atomicAdd(&a.cnt[row], 1u);
-                    if (pos < (unsigned)a.cap) a.buf[row * a.cap + pos] = q_key[e];
-                }
-                __syncthreads();
-                if (threadIdx.x == 0) q_cnt = 0u;
-                __syncthreads();
-            }
+            queue.flush(q0, a.cnt, a.buf, a.cap, !more);
         }
         t = tn;
         sg = sn;
