@@ -71,8 +71,8 @@ typedef enum { ANN_F32 = 0, ANN_U8 = 1, ANN_F16 = 2 } ann_dtype;
 typedef enum { ANN_L2 = 0, ANN_COSINE = 1 } ann_metric;
 
 /* Build parameters.  Defaults (ann_build_params_default): fp32 rows,
- * alpha = 1.2 (Sec. 3.2: "usually greater than 1.1"), lambda0 = 9 (so that the
- * paper's "lambda < 10" prefix of Sec. 5.4 means every stored edge),
+ * alpha = 1.2 (Sec. 3.2 recommends values above 1.1), lambda0 = 9 (so that the
+ * small-batch prefix of Sec. 5.4, lambda below 10, means every stored edge),
  * rev_cap = 0 meaning 2*K (length to which a list is cut after the reverse
  * edges are appended; the paper leaves it unbounded), stream NULL. */
 typedef struct {
@@ -82,8 +82,8 @@ typedef struct {
     int rev_cap;
     void* stream;
     ann_metric metric; /* default ANN_L2 */
-    /* Which k-NN graph the diversification starts from (Sec. 3 opening: "an approximate k-NN
-     * graph"; the default here is the exact one).  knn_mode 0 = exact (MFMA contraction);
+    /* Which k-NN graph the diversification starts from (Sec. 3 allows an approximate one;
+     * the default here is the exact one).  knn_mode 0 = exact (MFMA contraction);
      * 1 = neighbourhood propagation, see ann_knn_descent, with the four parameters below
      * (0 = defaults: S = largest power of two <= min(16, K/2), 12 iterations, delta 0.001, seed 0). */
     int knn_mode;
@@ -220,8 +220,8 @@ ann_status ann_ip_augment_rows(const float* src, int64_t n, int d, float M, int 
 
 /* Approximate k-NN lists by neighbourhood propagation (the published NN-descent idea in a form
  * where every node pulls its candidates from the previous iteration's lists, so the result does
- * not depend on execution order; the paper starts from "an approximate k-NN graph", Sec. 3, and
- * names no builder).  base[N,d] device rows of `dtype`; K in 1..64, K < N; S = sample size, a
+ * not depend on execution order; Sec. 3 starts from an approximate k-NN graph and names no
+ * builder).  base[N,d] device rows of `dtype`; K in 1..64, K < N; S = sample size, a
  * power of two in 2..16; at most max_iters iterations, stopping early once an iteration changes
  * no more than delta*N*K list entries; `seed` draws the start lists (2K draws per node from the
  * generator of the search's seeds), or init_ids[N,K] (device, may be NULL; -1 = none) gives them.
