@@ -23,6 +23,7 @@
 // rows that fail, or whose buffer overflowed, are redone by a plain scan of
 // all base rows with the canonical distance.
 #include <algorithm>
+#include <cmath>
 #include <type_traits>
 #include <cstdio>
 #include <cstdlib>
@@ -36,6 +37,7 @@ namespace tsdg {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 constexpr int kTile = 128;        // queries and candidates per workgroup tile
 constexpr float kInf = __builtin_inff();
@@ -384,6 +386,34 @@ __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x
     }
 }
 
+// one wave per row: centred rows as ONE binary16 part, scaled by a power of two (scale) that puts the
+// largest element near 2^14, well inside binary16's range; centred squared norm (unscaled), max norm
+template <typename T>
+__global__ __launch_bounds__(256) void half_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
+                                                        const float* __restrict__ mean, float scale,
+                                                        uint16_t* __restrict__ xh, float* __restrict__ norms,
+                                                        unsigned* maxnorm)
+{
+    const int64_t row = linear_block() * 4 + (threadIdx.x >> 6);
+    const int lane = lane_id();
+    if (row >= n) return;
+    double acc = 0.0;
+    for (int j = lane; j < dp; j += 64) {
+        float c = 0.f;
+        if (j < d) c = (float)x[row * d + j] - mean[j];
+        const _Float16 h = (_Float16)(c * scale);   // round to nearest even
+        xh[row * dp + j] = __builtin_bit_cast(uint16_t, h);
+        acc += (double)c * (double)c;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    if (lane == 0) {
+        const float nf = (float)acc;
+        norms[row] = nf;
+        if (__float_as_uint(nf) > *maxnorm) atomicMax(maxnorm, __float_as_uint(nf));
+    }
+}
+
 // rows of integers in [0,255], centred (x - 128, exact in bf16) and zero-padded to dp elements, with
 // |x - 128|^2 as an int; 8 lanes per row
 template <typename T>
@@ -425,20 +455,27 @@ struct SplitArgs {
     int64_t c_begin, c_end;
     int64_t self_offset;
     int cap, tiles_per_block;
+    float scale2, inv_scale2;   // square of the rows' scale and its inverse (powers of two; 1 for the hi + lo rows)
 };
 
 constexpr int kSplitQueue = 512;
 constexpr int kSplitQB = 2;   // blocks of 32 queries per wave
 
-template <int KS>
-__global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
+// SINGLE: the rows are one binary16 part (half_prep_kernel) instead of bf16 hi + lo: one MFMA per k-step
+// instead of three, |error of q.x| <= (2^-10 + d*2^-24) sum|q_j||x_j| instead of 3*2^-16: a wider margin in
+// the acceptance test of the re-scoring pass, the same answer.  Norms and thresholds stay in the rows'
+// own units in memory and are multiplied by scale2 where they meet the accumulators.
+template <int KS, bool SINGLE>
+__global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(SplitArgs a)
 {
     constexpr int QB = kSplitQB;
+    constexpr int PARTS = SINGLE ? 1 : 2;
+    using frag_t = std::conditional_t<SINGLE, half8, bf16x8>;
     constexpr int DP = KS * 16;
     constexpr int XS = DP + 8;
     constexpr int CHUNKS = kSplitRows * DP / 8;       // 16-byte chunks per part of a tile
     constexpr int PER_THREAD = (CHUNKS + 255) / 256;
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][2][kSplitRows * XS];   // [buffer][hi|lo]
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][PARTS][kSplitRows * XS];   // [buffer][hi|lo]
     __shared__ __attribute__((aligned(16))) float xn[2][kSplitRows];
     __shared__ SurvivorQueue<kSplitQueue> queue;
 
@@ -447,30 +484,34 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     if (threadIdx.x == 0) queue.count = 0u;
 
     // QB blocks of 32 queries per wave
-    bf16x8 qfh[QB][KS], qfl[QB][KS];
+    frag_t qfh[QB][KS], qfl[SINGLE ? 1 : QB][SINGLE ? 1 : KS];
     int64_t qg[QB];
-    float qn[QB], tq[QB];
+    float qn[QB], tq[QB];   // in the accumulators' units (times scale2)
 #pragma unroll
     for (int j = 0; j < QB; ++j) {
         qg[j] = (int64_t)blockIdx.x * (128 * QB) + wave * (32 * QB) + j * 32 + (lane & 31);
         const bool qok = qg[j] < a.nq;
-        qn[j] = qok ? a.qnorm[qg[j]] : 0.f;
-        tq[j] = qok ? a.tau[qg[j]] - qn[j] : -kInf;
+        qn[j] = qok ? a.qnorm[qg[j]] * a.scale2 : 0.f;
+        tq[j] = qok ? a.tau[qg[j]] * a.scale2 - qn[j] : -kInf;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             uint4 wh = make_uint4(0u, 0u, 0u, 0u), wl = wh;
             if (qok) {
                 wh = *reinterpret_cast<const uint4*>(a.qh + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
-                wl = *reinterpret_cast<const uint4*>(a.ql + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
+                if constexpr (!SINGLE) wl = *reinterpret_cast<const uint4*>(a.ql + qg[j] * DP + ks * 16 + 8 * (lane >> 5));
             }
-            // both parts of the query enter as -2q (exact), so that with |x|^2 as the accumulators'
-            // start value the contraction itself yields |x|^2 - 2 q.x
-            wh.x = bf16x2_times_minus2(wh.x); wh.y = bf16x2_times_minus2(wh.y);
-            wh.z = bf16x2_times_minus2(wh.z); wh.w = bf16x2_times_minus2(wh.w);
-            wl.x = bf16x2_times_minus2(wl.x); wl.y = bf16x2_times_minus2(wl.y);
-            wl.z = bf16x2_times_minus2(wl.z); wl.w = bf16x2_times_minus2(wl.w);
-            qfh[j][ks] = __builtin_bit_cast(bf16x8, wh);
-            qfl[j][ks] = __builtin_bit_cast(bf16x8, wl);
+            // the query enters as -2q (exact: the scale keeps 2|q_j| inside binary16's range), so that with
+            // |x|^2 as the accumulators' start value the contraction itself yields |x|^2 - 2 q.x
+            if constexpr (SINGLE) {
+                qfh[j][ks] = __builtin_bit_cast(half8, wh) * (_Float16)-2;
+            } else {
+                wh.x = bf16x2_times_minus2(wh.x); wh.y = bf16x2_times_minus2(wh.y);
+                wh.z = bf16x2_times_minus2(wh.z); wh.w = bf16x2_times_minus2(wh.w);
+                wl.x = bf16x2_times_minus2(wl.x); wl.y = bf16x2_times_minus2(wl.y);
+                wl.z = bf16x2_times_minus2(wl.z); wl.w = bf16x2_times_minus2(wl.w);
+                qfh[j][ks] = __builtin_bit_cast(bf16x8, wh);
+                qfl[j][ks] = __builtin_bit_cast(bf16x8, wl);
+            }
         }
     }
 
@@ -480,7 +521,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     const int ntiles = (int)((span1 - span0 + kSplitRows - 1) / kSplitRows);
 
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
-    u32x4 stage[2][PER_THREAD];
+    u32x4 stage[PARTS][PER_THREAD];
     float stage_n = 0.f;
     // A tile part is one contiguous block of kSplitRows * DP elements; a chunk index past the span's
     // end is clamped to the span's last chunk (rows read twice that way carry ids >= span1 and are
@@ -488,16 +529,17 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
     const int last_chunk = (int)(span1 - span0) * (DP / 8) - 1;
     const int last_row = (int)(span1 - span0) - 1;
     const uint16_t* xh_span = a.xh + span0 * DP;
-    const uint16_t* xl_span = a.xl + span0 * DP;
+    const uint16_t* xl_span = SINGLE ? nullptr : a.xl + span0 * DP;
     auto fetch = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int ch = min((int)threadIdx.x + i * 256, CHUNKS - 1);
             const int64_t off = (int64_t)min(t * CHUNKS + ch, last_chunk) * 8;
             stage[0][i] = *reinterpret_cast<const u32x4*>(xh_span + off);
-            stage[1][i] = *reinterpret_cast<const u32x4*>(xl_span + off);
+            if constexpr (!SINGLE) stage[PARTS - 1][i] = *reinterpret_cast<const u32x4*>(xl_span + off);
         }
-        if (threadIdx.x < kSplitRows) stage_n = a.xnorm[span0 + min(t * kSplitRows + (int)threadIdx.x, last_row)];
+        if (threadIdx.x < kSplitRows)
+            stage_n = a.xnorm[span0 + min(t * kSplitRows + (int)threadIdx.x, last_row)] * a.scale2;
     };
     auto commit = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
@@ -506,7 +548,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
             const int r = ch / (DP / 8), c8 = ch % (DP / 8);
             if (ch < CHUNKS) {
                 *reinterpret_cast<u32x4*>(&Xs[b][0][r * XS + c8 * 8]) = stage[0][i];
-                *reinterpret_cast<u32x4*>(&Xs[b][1][r * XS + c8 * 8]) = stage[1][i];
+                if constexpr (!SINGLE) *reinterpret_cast<u32x4*>(&Xs[b][PARTS - 1][r * XS + c8 * 8]) = stage[PARTS - 1][i];
             }
         }
         if (threadIdx.x < kSplitRows) xn[b][threadIdx.x] = stage_n;
@@ -537,13 +579,19 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int off = (i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
-                const bf16x8 xh = *reinterpret_cast<const bf16x8*>(&Xs[cur][0][off]);
-                const bf16x8 xl = *reinterpret_cast<const bf16x8*>(&Xs[cur][1][off]);
+                const frag_t xh = *reinterpret_cast<const frag_t*>(&Xs[cur][0][off]);
+                if constexpr (SINGLE) {
 #pragma unroll
-                for (int j = 0; j < QB; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[j][ks], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[j][ks], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < QB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
+                } else {
+                    const frag_t xl = *reinterpret_cast<const frag_t*>(&Xs[cur][PARTS - 1][off]);
+#pragma unroll
+                    for (int j = 0; j < QB; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[j][ks], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[j][ks], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -570,7 +618,7 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
                         const int64_t c = c0 + m;
                         if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
                             const uint64_t key =
-                                ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f)) << 32) | (uint64_t)(uint32_t)c;
+                                ((uint64_t)__float_as_uint(fmaxf(u + qn[j], 0.f) * a.inv_scale2) << 32) | (uint64_t)(uint32_t)c;
                             queue.push(key, wave * (32 * QB) + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                         }
                     }
@@ -584,8 +632,8 @@ __global__ __launch_bounds__(256, 2) void filter_split_kernel(SplitArgs a)
 }
 
 // ---------------------------------------------------------------- rows wider than 128 elements
-// The same hi + lo contraction when a query's fragments no longer fit the registers (LO = true; integer
-// rows, which are exact in bf16, run it with the hi parts alone, LO = false, one MFMA per k-step): both
+// The same contraction when a query's fragments no longer fit the registers (MODE 1: hi + lo parts; MODE 2:
+// one scaled binary16 part; MODE 0: integer rows, which are exact in bf16, one part, one MFMA per k-step): both
 // operands go through LDS in slabs of 32 elements of the k dimension, double buffered, with
 // the loads of slab g+1 in flight during the MFMAs of slab g.  One workgroup owns a tile of
 // 128 queries x 128 candidates (4 waves, 64 x 64 each = 2 x 2 blocks of 32 x 32, 12 MFMAs per
@@ -611,9 +659,14 @@ __device__ __forceinline__ int wide_lds_offset(int row, int chunk)
     return row * kWideDK + ((chunk ^ ((row >> 2) & 3)) << 3);
 }
 
-template <bool LO>
+// MODE 0: centred integer rows, one bf16 part, exact (filter in int32); 1: real-valued rows as bf16 hi + lo;
+// 2: real-valued rows as one scaled binary16 part (see filter_split_kernel's SINGLE).
+template <int MODE>
 __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
 {
+    constexpr bool LO = MODE == 1;    // lo parts staged and multiplied
+    constexpr bool FLT = MODE != 0;   // float arithmetic with a rounding margin downstream
+    using frag_t = std::conditional_t<MODE == 2, half8, bf16x8>;
     const SplitArgs& a = w.s;
     extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][4][128 * kWideDK]: qh, ql, xh, xl
     __shared__ __attribute__((aligned(16))) float xn[2][kTile];
@@ -634,19 +687,19 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int wq = wave >> 1, wc = wave & 1;
     if (threadIdx.x == 0) queue.count = 0u;
 
-    // LO: float arithmetic with a rounding margin downstream.  !LO: the rows are centred integers, every
+    // FLT: float arithmetic with a rounding margin downstream.  !FLT: the rows are centred integers, every
     // product and partial sum is an integer below 2^24 in magnitude (d <= 1024), so the accumulators are
     // exact and the norms, thresholds and the filter are taken in int32 (the norm arrays hold ints).
-    using V = std::conditional_t<LO, float, int>;
+    using V = std::conditional_t<FLT, float, int>;
     int64_t qg[2];
     V qn[2], tq[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         qg[j] = q0 + wq * 64 + j * 32 + (lane & 31);
         const bool ok = qg[j] < a.nq;
-        if constexpr (LO) {
-            qn[j] = ok ? a.qnorm[qg[j]] : 0.f;
-            tq[j] = ok ? a.tau[qg[j]] - qn[j] : -kInf;
+        if constexpr (FLT) {   // in the accumulators' units
+            qn[j] = ok ? a.qnorm[qg[j]] * a.scale2 : 0.f;
+            tq[j] = ok ? a.tau[qg[j]] * a.scale2 - qn[j] : -kInf;
         } else {
             qn[j] = ok ? reinterpret_cast<const int*>(a.qnorm)[qg[j]] : 0;
             const float tf = ok ? a.tau[qg[j]] : -1.f;   // an integer-valued float or +inf
@@ -680,7 +733,10 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                 st[3][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
             }
         }
-        if (threadIdx.x < kTile) st_n = a.xnorm[span0 + min(t * kTile + (int)threadIdx.x, last_row)];
+        if (threadIdx.x < kTile) {
+            st_n = a.xnorm[span0 + min(t * kTile + (int)threadIdx.x, last_row)];
+            if constexpr (FLT) st_n *= a.scale2;   // (the integer rows' norms are ints in these words)
+        }
     };
     auto commit = [&](int buf, int t, int sg) __attribute__((always_inline)) {
         uint16_t* slab = wide_slabs + buf * 4 * PART;
@@ -715,27 +771,31 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
 #pragma unroll
         for (int k16 = 0; k16 < kWideDK / 16; ++k16) {
             const int chunk = k16 * 2 + (lane >> 5);
-            bf16x8 qh[2], ql[2], xh[2], xl[2];
+            frag_t qh[2], ql[2], xh[2], xl[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int qo = wide_lds_offset(wq * 64 + i * 32 + (lane & 31), chunk);
                 const int xo = wide_lds_offset(wc * 64 + i * 32 + (lane & 31), chunk);
-                qh[i] = *reinterpret_cast<const bf16x8*>(slab + 0 * PART + qo);
-                xh[i] = *reinterpret_cast<const bf16x8*>(slab + 2 * PART + xo);
+                qh[i] = *reinterpret_cast<const frag_t*>(slab + 0 * PART + qo);
+                xh[i] = *reinterpret_cast<const frag_t*>(slab + 2 * PART + xo);
                 if constexpr (LO) {
-                    ql[i] = *reinterpret_cast<const bf16x8*>(slab + 1 * PART + qo);
-                    xl[i] = *reinterpret_cast<const bf16x8*>(slab + 3 * PART + xo);
+                    ql[i] = *reinterpret_cast<const frag_t*>(slab + 1 * PART + qo);
+                    xl[i] = *reinterpret_cast<const frag_t*>(slab + 3 * PART + xo);
                 }
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    if constexpr (LO) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[j], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[j], acc[i][j], 0, 0, 0);
+                    if constexpr (MODE == 2) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh[i], qh[j], acc[i][j], 0, 0, 0);
+                    } else {
+                        if constexpr (LO) {
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[j], acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[j], acc[i][j], 0, 0, 0);
+                        }
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[j], acc[i][j], 0, 0, 0);
                     }
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[j], acc[i][j], 0, 0, 0);
                 }
         }
         const bool tile_done = sg == nstage - 1;
@@ -748,7 +808,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                    if constexpr (LO) {
+                    if constexpr (FLT) {
                         xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
                     } else {  // the same words, read as the ints they are
                         xv[4 * r4 + 0] = __float_as_int(v.x); xv[4 * r4 + 1] = __float_as_int(v.y);
@@ -760,7 +820,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                     V u[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        if constexpr (LO) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
+                        if constexpr (FLT) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
                         else u[r] = xv[r] - 2 * (int)acc[i][j][r];
                     }
                     V lo = u[0] < u[1] ? u[0] : u[1];
@@ -783,7 +843,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                             const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                             const int64_t c = c0 + m;
                             if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
-                                const float sf = LO ? fmaxf((float)(uv + qn[j]), 0.f) : (float)max((int)(uv + qn[j]), 0);
+                                const float sf = FLT ? fmaxf((float)(uv + qn[j]), 0.f) * a.inv_scale2 : (float)max((int)(uv + qn[j]), 0);
                                 const uint64_t key = ((uint64_t)__float_as_uint(sf) << 32) | (uint64_t)(uint32_t)c;
                                 queue.push(key, wq * 64 + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                             }
@@ -899,7 +959,8 @@ struct RefineArgs {
     int32_t* redo_rows;   // local row indices that need the plain scan
     int64_t nq;
     int d, cap, k;
-    float err_scale;      // rounding-error bound of the expansion = err_scale * (|q|^2 + max|x|^2)
+    float err_scale;      // rounding-error bound of the expansion = err_scale * (|q|^2 + max|x|^2) + err_const
+    float err_const;
     float xnorm_max;
     int q_is_base;        // query rows are of the base type
 };
@@ -958,7 +1019,7 @@ __global__ __launch_bounds__(64) void refine_kernel(RefineArgs a)
     // acceptance: the k-th canonical distance must lie below tau - error bound
     const uint64_t kth = list[a.k - 1];
     const float tau = a.tau[row];
-    const float err = a.err_scale * (a.qnorm[row] + a.xnorm_max);
+    const float err = a.err_scale * (a.qnorm[row] + a.xnorm_max) + a.err_const;
     bool accept = !a.overflow[row];
     if (tau != kInf) accept = accept && kth != kKeyEmpty && key_dist(kth) < tau - err;
     if (!accept && lane == 0) a.redo_rows[atomicAdd(a.redo_cnt, 1u)] = (int32_t)row;
@@ -1066,8 +1127,9 @@ template <typename TQ, typename TB> struct RefineLaunch {
 
 template <typename TQ, typename TB>
 ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ* queries, int64_t nq, int k,
-                     bool self, hipStream_t stream, int32_t* out_ids, float* out_s)
+                     bool self, hipStream_t stream, int32_t* out_ids, float* out_s, bool allow_single, bool* retry)
 {
+    *retry = false;   // set when the one-part filter left too many rows to the plain scan: run again without it
     int kprime = std::min(2 * k, k + 64);
     int cap = kprime + 192 <= 256 ? 256 : 512;
     const int64_t row_block = 1ll << 21;  // query rows per sweep (bounds the candidate buffers: 4-8 GB)
@@ -1091,8 +1153,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     TSDG_HIP(hipMemcpyAsync(h_info, info.p, sizeof(h_info), hipMemcpyDeviceToHost, stream));
     TSDG_HIP(hipStreamSynchronize(stream));
     const bool integer_data = h_info[0] == 0 && (self || h_info[2] == 0);
-    float xnorm_max;
+    float xnorm_max, qnorm_max;
     std::memcpy(&xnorm_max, &h_info[1], 4);
+    std::memcpy(&qnorm_max, &h_info[self ? 1 : 3], 4);
     // Integer rows are centred to x - 128; their products and partial sums are then integers of at most
     // d * 2^14 in magnitude: exact in int32 (int8 path) and, up to d = 1024, in the fp32 accumulators
     // of the bf16 path as well.  Wider integer rows are treated like real-valued ones.
@@ -1109,6 +1172,19 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // fragments stay in registers (k-steps of 16), wider rows are staged through LDS in slabs of 32
     const bool split = !exact;
     const bool wide = split && d > 128;
+    // Real-valued rows go through the filter as ONE binary16 part, scaled by a power of
+    // two that puts the largest centred element (at most sqrt(max|q|^2) + sqrt(max|x|^2), the mean included)
+    // at or below 2^14: a third of the MFMAs of the hi + lo form for a wider, still rigorous, margin.
+    bool single = split && allow_single && std::isfinite(xnorm_max) && std::isfinite(qnorm_max);
+    float scale = 1.f;
+    if (single) {
+        const double bound = std::sqrt((double)std::max(xnorm_max, qnorm_max)) + std::sqrt((double)xnorm_max);
+        int e = bound > 0.0 ? (int)std::floor(std::log2(16384.0 / bound)) : 0;
+        e = std::max(-60, std::min(60, e));
+        if (bound * std::ldexp(1.0, e) > 16384.0) single = false;   // rows too large even at the smallest scale
+        else scale = std::ldexp(1.f, e);
+    }
+    const float scale2 = scale * scale;
     const int ks = (d + 15) / 16;
     const int dp = wide ? (d + kWideDK - 1) / kWideDK * kWideDK : ks * 16;
     const int ks8 = (d + 31) / 32, dp8 = ks8 * 32;
@@ -1153,7 +1229,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(cmean.alloc((size_t)d * 4));
         TSDG_HIP(cinfo.alloc(4));
         TSDG_HIP(xh.alloc((size_t)N * dp * 2));
-        TSDG_HIP(xl.alloc((size_t)N * dp * 2));
+        if (!single) TSDG_HIP(xl.alloc((size_t)N * dp * 2));
         TSDG_HIP(cxnorm.alloc((size_t)N * 4));
         TSDG_HIP(hipMemsetAsync(csum.p, 0, (size_t)d * 8, stream));
         TSDG_HIP(hipMemsetAsync(cinfo.p, 0, 4, stream));
@@ -1161,18 +1237,27 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                            csum.as<double>());
         hipLaunchKernelGGL(mean_kernel, dim3((unsigned)((d + 63) / 64)), dim3(64), 0, stream, csum.as<double>(), d, N,
                            cmean.as<float>());
-        hipLaunchKernelGGL((split_prep_kernel<TB>), folded_grid((N + 3) / 4), dim3(256), 0, stream, base, N, d, dp,
-                           cmean.as<float>(), xh.as<uint16_t>(), xl.as<uint16_t>(), cxnorm.as<float>(),
-                           cinfo.as<unsigned>());
+        if (single)
+            hipLaunchKernelGGL((half_prep_kernel<TB>), folded_grid((N + 3) / 4), dim3(256), 0, stream, base, N, d, dp,
+                               cmean.as<float>(), scale, xh.as<uint16_t>(), cxnorm.as<float>(), cinfo.as<unsigned>());
+        else
+            hipLaunchKernelGGL((split_prep_kernel<TB>), folded_grid((N + 3) / 4), dim3(256), 0, stream, base, N, d, dp,
+                               cmean.as<float>(), xh.as<uint16_t>(), xl.as<uint16_t>(), cxnorm.as<float>(),
+                               cinfo.as<unsigned>());
         unsigned h_max = 0;
         TSDG_HIP(hipMemcpyAsync(&h_max, cinfo.p, 4, hipMemcpyDeviceToHost, stream));
         if (!self) {
             TSDG_HIP(qh.alloc((size_t)nq * dp * 2));
-            TSDG_HIP(ql.alloc((size_t)nq * dp * 2));
+            if (!single) TSDG_HIP(ql.alloc((size_t)nq * dp * 2));
             TSDG_HIP(cqnorm.alloc((size_t)nq * 4));
-            hipLaunchKernelGGL((split_prep_kernel<TQ>), folded_grid((nq + 3) / 4), dim3(256), 0, stream, queries, nq,
-                               d, dp, cmean.as<float>(), qh.as<uint16_t>(), ql.as<uint16_t>(), cqnorm.as<float>(),
-                               cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
+            if (single)
+                hipLaunchKernelGGL((half_prep_kernel<TQ>), folded_grid((nq + 3) / 4), dim3(256), 0, stream, queries, nq,
+                                   d, dp, cmean.as<float>(), scale, qh.as<uint16_t>(), cqnorm.as<float>(),
+                                   cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
+            else
+                hipLaunchKernelGGL((split_prep_kernel<TQ>), folded_grid((nq + 3) / 4), dim3(256), 0, stream, queries, nq,
+                                   d, dp, cmean.as<float>(), qh.as<uint16_t>(), ql.as<uint16_t>(), cqnorm.as<float>(),
+                                   cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
         }
         TSDG_HIP(hipGetLastError());
         TSDG_HIP(hipStreamSynchronize(stream));
@@ -1181,12 +1266,19 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // rounding-error bound of the split expansion, as a multiple of (|q|^2 + max|x|^2) of the centred rows:
     // dropped terms 3*2^-16, fp32 accumulation over 3*dp products, norms and centring a few 2^-24
     // (the accumulation term is doubled because the accumulators also carry |x|^2 from the start)
-    const float split_err = (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
+    // One binary16 part: each element carries a relative error of 2^-11 or, below the normal range, an absolute
+    // one of delta = 2^-25 in scaled units, so |error of |x|^2 - 2 q.x| <= (2^-10 + 2^-22)(|q|^2 + |x|^2)
+    // + delta sqrt(dp) (2 + |q|^2 + |x|^2) + 2 dp delta^2 (scaled), plus the accumulation over dp products.
+    const double delta = 2.98023223876953125e-8, sq = std::sqrt((double)dp);
+    const float split_err = single ? (float)(1.05 * (1.0 / 1024.0 + 1.0 / 4194304.0 + delta * sq + (2.0 * dp + 64.0) * 5.9604645e-8))
+                                   : (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
+    const float split_err_const = single ? (float)(1.05 * (2.0 * delta * sq + 2.0 * dp * delta * delta) / (double)scale2) : 0.f;
 
     constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);   // dynamic part: the slabs
     if (wide || iwide) {
-        hipError_t e = hipFuncSetAttribute(wide ? reinterpret_cast<const void*>(&filter_wide_kernel<true>)
-                                                : reinterpret_cast<const void*>(&filter_wide_kernel<false>),
+        hipError_t e = hipFuncSetAttribute(!wide ? reinterpret_cast<const void*>(&filter_wide_kernel<0>)
+                                           : single ? reinterpret_cast<const void*>(&filter_wide_kernel<2>)
+                                                    : reinterpret_cast<const void*>(&filter_wide_kernel<1>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLds);
         if (e != hipSuccess) {
             set_error("hipFuncSetAttribute(%zu bytes of LDS) failed: %s", kWideLds, hipGetErrorString(e));
@@ -1270,9 +1362,11 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 WideArgs wa;
                 SplitArgs& sa = wa.s;
                 sa.qh = (self ? xh.as<uint16_t>() : qh.as<uint16_t>()) + r0 * dp;
-                sa.ql = (self ? xl.as<uint16_t>() : ql.as<uint16_t>()) + r0 * dp;
+                sa.ql = single ? nullptr : (self ? xl.as<uint16_t>() : ql.as<uint16_t>()) + r0 * dp;
                 sa.xh = xh.as<uint16_t>();
-                sa.xl = xl.as<uint16_t>();
+                sa.xl = single ? nullptr : xl.as<uint16_t>();
+                sa.scale2 = scale2;
+                sa.inv_scale2 = 1.f / scale2;
                 sa.qnorm = (self ? cxnorm.as<float>() : cqnorm.as<float>()) + r0;
                 sa.xnorm = cxnorm.as<float>();
                 sa.tau = f.tau;
@@ -1289,15 +1383,22 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     wa.q_tiles = (int)((nr + kTile - 1) / kTile);
                     wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                     wa.q_group = 64;
-                    hipLaunchKernelGGL(filter_wide_kernel<true>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
-                                       kWideLds, stream, wa);
+                    if (single)
+                        hipLaunchKernelGGL(filter_wide_kernel<2>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                                           kWideLds, stream, wa);
+                    else
+                        hipLaunchKernelGGL(filter_wide_kernel<1>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                                           kWideLds, stream, wa);
                 } else {
                     const int64_t ftiles = (ce - cb + kSplitRows - 1) / kSplitRows;
                     sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
                     constexpr int qpb = 128 * kSplitQB;   // queries per workgroup
                     dim3 sgrid((unsigned)((nr + qpb - 1) / qpb), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
                     switch (ks) {
-#define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_split_kernel<n>), sgrid, dim3(256), 0, stream, sa); break;
+#define TSDG_KS(n) case n: \
+    if (single) hipLaunchKernelGGL((filter_split_kernel<n, true>), sgrid, dim3(256), 0, stream, sa); \
+    else hipLaunchKernelGGL((filter_split_kernel<n, false>), sgrid, dim3(256), 0, stream, sa); \
+    break;
                         TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
 #undef TSDG_KS
                     }
@@ -1309,6 +1410,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 sa.ql = nullptr;
                 sa.xh = xb16.as<uint16_t>();
                 sa.xl = nullptr;
+                sa.scale2 = sa.inv_scale2 = 1.f;
                 sa.qnorm = reinterpret_cast<const float*>((self ? xn16.as<int>() : qn16.as<int>()) + r0);  // ints
                 sa.xnorm = reinterpret_cast<const float*>(xn16.as<int>());
                 sa.tau = f.tau;
@@ -1324,7 +1426,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 wa.q_tiles = (int)((nr + kTile - 1) / kTile);
                 wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                 wa.q_group = 64;
-                hipLaunchKernelGGL(filter_wide_kernel<false>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                hipLaunchKernelGGL(filter_wide_kernel<0>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                    kWideLds, stream, wa);
             }
             TSDG_HIP(hipGetLastError());
@@ -1359,6 +1461,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         rl.a.cap = cap;
         rl.a.k = k;
         rl.a.err_scale = split ? split_err : err_scale;
+        rl.a.err_const = split ? split_err_const : 0.f;
         rl.a.xnorm_max = split ? split_xmax : xnorm_max;
         rl.a.q_is_base = self ? 1 : 0;
         rl.N = N;
@@ -1374,6 +1477,16 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         unsigned redo = 0;
         TSDG_HIP(hipMemcpyAsync(&redo, redo_cnt.p, 4, hipMemcpyDeviceToHost, stream));
         TSDG_HIP(hipStreamSynchronize(stream));
+        if (progress) {
+            fprintf(stderr, "[knn] rows %lld..%lld: %u left to the plain scan%s\n", (long long)r0, (long long)(r0 + nr), redo,
+                    single ? " (one binary16 part)" : "");
+            fflush(stderr);
+        }
+        // the plain scan costs N distances per row: past a few rows in a thousand the hi + lo filter is cheaper
+        if (single && (int64_t)redo > nr / 256 + 64) {
+            *retry = true;
+            return ANN_OK;
+        }
         if (redo > 0) {
             rl.scan = true;
             rl.redo = redo;
@@ -1387,21 +1500,36 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 
 }  // namespace
 
+namespace {
+template <typename TQ, typename TB>
+ann_status knn_retrying(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ* queries, int64_t nq, int k, bool self,
+                        hipStream_t stream, int32_t* out_ids, float* out_s)
+{
+    const char* env = getenv("TSDG_KNN_PRECISE");   // 1: never use the one-part filter (for comparisons)
+    const bool precise = env && env[0] == '1';
+    bool retry = false;
+    ann_status rc = knn_typed<TQ, TB>(base, N, d, dtype, queries, nq, k, self, stream, out_ids, out_s, !precise, &retry);
+    if (rc == ANN_OK && retry)
+        rc = knn_typed<TQ, TB>(base, N, d, dtype, queries, nq, k, self, stream, out_ids, out_s, false, &retry);
+    return rc;
+}
+}  // namespace
+
 ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries, int64_t nq, int k,
                      bool exclude_self, hipStream_t stream, int32_t* out_ids, float* out_s)
 {
     if (exclude_self) {
         if (dtype == ANN_U8)
-            return knn_typed<uint8_t, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype,
-                                               static_cast<const uint8_t*>(base), N, k, true, stream, out_ids, out_s);
-        return knn_typed<float, float>(static_cast<const float*>(base), N, d, dtype, static_cast<const float*>(base),
-                                       N, k, true, stream, out_ids, out_s);
+            return knn_retrying<uint8_t, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype,
+                                                  static_cast<const uint8_t*>(base), N, k, true, stream, out_ids, out_s);
+        return knn_retrying<float, float>(static_cast<const float*>(base), N, d, dtype, static_cast<const float*>(base),
+                                          N, k, true, stream, out_ids, out_s);
     }
     if (dtype == ANN_U8)
-        return knn_typed<float, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype, queries, nq, k, false, stream,
-                                         out_ids, out_s);
-    return knn_typed<float, float>(static_cast<const float*>(base), N, d, dtype, queries, nq, k, false, stream,
-                                   out_ids, out_s);
+        return knn_retrying<float, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype, queries, nq, k, false, stream,
+                                            out_ids, out_s);
+    return knn_retrying<float, float>(static_cast<const float*>(base), N, d, dtype, queries, nq, k, false, stream,
+                                      out_ids, out_s);
 }
 
 }  // namespace tsdg

@@ -89,13 +89,32 @@ def test_knn_uint8(gpu, orc):
     assert_bitwise(s.cpu().numpy(), ref[1], "u8 knn dists")
 
 
+@pytest.mark.parametrize("precise", [False, True])
 @pytest.mark.parametrize("d", [8, 96, 128, 960])
-def test_knn_real_valued_shapes(gpu, orc, d):
-    step(f"ann_knn gaussian d={d}")
+def test_knn_real_valued_shapes(gpu, orc, d, precise, monkeypatch):
+    """Real-valued rows pass the filter as one scaled binary16 part, or (TSDG_KNN_PRECISE=1, also the
+    library's own fallback) as bf16 hi + lo parts: the lists equal the oracle's either way."""
+    step(f"ann_knn gaussian d={d} precise={precise}")
+    if precise:
+        monkeypatch.setenv("TSDG_KNN_PRECISE", "1")
     base = workloads.single_gaussian(3000 if d < 900 else 1500, d, seed=100 + d)
     ref = orc.knn(base, 16)
     ids, s = gpu.ann_knn(dev(base), 16)
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"knn d={d}") == 0
+
+
+@pytest.mark.parametrize("d", [16, 200])
+def test_knn_outlier_row_sends_every_row_to_the_fallbacks(gpu, orc, d):
+    """One row 10^4 times longer than the rest makes the acceptance margin (a multiple of the largest norm)
+    wider than every gap: the one-part filter gives up, the hi + lo filter runs, and its rejected rows are
+    redone by the plain scan.  The lists still equal the oracle's."""
+    step(f"ann_knn outlier d={d}")
+    g = np.random.default_rng(77 + d)
+    base = g.standard_normal((1500, d)).astype(np.float32)
+    base[123] *= 1.0e4
+    ref = orc.knn(base, 16)
+    ids, s = gpu.ann_knn(dev(base), 16)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"outlier d={d}") == 0
 
 
 @pytest.mark.parametrize("d,N", [(132, 1237), (200, 2100), (516, 1500), (2048, 700)])
