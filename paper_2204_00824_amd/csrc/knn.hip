@@ -8,9 +8,12 @@
 //     such rows of 129..1024 elements go through bf16 MFMA with both operands staged in LDS, one
 //     MFMA per k-step: centred to x - 128 they are exact in bf16 and every partial sum is an integer
 //     of at most 2^24 in magnitude, so the fp32 accumulators are exact and the filter runs in int32;
-//   * real-valued rows (and integer rows wider than 1024) are centred and split into bf16 hi + lo parts, three
-//     v_mfma_f32_32x32x16_bf16 per k-step, with an error near that of fp32 accumulation: with the
-//     query fragments in registers up to d = 128, with both operands staged through LDS beyond.
+//   * real-valued rows (and integer rows wider than 1024) are centred and written as one scaled binary16
+//     part, one v_mfma_f32_32x32x16_f16 per k-step (relative error 2^-10 of the norms, carried by the
+//     acceptance test below); when that margin rejects too many rows the call starts over with bf16
+//     hi + lo parts, three v_mfma_f32_32x32x16_bf16 per k-step, an error near that of fp32 accumulation.
+//     Either way the query fragments stay in registers up to d = 128 and both operands are staged
+//     through LDS beyond.
 // The contraction only SELECTS candidates: each query row keeps the K' = 2k
 // smallest approximate distances (K' = k + max(8, k/4) where the filter is exact) through a
 // threshold filter fused into the tile epilogue.  The base columns are swept in chunks of doubling
@@ -323,9 +326,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
 }
 
-// ---------------------------------------------------------------- bf16 split path (real-valued rows, d <= 128)
-// A real-valued row is centred (global mean removed: distances do not change, norms shrink) and
-// written as x = hi + lo with hi = bf16(x), lo = bf16(x - hi), both round-to-nearest; what is
+// ---------------------------------------------------------------- real-valued rows, d <= 128
+// A real-valued row is centred (global mean removed: distances do not change, norms shrink).  The
+// form tried first writes it as one binary16 part (half_prep_kernel, filter_split_kernel<KS, true>).
+// The fallback writes it as x = hi + lo with hi = bf16(x), lo = bf16(x - hi), both round-to-nearest; what is
 // left is below 2^-16 |x|.  q.x is taken as hi.hi + hi.lo + lo.hi on the bf16 matrix cores
 // (three MFMAs per k-step, products exact in fp32), which is 16/3 times the fp32-MFMA rate at
 // nearly the same accuracy: |error of q.x| <= (3*2^-16 + 3d*2^-24) sum|q_j||x_j|; the
