@@ -644,23 +644,29 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
 // 16 elements of k); the filter runs once per tile, after the last slab, so it is amortised
 // over d / 16 k-steps and needs none of the tricks of the register kernels: u = |x|^2 - 2 q.x
 // is formed from the finished accumulators.
-// LDS rows are 64 bytes with no padding; the 16-byte chunk c of row r is stored at chunk
-// c ^ ((r >> 2) & 3), which spreads the 16 rows a fragment read touches per cycle over all banks.
+// LDS rows are 64 bytes (hi + lo: slabs 32 deep) or 128 bytes (one part per operand: slabs 64 deep)
+// with no padding; the 16-byte chunk c of row r is stored at chunk c ^ ((r >> 2) & 3), resp. c ^ (r & 7),
+// which spreads the rows a fragment read touches per cycle over all banks.
 // Workgroups are numbered so that those resident together form a block of q_group query tiles
 // times a few candidate spans: the slabs they stream are then shared through the L2 caches
 // instead of each being fetched from memory once per workgroup.
-constexpr int kWideDK = 32;
+constexpr int kWideDK = 32;      // slab depth with hi + lo parts (MODE 1)
 
 struct WideArgs {
     SplitArgs s;
-    int dp;            // padded row length (multiple of kWideDK)
+    int dp;            // padded row length (a multiple of the slab depth)
     int q_tiles, ny;   // query tiles of 128 rows; candidate spans of tiles_per_block tiles
     int q_group;       // query tiles per group of the block numbering
 };
 
+constexpr int kWideDKOne = 64;   // slab depth with one part per operand (MODE 0 and 2): half the barriers for the same LDS
+
+// DK elements (2 bytes each) per LDS row, no padding: 16-byte chunk c of row r sits at chunk c ^ f(r)
+template <int DK>
 __device__ __forceinline__ int wide_lds_offset(int row, int chunk)
 {
-    return row * kWideDK + ((chunk ^ ((row >> 2) & 3)) << 3);
+    if constexpr (DK == 32) return row * DK + ((chunk ^ ((row >> 2) & 3)) << 3);
+    else return row * DK + ((chunk ^ (row & 7)) << 3);
 }
 
 // MODE 0: centred integer rows, one bf16 part, exact (filter in int32); 1: real-valued rows as bf16 hi + lo;
@@ -672,10 +678,12 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     constexpr bool FLT = MODE != 0;   // float arithmetic with a rounding margin downstream
     using frag_t = std::conditional_t<MODE == 2, half8, bf16x8>;
     const SplitArgs& a = w.s;
-    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][4][128 * kWideDK]: qh, ql, xh, xl
+    constexpr int DK = MODE == 1 ? kWideDK : kWideDKOne;   // elements of k per slab
+    constexpr int NP = LO ? 4 : 2, XP = LO ? 2 : 1;          // operand parts per slab: q (hi, lo), x (hi, lo)
+    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][NP][128 * DK]
     __shared__ __attribute__((aligned(16))) float xn[2][kTile];
     __shared__ SurvivorQueue<kSplitQueue> queue;
-    constexpr int PART = kTile * kWideDK;   // elements of one operand part of a slab
+    constexpr int PART = kTile * DK;   // elements of one operand part of a slab
 
     // block numbering: groups of q_group query tiles, inside a group the query tile varies fastest
     const int64_t b = linear_block();
@@ -715,26 +723,29 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kTile);
     if (span0 >= span1) return;
     const int ntiles = (int)((span1 - span0 + kTile - 1) / kTile);
-    const int nstage = w.dp / kWideDK;
+    const int nstage = w.dp / DK;
     const int G = ntiles * nstage;
 
-    // this thread's share of a slab: chunk (threadIdx & 3) of rows r and r + 64 of all four parts
+    // this thread's share of a slab: chunk fc of rows fr, fr + RP, ... of every part
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const int fr = (int)(threadIdx.x >> 2), fc = (int)(threadIdx.x & 3);
-    const int64_t qrow[2] = {min(q0 + fr, a.nq - 1), min(q0 + fr + 64, a.nq - 1)};   // clamped: rows past the end are
-    const int last_row = (int)(span1 - span0) - 1;                                   // re-reads whose results are dropped
-    u32x4 st[4][2];
+    constexpr int CH = DK / 8, RP = 256 / CH, H = kTile / RP;   // chunks per row, rows per pass, passes
+    const int fr = (int)threadIdx.x / CH, fc = (int)threadIdx.x % CH;
+    int64_t qrow[H];   // clamped: rows past the end are re-reads whose results are dropped
+#pragma unroll
+    for (int h = 0; h < H; ++h) qrow[h] = min(q0 + fr + h * RP, a.nq - 1);
+    const int last_row = (int)(span1 - span0) - 1;
+    u32x4 st[NP][H];
     float st_n = 0.f;
     auto fetch = [&](int t, int sg) __attribute__((always_inline)) {
-        const int ko = sg * kWideDK + fc * 8;
+        const int ko = sg * DK + fc * 8;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int64_t xr = span0 + min(t * kTile + fr + h * 64, last_row);
+        for (int h = 0; h < H; ++h) {
+            const int64_t xr = span0 + min(t * kTile + fr + h * RP, last_row);
             st[0][h] = *reinterpret_cast<const u32x4*>(a.qh + qrow[h] * w.dp + ko);
-            st[2][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
+            st[XP][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
             if constexpr (LO) {
                 st[1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
-                st[3][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
+                st[XP + 1][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
             }
         }
         if (threadIdx.x < kTile) {
@@ -743,12 +754,12 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         }
     };
     auto commit = [&](int buf, int t, int sg) __attribute__((always_inline)) {
-        uint16_t* slab = wide_slabs + buf * 4 * PART;
+        uint16_t* slab = wide_slabs + buf * NP * PART;
 #pragma unroll
-        for (int p = 0; p < 4; p += LO ? 1 : 2)
+        for (int p = 0; p < NP; ++p)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                *reinterpret_cast<u32x4*>(slab + p * PART + wide_lds_offset(fr + h * 64, fc)) = st[p][h];
+            for (int h = 0; h < H; ++h)
+                *reinterpret_cast<u32x4*>(slab + p * PART + wide_lds_offset<DK>(fr + h * RP, fc)) = st[p][h];
         if (sg == 0 && threadIdx.x < kTile) xn[t & 1][threadIdx.x] = st_n;
     };
 
@@ -771,20 +782,20 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
         }
-        const uint16_t* slab = wide_slabs + cur * 4 * PART;
+        const uint16_t* slab = wide_slabs + cur * NP * PART;
 #pragma unroll
-        for (int k16 = 0; k16 < kWideDK / 16; ++k16) {
+        for (int k16 = 0; k16 < DK / 16; ++k16) {
             const int chunk = k16 * 2 + (lane >> 5);
             frag_t qh[2], ql[2], xh[2], xl[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int qo = wide_lds_offset(wq * 64 + i * 32 + (lane & 31), chunk);
-                const int xo = wide_lds_offset(wc * 64 + i * 32 + (lane & 31), chunk);
+                const int qo = wide_lds_offset<DK>(wq * 64 + i * 32 + (lane & 31), chunk);
+                const int xo = wide_lds_offset<DK>(wc * 64 + i * 32 + (lane & 31), chunk);
                 qh[i] = *reinterpret_cast<const frag_t*>(slab + 0 * PART + qo);
-                xh[i] = *reinterpret_cast<const frag_t*>(slab + 2 * PART + xo);
+                xh[i] = *reinterpret_cast<const frag_t*>(slab + XP * PART + xo);
                 if constexpr (LO) {
                     ql[i] = *reinterpret_cast<const frag_t*>(slab + 1 * PART + qo);
-                    xl[i] = *reinterpret_cast<const frag_t*>(slab + 3 * PART + xo);
+                    xl[i] = *reinterpret_cast<const frag_t*>(slab + (XP + 1) * PART + xo);
                 }
             }
 #pragma unroll
@@ -1189,8 +1200,10 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         else scale = std::ldexp(1.f, e);
     }
     const float scale2 = scale * scale;
+    const int wdk = single ? kWideDKOne : kWideDK;   // slab depth of the staged kernel
     const int ks = (d + 15) / 16;
-    const int dp = wide ? (d + kWideDK - 1) / kWideDK * kWideDK : ks * 16;
+    const int dp = wide ? (d + wdk - 1) / wdk * wdk : ks * 16;
+
     const int ks8 = (d + 31) / 32, dp8 = ks8 * 32;
     DevBuf xc8, qc8, xn8, qn8;
     if (fast) {
@@ -1210,7 +1223,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // integer rows of 129..1024 elements: centred, exact in bf16, so the staged kernel runs on one part
     // per row (one MFMA per k-step) and filters in int32
     const bool iwide = exact && !fast;
-    const int dpi = (d + kWideDK - 1) / kWideDK * kWideDK;
+    const int dpi = (d + kWideDKOne - 1) / kWideDKOne * kWideDKOne;
     DevBuf xb16, qb16, xn16, qn16;
     if (iwide) {
         TSDG_HIP(xb16.alloc((size_t)N * dpi * 2));
@@ -1278,7 +1291,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                                    : (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
     const float split_err_const = single ? (float)(1.05 * (2.0 * delta * sq + 2.0 * dp * delta * delta) / (double)scale2) : 0.f;
 
-    constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);   // dynamic part: the slabs
+    // dynamic part, the slabs: two buffers of four parts 32 deep (hi + lo) or two parts 64 deep (one part)
+    constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);
+    static_assert(2 * kWideDKOne <= 4 * kWideDK, "the one-part slabs must fit the same allocation");
     if (wide || iwide) {
         hipError_t e = hipFuncSetAttribute(!wide ? reinterpret_cast<const void*>(&filter_wide_kernel<0>)
                                            : single ? reinterpret_cast<const void*>(&filter_wide_kernel<2>)
