@@ -1183,8 +1183,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 
     // int8 fast path: integer rows with d <= 128 are rewritten once as centred, padded int8
     const bool fast = exact && d <= 128;
-    // bf16 split path: real-valued rows are centred and written as hi + lo; up to d = 128 the query
-    // fragments stay in registers (k-steps of 16), wider rows are staged through LDS in slabs of 32
+    // real-valued rows are centred; up to d = 128 the query fragments stay in registers (k-steps of 16),
+    // wider rows are staged through LDS in slabs
     const bool split = !exact;
     const bool wide = split && d > 128;
     // Real-valued rows go through the filter as ONE binary16 part, scaled by a power of

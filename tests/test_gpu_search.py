@@ -61,6 +61,10 @@ def test_result_independent_of_visited_capacity(gpu, orc):
         assert_bitwise(ids, ref[0], f"slots={slots}")
         outs.append(int(st.dist_evals.sum()))
     assert outs[0] >= outs[1] >= outs[2] >= int(ref[2][:, 1].sum())   # a smaller set only costs evaluations
+    for slots in (192, 1280, 16320):   # table sizes that are no powers of two: probing wraps at the end
+        (ids, s, st), ref = run_both(gpu, orc, case, 10, 48, 10, 1, visited_slots=slots)
+        assert_bitwise(ids, ref[0], f"slots={slots}")
+        assert_bitwise(s, ref[1], f"slots={slots} dists")
     # a list of two entries per lane with a set that forgets: re-scored ids meet their copies in the list
     (ids, s, st), ref = run_both(gpu, orc, case, 10, 100, 10, 1, visited_slots=64)
     assert_bitwise(ids, ref[0], "L=100 slots=64")
