@@ -463,6 +463,7 @@ struct SplitArgs {
 };
 
 constexpr int kSplitQueue = 512;
+constexpr int split_tile_rows(int ks, bool single) { return single && ks >= 7 ? 2 * kSplitRows : kSplitRows; }
 constexpr int kSplitQB = 2;   // blocks of 32 queries per wave
 
 // SINGLE: the rows are one binary16 part (half_prep_kernel) instead of bf16 hi + lo: one MFMA per k-step
@@ -470,17 +471,21 @@ constexpr int kSplitQB = 2;   // blocks of 32 queries per wave
 // the acceptance test of the re-scoring pass, the same answer.  Norms and thresholds stay in the rows'
 // own units in memory and are multiplied by scale2 where they meet the accumulators.
 template <int KS, bool SINGLE>
-__global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(SplitArgs a)
+__global__ __launch_bounds__(256, (SINGLE && KS <= 6) ? 3 : 2) void filter_split_kernel(SplitArgs a)
 {
     constexpr int QB = kSplitQB;
     constexpr int PARTS = SINGLE ? 1 : 2;
+    // candidate rows per LDS tile (64-row halves per barrier).  One part, measured at N = 10^6: up to 96 elements
+    // three waves per SIMD on 64-row tiles win (0.246 s against 0.261 s at d = 96); beyond, three waves spill
+    // and two waves on 128-row tiles win (0.311 s against 0.351 s at d = 128).
+    constexpr int ROWS = split_tile_rows(KS, SINGLE);
     using frag_t = std::conditional_t<SINGLE, half8, bf16x8>;
     constexpr int DP = KS * 16;
     constexpr int XS = DP + 8;
-    constexpr int CHUNKS = kSplitRows * DP / 8;       // 16-byte chunks per part of a tile
+    constexpr int CHUNKS = ROWS * DP / 8;       // 16-byte chunks per part of a tile
     constexpr int PER_THREAD = (CHUNKS + 255) / 256;
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][PARTS][kSplitRows * XS];   // [buffer][hi|lo]
-    __shared__ __attribute__((aligned(16))) float xn[2][kSplitRows];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][PARTS][ROWS * XS];   // [buffer][hi|lo]
+    __shared__ __attribute__((aligned(16))) float xn[2][ROWS];
     __shared__ SurvivorQueue<kSplitQueue> queue;
 
     const int lane = lane_id();
@@ -519,15 +524,15 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
         }
     }
 
-    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * kSplitRows;
-    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kSplitRows);
+    const int64_t span0 = a.c_begin + (int64_t)blockIdx.y * a.tiles_per_block * ROWS;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * ROWS);
     if (span0 >= span1) return;
-    const int ntiles = (int)((span1 - span0 + kSplitRows - 1) / kSplitRows);
+    const int ntiles = (int)((span1 - span0 + ROWS - 1) / ROWS);
 
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a plain vector: stays in registers
     u32x4 stage[PARTS][PER_THREAD];
     float stage_n = 0.f;
-    // A tile part is one contiguous block of kSplitRows * DP elements; a chunk index past the span's
+    // A tile part is one contiguous block of ROWS * DP elements; a chunk index past the span's
     // end is clamped to the span's last chunk (rows read twice that way carry ids >= span1 and are
     // dropped by the filter), so the loads need no branch.
     const int last_chunk = (int)(span1 - span0) * (DP / 8) - 1;
@@ -542,8 +547,8 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
             stage[0][i] = *reinterpret_cast<const u32x4*>(xh_span + off);
             if constexpr (!SINGLE) stage[PARTS - 1][i] = *reinterpret_cast<const u32x4*>(xl_span + off);
         }
-        if (threadIdx.x < kSplitRows)
-            stage_n = a.xnorm[span0 + min(t * kSplitRows + (int)threadIdx.x, last_row)] * a.scale2;
+        if (threadIdx.x < ROWS)
+            stage_n = a.xnorm[span0 + min(t * ROWS + (int)threadIdx.x, last_row)] * a.scale2;
     };
     auto commit = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
@@ -555,7 +560,7 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
                 if constexpr (!SINGLE) *reinterpret_cast<u32x4*>(&Xs[b][PARTS - 1][r * XS + c8 * 8]) = stage[PARTS - 1][i];
             }
         }
-        if (threadIdx.x < kSplitRows) xn[b][threadIdx.x] = stage_n;
+        if (threadIdx.x < ROWS) xn[b][threadIdx.x] = stage_n;
     };
 
     fetch(0);
@@ -564,13 +569,14 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
     for (int t = 0; t < ntiles; ++t) {
         const int cur = t & 1;
         fetch(t + 1);  // clamped: past the last tile it re-reads the span's end, unused
+        for (int h = 0; h < ROWS / 64; ++h) {
         // the accumulators start at |x|^2 of their rows (lane l, register r: row 8*(r/4) + 4*(l/32) + r%4)
         floatx16 acc[2][QB];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                const float4 v = *reinterpret_cast<const float4*>(&xn[cur][h * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
 #pragma unroll
                 for (int j = 0; j < QB; ++j) {
                     acc[i][j][4 * r4 + 0] = v.x; acc[i][j][4 * r4 + 1] = v.y;
@@ -582,7 +588,7 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int off = (i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
+                const int off = (h * 64 + i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
                 const frag_t xh = *reinterpret_cast<const frag_t*>(&Xs[cur][0][off]);
                 if constexpr (SINGLE) {
 #pragma unroll
@@ -599,7 +605,7 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
                 }
             }
         }
-        const int64_t c0 = span0 + (int64_t)t * kSplitRows;
+        const int64_t c0 = span0 + (int64_t)t * ROWS + h * 64;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -628,6 +634,7 @@ __global__ __launch_bounds__(256, SINGLE ? 3 : 2) void filter_split_kernel(Split
                     }
                 }
             }
+        }
         }
         if (t + 1 < ntiles) commit(cur ^ 1);
         __syncthreads();
@@ -1409,8 +1416,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                         hipLaunchKernelGGL(filter_wide_kernel<1>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                            kWideLds, stream, wa);
                 } else {
-                    const int64_t ftiles = (ce - cb + kSplitRows - 1) / kSplitRows;
-                    sa.tiles_per_block = (int)std::min<int64_t>(32, ftiles);
+                    const int srows = split_tile_rows(ks, single);
+                    const int64_t ftiles = (ce - cb + srows - 1) / srows;
+                    sa.tiles_per_block = (int)std::min<int64_t>(32 * kSplitRows / srows, ftiles);
                     constexpr int qpb = 128 * kSplitQB;   // queries per workgroup
                     dim3 sgrid((unsigned)((nr + qpb - 1) / qpb), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
                     switch (ks) {
