@@ -647,17 +647,17 @@ __global__ __launch_bounds__(256, (SINGLE && KS <= 6) ? 3 : 2) void filter_split
 // one scaled binary16 part; MODE 0: integer rows, which are exact in bf16, one part, one MFMA per k-step): both
 // operands go through LDS in slabs of 32 elements of the k dimension, double buffered, with
 // the loads of slab g+1 in flight during the MFMAs of slab g.  One workgroup owns a tile of
-// 128 queries x 128 candidates (4 waves, 64 x 64 each = 2 x 2 blocks of 32 x 32, 12 MFMAs per
-// 16 elements of k); the filter runs once per tile, after the last slab, so it is amortised
+// 128 queries x 128 candidates with hi + lo parts (4 waves, 64 x 64 each = 2 x 2 blocks of 32 x 32, 12 MFMAs
+// per 16 elements of k) and of 128 x 256 with one part per operand (64 x 128 per wave, 8 MFMAs per 16
+// elements of k); the filter runs once per tile, after the last slab, so it is amortised
 // over d / 16 k-steps and needs none of the tricks of the register kernels: u = |x|^2 - 2 q.x
 // is formed from the finished accumulators.
-// LDS rows are 64 bytes (hi + lo: slabs 32 deep) or 128 bytes (one part per operand: slabs 64 deep)
-// with no padding; the 16-byte chunk c of row r is stored at chunk c ^ ((r >> 2) & 3), resp. c ^ (r & 7),
-// which spreads the rows a fragment read touches per cycle over all banks.
+// LDS rows are 64 bytes with no padding; the 16-byte chunk c of row r is stored at chunk
+// c ^ ((r >> 2) & 3), which spreads the 16 rows a fragment read touches per cycle over all banks.
 // Workgroups are numbered so that those resident together form a block of q_group query tiles
 // times a few candidate spans: the slabs they stream are then shared through the L2 caches
 // instead of each being fetched from memory once per workgroup.
-constexpr int kWideDK = 32;      // slab depth with hi + lo parts (MODE 1)
+constexpr int kWideDK = 32;
 
 struct WideArgs {
     SplitArgs s;
@@ -666,14 +666,16 @@ struct WideArgs {
     int q_group;       // query tiles per group of the block numbering
 };
 
-constexpr int kWideDKOne = 64;   // slab depth with one part per operand (MODE 0 and 2): half the barriers for the same LDS
+// 32-row candidate blocks per wave: with one part per operand a wave multiplies its 64 queries with 128
+// candidates (a 128 x 256 workgroup tile: a quarter fewer bytes fetched per MFMA), with hi + lo parts with 64
+constexpr int wide_x_blocks(int mode) { return mode == 1 ? 2 : 4; }
 
-// DK elements (2 bytes each) per LDS row, no padding: 16-byte chunk c of row r sits at chunk c ^ f(r)
+// DK = 32 elements (64 bytes) per LDS row, no padding: 16-byte chunk c of row r sits at chunk c ^ ((r >> 2) & 3)
 template <int DK>
 __device__ __forceinline__ int wide_lds_offset(int row, int chunk)
 {
-    if constexpr (DK == 32) return row * DK + ((chunk ^ ((row >> 2) & 3)) << 3);
-    else return row * DK + ((chunk ^ (row & 7)) << 3);
+    static_assert(DK == 32, "the swizzle is written for 64-byte rows");
+    return row * DK + ((chunk ^ ((row >> 2) & 3)) << 3);
 }
 
 // MODE 0: centred integer rows, one bf16 part, exact (filter in int32); 1: real-valued rows as bf16 hi + lo;
@@ -685,12 +687,15 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     constexpr bool FLT = MODE != 0;   // float arithmetic with a rounding margin downstream
     using frag_t = std::conditional_t<MODE == 2, half8, bf16x8>;
     const SplitArgs& a = w.s;
-    constexpr int DK = MODE == 1 ? kWideDK : kWideDKOne;   // elements of k per slab
-    constexpr int NP = LO ? 4 : 2, XP = LO ? 2 : 1;          // operand parts per slab: q (hi, lo), x (hi, lo)
-    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][NP][128 * DK]
-    __shared__ __attribute__((aligned(16))) float xn[2][kTile];
+    constexpr int DK = kWideDK;                   // elements of k per slab
+    constexpr int XB = wide_x_blocks(MODE);      // 32-row candidate blocks per wave
+    constexpr int XT = 2 * 32 * XB;              // candidate rows per workgroup tile (two waves side by side)
+    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][q parts: 128 * DK | x parts: XT * DK]
+    __shared__ __attribute__((aligned(16))) float xn[2][XT];
     __shared__ SurvivorQueue<kSplitQueue> queue;
-    constexpr int PART = kTile * DK;   // elements of one operand part of a slab
+    constexpr int QPART = kTile * DK, XPART = XT * DK;   // elements of one part of a slab, per operand
+    constexpr int QPARTS = LO ? 2 : 1;
+    constexpr int SLAB = QPARTS * (QPART + XPART);
 
     // block numbering: groups of q_group query tiles, inside a group the query tile varies fastest
     const int64_t b = linear_block();
@@ -726,51 +731,57 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         }
     }
 
-    const int64_t span0 = a.c_begin + y * a.tiles_per_block * kTile;
-    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * kTile);
+    const int64_t span0 = a.c_begin + y * a.tiles_per_block * XT;
+    const int64_t span1 = min(a.c_end, span0 + (int64_t)a.tiles_per_block * XT);
     if (span0 >= span1) return;
-    const int ntiles = (int)((span1 - span0 + kTile - 1) / kTile);
+    const int ntiles = (int)((span1 - span0 + XT - 1) / XT);
     const int nstage = w.dp / DK;
     const int G = ntiles * nstage;
 
     // this thread's share of a slab: chunk fc of rows fr, fr + RP, ... of every part
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    constexpr int CH = DK / 8, RP = 256 / CH, H = kTile / RP;   // chunks per row, rows per pass, passes
+    constexpr int CH = DK / 8, RP = 256 / CH;          // chunks per row, rows per pass
+    constexpr int HQ = kTile / RP, HX = XT / RP;       // passes over the query rows and the candidate rows
     const int fr = (int)threadIdx.x / CH, fc = (int)threadIdx.x % CH;
-    int64_t qrow[H];   // clamped: rows past the end are re-reads whose results are dropped
+    int64_t qrow[HQ];   // clamped: rows past the end are re-reads whose results are dropped
 #pragma unroll
-    for (int h = 0; h < H; ++h) qrow[h] = min(q0 + fr + h * RP, a.nq - 1);
+    for (int h = 0; h < HQ; ++h) qrow[h] = min(q0 + fr + h * RP, a.nq - 1);
     const int last_row = (int)(span1 - span0) - 1;
-    u32x4 st[NP][H];
+    u32x4 stq[QPARTS][HQ], stx[QPARTS][HX];
     float st_n = 0.f;
     auto fetch = [&](int t, int sg) __attribute__((always_inline)) {
         const int ko = sg * DK + fc * 8;
 #pragma unroll
-        for (int h = 0; h < H; ++h) {
-            const int64_t xr = span0 + min(t * kTile + fr + h * RP, last_row);
-            st[0][h] = *reinterpret_cast<const u32x4*>(a.qh + qrow[h] * w.dp + ko);
-            st[XP][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
-            if constexpr (LO) {
-                st[1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
-                st[XP + 1][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
-            }
+        for (int h = 0; h < HQ; ++h) {
+            stq[0][h] = *reinterpret_cast<const u32x4*>(a.qh + qrow[h] * w.dp + ko);
+            if constexpr (LO) stq[QPARTS - 1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
         }
-        if (threadIdx.x < kTile) {
-            st_n = a.xnorm[span0 + min(t * kTile + (int)threadIdx.x, last_row)];
+#pragma unroll
+        for (int h = 0; h < HX; ++h) {
+            const int64_t xr = span0 + min(t * XT + fr + h * RP, last_row);
+            stx[0][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
+            if constexpr (LO) stx[QPARTS - 1][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
+        }
+        if (threadIdx.x < XT) {
+            st_n = a.xnorm[span0 + min(t * XT + (int)threadIdx.x, last_row)];
             if constexpr (FLT) st_n *= a.scale2;   // (the integer rows' norms are ints in these words)
         }
     };
     auto commit = [&](int buf, int t, int sg) __attribute__((always_inline)) {
-        uint16_t* slab = wide_slabs + buf * NP * PART;
+        uint16_t* slab = wide_slabs + buf * SLAB;
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
+        for (int p = 0; p < QPARTS; ++p) {
 #pragma unroll
-            for (int h = 0; h < H; ++h)
-                *reinterpret_cast<u32x4*>(slab + p * PART + wide_lds_offset<DK>(fr + h * RP, fc)) = st[p][h];
-        if (sg == 0 && threadIdx.x < kTile) xn[t & 1][threadIdx.x] = st_n;
+            for (int h = 0; h < HQ; ++h)
+                *reinterpret_cast<u32x4*>(slab + p * QPART + wide_lds_offset<DK>(fr + h * RP, fc)) = stq[p][h];
+#pragma unroll
+            for (int h = 0; h < HX; ++h)
+                *reinterpret_cast<u32x4*>(slab + QPARTS * QPART + p * XPART + wide_lds_offset<DK>(fr + h * RP, fc)) = stx[p][h];
+        }
+        if (sg == 0 && threadIdx.x < XT) xn[t & 1][threadIdx.x] = st_n;
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[XB][2];
     int t = 0, sg = 0;       // slab being multiplied
     int tn = 0, sn = 0;      // slab being fetched
     fetch(0, 0);
@@ -783,30 +794,31 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         fetch(tn, sn);   // past the last slab this re-reads it, unused
         if (sg == 0) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < XB; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
         }
-        const uint16_t* slab = wide_slabs + cur * NP * PART;
+        const uint16_t* slab = wide_slabs + cur * SLAB;
 #pragma unroll
         for (int k16 = 0; k16 < DK / 16; ++k16) {
             const int chunk = k16 * 2 + (lane >> 5);
-            frag_t qh[2], ql[2], xh[2], xl[2];
+            frag_t qh[2], ql[2], xh[XB], xl[XB];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int qo = wide_lds_offset<DK>(wq * 64 + i * 32 + (lane & 31), chunk);
-                const int xo = wide_lds_offset<DK>(wc * 64 + i * 32 + (lane & 31), chunk);
-                qh[i] = *reinterpret_cast<const frag_t*>(slab + 0 * PART + qo);
-                xh[i] = *reinterpret_cast<const frag_t*>(slab + XP * PART + xo);
-                if constexpr (LO) {
-                    ql[i] = *reinterpret_cast<const frag_t*>(slab + 1 * PART + qo);
-                    xl[i] = *reinterpret_cast<const frag_t*>(slab + (XP + 1) * PART + xo);
-                }
+            for (int j = 0; j < 2; ++j) {
+                const int qo = wide_lds_offset<DK>(wq * 64 + j * 32 + (lane & 31), chunk);
+                qh[j] = *reinterpret_cast<const frag_t*>(slab + qo);
+                if constexpr (LO) ql[j] = *reinterpret_cast<const frag_t*>(slab + QPART + qo);
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < XB; ++i) {
+                const int xo = wide_lds_offset<DK>(wc * (32 * XB) + i * 32 + (lane & 31), chunk);
+                xh[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + xo);
+                if constexpr (LO) xl[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + XPART + xo);
+            }
+#pragma unroll
+            for (int i = 0; i < XB; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     if constexpr (MODE == 2) {
@@ -823,13 +835,13 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         const bool tile_done = sg == nstage - 1;
         if (tile_done) {
             // lane l, register r of block (i, j): candidate row 8*(r/4) + 4*(l/32) + r%4 of block i, query l%32 of block j
-            const int64_t c0 = span0 + (int64_t)t * kTile + wc * 64;
+            const int64_t c0 = span0 + (int64_t)t * XT + wc * (32 * XB);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < XB; ++i) {
                 V xv[16];
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * 64 + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                    const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * (32 * XB) + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
                     if constexpr (FLT) {
                         xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
                     } else {  // the same words, read as the ints they are
@@ -1207,7 +1219,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         else scale = std::ldexp(1.f, e);
     }
     const float scale2 = scale * scale;
-    const int wdk = single ? kWideDKOne : kWideDK;   // slab depth of the staged kernel
+    const int wdk = kWideDK;   // slab depth of the staged kernel
     const int ks = (d + 15) / 16;
     const int dp = wide ? (d + wdk - 1) / wdk * wdk : ks * 16;
 
@@ -1230,7 +1242,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // integer rows of 129..1024 elements: centred, exact in bf16, so the staged kernel runs on one part
     // per row (one MFMA per k-step) and filters in int32
     const bool iwide = exact && !fast;
-    const int dpi = (d + kWideDKOne - 1) / kWideDKOne * kWideDKOne;
+    const int dpi = (d + kWideDK - 1) / kWideDK * kWideDK;
     DevBuf xb16, qb16, xn16, qn16;
     if (iwide) {
         TSDG_HIP(xb16.alloc((size_t)N * dpi * 2));
@@ -1300,7 +1312,6 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 
     // dynamic part, the slabs: two buffers of four parts 32 deep (hi + lo) or two parts 64 deep (one part)
     constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);
-    static_assert(2 * kWideDKOne <= 4 * kWideDK, "the one-part slabs must fit the same allocation");
     if (wide || iwide) {
         hipError_t e = hipFuncSetAttribute(!wide ? reinterpret_cast<const void*>(&filter_wide_kernel<0>)
                                            : single ? reinterpret_cast<const void*>(&filter_wide_kernel<2>)
@@ -1360,7 +1371,6 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             const int64_t ce = std::min(N, cb + width);
             f.c_begin = cb;
             f.c_end = ce;
-            const int64_t tiles = (ce - cb + kTile - 1) / kTile;
             if (fast) {
                 I8Args fa;
                 fa.qc = (self ? xc8.as<uint8_t>() : qc8.as<uint8_t>()) + r0 * dp8;
@@ -1404,10 +1414,12 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 sa.self_offset = f.self_offset;
                 sa.cap = cap;
                 if (wide) {
-                    sa.tiles_per_block = (int)std::min<int64_t>(4, tiles);
+                    const int xt = 64 * wide_x_blocks(single ? 2 : 1);   // candidate rows per workgroup tile
+                    const int64_t wtiles = (ce - cb + xt - 1) / xt;
+                    sa.tiles_per_block = (int)std::min<int64_t>(512 / xt, wtiles);
                     wa.dp = dp;
                     wa.q_tiles = (int)((nr + kTile - 1) / kTile);
-                    wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
+                    wa.ny = (int)((wtiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                     wa.q_group = 64;
                     if (single)
                         hipLaunchKernelGGL(filter_wide_kernel<2>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
@@ -1448,10 +1460,12 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 sa.c_end = ce;
                 sa.self_offset = f.self_offset;
                 sa.cap = cap;
-                sa.tiles_per_block = (int)std::min<int64_t>(4, tiles);
+                const int xt = 64 * wide_x_blocks(0);
+                const int64_t wtiles = (ce - cb + xt - 1) / xt;
+                sa.tiles_per_block = (int)std::min<int64_t>(512 / xt, wtiles);
                 wa.dp = dpi;
                 wa.q_tiles = (int)((nr + kTile - 1) / kTile);
-                wa.ny = (int)((tiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
+                wa.ny = (int)((wtiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                 wa.q_group = 64;
                 hipLaunchKernelGGL(filter_wide_kernel<0>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                    kWideLds, stream, wa);
