@@ -164,6 +164,20 @@ def test_knn_integer_wide_rows(gpu, orc, d):
         assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), refb[0], refb[1], f"integer wide bf real q d={d}") == 0
 
 
+@pytest.mark.parametrize("d", [32, 160])
+def test_bruteforce_queries_far_longer_than_the_base_rows(gpu, orc, d):
+    """The scale of the one-part filter is set by the longest row of EITHER operand: queries 300 times longer
+    than the base rows must neither overflow binary16 nor lose the base rows' digits."""
+    step(f"ann_bruteforce long queries d={d}")
+    g = np.random.default_rng(31 + d)
+    base = g.standard_normal((2500, d)).astype(np.float32)
+    q = (g.standard_normal((70, d)) * 300.0).astype(np.float32)
+    q[::2] = base[:35] + (g.standard_normal((35, d)) * 0.05).astype(np.float32)   # and some queries among the rows
+    ref = orc.bruteforce(base, q, 10)
+    ids, s = gpu.ann_bruteforce(dev(base), dev(q), 10)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"long queries d={d}") == 0
+
+
 def test_bruteforce(gpu, orc):
     step("ann_bruteforce")
     base, queries = workloads.tiny()
