@@ -268,6 +268,18 @@ def test_knn_real_valued_with_large_offset_and_near_ties(gpu, orc):
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "near ties bf") == 0
 
 
+def test_knn_rows_that_differ_in_their_last_bits(gpu, orc):
+    """Rows near 1000 that differ by a few units in the last place: centred, they fall below binary16's normal
+    range at the scale the row lengths dictate (the filter's absolute error term), distances are multiples of
+    2^-28 with ties everywhere, and whatever the filters reject the plain scan redoes."""
+    step("ann_knn last-bit differences")
+    g = np.random.default_rng(5150)
+    x = (1000.0 + 1.0e-4 * g.standard_normal((2000, 16))).astype(np.float32)
+    ref = orc.knn(x, 12)
+    ids, s = gpu.ann_knn(dev(x), 12)
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "last bits") == 0
+
+
 @pytest.mark.parametrize("scale", [1e-12, 1e12])
 @pytest.mark.parametrize("d", [16, 200])
 def test_knn_extreme_magnitudes(gpu, orc, scale, d):
