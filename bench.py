@@ -6,7 +6,9 @@ d = 128 (seeded 256-component mixture, clipped to [0,255] and rounded), 10,000
 queries, L2, K = 32, k = 10, large batch (all 10,000 queries in one call).
 
 A "step" is one ann_search_ex call over the whole 10,000-query batch, at the
-smallest swept L whose recall@10 against brute-force ground truth is >= 0.95.
+smallest L whose recall@10 against brute-force ground truth is >= 0.95 (the
+grid 16..256 is swept first, then the gap below the first passing value is
+bisected).
 The graph build (exact k-NN contraction + two-stage diversification) runs once
 before the timed region and is reported in the same line under "build".
 
