@@ -71,32 +71,53 @@ __device__ __forceinline__ void pairwise_i8(const I8Rows& x, const int32_t* ids,
 {
     const int XS = x.dp8 + 16;
     const int cpr = x.dp8 / 16;  // 16-byte chunks per row
-    for (int c = lane; c < 64 * cpr; c += 64) {
-        const int r = c / cpr, k = c % cpr;
-        intx4 v = {0, 0, 0, 0};
-        if (r < m) v = *reinterpret_cast<const intx4*>(x.xc8 + (size_t)ids[r] * x.dp8 + k * 16);
-        *reinterpret_cast<intx4*>(rows + r * XS + k * 16) = v;
+    // eight of a lane's chunks are requested before the first is stored, so the list's rows arrive in one
+    // round trip (two beyond 128 bytes per row) instead of one per chunk
+    for (int t0 = 0; t0 < cpr; t0 += 8) {
+        intx4 v[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int c = lane + 64 * (t0 + t);
+            const int r = c / cpr, k = c % cpr;
+            v[t] = intx4{0, 0, 0, 0};
+            if (c < 64 * cpr && r < m) v[t] = *reinterpret_cast<const intx4*>(x.xc8 + (size_t)ids[r] * x.dp8 + k * 16);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int c = lane + 64 * (t0 + t);
+            const int r = c / cpr, k = c % cpr;
+            if (c < 64 * cpr) *reinterpret_cast<intx4*>(rows + r * XS + k * 16) = v[t];
+        }
     }
     nrm[lane] = lane < m ? x.xn8[ids[lane]] : 0;
     __syncthreads();
-    for (int blk = 0; blk < 3; ++blk) {  // 32x32 blocks (0,0), (0,1), (1,1) of the upper triangle
-        const int bi = blk >> 1, bj = (blk + 1) >> 1;
-        if (bj * 32 >= m) continue;
-        intx16 acc;
+    // 32x32 blocks (0,0), (0,1), (1,1) of the upper triangle, all three finished in registers before the first
+    // result is written: P may then lie over the staged rows (see stage2_kernel)
+    intx16 acc[3];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0;
+    for (int blk = 0; blk < 3; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[blk][r] = 0;
+        if (bj * 32 >= m) continue;
         for (int ks = 0; ks < x.dp8 / 32; ++ks) {
             const intx4 A = *reinterpret_cast<const intx4*>(rows + (bi * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5));
             const intx4 B = *reinterpret_cast<const intx4*>(rows + (bj * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5));
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(A, B, acc, 0, 0, 0);
+            acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A, B, acc[blk], 0, 0, 0);
         }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int blk = 0; blk < 3; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+        if (bj * 32 >= m) continue;
         // lane l, register r: row i = 8*(r/4) + 4*(l/32) + r%4 of block bi, column j = l%32 of block bj
         const int j = bj * 32 + (lane & 31);
         const int nj = nrm[j];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int i = bi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (i < j && j < m) P[i * stride + j] = (float)(nrm[i] + nj - 2 * acc[r]);
+            if (i < j && j < m) P[i * stride + j] = (float)(nrm[i] + nj - 2 * acc[blk][r]);
         }
     }
 }
@@ -328,8 +349,12 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     using RD = RowDist<T, G, C>;
     extern __shared__ float sm[];
     const int R = a.rev_cap;
+    // P and, on integer rows, the int8 copies of the list's rows share the front of the LDS block: the rows
+    // are dead once the products sit in registers (pairwise_i8), which leaves room for half as many
+    // workgroups again on a CU
+    const int front = a.i8.xc8 ? max(R * R, 16 * (a.i8.dp8 + 16)) : R * R;   // floats
     float* P = sm;                                         // [R*R], upper triangle used
-    float* s0 = P + R * R;                                 // [R]
+    float* s0 = P + front;                                 // [R]
     int32_t* ids = reinterpret_cast<int32_t*>(s0 + R);     // [R]
     int* lam = reinterpret_cast<int*>(ids + R);            // [R]
     const int64_t x0 = linear_block();
@@ -345,8 +370,7 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     __syncthreads();
     if (a.i8.xc8) {
         int* nrm = lam + R;
-        uint8_t* rows = reinterpret_cast<uint8_t*>(sm) + ((((size_t)R * R + 3 * (size_t)R + 64) * 4 + 15) & ~(size_t)15);
-        pairwise_i8(a.i8, ids, m, P, R, rows, nrm, lane);
+        pairwise_i8(a.i8, ids, m, P, R, reinterpret_cast<uint8_t*>(sm), nrm, lane);
     } else {
         RD rd;
         rd.init(a.d, lane);
@@ -358,6 +382,7 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     for (int j = lane; j < m; j += 64) {
         const float sj = s0[j];
         int cnt = 0;
+#pragma unroll 8   // eight LDS reads in flight: two waves per SIMD do not hide one read per iteration
         for (int i = 0; i < m; ++i) {
             if (i == j) continue;
             const float pij = i < j ? P[i * R + j] : P[j * R + i];
@@ -372,6 +397,7 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
         const int lj = lam[j];
         const uint64_t kj = make_key(s0[j], (uint32_t)ids[j]);
         int r = 0;
+#pragma unroll 8
         for (int i = 0; i < m; ++i) {
             const int li = lam[i];
             const uint64_t ki = make_key(s0[i], (uint32_t)ids[i]);
@@ -415,8 +441,10 @@ struct Stage2Launch {
     hipError_t err = hipSuccess;
     template <typename T, int G, int C> void operator()()
     {
-        size_t lds = (size_t)a.rev_cap * a.rev_cap * 4 + (size_t)a.rev_cap * 12;
-        if (a.i8.xc8) lds = ((lds + 64 * 4 + 15) & ~(size_t)15) + 64 * (size_t)(a.i8.dp8 + 16);
+        size_t front = (size_t)a.rev_cap * a.rev_cap * 4;   // P; on integer rows also the 64 staged rows (stage2_kernel)
+        if (a.i8.xc8) front = std::max(front, 64 * (size_t)(a.i8.dp8 + 16));
+        size_t lds = front + (size_t)a.rev_cap * 12;
+        if (a.i8.xc8) lds += 64 * 4;
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage2_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
