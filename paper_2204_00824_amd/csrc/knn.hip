@@ -361,36 +361,40 @@ __global__ void mean_kernel(const double* sums, int d, int64_t n, float* mean)
     if (c < d) mean[c] = (float)(sums[c] / (double)n);
 }
 
-// one wave per row: centred hi / lo rows (padded to dp), centred squared norm, max norm
+constexpr int kPrepRowsPerWave = 16;   // rows a wave of the two centring kernels walks through: one look at the
+                                       // shared maximum per wave instead of one per row
+
+// a wave walks through 16 rows: centred hi / lo rows (padded to dp), centred squared norm, max norm
 template <typename T>
 __global__ __launch_bounds__(256) void split_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
                                                          const float* __restrict__ mean, uint16_t* __restrict__ xh,
                                                          uint16_t* __restrict__ xl, float* __restrict__ norms,
                                                          unsigned* maxnorm)
 {
-    const int64_t row = linear_block() * 4 + (threadIdx.x >> 6);
+    const int64_t row0 = (linear_block() * 4 + (threadIdx.x >> 6)) * kPrepRowsPerWave;
     const int lane = lane_id();
-    if (row >= n) return;
-    double acc = 0.0;
-    for (int j = lane; j < dp; j += 64) {
-        float c = 0.f;
-        if (j < d) c = (float)x[row * d + j] - mean[j];
-        const uint16_t h = bf16_rne(c);
-        const uint16_t l = bf16_rne(c - bf16_to_f32(h));
-        xh[row * dp + j] = h;
-        xl[row * dp + j] = l;
-        acc += (double)c * (double)c;
-    }
+    unsigned wmax = 0u;
+    for (int64_t row = row0; row < min(n, row0 + kPrepRowsPerWave); ++row) {
+        double acc = 0.0;
+        for (int j = lane; j < dp; j += 64) {
+            float c = 0.f;
+            if (j < d) c = (float)x[row * d + j] - mean[j];
+            const uint16_t h = bf16_rne(c);
+            const uint16_t l = bf16_rne(c - bf16_to_f32(h));
+            xh[row * dp + j] = h;
+            xl[row * dp + j] = l;
+            acc += (double)c * (double)c;
+        }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
-    if (lane == 0) {
+        for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
         const float nf = (float)acc;
-        norms[row] = nf;
-        if (__float_as_uint(nf) > *maxnorm) atomicMax(maxnorm, __float_as_uint(nf));
+        if (lane == 0) norms[row] = nf;
+        wmax = max(wmax, __float_as_uint(nf));
     }
+    if (lane == 0 && wmax > *maxnorm) atomicMax(maxnorm, wmax);
 }
 
-// one wave per row: centred rows as ONE binary16 part, scaled by a power of two (scale) that puts the
+// a wave walks through 16 rows: centred rows as ONE binary16 part, scaled by a power of two (scale) that puts the
 // largest element near 2^14, well inside binary16's range; centred squared norm (unscaled), max norm
 template <typename T>
 __global__ __launch_bounds__(256) void half_prep_kernel(const T* __restrict__ x, int64_t n, int d, int dp,
@@ -398,24 +402,25 @@ __global__ __launch_bounds__(256) void half_prep_kernel(const T* __restrict__ x,
                                                         uint16_t* __restrict__ xh, float* __restrict__ norms,
                                                         unsigned* maxnorm)
 {
-    const int64_t row = linear_block() * 4 + (threadIdx.x >> 6);
+    const int64_t row0 = (linear_block() * 4 + (threadIdx.x >> 6)) * kPrepRowsPerWave;
     const int lane = lane_id();
-    if (row >= n) return;
-    double acc = 0.0;
-    for (int j = lane; j < dp; j += 64) {
-        float c = 0.f;
-        if (j < d) c = (float)x[row * d + j] - mean[j];
-        const _Float16 h = (_Float16)(c * scale);   // round to nearest even
-        xh[row * dp + j] = __builtin_bit_cast(uint16_t, h);
-        acc += (double)c * (double)c;
-    }
+    unsigned wmax = 0u;
+    for (int64_t row = row0; row < min(n, row0 + kPrepRowsPerWave); ++row) {
+        double acc = 0.0;
+        for (int j = lane; j < dp; j += 64) {
+            float c = 0.f;
+            if (j < d) c = (float)x[row * d + j] - mean[j];
+            const _Float16 h = (_Float16)(c * scale);   // round to nearest even
+            xh[row * dp + j] = __builtin_bit_cast(uint16_t, h);
+            acc += (double)c * (double)c;
+        }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
-    if (lane == 0) {
+        for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
         const float nf = (float)acc;
-        norms[row] = nf;
-        if (__float_as_uint(nf) > *maxnorm) atomicMax(maxnorm, __float_as_uint(nf));
+        if (lane == 0) norms[row] = nf;
+        wmax = max(wmax, __float_as_uint(nf));   // norms are not negative: their bit patterns order like the values
     }
+    if (lane == 0 && wmax > *maxnorm) atomicMax(maxnorm, wmax);
 }
 
 // rows of integers in [0,255], centred (x - 128, exact in bf16) and zero-padded to dp elements, with
@@ -1274,10 +1279,10 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         hipLaunchKernelGGL(mean_kernel, dim3((unsigned)((d + 63) / 64)), dim3(64), 0, stream, csum.as<double>(), d, N,
                            cmean.as<float>());
         if (single)
-            hipLaunchKernelGGL((half_prep_kernel<TB>), folded_grid((N + 3) / 4), dim3(256), 0, stream, base, N, d, dp,
+            hipLaunchKernelGGL((half_prep_kernel<TB>), folded_grid((N + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, base, N, d, dp,
                                cmean.as<float>(), scale, xh.as<uint16_t>(), cxnorm.as<float>(), cinfo.as<unsigned>());
         else
-            hipLaunchKernelGGL((split_prep_kernel<TB>), folded_grid((N + 3) / 4), dim3(256), 0, stream, base, N, d, dp,
+            hipLaunchKernelGGL((split_prep_kernel<TB>), folded_grid((N + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, base, N, d, dp,
                                cmean.as<float>(), xh.as<uint16_t>(), xl.as<uint16_t>(), cxnorm.as<float>(),
                                cinfo.as<unsigned>());
         unsigned h_max = 0;
@@ -1287,11 +1292,11 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             if (!single) TSDG_HIP(ql.alloc((size_t)nq * dp * 2));
             TSDG_HIP(cqnorm.alloc((size_t)nq * 4));
             if (single)
-                hipLaunchKernelGGL((half_prep_kernel<TQ>), folded_grid((nq + 3) / 4), dim3(256), 0, stream, queries, nq,
+                hipLaunchKernelGGL((half_prep_kernel<TQ>), folded_grid((nq + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, queries, nq,
                                    d, dp, cmean.as<float>(), scale, qh.as<uint16_t>(), cqnorm.as<float>(),
                                    cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
             else
-                hipLaunchKernelGGL((split_prep_kernel<TQ>), folded_grid((nq + 3) / 4), dim3(256), 0, stream, queries, nq,
+                hipLaunchKernelGGL((split_prep_kernel<TQ>), folded_grid((nq + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, queries, nq,
                                    d, dp, cmean.as<float>(), qh.as<uint16_t>(), ql.as<uint16_t>(), cqnorm.as<float>(),
                                    cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
         }
