@@ -54,38 +54,43 @@ __device__ __forceinline__ float4 load4(const uint8_t* p)
 
 // ---------------------------------------------------------------- row norms, integer test
 // info[0] = 1 if some element is not an integer in [0,255]; info[1] = max norm (fp32 bits)
+constexpr int kNormPasses = 8;   // a workgroup walks through 8 x 32 rows and looks at the shared maximum once per wave
+
 template <typename T>
 __global__ __launch_bounds__(256) void norms_kernel(const T* __restrict__ x, int64_t n, int d,
                                                     float* __restrict__ norms, unsigned* info)
 {
     // 8 lanes per row, 4 elements per lane and step (128 contiguous bytes per group for fp32)
-    const int64_t row = linear_block() * 32 + (threadIdx.x >> 3);
     const int g = (int)(threadIdx.x & 7);
-    double acc = 0.0;
     bool nonint = false;
-    if (row < n) {
-        const T* xr = x + row * d;
-        for (int j = 4 * g; j < d; j += 32) {
-            const float4 v = load4(xr + j);
-            acc += (double)v.x * (double)v.x;
-            acc += (double)v.y * (double)v.y;
-            acc += (double)v.z * (double)v.z;
-            acc += (double)v.w * (double)v.w;
-            if constexpr (sizeof(T) != 1) {
-                nonint |= !(v.x >= 0.f && v.x <= 255.f && v.x == rintf(v.x));
-                nonint |= !(v.y >= 0.f && v.y <= 255.f && v.y == rintf(v.y));
-                nonint |= !(v.z >= 0.f && v.z <= 255.f && v.z == rintf(v.z));
-                nonint |= !(v.w >= 0.f && v.w <= 255.f && v.w == rintf(v.w));
+    unsigned m = 0u;   // largest norm this lane has seen (norms are not negative: bit patterns order like values)
+    for (int pass = 0; pass < kNormPasses; ++pass) {
+        const int64_t row = (linear_block() * kNormPasses + pass) * 32 + (threadIdx.x >> 3);
+        double acc = 0.0;
+        if (row < n) {
+            const T* xr = x + row * d;
+            for (int j = 4 * g; j < d; j += 32) {
+                const float4 v = load4(xr + j);
+                acc += (double)v.x * (double)v.x;
+                acc += (double)v.y * (double)v.y;
+                acc += (double)v.z * (double)v.z;
+                acc += (double)v.w * (double)v.w;
+                if constexpr (sizeof(T) != 1) {
+                    nonint |= !(v.x >= 0.f && v.x <= 255.f && v.x == rintf(v.x));
+                    nonint |= !(v.y >= 0.f && v.y <= 255.f && v.y == rintf(v.y));
+                    nonint |= !(v.z >= 0.f && v.z <= 255.f && v.z == rintf(v.z));
+                    nonint |= !(v.w >= 0.f && v.w <= 255.f && v.w == rintf(v.w));
+                }
             }
         }
-    }
 #pragma unroll
-    for (int o = 4; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
-    const float nf = (float)acc;
-    if (row < n && g == 0) norms[row] = nf;
+        for (int o = 4; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+        const float nf = (float)acc;
+        if (row < n && g == 0) norms[row] = nf;
+        if (row < n) m = max(m, __float_as_uint(nf));
+    }
     // the wave's largest norm, then at most one atomic per wave, and only when the value read
     // first is smaller (the maximum only grows, so a stale read costs a harmless extra atomic)
-    unsigned m = row < n ? __float_as_uint(nf) : 0u;
 #pragma unroll
     for (int o = 32; o >= 8; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o, 64));
     const int lane = lane_id();
@@ -1177,13 +1182,13 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     TSDG_HIP(xnorm.alloc((size_t)N * 4));
     TSDG_HIP(info.alloc(4 * sizeof(unsigned)));
     TSDG_HIP(hipMemsetAsync(info.p, 0, 4 * sizeof(unsigned), stream));
-    hipLaunchKernelGGL((norms_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d,
+    hipLaunchKernelGGL((norms_kernel<TB>), folded_grid((N + 32 * kNormPasses - 1) / (32 * kNormPasses)), dim3(256), 0, stream, base, N, d,
                        xnorm.as<float>(), info.as<unsigned>());
     TSDG_HIP(hipGetLastError());
     float* qn = xnorm.as<float>();
     if (!self) {
         TSDG_HIP(qnorm.alloc((size_t)nq * 4));
-        hipLaunchKernelGGL((norms_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
+        hipLaunchKernelGGL((norms_kernel<TQ>), folded_grid((nq + 32 * kNormPasses - 1) / (32 * kNormPasses)), dim3(256), 0, stream, queries, nq, d,
                            qnorm.as<float>(), info.as<unsigned>() + 2);
         TSDG_HIP(hipGetLastError());
         qn = qnorm.as<float>();
