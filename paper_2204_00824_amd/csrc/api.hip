@@ -49,7 +49,11 @@ __global__ void pack_kernel(const int32_t* __restrict__ adj, const uint8_t* __re
     }
     if (lane < K) packed[row * K + lane] = used ? ((uint32_t)id | ((uint32_t)l << kIdBits)) : kPackPad;
     if (bad) atomicCAS(&flags[0], 0, bad);
-    if (used) atomicMax(&flags[1], l);
+    // the row's largest lambda, then at most one atomic per row, and only when the value read first is smaller
+    int lw = used ? l : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lw = max(lw, __shfl_xor(lw, o, 64));
+    if (lane == 0 && lw > flags[1]) atomicMax(&flags[1], lw);
 }
 
 __global__ void unpack_kernel(const uint32_t* __restrict__ packed, int64_t total, int32_t* __restrict__ adj,

@@ -331,13 +331,15 @@ __global__ __launch_bounds__(64) void merge_kernel(MergeArgs a)
 }
 
 // ------------------------------------------------------------------ stage 2
+constexpr int kLambdaSlots = 1024;
+
 struct Stage2Args {
     const void* base;
     const int32_t* g2_id;
     const float* g2_s;
     const int32_t* g2_deg;
     uint32_t* packed;  // [N,K]
-    int* max_lambda;
+    int* max_lambda;   // [kLambdaSlots]: a node reports to slot (node % kLambdaSlots), so no address takes every atomic
     int64_t N;
     int d, K, rev_cap, lambda0;
     I8Rows i8;
@@ -409,7 +411,7 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
         }
     }
     for (int o = 32; o > 0; o >>= 1) lmax = max(lmax, __shfl_xor(lmax, o, 64));
-    if (lane == 0 && lmax > 0) atomicMax(a.max_lambda, lmax);
+    if (lane == 0 && lmax > 0) atomicMax(&a.max_lambda[x0 % kLambdaSlots], lmax);
 }
 
 // ------------------------------------------------------------------ host driver
@@ -467,10 +469,10 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     TSDG_HIP(start.alloc(((size_t)N + 1) * 8));
     const int64_t nb = (N + kScanBlock - 1) / kScanBlock;
     TSDG_HIP(bsums.alloc(((size_t)nb + 1) * 8));
-    TSDG_HIP(mlam.alloc(4));
+    TSDG_HIP(mlam.alloc(kLambdaSlots * sizeof(int)));
     TSDG_HIP(hipMemsetAsync(indeg.p, 0, (size_t)N * 4, stream));
     TSDG_HIP(hipMemsetAsync(cursor.p, 0, (size_t)N * 4, stream));
-    TSDG_HIP(hipMemsetAsync(mlam.p, 0, 4, stream));
+    TSDG_HIP(hipMemsetAsync(mlam.p, 0, kLambdaSlots * sizeof(int), stream));
 
     // Rows that are integers in [0,255] (uint8 storage, or fp32 that passes the test) with lists of at
     // most 64 entries take their pairwise distances from the int8 matrix cores.
@@ -574,8 +576,10 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     dispatch_row_shape(dtype, d, s2);
     TSDG_HIP(s2.err);
     TSDG_HIP(hipGetLastError());
-    TSDG_HIP(hipMemcpyAsync(max_lambda, mlam.p, 4, hipMemcpyDeviceToHost, stream));
+    int h_lam[kLambdaSlots];
+    TSDG_HIP(hipMemcpyAsync(h_lam, mlam.p, sizeof(h_lam), hipMemcpyDeviceToHost, stream));
     TSDG_HIP(hipStreamSynchronize(stream));
+    *max_lambda = *std::max_element(h_lam, h_lam + kLambdaSlots);
     return ANN_OK;
 }
 
