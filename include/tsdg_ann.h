@@ -181,6 +181,20 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
                             int t0, const ann_search_params* params, int32_t* out_ids,
                             float* out_dists, ann_query_stats* stats);
 
+/* ann_search_multi for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same result as ann_search_multi, but the t0 rankings go to a scratch array that is part of the
+ * library's device image (540,672 bytes on every GPU the library runs on, held until the process
+ * ends) instead of the graph's buffer, so the graph is const and the call never calls hipMalloc,
+ * hipFree or any allocating routine.  Limit: nq * t0 <= 2048 searches per call (ANN_EUNSUPPORTED
+ * beyond, outputs untouched).  The first call on a device looks the array's address up once.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race and must be serialised by the caller; consecutive calls on one stream are safe.
+ * Nothing in the array needs clearing between calls (every word a call reads it has written). */
+ann_status ann_search_multi_static(const ann_graph* graph, const void* base, const void* queries, int nq,
+                                   int k, int t0, const ann_search_params* params, int32_t* out_ids,
+                                   float* out_dists, ann_query_stats* stats);
+
 /* Large-batch search with the structures of Alg. 2 / Sec. 4.2 as printed: a ranking array R of
  * fixed size k (k <= 64), an expansion queue C of m_c segments of 32 sorted entries (segment =
  * id mod m_c; a push into a full segment drops its most distant entry; pop = smallest head), a

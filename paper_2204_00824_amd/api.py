@@ -63,6 +63,7 @@ def load_library():
     L.ann_search.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     L.ann_search_ex.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
     L.ann_search_multi.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
+    L.ann_search_multi_static.argtypes = L.ann_search_multi.argtypes
     L.ann_search_alg2.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
     L.ann_graph_export.argtypes = [vp, vp, vp, vp]
     L.ann_graph_import.argtypes = [vp, vp, i64, i32, i32, vp, C.POINTER(vp)]
@@ -77,7 +78,7 @@ def load_library():
                                   C.POINTER(i32), C.POINTER(i64)]
     L.ann_graph_free.restype = None
     for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
-                 "ann_search_ex", "ann_search_multi", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_probe_mfma", "ann_normalize_rows", "ann_knn_descent", "ann_max_row_norm", "ann_ip_augment_rows"):
+                 "ann_search_ex", "ann_search_multi", "ann_search_multi_static", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_probe_mfma", "ann_normalize_rows", "ann_knn_descent", "ann_max_row_norm", "ann_ip_augment_rows"):
         getattr(L, name).restype = C.c_int
     del u64
     _lib = L
@@ -240,7 +241,7 @@ def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: in
 
 def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, t0: int, *,
                      lambda_visit: int = 0, seed: int = 0, max_hops: int = 0, qi_offset: int = 0, stream=None,
-                     want_stats: bool = False, out=None, metric="l2"):
+                     want_stats: bool = False, out=None, metric="l2", _entry="ann_search_multi"):
     """Small-batch multi-search (Alg. 1).  Returns (ids, dists) or (ids, dists, QueryStats)."""
     lib = load_library()
     p, dt = _base_ptr(base)
@@ -258,11 +259,17 @@ def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k:
     prm.dtype, prm.lambda_visit, prm.seed, prm.max_hops = dt, lambda_visit, seed, max_hops
     prm.qi_offset, prm.stream, prm.metric = qi_offset, _stream_ptr(stream), _METRICS[metric]
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
-    _check(lib.ann_search_multi(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(),
+    _check(getattr(lib, _entry)(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(),
                                 st.data_ptr() if st is not None else None))
     if want_stats:
         return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
     return ids, s
+
+
+def ann_search_multi_static(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, t0: int, **kw):
+    """ann_search_multi on the library's own scratch: the C call allocates nothing (nq * t0 <= 2048).
+    Pass `out=(ids, dists)` to keep this wrapper from allocating the outputs too."""
+    return ann_search_multi(graph, base, queries, k, t0, _entry="ann_search_multi_static", **kw)
 
 
 def ann_search_alg2(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, delta: float, *, m_c: int = 16,

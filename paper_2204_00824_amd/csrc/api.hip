@@ -618,39 +618,52 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
 }
 
-ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k, int t0,
-                            const ann_search_params* params, int32_t* out_ids, float* out_dists,
-                            ann_query_stats* stats)
+// Argument checks and launch shared by the two multi-search entry points.  `own_scratch`: take the
+// rankings' scratch from the library's file-scope array (no allocation) instead of the graph's buffer.
+static ann_status search_multi_common(ann_graph_impl* g, const void* base, const void* queries, int nq, int k, int t0,
+                                      const ann_search_params* params, int32_t* out_ids, float* out_dists,
+                                      ann_query_stats* stats, bool own_scratch, const char* what)
 {
     g_err[0] = 0;
     ann_search_params p;
     ann_search_params_default(&p);
     if (params) p = *params;
-    if (!graph) { set_error("ann_search_multi: null graph"); return ANN_EINVAL; }
-    ann_graph_impl* g = reinterpret_cast<ann_graph_impl*>(graph);
-    if (nq < 0) { set_error("ann_search_multi: negative nq"); return ANN_EINVAL; }
-    if (k < 1 || k > 32) { set_error("ann_search_multi: need 1 <= k <= 32 (k=%d)", k); return ANN_EINVAL; }
-    if (t0 < 1 || t0 > 1024) { set_error("ann_search_multi: need 1 <= t0 <= 1024 (t0=%d)", t0); return ANN_EINVAL; }
-    if (p.max_hops < 0 || p.lambda_visit < 0) { set_error("ann_search_multi: negative max_hops / lambda_visit"); return ANN_EINVAL; }
+    if (!g) { set_error("%s: null graph", what); return ANN_EINVAL; }
+    if (nq < 0) { set_error("%s: negative nq", what); return ANN_EINVAL; }
+    if (k < 1 || k > 32) { set_error("%s: need 1 <= k <= 32 (k=%d)", what, k); return ANN_EINVAL; }
+    if (t0 < 1 || t0 > 1024) { set_error("%s: need 1 <= t0 <= 1024 (t0=%d)", what, t0); return ANN_EINVAL; }
+    if (p.max_hops < 0 || p.lambda_visit < 0) { set_error("%s: negative max_hops / lambda_visit", what); return ANN_EINVAL; }
     if (nq == 0) return ANN_OK;
-    if (!queries || !out_ids || !out_dists) { set_error("ann_search_multi: null pointer"); return ANN_EINVAL; }
-    ann_status rc = check_rows(base, g->N, g->d, p.dtype, "ann_search_multi", true);
+    if (!queries || !out_ids || !out_dists) { set_error("%s: null pointer", what); return ANN_EINVAL; }
+    ann_status rc = check_rows(base, g->N, g->d, p.dtype, what, true);
     if (rc != ANN_OK) return rc;
-    rc = check_metric(p.metric, p.dtype, "ann_search_multi");
+    rc = check_metric(p.metric, p.dtype, what);
     if (rc != ANN_OK) return rc;
-    if (!aligned16(queries)) { set_error("ann_search_multi: query rows must be 16-byte aligned"); return ANN_EINVAL; }
-    if ((int64_t)nq * t0 > 65535ll * 1024) { set_error("ann_search_multi: nq * t0 too large"); return ANN_EUNSUPPORTED; }
-    if (nq > 65535) { set_error("ann_search_multi: at most 65535 queries per call"); return ANN_EUNSUPPORTED; }
-    const size_t need = (size_t)nq * (size_t)t0 * 33 * sizeof(uint64_t);
-    if (need > g->ws_bytes) {
-        hipStream_t st = static_cast<hipStream_t>(p.stream);
-        TSDG_HIP(hipStreamSynchronize(st));
-        if (g->ws) (void)hipFree(g->ws);
-        g->ws = nullptr;
-        g->ws_bytes = 0;
-        hipError_t e = hipMalloc(&g->ws, need);
-        if (e != hipSuccess) { set_error("hipMalloc of the multi-search scratch failed: %s", hipGetErrorString(e)); return ANN_ENOMEM; }
-        g->ws_bytes = need;
+    if (!aligned16(queries)) { set_error("%s: query rows must be 16-byte aligned", what); return ANN_EINVAL; }
+    if ((int64_t)nq * t0 > 65535ll * 1024) { set_error("%s: nq * t0 too large", what); return ANN_EUNSUPPORTED; }
+    if (nq > 65535) { set_error("%s: at most 65535 queries per call", what); return ANN_EUNSUPPORTED; }
+    uint64_t* scratch = nullptr;
+    if (own_scratch) {
+        if ((int64_t)nq * t0 > kMultiStaticSearches) {
+            set_error("%s: nq * t0 = %lld searches exceed the %d the library's own scratch holds", what,
+                      (long long)nq * t0, kMultiStaticSearches);
+            return ANN_EUNSUPPORTED;
+        }
+        rc = multi_static_scratch(&scratch);
+        if (rc != ANN_OK) return rc;
+    } else {
+        const size_t need = (size_t)nq * (size_t)t0 * 33 * sizeof(uint64_t);
+        if (need > g->ws_bytes) {
+            hipStream_t st = static_cast<hipStream_t>(p.stream);
+            TSDG_HIP(hipStreamSynchronize(st));
+            if (g->ws) (void)hipFree(g->ws);
+            g->ws = nullptr;
+            g->ws_bytes = 0;
+            hipError_t e = hipMalloc(&g->ws, need);
+            if (e != hipSuccess) { set_error("hipMalloc of the multi-search scratch failed: %s", hipGetErrorString(e)); return ANN_ENOMEM; }
+            g->ws_bytes = need;
+        }
+        scratch = static_cast<uint64_t*>(g->ws);
     }
     MultiLaunch s;
     s.packed = g->packed;
@@ -669,7 +682,7 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
     s.max_hops = p.max_hops == 0 ? 16 : p.max_hops;
     s.seed = p.seed;
     s.qi_offset = p.qi_offset;
-    s.scratch = static_cast<uint64_t*>(g->ws);
+    s.scratch = scratch;
     s.out_ids = out_ids;
     s.out_dists = out_dists;
     s.stats = stats;
@@ -677,6 +690,23 @@ ann_status ann_search_multi(ann_graph* graph, const void* base, const void* quer
     rc = launch_search_multi(s);
     if (rc != ANN_OK) return rc;
     return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
+}
+
+ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k, int t0,
+                            const ann_search_params* params, int32_t* out_ids, float* out_dists,
+                            ann_query_stats* stats)
+{
+    return search_multi_common(reinterpret_cast<ann_graph_impl*>(graph), base, queries, nq, k, t0, params, out_ids,
+                               out_dists, stats, false, "ann_search_multi");
+}
+
+ann_status ann_search_multi_static(const ann_graph* graph, const void* base, const void* queries, int nq, int k,
+                                   int t0, const ann_search_params* params, int32_t* out_ids, float* out_dists,
+                                   ann_query_stats* stats)
+{
+    // the graph is only read on this path (its own scratch buffer is left alone)
+    return search_multi_common(const_cast<ann_graph_impl*>(reinterpret_cast<const ann_graph_impl*>(graph)), base,
+                               queries, nq, k, t0, params, out_ids, out_dists, stats, true, "ann_search_multi_static");
 }
 
 ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void* queries, int nq, int k,

@@ -104,6 +104,10 @@ struct MultiLaunch {
     hipStream_t stream;
 };
 ann_status launch_search_multi(const MultiLaunch& a);
+// Device address, on the current device, of the library's own scratch for up to
+// kMultiStaticSearches searches of one multi-search call (a file-scope array in multi.hip).
+constexpr int kMultiStaticSearches = 2048;
+ann_status multi_static_scratch(uint64_t** out);
 
 struct Alg2Launch {
     const uint32_t* packed;

@@ -11,6 +11,8 @@
 // keeps the 16 smallest, merges them with the kept half of R (first 16) and
 // decides whether the search goes on (an id new to the first 16 entered them).
 // No visited set and no expansion queue, as in the paper.
+#include <mutex>
+
 #include "dist.hpp"
 #include "ranklist.hpp"
 
@@ -326,6 +328,40 @@ __global__ __launch_bounds__(256) void multi_merge_kernel(MultiMergeArgs a)
         s.dedup_hits = 0;
         a.stats[qi] = s;
     }
+}
+
+// ---- scratch of ann_search_multi_static, the entry point that allocates nothing
+// The rankings of up to kStaticSearches searches (nq * t0) live in this file-scope array: 540,672
+// bytes that every GPU the library runs on holds until the process ends.  In host code the
+// array's name is only a handle: the device address comes from hipGetSymbolAddress, asked once
+// per device with that device current, and only that pointer is handed to kernels.  Nothing in
+// the array has to start at zero: multi_kernel writes all 33 words of every search of a call
+// before multi_merge_kernel reads them.
+static __device__ __align__(256) unsigned long long scratch[(size_t)kMultiStaticSearches * 33];
+
+ann_status multi_static_scratch(uint64_t** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static uint64_t* ptr[kMaxDevices] = {};
+    int dev = -1;
+    TSDG_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("ann_search_multi_static: device index %d outside 0..%d", dev, kMaxDevices - 1);
+        return ANN_EUNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        TSDG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) {
+            set_error("ann_search_multi_static: no device address for the static scratch");
+            return ANN_EDEVICE;
+        }
+        ptr[dev] = static_cast<uint64_t*>(p);
+    }
+    *out = ptr[dev];
+    return ANN_OK;
 }
 
 namespace {
