@@ -389,9 +389,11 @@ def main():
 
     # ---- the paper's own structures (Alg. 2: R of size k, segmented queue C, segmented table V, Delta stop)
     if not args.skip_small:
-        typical = float(P.ann_bruteforce(base, queries[:512].contiguous(), k)[1][:, -1].median().item())
+        # Delta is a difference of L2 distances (Alg. 2 compares the measure itself): fractions of the typical
+        # distance to the 10th neighbour
+        typical = float(P.ann_bruteforce(base, queries[:512].contiguous(), k)[1][:, -1].median().sqrt().item())
         rows = []
-        for k2, frac in ((16, 0.0), (32, 0.0), (32, 0.1), (64, 0.0)):
+        for k2, frac in ((16, 0.0), (32, 0.0), (32, 0.05), (64, 0.0)):
             i2, s2, st2 = P.ann_search_alg2(graph, base, queries, k2, frac * typical, want_stats=True)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

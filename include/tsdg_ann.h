@@ -199,9 +199,12 @@ ann_status ann_search_multi_static(const ann_graph* graph, const void* base, con
  * fixed size k (k <= 64), an expansion queue C of m_c segments of 32 sorted entries (segment =
  * id mod m_c; a push into a full segment drops its most distant entry; pop = smallest head), a
  * look-up table V of m_v segments of 32 slots holding only expanded nodes (round-robin
- * overwrite), start from the closest of 32 seeds, stop when the popped candidate is further
- * than the furthest of R by more than delta (in squared-distance units), when C is empty or at
- * the hop limit.  1 <= m_c, m_v <= 64.  Unlike ann_search its result depends on m_c and m_v.
+ * overwrite), start from the closest of 32 seeds, stop when the popped candidate u is further
+ * than the furthest f of R by more than delta ON THE MEASURE ITSELF, m(u,q) > m(f,q) + delta as
+ * Alg. 2 prints it: for ANN_L2 delta is an L2 distance (sqrt(s_u) > sqrt(s_f) + delta, evaluated
+ * as (s_u - s_f) - delta^2 > 0 and its square above 4 delta^2 s_f in fp64, so that no square root is
+ * taken), for ANN_COSINE a difference of 1 - cos; or when C is empty or at the hop limit.  The
+ * distances returned stay squared L2 (or 1 - cos).  1 <= m_c, m_v <= 64.  Unlike ann_search its result depends on m_c and m_v.
  * Of params it reads dtype, lambda_visit (0 = 5), seed, max_hops (0 = unbounded), qi_offset,
  * stream; stats->dedup_hits counts neighbours skipped because V or C held them. */
 ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void* queries, int nq, int k,

@@ -31,6 +31,10 @@ def lib():
         L.orc_recall.restype = C.c_double
         L.orc_recall.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int]
         L.orc_max_threads.restype = C.c_int
+        L.orc_descent_slot.restype = C.c_uint32
+        L.orc_descent_slot.argtypes = [C.c_uint32, C.c_int]
+        L.orc_alg2_stop.restype = C.c_int
+        L.orc_alg2_stop.argtypes = [C.c_float, C.c_float, C.c_float, C.c_int]
         _lib = L
     return _lib
 
@@ -72,6 +76,11 @@ def sqdist(a: np.ndarray, b: np.ndarray) -> np.float32:
 
 def seed_id(seed: int, qi: int, j: int, N: int) -> int:
     return int(lib().orc_seed_id(seed, qi, j, N))
+
+
+def alg2_stop(s_u: float, s_f: float, delta: float, metric="l2") -> bool:
+    """Stop test of Alg. 2 on squared distances s_u (popped candidate), s_f (furthest of R)."""
+    return bool(lib().orc_alg2_stop(s_u, s_f, delta, METRICS[metric]))
 
 
 def bruteforce(base, queries, k, threads=0):
@@ -247,10 +256,8 @@ def search_multi(adj, lam, base, queries, k, t0, max_hops=16, lambda_visit=10, s
 def search_alg2(adj, lam, base, queries, k, delta, m_c=16, m_v=16, max_hops=0, lambda_visit=5, seed=0, qi_offset=0,
                 threads=0, want_stats=False, metric="l2"):
     """Large-batch search with the paper's own R / C / V structures and the Delta stop (Alg. 2).
-    metric="cosine": unit rows; delta is given in units of m = 1 - cos, the walk compares s = 2m,
-    so it runs with 2*delta, and the distances returned are m = s/2."""
-    if METRICS[metric] == 1:
-        delta = float(np.float32(2.0) * np.float32(delta))
+    delta is in units of the measure m: the L2 distance sqrt(s) for metric="l2", 1 - cos = s/2 for
+    metric="cosine" (unit rows; the distances returned are then m = s/2)."""
     adj = _c(adj, np.int32)
     lam = _c(lam, np.uint8)
     base = _c(base)
@@ -262,12 +269,17 @@ def search_alg2(adj, lam, base, queries, k, delta, m_c=16, m_v=16, max_hops=0, l
     s = np.empty((nq, k), np.float32)
     stats = np.zeros((nq, 3), np.uint32) if want_stats else None
     rc = lib().orc_search_alg2(_p(adj), _p(lam), C.c_int64(N), K, _p(base), _dtype_code(base), d, _p(queries),
-                               C.c_int64(nq), k, m_c, m_v, C.c_float(delta), max_hops, lambda_visit,
+                               C.c_int64(nq), k, m_c, m_v, C.c_float(delta), METRICS[metric], max_hops, lambda_visit,
                                C.c_uint64(seed), C.c_int64(qi_offset), _p(ids), _p(s), _p(stats), threads)
     _check(rc, "search_alg2")
     if METRICS[metric] == 1:
         s = s * np.float32(0.5)
     return (ids, s, stats) if want_stats else (ids, s)
+
+
+def descent_slot(u: int, S: int) -> int:
+    """Cell of source u in a reverse-sample table of S cells (neighbourhood propagation)."""
+    return int(lib().orc_descent_slot(u, S.bit_length() - 1))
 
 
 def knn_descent(base, K, S=8, max_iters=10, delta=0.001, seed=0, init_ids=None, threads=0):

@@ -32,7 +32,10 @@
  * accumulated in fp64 and the sum is rounded once to fp32.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
- * (closed forms, brute force written independently in numpy, invariants).
+ * (closed forms, brute force written independently in numpy, invariants,
+ * and hand-worked examples under tests/golden/: Eq. 1 / Eq. 2 / lambda in 2-D,
+ * a hop of Alg. 2 that overflows a queue segment, two iterations of the
+ * neighbourhood propagation on eight points).  No function is left unpinned.
  *
  * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (see build.py).
  */
@@ -808,30 +811,40 @@ int orc_search_multi(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
 }
 
 /* ------------------------------------------------------------------------
- * Large-batch search with the paper's own structures (Alg. 2 and Sec. 4.2):
- * a top ranking array R of fixed size k, an expansion queue C cut into m_c
- * segments of 32, a look-up table V cut into m_v segments of 32 that holds only
- * expanded nodes, and the probe threshold Delta as termination.
+ * Large-batch search with the paper's own structures (Alg. 2 and Sec. 4.2).
+ * The loop below takes the listing's statements in the listing's order; this
+ * comment only says how its three containers are represented and which
+ * readings were taken where the text is silent.
  *
- *   U = 32 seeds; u = the closest; R = {u}; C = {u}; V = {}; t = 0
- *   while C not empty and t < T:
- *       t++;  u = pop the nearest of C;  f = furthest of R
- *       if s(u) > s(f) + delta: stop
- *       V.add(u)
- *       for each neighbour e of u (lambda-prefix, stored order):
- *           if e in V or e in C: skip
- *           f = furthest of R
- *           if s(e) < s(f) or |R| < k:  R.push(e); C.push(e); if |R| > k drop the furthest
- *   return R
- * (the V / C tests of all neighbours of u are made before any of them is pushed)
+ * R  top ranking array: at most k pairs sorted by (s,id); a push beyond k
+ *    removes the furthest.
+ * C  expansion queue: m_c segments of at most 32 pairs, each sorted by (s,id);
+ *    a pair goes to segment id % m_c; a push into a full segment drops that
+ *    segment's most distant pair (possibly the pushed one); pop = the smallest
+ *    of the segment heads.
+ * V  look-up table: m_v segments of 32 ids written round-robin (the oldest is
+ *    overwritten), segment id % m_v; only expanded nodes enter it.
  *
- * C: segment id % m_c, each kept sorted by (s,id), at most 32 entries; a push
- * into a full segment drops that segment's most distant entry; pop = the
- * smallest head over the segments.  V: segment id % m_v, 32 slots written
- * round-robin (the oldest is overwritten).
- * Readings where the paper is silent: distances are squared, so delta is in
- * squared units; an id already in R is neither pushed to R nor to C (R would
- * hold it twice otherwise); all orders are (s,id).  T = 0 means no hop limit.
+ * Order of the look-ups: the listing tests "e in V, e in C" for one neighbour
+ * at a time, after the pushes of the neighbours before it, and so does this
+ * loop.  It matters when an earlier neighbour's push into a full segment drops
+ * a later neighbour of the same node from C: at its turn that neighbour is in
+ * neither container, so it is scored again.  It is never pushed again (it
+ * entered R together with C; either R still holds it, or R dropped it as its
+ * furthest and every later furthest is at most as far, so the strict test
+ * fails), hence R, C and V are what look-ups made before the hop's pushes
+ * would give; only the two counters differ, by one each per such event.
+ *
+ * Readings where the paper is silent:
+ *   - the stop test compares the measure m of Table 1, not its square:
+ *     L2 (metric 0): m = sqrt(s), stop iff sqrt(s_u) > sqrt(s_f) + Delta.  To keep
+ *     every operation a correctly rounded IEEE one (no square root), the test is
+ *     taken in the equivalent form, all in fp64:
+ *         t = (s_u - s_f) - Delta*Delta;   stop iff t > 0 and t*t > (4*(Delta*Delta))*s_f
+ *     (both sides of sqrt(s_u) - sqrt(s_f) > Delta are squared twice; Delta >= 0).
+ *     1 - cos on unit rows (metric 1): m = s/2, stop iff s_u > s_f + 2*Delta in fp32;
+ *   - an id already in R is pushed neither to R nor to C (R would hold it twice);
+ *   - all orders are (s,id); T = 0 means no hop limit.
  * stats [nq,3]: hops t, distance evaluations (seeds included), skips by V or C.
  * ---------------------------------------------------------------------- */
 typedef struct {
@@ -839,10 +852,19 @@ typedef struct {
     int n;
 } cseg_t;
 
+/* stop test of Alg. 2 on the measure itself (see above) */
+int orc_alg2_stop(float s_u, float s_f, float delta, int metric)
+{
+    if (metric == 1) return s_u > s_f + 2.0f * delta;
+    const double dd = (double)delta * (double)delta;
+    const double t = ((double)s_u - (double)s_f) - dd;
+    return t > 0.0 && t * t > (4.0 * dd) * (double)s_f;
+}
+
 static void alg2_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, const void* base, int dtype,
-                     int d, const float* q, int k, int m_c, int m_v, float delta, int T, int lambda_visit,
-                     uint64_t seed, uint64_t qi, cseg_t* C, int32_t* V, int* vpos, pair_t* R, float* tmp,
-                     int32_t* out_ids, float* out_s, uint32_t* stats)
+                     int d, const float* q, int k, int m_c, int m_v, float delta, int metric, int T,
+                     int lambda_visit, uint64_t seed, uint64_t qi, cseg_t* C, int32_t* V, int* vpos, pair_t* R,
+                     float* tmp, int32_t* out_ids, float* out_s, uint32_t* stats)
 {
     uint32_t hops = 0, evals = 0, skips = 0;
     int nR = 0;
@@ -872,31 +894,22 @@ static void alg2_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
         pair_t u = C[gbest].e[0];
         for (int t = 1; t < C[gbest].n; ++t) C[gbest].e[t - 1] = C[gbest].e[t];
         --C[gbest].n;
-        if (u.s > R[nR - 1].s + delta) break;
+        if (orc_alg2_stop(u.s, R[nR - 1].s, delta, metric)) break;
         int gv = u.id % m_v;
         V[gv * 32 + vpos[gv]] = u.id;
         vpos[gv] = (vpos[gv] + 1) % 32;
-        int deg = 0;
-        while (deg < K && adj[(int64_t)u.id * K + deg] >= 0 && (int)lam[(int64_t)u.id * K + deg] < lambda_visit) ++deg;
-        /* the look-ups of all neighbours come first (on the GPU the lanes test in parallel,
-         * Sec. 4.2), then the survivors are scored, then pushed one by one in stored order */
-        pair_t fresh[64];
-        int nf = 0;
-        for (int p = 0; p < deg; ++p) {
-            int32_t e = adj[(int64_t)u.id * K + p];
+        for (int p = 0; p < K; ++p) {
+            const int32_t e = adj[(int64_t)u.id * K + p];
+            if (e < 0 || (int)lam[(int64_t)u.id * K + p] >= lambda_visit) break; /* the visited prefix ends */
             int found = 0;
             for (int t = 0; t < 32 && !found; ++t) found = (V[(e % m_v) * 32 + t] == e);
             cseg_t* sg = &C[e % m_c];
             for (int t = 0; t < sg->n && !found; ++t) found = (sg->e[t].id == e);
             if (found) { ++skips; continue; }
-            fresh[nf].id = e;
-            fresh[nf].s = orc_sqdist(q, row_f32(base, dtype, e, d, tmp), d);
-            ++nf;
+            pair_t c;
+            c.id = e;
+            c.s = orc_sqdist(q, row_f32(base, dtype, e, d, tmp), d);
             ++evals;
-        }
-        for (int p = 0; p < nf; ++p) {
-            pair_t c = fresh[p];
-            cseg_t* sg = &C[c.id % m_c];
             if (!(nR < k || c.s < R[nR - 1].s)) continue;
             int inR = 0;
             for (int t = 0; t < nR && !inR; ++t) inR = (R[t].id == c.id);
@@ -925,12 +938,13 @@ static void alg2_one(const int32_t* adj, const uint8_t* lam, int64_t N, int K, c
 }
 
 int orc_search_alg2(const int32_t* adj, const uint8_t* lam, int64_t N, int K, const void* base, int dtype, int d,
-                    const float* queries, int64_t nq, int k, int m_c, int m_v, float delta, int T,
+                    const float* queries, int64_t nq, int k, int m_c, int m_v, float delta, int metric, int T,
                     int lambda_visit, uint64_t seed, int64_t qi_offset, int32_t* out_ids, float* out_s,
                     uint32_t* stats, int threads)
 {
     if (!adj || !lam || !base || !queries || !out_ids || !out_s) return 1;
     if (N <= 0 || K <= 0 || d <= 0 || k <= 0 || m_c <= 0 || m_v <= 0 || T < 0 || nq < 0 || !(delta >= 0.0f)) return 1;
+    if (metric != 0 && metric != 1) return 1;
     threads = use_threads(threads);
     int failed = 0;
 #pragma omp parallel num_threads(threads)
@@ -946,7 +960,7 @@ int orc_search_alg2(const int32_t* adj, const uint8_t* lam, int64_t N, int K, co
         } else {
 #pragma omp for schedule(dynamic, 8)
             for (int64_t qi = 0; qi < nq; ++qi)
-                alg2_one(adj, lam, N, K, base, dtype, d, queries + qi * (int64_t)d, k, m_c, m_v, delta, T,
+                alg2_one(adj, lam, N, K, base, dtype, d, queries + qi * (int64_t)d, k, m_c, m_v, delta, metric, T,
                          lambda_visit, seed, (uint64_t)(qi + qi_offset), C, V, vpos, R, tmp, out_ids + qi * k,
                          out_s + qi * k, stats ? stats + qi * 3 : NULL);
         }
@@ -1025,6 +1039,12 @@ static int dlist_insert(dnode_t* l, int* m, int K, float s, int32_t id)
     return 1;
 }
 
+/* slot of source u in a reverse table of S = 2^log2s cells: the top log2s bits of u * 2654435761 mod 2^32 */
+uint32_t orc_descent_slot(uint32_t u, int log2s)
+{
+    return (uint32_t)(u * 2654435761u) >> (32 - log2s);
+}
+
 int orc_knn_descent(const void* base, int dtype, int64_t N, int d, int K, int S, int max_iters, float delta,
                     uint64_t seed, const int32_t* init_ids, int32_t* knn_id, float* knn_s,
                     int32_t* iters_done, int64_t* changed_per_iter, int threads)
@@ -1084,7 +1104,7 @@ int orc_knn_descent(const void* base, int dtype, int64_t N, int d, int K, int S,
             Rold[i].id = -1; Rold[i].s = INFINITY;
         }
         for (int64_t u = 0; u < N; ++u) {
-            const uint32_t slot = ((uint32_t)u * 2654435761u) >> (32 - log2s);
+            const uint32_t slot = orc_descent_slot((uint32_t)u, log2s);
             int nn = 0, no = 0;
             for (int t = 0; t < cnt[u]; ++t) {
                 const dnode_t* e = &B[u * K + t];

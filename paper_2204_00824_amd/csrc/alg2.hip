@@ -9,10 +9,19 @@
 //   V  look-up table of expanded nodes, m_v segments of 32 slots in LDS written
 //      round-robin, segment = id mod m_v;
 //   stop when the popped candidate is further than the furthest of R by more than
-//   delta (squared units), when C is empty, or at the hop limit T.
-// The distances of a hop's surviving neighbours are computed together (same gather as
-// search.hip); the pushes then run one by one in stored neighbour order, because each
-// acceptance test reads the furthest entry of R as left by the previous push.
+//   delta on the measure itself (the L2 distance, or 1 - cos), when C is empty, or at
+//   the hop limit T.
+// Alg. 2 tests one neighbour at a time against V and C, after the pushes of the
+// neighbours before it.  Here the look-ups of a hop are made by all lanes at once and the
+// survivors' distances are computed together (same gather as search.hip); the pushes then
+// run one by one in stored neighbour order, because each acceptance test reads the
+// furthest entry of R as left by the previous push.  The two orders differ only when a
+// push into a full segment of C drops a LATER neighbour of the same hop: in the listing's
+// order that neighbour is then in neither container at its turn and is scored once more,
+// but never pushed again (R holds it, or dropped it as its furthest and has only come
+// closer since).  So R, C and V are the same either way; the kernel watches for that
+// eviction and moves one count from the skips to the evaluations, which keeps both
+// counters equal to the listing's.
 #include "dist.hpp"
 #include "ranklist.hpp"
 
@@ -29,8 +38,19 @@ struct Alg2Args {
     uint64_t seed;
     int64_t qi_offset;
     float delta;
-    int K, d, k, m_c, m_v, T, lambda_visit;
+    int K, d, k, m_c, m_v, T, lambda_visit, metric;
 };
+
+// Stop test of Alg. 2 on the measure m itself.  1 - cos on unit rows: m = s/2, so
+// s_u > s_f + 2*delta.  L2: sqrt(s_u) > sqrt(s_f) + delta, taken without a square root as
+// t = (s_u - s_f) - delta^2 > 0 and t^2 > 4 delta^2 s_f in fp64 (every operation correctly rounded).
+__device__ __forceinline__ bool alg2_stop(float s_u, float s_f, float delta, int metric)
+{
+    if (metric == 1) return s_u > s_f + 2.0f * delta;
+    const double dd = (double)delta * (double)delta;
+    const double t = ((double)s_u - (double)s_f) - dd;
+    return t > 0.0 && t * t > (4.0 * dd) * (double)s_f;
+}
 
 __device__ __forceinline__ uint32_t seed_node_alg2(uint64_t seed, uint64_t qi, uint32_t j, uint64_t N)
 {
@@ -147,7 +167,7 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
         if (lane < nu - 1) Cseg[gu * 32 + lane] = nxt;
         if (lane == 0) Cn[gu] = nu - 1;
         const float fs = key_dist(readlane64(rkey, nR - 1));
-        if (key_dist(ukey) > fs + a.delta) break;
+        if (alg2_stop(key_dist(ukey), fs, a.delta, a.metric)) break;
         if (lane == 0) {
             const int gv = (int)(u % (uint32_t)a.m_v);
             const int p = vpos[gv];
@@ -164,14 +184,16 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
         const int deg = bad ? ctz64(bad) : 64;
         const uint32_t e = w & kIdMask;
         bool fresh = lane < deg;
+        bool only_in_c = false;  // skipped because C holds it (and V does not)
         if (fresh) {
             const int gv = (int)(e % (uint32_t)a.m_v);
             const int gc = (int)(e % (uint32_t)a.m_c);
-            bool found = false;
-            for (int t = 0; t < 32; ++t) found = found || V[gv * 32 + t] == e;
+            bool in_v = false, in_c = false;
+            for (int t = 0; t < 32; ++t) in_v = in_v || V[gv * 32 + t] == e;
             const int nc = Cn[gc];
-            for (int t = 0; t < nc; ++t) found = found || key_id(Cseg[gc * 32 + t]) == e;
-            fresh = !found;
+            for (int t = 0; t < nc; ++t) in_c = in_c || key_id(Cseg[gc * 32 + t]) == e;
+            fresh = !in_v && !in_c;
+            only_in_c = !in_v && in_c;
         }
         const uint64_t fm = ballot64(fresh);
         skips += (uint32_t)(deg - popc64(fm));
@@ -184,8 +206,11 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
         __syncthreads();
 
         // pushes, one by one in stored order
+        uint64_t rest = fm;
         for (int j = 0; j < m; ++j) {
             const uint64_t c = ckey[j];
+            const int p = ctz64(rest);  // position of this neighbour in the row
+            rest &= rest - 1;
             const float fcur = key_dist(readlane64(rkey, nR - 1));
             const bool accept = nR < a.k || key_dist(c) < fcur;
             if (!accept) continue;
@@ -207,6 +232,17 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
                 const int pos = popc64(ballot64(sk < c));
                 const uint64_t below = from_lane_below(sk);
                 const uint64_t nk = lane < pos ? sk : (lane == pos ? c : below);
+                if (n == 32 && pos < 32) {
+                    // the segment's most distant entry falls out; a later neighbour of this hop that was
+                    // skipped because C held it is scored again at its turn in the listing's order
+                    const uint32_t gone = key_id(readlane64(sk, 31));
+                    const bool again = only_in_c && lane > p && e == gone;
+                    if (ballot64(again)) {
+                        ++evals;
+                        --skips;
+                    }
+                    if (again) only_in_c = false;
+                }
                 __syncthreads();
                 if (lane < 32 && lane <= n) Cseg[g * 32 + lane] = nk;
                 if (lane == 0) Cn[g] = n < 32 ? n + 1 : 32;
@@ -263,6 +299,7 @@ ann_status launch_search_alg2(const Alg2Launch& s)
     disp.a.m_v = s.m_v;
     disp.a.T = s.max_hops;
     disp.a.lambda_visit = s.lambda_visit;
+    disp.a.metric = s.metric;
     disp.nq = s.nq;
     disp.stream = s.stream;
     if (!dispatch_search_row_shape(s.dtype, s.d, disp)) {

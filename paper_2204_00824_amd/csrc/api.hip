@@ -748,7 +748,8 @@ ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void*
     if (lv > 31) lv = 32;
     s.lambda_visit = lv;
     s.max_hops = p.max_hops;
-    s.delta = p.metric == ANN_COSINE ? 2.0f * delta : delta;  // delta is in units of m; the walk compares s = 2m
+    s.delta = delta;  // in units of the measure m (Alg. 2 compares m itself)
+    s.metric = p.metric == ANN_COSINE ? 1 : 0;
     s.seed = p.seed;
     s.qi_offset = p.qi_offset;
     s.out_ids = out_ids;

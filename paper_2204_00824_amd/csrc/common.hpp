@@ -118,7 +118,8 @@ struct Alg2Launch {
     int d;
     const float* queries;
     int nq, k, m_c, m_v, lambda_visit, max_hops;
-    float delta;
+    int metric;   // 0: the measure is the L2 distance sqrt(s); 1: 1 - cos = s/2
+    float delta;  // in units of the measure
     uint64_t seed;
     int64_t qi_offset;
     int32_t* out_ids;

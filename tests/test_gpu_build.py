@@ -15,9 +15,11 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def check_graph(gpu, orc, base, K, what, ref=None, **kw):
-    """GPU build vs oracle build: adjacency and lambda identical, except in rows where the
-    oracle's own competing distances are closer than 1e-5 relative."""
+def check_graph(gpu, orc, base, K, what, ref=None, max_excused=0, **kw):
+    """GPU build vs oracle build: adjacency and lambda identical.  A caller whose data holds
+    constructed near-ties may allow `max_excused` rows to differ, and only rows in which the
+    oracle's own competing distances are closer than 1e-5 relative; no caller needs it so far,
+    so every call asserts that no row differs."""
     okw = dict(alpha=kw.get("alpha", 1.2), lambda0=kw.get("lambda0", 9))
     if kw.get("rev_cap"):
         okw["rev_cap"] = kw["rev_cap"]
@@ -32,7 +34,7 @@ def check_graph(gpu, orc, base, K, what, ref=None, **kw):
         gaps = np.diff(s) / np.maximum(s[1:], 1e-30)
         assert gaps.size and gaps.min() < 1e-5, (f"{what}: row {r} differs without a near-tie: "
                                                  f"{adj[r]} / {lam[r]} vs {adj_o[r]} / {lam_o[r]}")
-    assert len(rows) <= 0.01 * base.shape[0], f"{what}: {len(rows)} rows excused"
+    assert len(rows) <= max_excused, f"{what}: {len(rows)} rows differ at near-ties (allowed: {max_excused})"
     valid = adj >= 0
     assert np.all(lam[valid] <= okw["lambda0"]) and np.all(lam[~valid] == 255)
     return len(rows)

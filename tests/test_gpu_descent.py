@@ -44,6 +44,19 @@ def test_shapes_and_sample_sizes(gpu, orc, K, S, d, u8):
     assert last == ch_o[-1]
 
 
+@pytest.mark.parametrize("which", ["A", "B"])
+def test_hand_worked_example(gpu, orc, which):
+    """tests/golden/knn_descent_line8.json: the lists derived by hand, not only the oracle's."""
+    step(f"descent hand-worked line of 8 points, case {which}")
+    from test_oracle_descent import line8_case
+    doc, case, base, init = line8_case(which)
+    for it in (1, 2):
+        want = case[f"after_iteration_{it}"]
+        ids, s, done, last = gpu.ann_knn_descent(dev(base), doc["K"], S=doc["S"], max_iters=it, delta=0.0,
+                                                 init_ids=dev(init))
+        assert done == it and ids.cpu().numpy().tolist() == want["ids"] and last == want["changed"]
+
+
 def test_stops_by_delta_and_accepts_start_lists(gpu, orc):
     step("descent: delta stop, caller's start lists, exact graph as fixed point")
     base = workloads.single_gaussian(3000, 8, seed=44)

@@ -1,7 +1,37 @@
 """Pins for the oracle's search with the paper's own R / C / V structures (Alg. 2).  CPU only."""
+import json
+import os
+from fractions import Fraction
+
 import numpy as np
 
 import workloads
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "alg2_segment_overflow.json")
+
+
+def exact_stop_l2(s_u, s_f, delta):
+    """sqrt(s_u) > sqrt(s_f) + delta decided in exact rational arithmetic (delta >= 0):
+    s_u - s_f - delta^2 > 2 delta sqrt(s_f)  <=>  lhs > 0 and lhs^2 > 4 delta^2 s_f."""
+    su, sf, dl = Fraction(float(s_u)), Fraction(float(s_f)), Fraction(float(delta))
+    t = su - sf - dl * dl
+    return t > 0 and t * t > 4 * dl * dl * sf
+
+
+def overflow_case():
+    """The hand-worked example of tests/golden/alg2_segment_overflow.json as arrays."""
+    doc = json.load(open(GOLDEN))
+    x = np.array(doc["x"], np.float32)
+    N, K = len(x), 40
+    base = np.zeros((N, 4), np.float32)
+    base[:, 0] = x
+    adj = np.full((N, K), -1, np.int32)
+    lam = np.full((N, K), 255, np.uint8)
+    for i in range(N):
+        row = doc["rows"].get(str(i), doc["default_row"])
+        adj[i, :len(row)] = row
+        lam[i, :len(row)] = 0
+    return doc, base, adj, lam, np.zeros((1, 4), np.float32)
 
 
 def np_canonical(base, q):
@@ -27,21 +57,18 @@ def py_alg2(adj, lam, base, q, k, m_c, m_v, delta, T, lv, seeds):
         u = min(heads)
         hops += 1
         C[u[1] % m_c].remove(u)
-        if u[0] > np.float32(R[-1][0] + np.float32(delta)):
+        if exact_stop_l2(u[0], R[-1][0], delta):
             break
         V[u[1] % m_v][vpos[u[1] % m_v]] = u[1]
         vpos[u[1] % m_v] = (vpos[u[1] % m_v] + 1) % 32
-        fresh = []
         for p in range(adj.shape[1]):
             e = int(adj[u[1], p])
             if e < 0 or lam[u[1], p] >= lv:
                 break
-            if e in V[e % m_v] or any(i == e for _, i in C[e % m_c]):
+            if e in V[e % m_v] or any(i == e for _, i in C[e % m_c]):   # one neighbour at a time, as listed
                 continue
-            fresh.append((s_of(e), e))          # all look-ups of the hop precede its pushes
-        evals += len(fresh)
-        for c in fresh:
-            e = c[1]
+            c = (s_of(e), e)
+            evals += 1
             if not (len(R) < k or c[0] < R[-1][0]):
                 continue
             if any(i == e for _, i in R):
@@ -55,7 +82,8 @@ def test_matches_independent_python_version(orc):
     base, queries = workloads.single_gaussian(1500, 8, seed=51, nq=10)
     adj, lam = orc.build_graph(base, 16)
     typical = float(np.median(orc.bruteforce(base, queries, 10)[1][:, 9]))
-    for k, m_c, m_v, delta, T in ((10, 4, 4, 0.0, 0), (20, 2, 1, 0.5 * typical, 0), (5, 1, 8, 10 * typical, 12)):
+    typical = float(np.sqrt(typical))                    # Delta is an L2 distance
+    for k, m_c, m_v, delta, T in ((10, 4, 4, 0.0, 0), (20, 2, 1, 0.2 * typical, 0), (5, 1, 8, 3 * typical, 12)):
         ids, s, st = orc.search_alg2(adj, lam, base, queries, k, delta, m_c=m_c, m_v=m_v, max_hops=T,
                                      lambda_visit=10, seed=3, want_stats=True)
         for qi in range(10):
@@ -65,6 +93,55 @@ def test_matches_independent_python_version(orc):
             assert [i for _, i in R] == list(ids[qi])
             assert np.array_equal(np.array([v for v, _ in R], np.float32), s[qi])
             assert (hops, evals) == (st[qi][0], st[qi][1])
+
+
+def test_hand_worked_segment_overflow(orc):
+    """A push into the full segment of C drops a later neighbour of the same hop: in the
+    listing's order that neighbour is scored once more (and pushed nowhere).  Expected counters
+    and rankings are the hand-derived ones of the golden file."""
+    doc, base, adj, lam, q = overflow_case()
+    prm = doc["params"]
+    seed = next(sd for sd in range(300) if 0 in [orc.seed_id(sd, 0, t, len(base)) for t in range(32)])
+    for T in (1, 2, 3):
+        want = doc["expected"][f"T={T}"]
+        ids, s, st = orc.search_alg2(adj, lam, base, q, prm["k"], prm["delta"], m_c=prm["m_c"], m_v=prm["m_v"],
+                                     max_hops=T, lambda_visit=prm["lambda_visit"], seed=seed, want_stats=True)
+        assert [int(v) for v in st[0]] == [want["hops"], want["dist_evals"], want["skips"]], f"T={T}"
+        n = len(want["ids"])
+        assert list(ids[0][:n]) == want["ids"] and np.all(ids[0][n:] == -1)
+        assert np.array_equal(s[0][:n], base[want["ids"], 0] ** 2)
+    # what look-ups made before the hop's pushes would report: same ranking, one count moved
+    other = doc["batched_lookups_would_give"]["T=2"]
+    assert other["ids"] == doc["expected"]["T=2"]["ids"]
+    assert (other["dist_evals"], other["skips"]) == (doc["expected"]["T=2"]["dist_evals"] - 1, 1)
+
+
+def test_stop_rule_is_on_the_distance_itself(orc):
+    """Alg. 2 compares m(u,q) > m(f,q) + Delta with m the L2 distance.  The oracle's square-root-free
+    fp64 form against the same inequality in exact rational arithmetic, and closed cases."""
+    assert not orc.alg2_stop(12.25, 9.0, 0.5)                      # 3.5 > 3 + 0.5 is false (equality)
+    assert orc.alg2_stop(np.nextafter(np.float32(12.25), np.float32(20)), 9.0, 0.5)
+    assert not orc.alg2_stop(16.0, 9.0, 1.0) and orc.alg2_stop(16.5, 9.0, 1.0)
+    assert orc.alg2_stop(9.5, 9.0, 0.0) and not orc.alg2_stop(9.0, 9.0, 0.0)   # Delta = 0: plain comparison
+    assert not orc.alg2_stop(1e30, 1.0, 3.0e38)
+    # a test on squared distances with the same Delta would already stop at s_u = 12 (12 > 9 + 1);
+    # on the distance itself sqrt(12) = 3.46 is not beyond 3 + 1
+    assert not orc.alg2_stop(12.0, 9.0, 1.0)
+    g = np.random.default_rng(5)
+    n_stop = 0
+    for _ in range(4000):
+        s_f = np.float32(g.uniform(0.0, 100.0))
+        delta = np.float32(g.choice([0.0, g.uniform(0, 3.0)]))
+        s_u = np.float32((np.sqrt(float(s_f)) + float(delta)) ** 2 * g.choice([1.0, g.uniform(0.9, 1.1), 1 + 1e-6, 1 - 1e-6]))
+        want = exact_stop_l2(s_u, s_f, delta)
+        t = Fraction(float(s_u)) - Fraction(float(s_f)) - Fraction(float(delta)) ** 2
+        knife = abs(t * t - 4 * Fraction(float(delta)) ** 2 * Fraction(float(s_f))) <= Fraction(1, 10 ** 9) * max(t * t, Fraction(1, 10 ** 30))
+        if not knife:
+            assert orc.alg2_stop(s_u, s_f, delta) == want
+        n_stop += want
+    assert 500 < n_stop < 3500
+    # 1 - cos on unit rows: m = s/2
+    assert orc.alg2_stop(1.01, 0.5, 0.25, "cosine") and not orc.alg2_stop(1.0, 0.5, 0.25, "cosine")
 
 
 def test_everything_expanded_is_exact(orc):
@@ -111,9 +188,9 @@ def test_queue_segment_drops_its_most_distant_entry(orc):
 def test_delta_and_hop_limit(orc):
     base, queries = workloads.single_gaussian(2000, 8, seed=54, nq=30)
     adj, lam = orc.build_graph(base, 16)
-    typical = float(np.median(orc.bruteforce(base, queries, 10)[1][:, 9]))
+    typical = float(np.sqrt(np.median(orc.bruteforce(base, queries, 10)[1][:, 9])))
     prev = None
-    for delta in (0.0, 0.2 * typical, typical, 5 * typical):
+    for delta in (0.0, 0.1 * typical, 0.5 * typical, 2 * typical):
         ids, s, st = orc.search_alg2(adj, lam, base, queries, 10, delta, want_stats=True)
         if prev is not None:
             assert np.all(st[:, 0] >= prev)              # a larger Delta never stops earlier
@@ -121,7 +198,7 @@ def test_delta_and_hop_limit(orc):
         for r in range(30):
             assert len(set(ids[r])) == 10 and list(zip(s[r], ids[r])) == sorted(zip(s[r], ids[r]))
             assert np.array_equal(np_canonical(base[ids[r]], queries[r]), s[r])
-    _, _, st = orc.search_alg2(adj, lam, base, queries, 10, 5 * typical, max_hops=4, want_stats=True)
+    _, _, st = orc.search_alg2(adj, lam, base, queries, 10, 2 * typical, max_hops=4, want_stats=True)
     assert np.all(st[:, 0] <= 4)
     gt = orc.bruteforce(base, queries, 10)[0]
-    assert orc.recall(orc.search_alg2(adj, lam, base, queries, 32, typical)[0][:, :10].copy(), gt) > 0.9
+    assert orc.recall(orc.search_alg2(adj, lam, base, queries, 32, 0.5 * typical)[0][:, :10].copy(), gt) > 0.9

@@ -3,10 +3,49 @@
 It is a heuristic, so what pins it: an independent re-statement of the same rules with Python sets
 on a small input (ids must agree exactly), the invariants every iteration must keep, the exact k-NN
 graph as a fixed point, and convergence towards the brute-force lists on a connected cloud."""
+import json
+import os
+
 import numpy as np
 import pytest
 
 import workloads
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "knn_descent_line8.json")
+
+
+def line8_case(which):
+    """A hand-worked case of tests/golden/knn_descent_line8.json: rows of d = 4 (x, 0, 0, 0)."""
+    doc = json.load(open(GOLDEN))
+    base = np.zeros((len(doc["x"]), 4), np.float32)
+    base[:, 0] = doc["x"]
+    case = doc["cases"][which]
+    return doc, case, base, np.array(case["init_ids"], np.int32)
+
+
+@pytest.mark.parametrize("which", ["A", "B"])
+def test_hand_worked_example(orc, which):
+    """Eight points on a line, K = 3, S = 2: the lists after one and two iterations and the number of
+    changed entries equal the values derived by hand in the golden file (its derivations walk through
+    the sample cap, the slot of every reverse offer, the smallest-key rule, the new/old flags and the
+    'old edge offers only its new part' rule; a mistake in any of them changes one of these lists)."""
+    doc, case, base, init = line8_case(which)
+    for it in (1, 2):
+        want = case[f"after_iteration_{it}"]
+        ids, s, done, changed = orc.knn_descent(base, doc["K"], S=doc["S"], max_iters=it, delta=0.0, init_ids=init)
+        assert done == it and ids.tolist() == want["ids"] and int(changed[-1]) == want["changed"]
+        x = np.array(doc["x"], np.float64)
+        assert np.array_equal(s, ((x[:, None] - x[ids]) ** 2).astype(np.float32))
+
+
+def test_reverse_table_slot(orc):
+    """The cell a source takes in a reverse table, against products reduced by hand (golden file)."""
+    doc = json.load(open(GOLDEN))
+    assert [orc.descent_slot(u, 2) for u in range(8)] == doc["slot"]
+    for c in doc["slot_examples_S16"]["cases"]:
+        assert c["product"] - c["minus_multiples_of_2^32"] * 2 ** 32 == c["remainder"] < 2 ** 32
+        assert orc.descent_slot(c["u"], 16) == c["slot"] == c["remainder"] >> 28
+    assert len({c["slot"] for c in doc["slot_examples_S16"]["cases"]}) >= 5
 
 
 def python_descent(orc, base, K, S, iters, seed):
