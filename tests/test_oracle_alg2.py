@@ -22,7 +22,7 @@ def overflow_case():
     """The hand-worked example of tests/golden/alg2_segment_overflow.json as arrays."""
     doc = json.load(open(GOLDEN))
     x = np.array(doc["x"], np.float32)
-    N, K = len(x), 40
+    N, K = len(x), 34                      # the longest row has 33 entries; an imported graph needs K < N
     base = np.zeros((N, 4), np.float32)
     base[:, 0] = x
     adj = np.full((N, K), -1, np.int32)
