@@ -37,6 +37,161 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def kernel_source_sha256():
+    """Hash of the sources the search kernel is compiled from; a counter summary under profiles/ carries the hash
+    it was taken with, and its byte count is only quoted while the two agree."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("search.hip", "dist.hpp", "ranklist.hpp", "common.hpp"):
+        h.update(open(os.path.join(ROOT, "paper_2204_00824_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profile_traffic(name, L, n, nq):
+    """HBM-side bytes per launch as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in a SEPARATE run of this
+    command (the summary under profiles/ gives the commands and the copy calibration).  Returns (bytes, source),
+    or (None, why) when there is no summary for this workload, list length and kernel source."""
+    tpath = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(tpath):
+        return None, f"no profiles/{name}"
+    keys = ("hbm_bytes_per_launch:", "L:", "N:", "nq:", "kernel_source_sha256:")
+    prof = {k.strip(): v.strip() for k, v in (line.split(":", 1) for line in open(tpath) if line.startswith(keys))}
+    if int(prof.get("L", -1)) != L or int(prof.get("N", -1)) != n or int(prof.get("nq", -1)) != nq:
+        return None, f"profiles/{name} was taken at L={prof.get('L')}, N={prof.get('N')}, nq={prof.get('nq')}"
+    if prof.get("kernel_source_sha256") != kernel_source_sha256():
+        return None, f"profiles/{name} is stale: the search kernel's sources changed since it was taken"
+    return int(prof["hbm_bytes_per_launch"]), f"profiles/{name} (separate rocprofv3 --pmc runs of this command, same kernel sources)"
+
+
+class Workload:
+    """Base set, queries, graph and ground truth of one sift-like configuration, resident in HBM."""
+
+    def __init__(self, P, torch, n, nq, K, k, d, knn_alone=False):
+        import workloads
+        self.P, self.torch, self.n, self.nq, self.K, self.k, self.d = P, torch, n, nq, K, k, d
+        dev = torch.device("cuda:0")
+        t0 = time.time()
+        self.base_h, self.queries_h = workloads.sift_like(N=n, nq=nq)
+        log(f"generated {self.base_h.shape} base, {self.queries_h.shape} queries in {time.time() - t0:.1f}s")
+        self.base = torch.from_numpy(self.base_h).to(dev)
+        self.queries = torch.from_numpy(self.queries_h).to(dev)
+        torch.cuda.synchronize()
+        build = {}
+        if knn_alone:   # the k-NN step on its own (wall clock of the call and device time of its kernels)
+            t0 = time.time()
+            ids_knn, _, kst = P.ann_knn(self.base, K, want_stats=True)
+            torch.cuda.synchronize()
+            knn_s = time.time() - t0
+            del ids_knn
+            flop = 2.0 * n * n * d
+            build.update({"knn_seconds": round(knn_s, 3), "knn_device_ms": round(kst["knn_ms"], 2), "knn_flop": flop,
+                          "knn_mfma_tops": round(flop / knn_s / 1e12, 2), "knn_mfma_dtype": "int8",
+                          "knn_mfma_frac_of_int8_peak": round(flop / knn_s / 1e12 / MFMA_I8_PEAK_TOPS, 4),
+                          "knn_plain_scan_rows": kst["knn_plain_scan_rows"]})
+        t0 = time.time()
+        self.graph, st = P.ann_build_graph_ex(self.base, K, want_stats=True)
+        torch.cuda.synchronize()
+        build["seconds"] = round(time.time() - t0, 3)
+        # the diversification steps: device time, rows gathered (own row + list entries, gather_row_bytes each:
+        # the centred int8 copy for these integer-valued rows) and the HBM fraction of those gathered bytes
+        rb = st["gather_row_bytes"]
+        for name, rows in (("stage1", st["stage1_rows"]), ("stage2", st["stage2_rows"])):
+            ms = st[name + "_ms"]
+            build[name] = {"ms": round(ms, 3), "rows_gathered": rows, "row_bytes": rb, "gathered_bytes": rows * rb,
+                           "GBps": round(rows * rb / ms / 1e6, 1), "frac_of_hbm_peak": round(rows * rb / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        build["reverse_edges"] = {"ms": round(st["reverse_ms"], 3), "edges": st["reverse_edges"]}
+        build["knn_in_build_device_ms"] = round(st["knn_ms"], 2)
+        self.adj, self.lam = P.ann_graph_export(self.graph)
+        build["avg_degree"] = round((self.adj >= 0).sum(dim=1).float().mean().item(), 2)
+        log(f"build {build['seconds']:.2f}s: k-NN {st['knn_ms']:.1f} ms, stage 1 {st['stage1_ms']:.2f} ms, reverse edges "
+            f"{st['reverse_ms']:.2f} ms, stage 2 {st['stage2_ms']:.2f} ms")
+        self.build = build
+        # ground truth (GPU brute force, checked on a subset against the oracle's brute force)
+        t0 = time.time()
+        gt, _ = P.ann_bruteforce(self.base, self.queries, k)
+        torch.cuda.synchronize()
+        log(f"ground truth in {time.time() - t0:.2f}s")
+        self.gt_h = gt.cpu().numpy()
+
+    def recall_of(self, ids_t):
+        found = ids_t.cpu().numpy()
+        hit = (found[:, :, None] == self.gt_h[:, None, :]).any(axis=2).sum()
+        return float(hit) / self.gt_h.size
+
+    def point(self, L, lambda_visit, reps):
+        """One list length: recall, per-query counters, rough launch time."""
+        P, torch = self.P, self.torch
+        ids, s, st = P.ann_search_ex(self.graph, self.base, self.queries, self.k, L, mode=1, lambda_visit=lambda_visit,
+                                     want_stats=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            P.ann_search_ex(self.graph, self.base, self.queries, self.k, L, mode=1, lambda_visit=lambda_visit, out=(ids, s))
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        return {"L": L, "recall@10": round(self.recall_of(ids), 4), "qps": round(self.nq / ms * 1e3), "ms": round(ms, 4),
+                "hops": round(st.hops.double().mean().item(), 1), "dist_evals": round(st.dist_evals.double().mean().item(), 1)}, \
+            (st.hops.double().mean().item(), st.dist_evals.double().mean().item())
+
+    def smallest_L(self, Ls, lambda_visit, target, bisect=True):
+        """Sweeps the grid upward, then bisects the gap below the first list length that meets the target.
+        Returns (sweep rows, (L, recall, hops, evals), refined row or None)."""
+        sweep, chosen, exact = [], None, {}
+        for L in Ls:
+            row, he = self.point(L, lambda_visit, 3)
+            sweep.append(row)
+            exact[L] = he
+            log(str(row))
+            if chosen is None and row["recall@10"] >= target:
+                chosen = L
+        if chosen is None:
+            chosen = Ls[-1]
+            log(f"target recall {target} not reached; timing L={chosen}")
+        refined = None
+        rows = {r["L"]: r for r in sweep}
+        if bisect and len(Ls) > 1 and chosen != Ls[0] and rows[chosen]["recall@10"] >= target:
+            a_, b_ = Ls[Ls.index(chosen) - 1], chosen          # a_ fails, b_ passes
+            refined = {x: rows[b_][x] for x in ("L", "recall@10", "qps", "ms")}
+            while b_ - a_ > 1:
+                m_ = (a_ + b_) // 2
+                row, he = self.point(m_, lambda_visit, 5)
+                if row["recall@10"] >= target:
+                    b_, chosen, refined = m_, m_, {x: row[x] for x in ("L", "recall@10", "qps", "ms")}
+                    rows[m_], exact[m_] = row, he
+                else:
+                    a_ = m_
+            log(f"smallest L meeting the target: {refined}")
+        return sweep, (chosen, rows[chosen]["recall@10"], exact[chosen][0], exact[chosen][1]), refined
+
+    def bytes_per_launch(self, hops, evals):
+        """Algorithmic bytes of one launch: seeds and neighbours gathered (d*4 B each), one packed adjacency row
+        per hop (K*4 B), the query (d*4 B) and the result (k*8 B), per query."""
+        return (evals * self.d * 4 + hops * self.K * 4 + self.d * 4 + self.k * 8) * self.nq
+
+    def timed(self, L, lambda_visit, steps, warmup):
+        """The timed region: `steps` launches over the whole batch, a HIP event after each (the calls go to torch's
+        current stream, which is the stream the events are recorded on)."""
+        P, torch = self.P, self.torch
+        ids = torch.empty((self.nq, self.k), dtype=torch.int32, device=self.base.device)
+        s = torch.empty((self.nq, self.k), dtype=torch.float32, device=self.base.device)
+        out = (ids, s)
+        for _ in range(warmup):
+            P.ann_search_ex(self.graph, self.base, self.queries, self.k, L, mode=1, lambda_visit=lambda_visit, out=out)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for i in range(steps):
+            P.ann_search_ex(self.graph, self.base, self.queries, self.k, L, mode=1, lambda_visit=lambda_visit, out=out)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kern_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+        return wall, kern_ms, ids
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,17 +203,23 @@ def main():
     ap.add_argument("--L", type=int, default=0, help="fix L instead of picking it from the sweep")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-small", action="store_true")
+    ap.add_argument("--large-base-n", type=int, default=4_200_000,
+                    help="rows of the second, larger base set (2.15 GB: 8 x the 256 MB last-level cache) on which the "
+                         "same kernel is timed once more; 0 skips it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a dispatch of known size that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--print-kernel-hash", action="store_true", help="print the hash a counter summary must carry and exit")
     args = ap.parse_args()
+    if args.print_kernel_hash:
+        print(kernel_source_sha256())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every figure is one MI355X's throughput); "
               "--gpus above 1 is not supported.", file=sys.stderr)
         sys.exit(2)
 
     import torch
-    import workloads
     import paper_2204_00824_amd as P
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -67,43 +228,12 @@ def main():
     K, k, d = 32, 10, 128
     lambda_visit = 5            # large-batch prefix (paper Sec. 5.4)
 
-    t0 = time.time()
-    base_h, queries_h = workloads.sift_like(N=args.n, nq=args.nq)
-    log(f"generated {base_h.shape} base, {queries_h.shape} queries in {time.time() - t0:.1f}s")
-    base = torch.from_numpy(base_h).to(dev)
-    queries = torch.from_numpy(queries_h).to(dev)
-    torch.cuda.synchronize()
-
-    # ---- build (once, outside the timed search region; reported separately)
-    t0 = time.time()
-    knn_t0 = time.time()
-    ids_knn, _ = P.ann_knn(base, K)
-    torch.cuda.synchronize()
-    knn_s = time.time() - knn_t0
-    del ids_knn
-    t1 = time.time()
-    graph = P.ann_build_graph_ex(base, K)
-    torch.cuda.synchronize()
-    build_s = time.time() - t1
-    log(f"k-NN alone {knn_s:.2f}s; full build (k-NN + diversification) {build_s:.2f}s")
-    adj, lam = P.ann_graph_export(graph)
-    deg = (adj >= 0).sum(dim=1).float().mean().item()
-    build = {
-        "seconds": round(build_s, 3),
-        "knn_seconds": round(knn_s, 3),
-        "knn_flop": 2.0 * args.n * args.n * d,
-        "knn_mfma_tops": round(2.0 * args.n * args.n * d / knn_s / 1e12, 2),
-        "knn_mfma_dtype": "int8",
-        "knn_mfma_frac_of_int8_peak": round(2.0 * args.n * args.n * d / knn_s / 1e12 / MFMA_I8_PEAK_TOPS, 4),
-        "avg_degree": round(deg, 2),
-    }
-
-    # ---- ground truth (GPU brute force, checked on a subset against the oracle's brute force)
-    t0 = time.time()
-    gt, _ = P.ann_bruteforce(base, queries, k)
-    torch.cuda.synchronize()
-    log(f"ground truth in {time.time() - t0:.2f}s")
-    gt_h = gt.cpu().numpy()
+    # ---- build (once, outside the timed search region; reported separately) and ground truth
+    W = Workload(P, torch, args.n, args.nq, K, k, d, knn_alone=True)
+    base, queries, graph, adj, lam, gt_h = W.base, W.queries, W.graph, W.adj, W.lam, W.gt_h
+    base_h, queries_h = W.base_h, W.queries_h
+    build = W.build
+    recall_of = W.recall_of
 
     # local intrinsic dimensionality of the base set (MLE over the 20 nearest neighbours of 2,000 rows)
     _, nn_s = P.ann_bruteforce(base, base[:2000].contiguous(), 21)
@@ -111,73 +241,13 @@ def main():
     lid = float((-1.0 / torch.log(r[:, :-1] / r[:, -1:]).mean(dim=1)).mean().item())
     build["lid_mle20"] = round(lid, 2)
 
-    def recall_of(ids_t):
-        found = ids_t.cpu().numpy()
-        hit = (found[:, :, None] == gt_h[:, None, :]).any(axis=2).sum()
-        return float(hit) / gt_h.size
-
-    # ---- L sweep: recall and per-query counters
-    sweep = []
-    chosen = None
+    # ---- L sweep: recall and per-query counters.  L is a free parameter of the search (the paper's curves sweep
+    # it): the metric is quoted at the smallest L that meets the target, found by bisection between the bracketing
+    # values of the grid
     Ls = [args.L] if args.L else [16, 24, 32, 48, 64, 96, 128, 192, 256]
-    for L in Ls:
-        ids, s, st = P.ann_search_ex(graph, base, queries, k, L, mode=1, lambda_visit=lambda_visit, want_stats=True)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        out = (ids, s)
-        e0.record()
-        for _ in range(3):
-            P.ann_search_ex(graph, base, queries, k, L, mode=1, lambda_visit=lambda_visit, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 3
-        rec = recall_of(ids)
-        hops = st.hops.double().mean().item()
-        evals = st.dist_evals.double().mean().item()
-        row = {"L": L, "recall@10": round(rec, 4), "qps": round(args.nq / ms * 1e3), "ms": round(ms, 4),
-               "hops": round(hops, 1), "dist_evals": round(evals, 1)}
-        sweep.append(row)
-        log(str(row))
-        if chosen is None and rec >= args.target_recall:
-            chosen = (L, rec, hops, evals)
-    if chosen is None:
-        L = Ls[-1]
-        chosen = (L, sweep[-1]["recall@10"], sweep[-1]["hops"], sweep[-1]["dist_evals"])
-        log(f"target recall {args.target_recall} not reached; timing L={L}")
-    # L is a free parameter of the search (the paper's curves sweep it): the metric is quoted at the smallest L
-    # that meets the target, found by bisection between the bracketing values of the grid above
-    refined = None
-    if not args.L:
-        for lo_, hi_ in zip(sweep, sweep[1:]):
-            if lo_["recall@10"] < args.target_recall <= hi_["recall@10"] and hi_["L"] == chosen[0]:
-                a_, b_ = lo_["L"], hi_["L"]          # a_ fails, b_ passes
-                refined = {"L": b_, "recall@10": hi_["recall@10"], "qps": hi_["qps"], "ms": hi_["ms"]}
-                while b_ - a_ > 1:
-                    m_ = (a_ + b_) // 2
-                    ids_m, s_m, st_m = P.ann_search_ex(graph, base, queries, k, m_, mode=1, lambda_visit=lambda_visit,
-                                                       want_stats=True)
-                    torch.cuda.synchronize()
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(5):
-                        P.ann_search_ex(graph, base, queries, k, m_, mode=1, lambda_visit=lambda_visit, out=(ids_m, s_m))
-                    e1.record()
-                    torch.cuda.synchronize()
-                    ms_m = e0.elapsed_time(e1) / 5
-                    rec_m = recall_of(ids_m)
-                    if rec_m >= args.target_recall:
-                        b_ = m_
-                        refined = {"L": m_, "recall@10": round(rec_m, 4), "qps": round(args.nq / ms_m * 1e3), "ms": round(ms_m, 4)}
-                        chosen = (m_, rec_m, st_m.hops.double().mean().item(), st_m.dist_evals.double().mean().item())
-                    else:
-                        a_ = m_
-                log(f"smallest L meeting the target: {refined}")
+    sweep, chosen, refined = W.smallest_L(Ls, lambda_visit, args.target_recall)
     L, rec, hops, evals = chosen
-
-    # algorithmic bytes of one launch: seeds and neighbours gathered (d*4 B each), one packed
-    # adjacency row per hop (K*4 B), the query (d*4 B) and the result (k*8 B), per query
-    bytes_per_query = evals * d * 4 + hops * K * 4 + d * 4 + k * 8
-    bytes_per_launch = bytes_per_query * args.nq
+    bytes_per_launch = W.bytes_per_launch(hops, evals)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)   # 1 GiB
@@ -188,34 +258,12 @@ def main():
         del src, dst
 
     # ---- timed region
-    ids = torch.empty((args.nq, k), dtype=torch.int32, device=dev)
-    s = torch.empty((args.nq, k), dtype=torch.float32, device=dev)
-    out = (ids, s)
-    for _ in range(args.warmup):
-        P.ann_search_ex(graph, base, queries, k, L, mode=1, lambda_visit=lambda_visit, out=out)
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    ev[0].record()
-    for i in range(args.steps):
-        P.ann_search_ex(graph, base, queries, k, L, mode=1, lambda_visit=lambda_visit, out=out)
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    wall, kern_ms, ids = W.timed(L, lambda_visit, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
-    kern_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
     kern_avg_ms = float(np.mean(kern_ms))
     qps = args.nq / (wall / args.steps)
     achieved = bytes_per_launch / (kern_avg_ms * 1e-3) / 1e9
-
-    traffic = None
-    # HBM-side bytes per launch as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in a separate
-    # run of this command (the summary under profiles/ gives the commands and the copy calibration)
-    tpath = os.path.join(ROOT, "profiles", "search_large_sift1m_pmc.txt")
-    if os.path.exists(tpath) and args.n == 1_000_000 and args.nq == 10_000:
-        prof = dict(line.split(":", 1) for line in open(tpath) if line.startswith(("hbm_bytes_per_launch:", "L:")))
-        if int(prof.get("L", -1)) == L:     # counted for this list length
-            traffic = int(prof["hbm_bytes_per_launch"])
+    traffic, traffic_source = profile_traffic("search_large_sift1m_pmc.txt", L, args.n, args.nq)
 
     result = {
         "metric": "QPS at recall@10>=0.95 (1Mx128, 10K-query batch)",
@@ -234,13 +282,39 @@ def main():
                                f"L={L}, lambda_visit={lambda_visit}, large batch (one wave64 per query)",
                    "recall@10": round(rec, 4), "L": L},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "search_kernel<float,8,4,1>", "kernel_ms": round(kern_avg_ms, 4),
-                     "algorithmic_bytes_per_launch": round(bytes_per_launch)},
+                     "algorithmic_bytes_per_launch": round(bytes_per_launch),
+                     "dist_evals_per_query": round(evals, 2), "hops_per_query": round(hops, 2),
+                     "base_bytes": args.n * d * 4},
         "sweep": sweep,
         "build": build,
     }
     result["roofline"]["kernel_ms_min_max"] = [round(min(kern_ms), 4), round(max(kern_ms), 4)]
+
+    # ---- the same kernel on a base set 8 x the 256 MB last-level cache, so that what is measured is HBM alone
+    # (FETCH_SIZE counts bytes that reach the L2 from the fabric: Infinity Cache and HBM together; at 512 MB a
+    # good part of the base stays in that cache).  The headline stays at N = 1e6.
+    if args.large_base_n and not args.L:
+        WL = Workload(P, torch, args.large_base_n, args.nq, K, k, d)
+        _, (L2, rec2, hops2, evals2), _ = WL.smallest_L([24, 32, 48, 64, 96, 128], lambda_visit, args.target_recall)
+        wall2, kern2, _ = WL.timed(L2, lambda_visit, max(5, args.steps // 2), args.warmup)
+        b2 = WL.bytes_per_launch(hops2, evals2)
+        k2ms = float(np.mean(kern2))
+        t2, t2src = profile_traffic("search_large_sift4m_pmc.txt", L2, args.large_base_n, args.nq)
+        result["roofline_large_base"] = {
+            "workload": f"sift-like N={args.large_base_n} d={d} fp32 ({args.large_base_n * d * 4 / 2**20:.0f} MiB of rows, "
+                        f"{args.large_base_n * d * 4 / 2**28:.1f} x the 256 MiB last-level cache), nq={args.nq}, L={L2}",
+            "L": L2, "recall@10": round(rec2, 4), "qps": round(args.nq / k2ms * 1e3), "bound": "hbm",
+            "achieved": round(b2 / k2ms / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(b2 / k2ms / 1e6 / HBM_PEAK_GBS, 4), "traffic": t2, "traffic_source": t2src,
+            "kernel": "search_kernel<float,8,4,1>", "kernel_ms": round(k2ms, 4), "launches_timed": len(kern2),
+            "algorithmic_bytes_per_launch": round(b2), "dist_evals_per_query": round(evals2, 2),
+            "hops_per_query": round(hops2, 2), "base_bytes": args.large_base_n * d * 4,
+            "build_seconds": WL.build["seconds"], "build_stage1": WL.build["stage1"], "build_stage2": WL.build["stage2"]}
+        log(f"large base: {result['roofline_large_base']}")
+        del WL
+        torch.cuda.empty_cache()
 
     # queries/s at recall exactly `target`, by log-linear interpolation between the bracketing L values
     for lo_, hi_ in zip(sweep, sweep[1:]):
@@ -341,14 +415,15 @@ def main():
             o = (torch.empty((bs, k), dtype=torch.int32, device=dev), torch.empty((bs, k), dtype=torch.float32, device=dev))
             qs = [queries[i * bs:(i + 1) * bs].contiguous() for i in range(n_calls)]
             rows = []
+            ws = torch.empty(P.ann_search_multi_workspace_bytes(bs, 128), dtype=torch.uint8, device=dev)
             for t0 in (8, 16, 32, 64, 128):
                 for i in range(3):
-                    P.ann_search_multi(graph, base, qs[i % n_calls], k, t0, max_hops=6, out=o, qi_offset=i * bs)
+                    P.ann_search_multi(graph, base, qs[i % n_calls], k, t0, max_hops=6, out=o, qi_offset=i * bs, workspace=ws)
                 torch.cuda.synchronize()
                 lat, hit = [], 0
                 for i in range(n_calls):
                     t0_ = time.perf_counter()
-                    P.ann_search_multi(graph, base, qs[i], k, t0, max_hops=6, out=o, qi_offset=i * bs)
+                    P.ann_search_multi(graph, base, qs[i], k, t0, max_hops=6, out=o, qi_offset=i * bs, workspace=ws)
                     torch.cuda.synchronize()
                     lat.append(time.perf_counter() - t0_)
                     found = o[0].cpu().numpy()
@@ -420,10 +495,21 @@ def main():
         ref = None
         while t_cpu < 10.0 and reps < 50:
             t0 = time.perf_counter()
-            ref = oracle.search(adj_h, lam_h, base_h, queries_h[:sample], k, L, lambda_visit, threads=threads)
+            ref = oracle.search(adj_h, lam_h, base_h, queries_h[:sample], k, L, lambda_visit, threads=threads,
+                                want_stats=True)
             t_cpu += time.perf_counter() - t0
             reps += 1
         same = bool(np.array_equal(ref[0], ids.cpu().numpy()[:sample]))
+        # The method's own work: the oracle's visited set is an exact bitmap, so its count of distance evaluations
+        # holds no row scored twice (the kernel's 1,280-slot hashed set forgets some and scores them again).  The
+        # same kernel time priced with those counts:
+        o_hops, o_evals = float(ref[2][:, 0].mean()), float(ref[2][:, 1].mean())
+        b_exact = (o_evals * d * 4 + o_hops * K * 4 + d * 4 + k * 8) * args.nq
+        result["roofline"]["exact_visited_set"] = {
+            "dist_evals_per_query": round(o_evals, 2), "hops_per_query": round(o_hops, 2), "queries": sample,
+            "algorithmic_bytes_per_launch": round(b_exact), "achieved": round(b_exact / kern_avg_ms / 1e6, 1),
+            "frac": round(b_exact / kern_avg_ms / 1e6 / HBM_PEAK_GBS, 4),
+            "rows_scored_again_by_the_kernel": round(evals / o_evals - 1.0, 4)}
         t0 = time.perf_counter()
         oracle.search(adj_h, lam_h, base_h, queries_h[:2000], k, L, lambda_visit, threads=1)
         one_thread = 2000 / (time.perf_counter() - t0)

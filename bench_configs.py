@@ -2,7 +2,7 @@
 """Measurements on the other workload shapes (one MI355X): gist-like 1M x 960,
 deep-like 10M x 96, glove-like 1M x 100 under the cosine metric, and the 100M x 128 uint8 set.  bench.py stays the headline
 (sift-like 1M x 128); this script prints one JSON line per run with the same
-kind of fields.  Long builds print progress (TSDG_PROGRESS=1 is set here).
+kind of fields.  Long builds print progress (the build calls get a progress callback).
 
 The 100M set cannot get an exact k-NN graph in one session (2.6e18 flop), so it
 is built as 25 independent blocks of 4M rows, each an exact TSDG of its block,
@@ -22,11 +22,15 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-os.environ.setdefault("TSDG_PROGRESS", "1")
 
 
 def log(msg):
     print(f"[bench_configs] {msg}", file=sys.stderr, flush=True)
+
+
+def progress(step, done, total):
+    """Progress callback of the long builds: one line per finished chunk / iteration."""
+    print(f"[tsdg] {step}: {done} / {total}", file=sys.stderr, flush=True)
 
 
 def recall(found, gt):
@@ -58,7 +62,7 @@ def run_single_graph(args, name, base_h, queries_h, ks, Ls, metric="l2"):
         P.ann_normalize_rows(base, out=base)
         P.ann_normalize_rows(queries, out=queries)
     t0 = time.time()
-    graph = P.ann_build_graph_ex(base, K, metric=metric)
+    graph = P.ann_build_graph_ex(base, K, metric=metric, progress=progress)
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"{name}: build {build_s:.1f}s")
@@ -117,7 +121,7 @@ def run_sharded_u8(args):
     for lo, x in workloads.scale_u8_torch(N=N, chunk=block):
         torch.cuda.synchronize()
         t1 = time.time()
-        g = P.ann_build_graph_ex(x, K)
+        g = P.ann_build_graph_ex(x, K, progress=progress)
         torch.cuda.synchronize()
         t_build += time.time() - t1
         shards.append((lo, x, g))
@@ -201,7 +205,7 @@ def run_whole_u8(args):
     del ids, ex
     torch.cuda.empty_cache()                                  # the library allocates outside torch's cache
     t0 = time.time()
-    graph = P.ann_build_graph_ex(base, K, knn_mode=1, descent_iters=args.iters)
+    graph = P.ann_build_graph_ex(base, K, knn_mode=1, descent_iters=args.iters, progress=progress)
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"whole build (propagation + diversification): {build_s:.1f}s; list recall on 2000 rows {list_recall:.4f}")
@@ -223,13 +227,14 @@ def run_whole_u8(args):
     # small batches (1 and 16 queries per call): Alg. 1's multi-search and the best-first search
     for bs in (1, 16):
         rows = []
+        ws = torch.empty(P.ann_search_multi_workspace_bytes(bs, 128), dtype=torch.uint8, device="cuda")
         for t0_ in (32, 64, 128):
             lat, hit = [], 0
             for c in range(50):
                 q = queries[c * bs:(c + 1) * bs].contiguous()
                 torch.cuda.synchronize()
                 t1 = time.perf_counter()
-                ids, _ = P.ann_search_multi(graph, base, q, k, t0_, max_hops=8, qi_offset=c * bs)
+                ids, _ = P.ann_search_multi(graph, base, q, k, t0_, max_hops=8, qi_offset=c * bs, workspace=ws)
                 torch.cuda.synchronize()
                 lat.append(time.perf_counter() - t1)
                 hit += recall(ids.cpu().numpy(), gt_h[c * bs:(c + 1) * bs])

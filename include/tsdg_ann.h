@@ -26,10 +26,9 @@
  *     default stream).  ann_search* return after enqueueing; ann_build_graph*,
  *     ann_knn, ann_bruteforce, import and export synchronise the stream before
  *     returning because they size or free temporary device memory (hipFree also
- *     waits for work on the caller's other streams).  ann_search_ex and
- *     ann_search_alg2 allocate nothing; ann_search_multi allocates only when the
- *     graph's scratch buffer has to grow (it starts large enough for 16 queries x
- *     128 searches).
+ *     waits for work on the caller's other streams).  The search calls
+ *     (ann_search_ex, ann_search_alg2, ann_search_multi with the caller's
+ *     workspace, ann_search_multi_static) allocate nothing and only read the graph.
  *   - Errors: a status code is returned, never an exception or abort; outputs
  *     are untouched when argument validation fails; ann_last_error() gives a
  *     thread-local message for the last failing call.
@@ -70,6 +69,30 @@ typedef enum { ANN_F32 = 0, ANN_U8 = 1, ANN_F16 = 2 } ann_dtype;
  *               (alpha on s), and the distances returned are m = s/2. */
 typedef enum { ANN_L2 = 0, ANN_COSINE = 1 } ann_metric;
 
+/* Progress of a long build: called on the calling thread, between launches, after the build's
+ * stream has been synchronised (so a build that reports progress is slower than one that does
+ * not).  step names what was finished ("knn-sweep": done/total = base columns swept for the current
+ * block of rows; "knn-rows": rows finished; "descent": iterations done / the limit), user is
+ * passed through.  The callback must not call back into the library on the same graph. */
+typedef void (*ann_progress_fn)(void* user, const char* step, int64_t done, int64_t total);
+
+/* Optional report of a build, filled on the host when ann_build_params.stats points at one:
+ * device time of the four steps (events on the build's stream) and the work they did. */
+typedef struct {
+    float knn_ms;            /* k-NN lists (exact contraction + re-scoring, or the propagation) */
+    float stage1_ms;         /* Eq. 2 pruning */
+    float reverse_ms;        /* reverse edges: count scan, scatter, per-node merge and cut */
+    float stage2_ms;         /* lambda by Eq. 1, order, cuts, packing */
+    uint64_t stage1_rows;    /* base rows stage 1 reads: every node's own row and its K list entries */
+    uint64_t stage2_rows;    /* likewise for stage 2: own row + list length after the reverse edges and the cut */
+    uint64_t reverse_edges;  /* edges that survive stage 1 (each is scattered once as a reverse edge) */
+    int gather_row_bytes;    /* bytes of one gathered row in stages 1 and 2 (d for the centred int8 copy of
+                                integer-valued rows, else d * element size) */
+    int knn_contraction;     /* 0: int8 matrix cores (exact), 1: one binary16 part, 2: bf16 hi + lo parts,
+                                3: integer rows wider than 128 as one bf16 part (exact), 4: propagation */
+    uint32_t knn_plain_scan_rows; /* rows whose list the re-scoring pass could not certify and a plain scan redid */
+} ann_build_stats;
+
 /* Build parameters.  Defaults (ann_build_params_default): fp32 rows,
  * alpha = 1.2 (Sec. 3.2 recommends values above 1.1), lambda0 = 9 (so that the
  * small-batch prefix of Sec. 5.4, lambda below 10, means every stored edge),
@@ -91,6 +114,16 @@ typedef struct {
     int descent_iters;
     float descent_delta;
     uint64_t descent_seed;
+    /* Form of the exact contraction for real-valued rows: 0 = one scaled binary16 part per row, falling back
+     * to two bf16 parts (hi + lo) when too many rows fail the re-scoring pass's acceptance test; 1 = hi + lo
+     * from the start.  Both give the exact lists; integer-valued rows ignore it. */
+    int knn_filter;
+    /* Query rows per sweep of the exact contraction; 0 = 2^21 (bounds the candidate buffers to a few GB).
+     * A multiple of 256; smaller values only cost time (a hook for tests of the multi-sweep path). */
+    int64_t knn_row_block;
+    ann_progress_fn progress; /* NULL = no reports and no extra synchronisation */
+    void* progress_user;
+    ann_build_stats* stats;   /* host pointer or NULL */
 } ann_build_params;
 
 /* Search parameters.  Defaults (ann_search_params_default): fp32 rows, mode 0
@@ -150,6 +183,10 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K,
  * row i = the K nearest other rows by (distance, id). */
 ann_status ann_knn(const void* base, int64_t N, int d, int K, ann_dtype dtype, void* stream,
                    int32_t* knn_ids, float* knn_dists);
+/* The same with build parameters: of params it reads dtype, stream, knn_filter, knn_row_block,
+ * progress / progress_user and stats (knn_ms, knn_contraction, knn_plain_scan_rows). */
+ann_status ann_knn_ex(const void* base, int64_t N, int d, int K, const ann_build_params* params,
+                      int32_t* knn_ids, float* knn_dists);
 
 /* Exact top-k of each query against the whole base set (the definition the
  * search approximates; used for ground truth, Eq. 3).  queries [nq,d] fp32.
@@ -174,19 +211,24 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
  * distance evaluations for latency (a search converges in a handful of hops) and lets a batch
  * of one use many compute units; its result is NOT the best-first result of ann_search.
  * 1 <= k <= 32, 1 <= t0 <= 1024, nq <= 65535.  Of params it reads dtype, lambda_visit
- * (0 = 10), seed, max_hops (the hop limit T; 0 = 16), qi_offset and stream.  The graph keeps a
- * grow-only scratch buffer for the t0 rankings (hence the non-const graph): calls on one
- * graph must not overlap, and the first call (or a larger nq*t0) allocates. */
-ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k,
-                            int t0, const ann_search_params* params, int32_t* out_ids,
-                            float* out_dists, ann_query_stats* stats);
+ * (0 = 10), seed, max_hops (the hop limit T; 0 = 16), qi_offset and stream.
+ * The t0 rankings of every query pass through `workspace`, device memory of the caller of at
+ * least ann_search_multi_workspace_bytes(nq, t0) = nq * t0 * 264 bytes, 8-byte aligned, which
+ * the call may overwrite and which must stay untouched until the work enqueued on the stream has
+ * run; calls with different workspaces may overlap.  workspace = NULL: the call allocates one,
+ * waits for the stream and frees it (convenient, not for latency-critical callers). */
+size_t ann_search_multi_workspace_bytes(int nq, int t0);
+ann_status ann_search_multi(const ann_graph* graph, const void* base, const void* queries, int nq, int k,
+                            int t0, const ann_search_params* params, void* workspace,
+                            size_t workspace_bytes, int32_t* out_ids, float* out_dists,
+                            ann_query_stats* stats);
 
-/* ann_search_multi for callers that cannot allocate device memory: code under HIP graph capture,
- * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
- * same result as ann_search_multi, but the t0 rankings go to a scratch array that is part of the
- * library's device image (540,672 bytes on every GPU the library runs on, held until the process
- * ends) instead of the graph's buffer, so the graph is const and the call never calls hipMalloc,
- * hipFree or any allocating routine.  Limit: nq * t0 <= 2048 searches per call (ANN_EUNSUPPORTED
+/* ann_search_multi for callers that can neither allocate device memory nor bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels and the same result as ann_search_multi, but the t0 rankings go to a scratch array that
+ * is part of the library's device image (540,672 bytes on every GPU the library runs on, held until
+ * the process ends) instead of a workspace, and the call never calls hipMalloc, hipFree or any
+ * allocating routine.  Limit: nq * t0 <= 2048 searches per call (ANN_EUNSUPPORTED
  * beyond, outputs untouched).  The first call on a device looks the array's address up once.
  * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
  * threads) race and must be serialised by the caller; consecutive calls on one stream are safe.
@@ -254,26 +296,6 @@ ann_status ann_knn_descent(const void* base, int64_t N, int d, int K, ann_dtype 
  * buffer).  The norm is fl32(sqrt(sum of squares in fp64)), each quotient is formed in fp64 and
  * rounded once; a zero row stays zero.  Asynchronous on `stream`. */
 ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, void* stream);
-
-/* Measurement probe, not a step of the method: gathers n rows of row_bytes bytes (a multiple of 16,
- * at most 8192) from base[N rows] (device, 16-byte aligned) at ids[n] (device; an id >= N reads row
- * N-1) with the access shape of search step S5 (Alg. 2's distance step) and writes one xor-folded
- * word per row to out[n] (device).  Asynchronous on `stream`.  Timing it gives the random-row
- * bandwidth this GPU reaches with no search logic around the loads. */
-ann_status ann_probe_gather(const void* base, int64_t N, int row_bytes, const uint32_t* ids, int64_t n,
-                            uint32_t* out, void* stream);
-
-/* Measurement probe, not a step of the method: `blocks` workgroups of 4 wavefronts each issue
- * 4 * iters matrix-core instructions on constant register fragments, with no memory access in
- * the loop (kind 0: v_mfma_i32_32x32x32_i8, 65,536 operations each; kind 1:
- * v_mfma_f32_32x32x16_bf16, 32,768 each), and write one float per wavefront to out[4 * blocks]
- * (device): 4 * iters * 32 (kind 0) or 4 * iters * 16 (kind 1).  Kinds 2 and 3 are kinds 0 and
- * 1 with pseudo-random fragments instead of ones (the same instructions; more wires toggle, so
- * more power is drawn and the sustained rate falls; out then holds data-dependent sums).  Timing
- * it gives the rate the matrix cores sustain on this GPU with nothing else in the way, against
- * which the k-NN contraction of the build (the exact k-NN graph under Sec. 3's diversification)
- * is read.  1 <= blocks <= 2^20, 1 <= iters <= 100000.  Asynchronous on `stream`. */
-ann_status ann_probe_mfma(int kind, int blocks, int iters, float* out, void* stream);
 
 /* Message of the last failing call on this thread ("" if none). */
 const char* ann_last_error(void);

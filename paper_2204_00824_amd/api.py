@@ -22,10 +22,24 @@ class AnnError(RuntimeError):
         self.status = status
 
 
+_PROGRESS_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_char_p, C.c_int64, C.c_int64)
+
+
+class _BuildStats(C.Structure):
+    _fields_ = [("knn_ms", C.c_float), ("stage1_ms", C.c_float), ("reverse_ms", C.c_float), ("stage2_ms", C.c_float),
+                ("stage1_rows", C.c_uint64), ("stage2_rows", C.c_uint64), ("reverse_edges", C.c_uint64),
+                ("gather_row_bytes", C.c_int), ("knn_contraction", C.c_int), ("knn_plain_scan_rows", C.c_uint32)]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
 class _BuildParams(C.Structure):
     _fields_ = [("dtype", C.c_int), ("alpha", C.c_float), ("lambda0", C.c_int), ("rev_cap", C.c_int),
                 ("stream", C.c_void_p), ("metric", C.c_int), ("knn_mode", C.c_int), ("descent_S", C.c_int),
-                ("descent_iters", C.c_int), ("descent_delta", C.c_float), ("descent_seed", C.c_uint64)]
+                ("descent_iters", C.c_int), ("descent_delta", C.c_float), ("descent_seed", C.c_uint64),
+                ("knn_filter", C.c_int), ("knn_row_block", C.c_int64), ("progress", _PROGRESS_FN),
+                ("progress_user", C.c_void_p), ("stats", C.POINTER(_BuildStats))]
 
 
 class _SearchParams(C.Structure):
@@ -59,11 +73,14 @@ def load_library():
     L.ann_build_graph.argtypes = [vp, i64, i32, i32, C.POINTER(vp)]
     L.ann_build_graph_ex.argtypes = [vp, i64, i32, i32, C.POINTER(_BuildParams), C.POINTER(vp)]
     L.ann_knn.argtypes = [vp, i64, i32, i32, i32, vp, vp, vp]
+    L.ann_knn_ex.argtypes = [vp, i64, i32, i32, C.POINTER(_BuildParams), vp, vp]
     L.ann_bruteforce.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
     L.ann_search.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
     L.ann_search_ex.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
-    L.ann_search_multi.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
-    L.ann_search_multi_static.argtypes = L.ann_search_multi.argtypes
+    L.ann_search_multi.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, C.c_size_t, vp, vp, vp]
+    L.ann_search_multi_static.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
+    L.ann_search_multi_workspace_bytes.argtypes = [i32, i32]
+    L.ann_search_multi_workspace_bytes.restype = C.c_size_t
     L.ann_search_alg2.argtypes = [vp, vp, vp, i32, i32, C.c_float, i32, i32, C.POINTER(_SearchParams), vp, vp, vp]
     L.ann_graph_export.argtypes = [vp, vp, vp, vp]
     L.ann_graph_import.argtypes = [vp, vp, i64, i32, i32, vp, C.POINTER(vp)]
@@ -77,7 +94,7 @@ def load_library():
     L.ann_knn_descent.argtypes = [vp, i64, i32, i32, i32, i32, i32, C.c_float, u64, vp, vp, vp, vp,
                                   C.POINTER(i32), C.POINTER(i64)]
     L.ann_graph_free.restype = None
-    for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_bruteforce", "ann_search",
+    for name in ("ann_build_graph", "ann_build_graph_ex", "ann_knn", "ann_knn_ex", "ann_bruteforce", "ann_search",
                  "ann_search_ex", "ann_search_multi", "ann_search_multi_static", "ann_search_alg2", "ann_graph_export", "ann_graph_import", "ann_graph_info", "ann_probe_gather", "ann_probe_mfma", "ann_normalize_rows", "ann_knn_descent", "ann_max_row_norm", "ann_ip_augment_rows"):
         getattr(L, name).restype = C.c_int
     del u64
@@ -145,29 +162,61 @@ def ann_build_graph(base: torch.Tensor, K: int) -> Graph:
     return Graph(out.value)
 
 
-def ann_build_graph_ex(base: torch.Tensor, K: int, alpha: float = 1.2, lambda0: int = 9, rev_cap: int = 0,
-                       stream=None, metric="l2", knn_mode: int = 0, descent_S: int = 0, descent_iters: int = 0,
-                       descent_delta: float = 0.0, descent_seed: int = 0) -> Graph:
-    L = load_library()
-    p, dt = _base_ptr(base)
+def _build_params(L, dt, stream, *, alpha=1.2, lambda0=9, rev_cap=0, metric="l2", knn_mode=0, descent_S=0,
+                  descent_iters=0, descent_delta=0.0, descent_seed=0, knn_filter=0, knn_row_block=0, progress=None,
+                  want_stats=False):
+    """Fills an ann_build_params; returns it with the objects that must outlive the call."""
     prm = _BuildParams()
     L.ann_build_params_default(C.byref(prm))
     prm.dtype, prm.alpha, prm.lambda0, prm.rev_cap, prm.stream = dt, alpha, lambda0, rev_cap, _stream_ptr(stream)
     prm.metric = _METRICS[metric]
     prm.knn_mode, prm.descent_S, prm.descent_iters = knn_mode, descent_S, descent_iters
     prm.descent_delta, prm.descent_seed = descent_delta, descent_seed
+    prm.knn_filter, prm.knn_row_block = knn_filter, knn_row_block
+    keep = []
+    if progress is not None:
+        cb = _PROGRESS_FN(lambda user, step, done, total: progress(step.decode(), done, total))
+        prm.progress = cb
+        keep.append(cb)
+    stats = None
+    if want_stats:
+        stats = _BuildStats()
+        prm.stats = C.pointer(stats)
+    return prm, stats, keep
+
+
+def ann_build_graph_ex(base: torch.Tensor, K: int, alpha: float = 1.2, lambda0: int = 9, rev_cap: int = 0,
+                       stream=None, metric="l2", knn_mode: int = 0, descent_S: int = 0, descent_iters: int = 0,
+                       descent_delta: float = 0.0, descent_seed: int = 0, knn_filter: int = 0, knn_row_block: int = 0,
+                       progress=None, want_stats: bool = False):
+    """Returns the graph, or (graph, stats dict) with want_stats.  progress(step, done, total) is called
+    between launches of a long build."""
+    L = load_library()
+    p, dt = _base_ptr(base)
+    prm, stats, keep = _build_params(L, dt, stream, alpha=alpha, lambda0=lambda0, rev_cap=rev_cap, metric=metric,
+                                     knn_mode=knn_mode, descent_S=descent_S, descent_iters=descent_iters,
+                                     descent_delta=descent_delta, descent_seed=descent_seed, knn_filter=knn_filter,
+                                     knn_row_block=knn_row_block, progress=progress, want_stats=want_stats)
     out = C.c_void_p()
     _check(L.ann_build_graph_ex(p, base.shape[0], base.shape[1], K, C.byref(prm), C.byref(out)))
-    return Graph(out.value)
+    del keep
+    g = Graph(out.value)
+    return (g, stats.as_dict()) if want_stats else g
 
 
-def ann_knn(base: torch.Tensor, K: int, stream=None):
+def ann_knn(base: torch.Tensor, K: int, stream=None, knn_filter: int = 0, knn_row_block: int = 0, progress=None,
+            want_stats: bool = False):
+    """Exact K nearest neighbours of every row: (ids, dists) or (ids, dists, stats dict)."""
+    L = load_library()
     p, dt = _base_ptr(base)
     N, d = base.shape
     ids = torch.empty((N, K), dtype=torch.int32, device=base.device)
     s = torch.empty((N, K), dtype=torch.float32, device=base.device)
-    _check(load_library().ann_knn(p, N, d, K, dt, _stream_ptr(stream), ids.data_ptr(), s.data_ptr()))
-    return ids, s
+    prm, stats, keep = _build_params(L, dt, stream, knn_filter=knn_filter, knn_row_block=knn_row_block,
+                                     progress=progress, want_stats=want_stats)
+    _check(L.ann_knn_ex(p, N, d, K, C.byref(prm), ids.data_ptr(), s.data_ptr()))
+    del keep
+    return (ids, s, stats.as_dict()) if want_stats else (ids, s)
 
 
 def ann_knn_descent(base: torch.Tensor, K: int, S: int = 8, max_iters: int = 12, delta: float = 0.001, seed: int = 0,
@@ -239,10 +288,16 @@ def ann_search_ex(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: in
     return ids, s
 
 
+def ann_search_multi_workspace_bytes(nq: int, t0: int) -> int:
+    return int(load_library().ann_search_multi_workspace_bytes(nq, t0))
+
+
 def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, t0: int, *,
                      lambda_visit: int = 0, seed: int = 0, max_hops: int = 0, qi_offset: int = 0, stream=None,
-                     want_stats: bool = False, out=None, metric="l2", _entry="ann_search_multi"):
-    """Small-batch multi-search (Alg. 1).  Returns (ids, dists) or (ids, dists, QueryStats)."""
+                     want_stats: bool = False, out=None, metric="l2", workspace: torch.Tensor = None, _static=False):
+    """Small-batch multi-search (Alg. 1).  Returns (ids, dists) or (ids, dists, QueryStats).
+    `workspace`: a uint8 device tensor of at least ann_search_multi_workspace_bytes(nq, t0) bytes that the
+    caller keeps for its calls; without one this wrapper takes one from torch's allocator for the call."""
     lib = load_library()
     p, dt = _base_ptr(base)
     q = _dev(queries, torch.float32, "queries")
@@ -259,8 +314,18 @@ def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k:
     prm.dtype, prm.lambda_visit, prm.seed, prm.max_hops = dt, lambda_visit, seed, max_hops
     prm.qi_offset, prm.stream, prm.metric = qi_offset, _stream_ptr(stream), _METRICS[metric]
     st = torch.zeros((nq, 3), dtype=torch.int32, device=base.device) if want_stats else None
-    _check(getattr(lib, _entry)(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(),
-                                st.data_ptr() if st is not None else None))
+    stp = st.data_ptr() if st is not None else None
+    if _static:
+        _check(lib.ann_search_multi_static(graph.ptr, p, q, nq, k, t0, C.byref(prm), ids.data_ptr(), s.data_ptr(), stp))
+    else:
+        if workspace is None:
+            need = int(lib.ann_search_multi_workspace_bytes(nq, max(t0, 1))) if nq > 0 else 0
+            workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=base.device)
+            if stream is not None:          # the block must not be handed out again before that stream is done with it
+                workspace.record_stream(stream)
+        _dev(workspace, torch.uint8, "workspace")
+        _check(lib.ann_search_multi(graph.ptr, p, q, nq, k, t0, C.byref(prm), workspace.data_ptr(), workspace.numel(),
+                                    ids.data_ptr(), s.data_ptr(), stp))
     if want_stats:
         return ids, s, QueryStats(st[:, 0], st[:, 1], st[:, 2])
     return ids, s
@@ -269,7 +334,7 @@ def ann_search_multi(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k:
 def ann_search_multi_static(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, t0: int, **kw):
     """ann_search_multi on the library's own scratch: the C call allocates nothing (nq * t0 <= 2048).
     Pass `out=(ids, dists)` to keep this wrapper from allocating the outputs too."""
-    return ann_search_multi(graph, base, queries, k, t0, _entry="ann_search_multi_static", **kw)
+    return ann_search_multi(graph, base, queries, k, t0, _static=True, **kw)
 
 
 def ann_search_alg2(graph: Graph, base: torch.Tensor, queries: torch.Tensor, k: int, delta: float, *, m_c: int = 16,

@@ -273,7 +273,7 @@ struct Alg2Dispatch {
     template <typename T, int G, int C> void operator()()
     {
         const size_t lds = (size_t)a.m_c * 32 * 8 + 64 * 8 + 64 * 4 + (size_t)a.m_v * 32 * 4 + (size_t)(a.m_c + a.m_v) * 4;
-        hipLaunchKernelGGL((alg2_kernel<T, G, C>), dim3((unsigned)nq), dim3(64), lds, stream, a);
+        TSDG_LAUNCH((alg2_kernel<T, G, C>), dim3((unsigned)nq), dim3(64), lds, stream, a);
     }
 };
 }  // namespace
@@ -306,7 +306,7 @@ ann_status launch_search_alg2(const Alg2Launch& s)
         set_error("unsupported row shape: d=%d dtype=%d", s.d, (int)s.dtype);
         return ANN_EUNSUPPORTED;
     }
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 

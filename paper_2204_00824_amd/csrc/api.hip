@@ -21,6 +21,39 @@ void set_error(const char* fmt, ...)
     va_end(ap);
 }
 
+void hip_failed(const char* call, hipError_t e, const char* file, int line)
+{
+    // a launch refused by launch_fits() has already said which kernel and why
+    if (e == hipErrorInvalidConfiguration && std::strncmp(g_err, "launch of ", 10) == 0) return;
+    set_error("%s failed: %s (%s:%d)", call, hipGetErrorString(e), file, line);
+}
+
+static thread_local bool g_launch_refused = false;
+
+bool launch_fits(dim3 grid, dim3 block, const char* kernel)
+{
+    const uint64_t lim = 1ull << 32;
+    const bool ok = grid.x > 0 && grid.y > 0 && grid.z > 0 && (uint64_t)grid.x * block.x < lim &&
+                    (uint64_t)grid.y * block.y < lim && (uint64_t)grid.z * block.z < lim && grid.y <= 65535u &&
+                    grid.z <= 65535u && (uint64_t)block.x * block.y * block.z <= 1024u;
+    if (!ok) {
+        set_error("launch of %s refused: grid %u x %u x %u of %u x %u x %u threads exceeds what one dispatch can count",
+                  kernel, grid.x, grid.y, grid.z, block.x, block.y, block.z);
+        g_launch_refused = true;
+    }
+    return ok;
+}
+
+hipError_t launch_error()
+{
+    if (g_launch_refused) {
+        g_launch_refused = false;
+        (void)hipGetLastError();
+        return hipErrorInvalidConfiguration;
+    }
+    return hipGetLastError();
+}
+
 // ---- pack / unpack / validate --------------------------------------------------------------
 // flags[0]: first violation code; flags[1]: max lambda seen
 __global__ void pack_kernel(const int32_t* __restrict__ adj, const uint8_t* __restrict__ lam, int64_t N,
@@ -74,9 +107,9 @@ ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, 
     hipError_t e = hipMemsetAsync(flags, 0, 2 * sizeof(int), stream);
     if (e == hipSuccess) {
         const int rows_per_block = 4;
-        hipLaunchKernelGGL(pack_kernel, folded_grid((N + rows_per_block - 1) / rows_per_block), dim3(64 * rows_per_block), 0, stream, adj, lam, N, K, packed,
+        TSDG_LAUNCH(pack_kernel, folded_grid((N + rows_per_block - 1) / rows_per_block), dim3(64 * rows_per_block), 0, stream, adj, lam, N, K, packed,
                            flags);
-        e = hipGetLastError();
+        e = launch_error();
     }
     int h[2] = {0, 0};
     if (e == hipSuccess) e = hipMemcpyAsync(h, flags, sizeof(h), hipMemcpyDeviceToHost, stream);
@@ -99,8 +132,8 @@ ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, 
 ann_status unpack_graph(const uint32_t* packed, int64_t N, int K, hipStream_t stream, int32_t* adj, uint8_t* lam)
 {
     const int64_t total = N * K;
-    hipLaunchKernelGGL(unpack_kernel, folded_grid((total + 255) / 256), dim3(256), 0, stream, packed, total, adj, lam);
-    TSDG_HIP(hipGetLastError());
+    TSDG_LAUNCH(unpack_kernel, folded_grid((total + 255) / 256), dim3(256), 0, stream, packed, total, adj, lam);
+    TSDG_HIP(launch_error());
     TSDG_HIP(hipStreamSynchronize(stream));
     return ANN_OK;
 }
@@ -156,8 +189,8 @@ __global__ __launch_bounds__(256) void halve_kernel(float* __restrict__ v, int64
 static ann_status report_metric(ann_metric metric, float* out_dists, int64_t n, hipStream_t stream)
 {
     if (metric != ANN_COSINE || n == 0) return ANN_OK;
-    hipLaunchKernelGGL(halve_kernel, folded_grid((n + 255) / 256), dim3(256), 0, stream, out_dists, n);
-    TSDG_HIP(hipGetLastError());
+    TSDG_LAUNCH(halve_kernel, folded_grid((n + 255) / 256), dim3(256), 0, stream, out_dists, n);
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 
@@ -259,6 +292,11 @@ void ann_build_params_default(ann_build_params* p)
     p->descent_iters = 0;
     p->descent_delta = 0.f;
     p->descent_seed = 0;
+    p->knn_filter = 0;
+    p->knn_row_block = 0;
+    p->progress = nullptr;
+    p->progress_user = nullptr;
+    p->stats = nullptr;
 }
 
 void ann_search_params_default(ann_search_params* p)
@@ -281,7 +319,6 @@ static void destroy_graph(ann_graph_impl* g)
 {
     if (!g) return;
     if (g->packed) (void)hipFree(g->packed);
-    if (g->ws) (void)hipFree(g->ws);
     delete g;
 }
 
@@ -295,8 +332,6 @@ static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
     g->max_lambda = 0;
     g->packed = nullptr;
     g->device = 0;
-    g->ws = nullptr;
-    g->ws_bytes = 0;
     (void)hipGetDevice(&g->device);
     hipError_t e = hipMalloc(&g->packed, (size_t)N * (size_t)K * sizeof(uint32_t));
     if (e != hipSuccess) {
@@ -304,11 +339,6 @@ static ann_status new_graph(int64_t N, int K, int d, ann_graph_impl** out)
         delete g;
         return ANN_ENOMEM;
     }
-    // scratch of the multi-search for its usual calls (up to 16 queries x 128 searches), so that those never
-    // allocate; larger calls grow it
-    const size_t ws = (size_t)16 * 128 * 33 * sizeof(uint64_t);
-    if (hipMalloc(&g->ws, ws) == hipSuccess) g->ws_bytes = ws;
-    else { g->ws = nullptr; (void)hipGetLastError(); }
     *out = g;
     return ANN_OK;
 }
@@ -357,18 +387,91 @@ void ann_graph_free(ann_graph* graph)
     destroy_graph(reinterpret_cast<ann_graph_impl*>(graph));
 }
 
-ann_status ann_knn(const void* base, int64_t N, int d, int K, ann_dtype dtype, void* stream, int32_t* knn_ids,
-                   float* knn_dists)
+static ann_status make_ctx(const ann_build_params& p, const char* what, BuildCtx* ctx)
+{
+    if (p.knn_filter != 0 && p.knn_filter != 1) { set_error("%s: knn_filter must be 0 or 1", what); return ANN_EINVAL; }
+    if (p.knn_row_block < 0 || p.knn_row_block % 256 != 0 || p.knn_row_block > (1ll << 21)) {
+        set_error("%s: knn_row_block must be 0 or a multiple of 256 up to 2^21", what);
+        return ANN_EINVAL;
+    }
+    ctx->progress = p.progress;
+    ctx->progress_user = p.progress_user;
+    ctx->stats = p.stats;
+    ctx->knn_filter = p.knn_filter;
+    ctx->knn_row_block = p.knn_row_block;
+    if (p.stats) std::memset(p.stats, 0, sizeof(*p.stats));
+    return ANN_OK;
+}
+
+// k-NN lists with the device time of the call written to the caller's report
+static ann_status timed_knn(const void* base, int64_t N, int d, int K, const ann_build_params& p, const BuildCtx& ctx,
+                            int32_t* knn_ids, float* knn_dists)
+{
+    hipStream_t stream = static_cast<hipStream_t>(p.stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (ctx.stats) {
+        TSDG_HIP(hipEventCreate(&e0));
+        if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); set_error("hipEventCreate failed"); return ANN_EDEVICE; }
+        (void)hipEventRecord(e0, stream);
+    }
+    ann_status rc;
+    if (p.knn_mode == 1) {
+        int S = p.descent_S;
+        if (S == 0) {
+            S = 2;
+            while (S * 2 <= std::min(16, K / 2)) S *= 2;
+        }
+        rc = check_descent(N, K, S, p.descent_iters, p.descent_delta, "ann_build_graph");
+        if (rc == ANN_OK)
+            rc = knn_descent(base, N, d, p.dtype, K, S, p.descent_iters == 0 ? 12 : p.descent_iters,
+                             p.descent_delta == 0.f ? 0.001f : p.descent_delta, p.descent_seed, nullptr, stream, knn_ids,
+                             knn_dists, nullptr, nullptr, ctx);
+        if (rc == ANN_OK && ctx.stats) ctx.stats->knn_contraction = 4;
+    } else {
+        rc = knn_exact(base, N, d, p.dtype, nullptr, N, K, true, stream, knn_ids, knn_dists, ctx);
+    }
+    if (ctx.stats) {
+        if (rc == ANN_OK) {
+            hipError_t e = hipEventRecord(e1, stream);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+            if (e == hipSuccess) e = hipEventElapsedTime(&ctx.stats->knn_ms, e0, e1);
+            if (e != hipSuccess) { set_error("timing of the k-NN step failed: %s", hipGetErrorString(e)); rc = ANN_EDEVICE; }
+        }
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+    }
+    return rc;
+}
+
+ann_status ann_knn_ex(const void* base, int64_t N, int d, int K, const ann_build_params* params, int32_t* knn_ids,
+                      float* knn_dists)
 {
     g_err[0] = 0;
-    ann_status rc = check_rows(base, N, d, dtype, "ann_knn");
+    ann_build_params p;
+    ann_build_params_default(&p);
+    if (params) p = *params;
+    ann_status rc = check_rows(base, N, d, p.dtype, "ann_knn");
     if (rc != ANN_OK) return rc;
     if (!knn_ids || !knn_dists) { set_error("ann_knn: null output"); return ANN_EINVAL; }
     if (K < 1 || K > kMaxK || N <= K || N >= (1ll << kIdBits)) {
         set_error("ann_knn: need 1 <= K <= 64 and K < N < 2^27");
         return ANN_EINVAL;
     }
-    return knn_exact(base, N, d, dtype, nullptr, N, K, true, static_cast<hipStream_t>(stream), knn_ids, knn_dists);
+    BuildCtx ctx;
+    rc = make_ctx(p, "ann_knn", &ctx);
+    if (rc != ANN_OK) return rc;
+    p.knn_mode = 0;
+    return timed_knn(base, N, d, K, p, ctx, knn_ids, knn_dists);
+}
+
+ann_status ann_knn(const void* base, int64_t N, int d, int K, ann_dtype dtype, void* stream, int32_t* knn_ids,
+                   float* knn_dists)
+{
+    ann_build_params p;
+    ann_build_params_default(&p);
+    p.dtype = dtype;
+    p.stream = stream;
+    return ann_knn_ex(base, N, d, K, &p, knn_ids, knn_dists);
 }
 
 ann_status ann_bruteforce(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries, int nq,
@@ -387,7 +490,8 @@ ann_status ann_bruteforce(const void* base, int64_t N, int d, ann_dtype dtype, c
         return ANN_EINVAL;
     }
     if (nq == 0) return ANN_OK;
-    return knn_exact(base, N, d, dtype, queries, nq, k, false, static_cast<hipStream_t>(stream), out_ids, out_dists);
+    return knn_exact(base, N, d, dtype, queries, nq, k, false, static_cast<hipStream_t>(stream), out_ids, out_dists,
+                     BuildCtx());
 }
 
 ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const ann_build_params* params,
@@ -414,6 +518,9 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
     int rev_cap = p.rev_cap == 0 ? 2 * K : p.rev_cap;
     if (rev_cap < K || rev_cap > 2 * kMaxK) { set_error("ann_build_graph: rev_cap must be in K..128"); return ANN_EINVAL; }
     hipStream_t stream = static_cast<hipStream_t>(p.stream);
+    BuildCtx ctx;
+    rc = make_ctx(p, "ann_build_graph", &ctx);
+    if (rc != ANN_OK) return rc;
 
     int32_t* knn_id = nullptr;
     float* knn_s = nullptr;
@@ -425,24 +532,11 @@ ann_status ann_build_graph_ex(const void* base, int64_t N, int d, int K, const a
         return ANN_ENOMEM;
     }
     ann_graph_impl* g = nullptr;
-    if (p.knn_mode == 1) {
-        int S = p.descent_S;
-        if (S == 0) {
-            S = 2;
-            while (S * 2 <= std::min(16, K / 2)) S *= 2;
-        }
-        rc = check_descent(N, K, S, p.descent_iters, p.descent_delta, "ann_build_graph");
-        if (rc == ANN_OK)
-            rc = knn_descent(base, N, d, p.dtype, K, S, p.descent_iters == 0 ? 12 : p.descent_iters,
-                             p.descent_delta == 0.f ? 0.001f : p.descent_delta, p.descent_seed, nullptr, stream, knn_id,
-                             knn_s, nullptr, nullptr);
-    } else {
-        rc = knn_exact(base, N, d, p.dtype, nullptr, N, K, true, stream, knn_id, knn_s);
-    }
+    rc = timed_knn(base, N, d, K, p, ctx, knn_id, knn_s);
     if (rc == ANN_OK) rc = new_graph(N, K, d, &g);
     if (rc == ANN_OK)
         rc = diversify(base, N, d, p.dtype, K, knn_id, knn_s, alpha_on_s, p.lambda0, rev_cap, stream, g->packed,
-                       &g->max_lambda);
+                       &g->max_lambda, ctx);
     (void)hipFree(knn_id);
     (void)hipFree(knn_s);
     if (rc != ANN_OK) {
@@ -469,7 +563,7 @@ ann_status ann_knn_descent(const void* base, int64_t N, int d, int K, ann_dtype 
     if (rc != ANN_OK) return rc;
     if (!knn_ids || !knn_dists) { set_error("ann_knn_descent: null output"); return ANN_EINVAL; }
     return knn_descent(base, N, d, dtype, K, S, max_iters, delta, seed, init_ids, static_cast<hipStream_t>(stream),
-                       knn_ids, knn_dists, iters_done, last_changed);
+                       knn_ids, knn_dists, iters_done, last_changed, BuildCtx());
 }
 
 ann_status ann_max_row_norm(const float* src, int64_t n, int d, void* stream, float* M)
@@ -484,9 +578,9 @@ ann_status ann_max_row_norm(const float* src, int64_t n, int d, void* stream, fl
     hipError_t e = hipMemsetAsync(bits, 0, sizeof(unsigned), st);
     unsigned h = 0;
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(ip_augment_kernel, folded_grid((n + 31) / 32), dim3(256), 0, st, src, n, d, 0.f, 1,
+        TSDG_LAUNCH(ip_augment_kernel, folded_grid((n + 31) / 32), dim3(256), 0, st, src, n, d, 0.f, 1,
                            static_cast<float*>(nullptr), bits);
-        e = hipGetLastError();
+        e = launch_error();
     }
     if (e == hipSuccess) e = hipMemcpyAsync(&h, bits, sizeof(h), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
@@ -505,9 +599,9 @@ ann_status ann_ip_augment_rows(const float* src, int64_t n, int d, float M, int 
     if (d + 4 > 2048) { set_error("ann_ip_augment_rows: d + 4 must not exceed 2048"); return ANN_EUNSUPPORTED; }
     if (!dst || !aligned16(dst) || dst == src) { set_error("ann_ip_augment_rows: dst must be another 16-byte aligned device buffer"); return ANN_EINVAL; }
     if (!is_query && !(M > 0.f)) { set_error("ann_ip_augment_rows: base rows need M > 0"); return ANN_EINVAL; }
-    hipLaunchKernelGGL(ip_augment_kernel, folded_grid((n + 31) / 32), dim3(256), 0, static_cast<hipStream_t>(stream),
+    TSDG_LAUNCH(ip_augment_kernel, folded_grid((n + 31) / 32), dim3(256), 0, static_cast<hipStream_t>(stream),
                        src, n, d, M, is_query ? 1 : 0, dst, static_cast<unsigned*>(nullptr));
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 
@@ -518,9 +612,9 @@ ann_status ann_normalize_rows(const float* src, int64_t n, int d, float* dst, vo
     ann_status rc = check_rows(src, n, d, ANN_F32, "ann_normalize_rows");
     if (rc != ANN_OK) return rc;
     if (!dst || !aligned16(dst)) { set_error("ann_normalize_rows: dst must be a 16-byte aligned device pointer"); return ANN_EINVAL; }
-    hipLaunchKernelGGL(normalize_kernel, folded_grid((n + 31) / 32), dim3(256), 0, static_cast<hipStream_t>(stream),
+    TSDG_LAUNCH(normalize_kernel, folded_grid((n + 31) / 32), dim3(256), 0, static_cast<hipStream_t>(stream),
                        src, n, d, dst);
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 
@@ -618,11 +712,12 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
 }
 
-// Argument checks and launch shared by the two multi-search entry points.  `own_scratch`: take the
-// rankings' scratch from the library's file-scope array (no allocation) instead of the graph's buffer.
-static ann_status search_multi_common(ann_graph_impl* g, const void* base, const void* queries, int nq, int k, int t0,
-                                      const ann_search_params* params, int32_t* out_ids, float* out_dists,
-                                      ann_query_stats* stats, bool own_scratch, const char* what)
+// Argument checks and launch shared by the two multi-search entry points.  `own_scratch`: the rankings pass
+// through the library's file-scope array (no allocation) instead of the caller's workspace.
+static ann_status search_multi_common(const ann_graph_impl* g, const void* base, const void* queries, int nq, int k,
+                                      int t0, const ann_search_params* params, void* workspace, size_t workspace_bytes,
+                                      int32_t* out_ids, float* out_dists, ann_query_stats* stats, bool own_scratch,
+                                      const char* what)
 {
     g_err[0] = 0;
     ann_search_params p;
@@ -642,7 +737,10 @@ static ann_status search_multi_common(ann_graph_impl* g, const void* base, const
     if (!aligned16(queries)) { set_error("%s: query rows must be 16-byte aligned", what); return ANN_EINVAL; }
     if ((int64_t)nq * t0 > 65535ll * 1024) { set_error("%s: nq * t0 too large", what); return ANN_EUNSUPPORTED; }
     if (nq > 65535) { set_error("%s: at most 65535 queries per call", what); return ANN_EUNSUPPORTED; }
+    hipStream_t stream = static_cast<hipStream_t>(p.stream);
+    const size_t need = ann_search_multi_workspace_bytes(nq, t0);
     uint64_t* scratch = nullptr;
+    void* temporary = nullptr;
     if (own_scratch) {
         if ((int64_t)nq * t0 > kMultiStaticSearches) {
             set_error("%s: nq * t0 = %lld searches exceed the %d the library's own scratch holds", what,
@@ -651,19 +749,16 @@ static ann_status search_multi_common(ann_graph_impl* g, const void* base, const
         }
         rc = multi_static_scratch(&scratch);
         if (rc != ANN_OK) return rc;
-    } else {
-        const size_t need = (size_t)nq * (size_t)t0 * 33 * sizeof(uint64_t);
-        if (need > g->ws_bytes) {
-            hipStream_t st = static_cast<hipStream_t>(p.stream);
-            TSDG_HIP(hipStreamSynchronize(st));
-            if (g->ws) (void)hipFree(g->ws);
-            g->ws = nullptr;
-            g->ws_bytes = 0;
-            hipError_t e = hipMalloc(&g->ws, need);
-            if (e != hipSuccess) { set_error("hipMalloc of the multi-search scratch failed: %s", hipGetErrorString(e)); return ANN_ENOMEM; }
-            g->ws_bytes = need;
+    } else if (workspace) {
+        if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 7u) != 0) {
+            set_error("%s: the workspace must be 8-byte aligned and hold %zu bytes (got %zu)", what, need, workspace_bytes);
+            return ANN_EINVAL;
         }
-        scratch = static_cast<uint64_t*>(g->ws);
+        scratch = static_cast<uint64_t*>(workspace);
+    } else {
+        hipError_t e = hipMalloc(&temporary, need);
+        if (e != hipSuccess) { set_error("hipMalloc of the multi-search workspace failed: %s", hipGetErrorString(e)); return ANN_ENOMEM; }
+        scratch = static_cast<uint64_t*>(temporary);
     }
     MultiLaunch s;
     s.packed = g->packed;
@@ -686,27 +781,37 @@ static ann_status search_multi_common(ann_graph_impl* g, const void* base, const
     s.out_ids = out_ids;
     s.out_dists = out_dists;
     s.stats = stats;
-    s.stream = static_cast<hipStream_t>(p.stream);
+    s.stream = stream;
     rc = launch_search_multi(s);
-    if (rc != ANN_OK) return rc;
-    return report_metric(p.metric, out_dists, (int64_t)nq * k, s.stream);
+    if (rc == ANN_OK) rc = report_metric(p.metric, out_dists, (int64_t)nq * k, stream);
+    if (temporary) {   // the convenience path: wait for the kernels, then give the memory back
+        const hipError_t e = hipStreamSynchronize(stream);
+        (void)hipFree(temporary);
+        if (e != hipSuccess && rc == ANN_OK) { set_error("%s failed on the device: %s", what, hipGetErrorString(e)); rc = ANN_EDEVICE; }
+    }
+    return rc;
 }
 
-ann_status ann_search_multi(ann_graph* graph, const void* base, const void* queries, int nq, int k, int t0,
-                            const ann_search_params* params, int32_t* out_ids, float* out_dists,
-                            ann_query_stats* stats)
+size_t ann_search_multi_workspace_bytes(int nq, int t0)
 {
-    return search_multi_common(reinterpret_cast<ann_graph_impl*>(graph), base, queries, nq, k, t0, params, out_ids,
-                               out_dists, stats, false, "ann_search_multi");
+    if (nq <= 0 || t0 <= 0) return 0;
+    return (size_t)nq * (size_t)t0 * 33 * sizeof(uint64_t);
+}
+
+ann_status ann_search_multi(const ann_graph* graph, const void* base, const void* queries, int nq, int k, int t0,
+                            const ann_search_params* params, void* workspace, size_t workspace_bytes, int32_t* out_ids,
+                            float* out_dists, ann_query_stats* stats)
+{
+    return search_multi_common(reinterpret_cast<const ann_graph_impl*>(graph), base, queries, nq, k, t0, params, workspace,
+                               workspace_bytes, out_ids, out_dists, stats, false, "ann_search_multi");
 }
 
 ann_status ann_search_multi_static(const ann_graph* graph, const void* base, const void* queries, int nq, int k,
                                    int t0, const ann_search_params* params, int32_t* out_ids, float* out_dists,
                                    ann_query_stats* stats)
 {
-    // the graph is only read on this path (its own scratch buffer is left alone)
-    return search_multi_common(const_cast<ann_graph_impl*>(reinterpret_cast<const ann_graph_impl*>(graph)), base,
-                               queries, nq, k, t0, params, out_ids, out_dists, stats, true, "ann_search_multi_static");
+    return search_multi_common(reinterpret_cast<const ann_graph_impl*>(graph), base, queries, nq, k, t0, params, nullptr,
+                               0, out_ids, out_dists, stats, true, "ann_search_multi_static");
 }
 
 ann_status ann_search_alg2(const ann_graph* graph, const void* base, const void* queries, int nq, int k,

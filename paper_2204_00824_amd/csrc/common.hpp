@@ -30,8 +30,20 @@ struct ann_graph_impl {
     int max_lambda;    // largest lambda stored
     uint32_t* packed;  // [N,K] device
     int device;
-    void* ws;          // grow-only scratch of the multi-search (rankings of the t0 searches)
-    size_t ws_bytes;
+};
+
+// What a build call hands down to its steps: the caller's progress callback and report (both
+// optional) and the two switches of the exact contraction.
+struct BuildCtx {
+    ann_progress_fn progress = nullptr;
+    void* progress_user = nullptr;
+    ann_build_stats* stats = nullptr;
+    int knn_filter = 0;        // 1: hi + lo bf16 parts from the start
+    int64_t knn_row_block = 0; // 0: default
+    void report(const char* step, int64_t done, int64_t total) const
+    {
+        if (progress) progress(progress_user, step, done, total);
+    }
 };
 
 // ---- grids that grow with the number of base rows
@@ -51,11 +63,25 @@ __device__ __forceinline__ int64_t linear_block() { return (int64_t)blockIdx.y *
 
 // ---- error plumbing (host)
 void set_error(const char* fmt, ...);
+
+// ---- every kernel launch goes through this check
+// A dispatch counts the work-items of each grid dimension in 32 bits and takes at most 65,535
+// workgroups in y and z.  A launch outside that is refused on the host (it would otherwise run with
+// a truncated grid or fault): the launch is skipped, the thread's error message says which kernel,
+// and launch_error(), which the launchers ask instead of hipGetLastError(), reports it once.
+bool launch_fits(dim3 grid, dim3 block, const char* kernel);
+hipError_t launch_error();
+#define TSDG_LAUNCH(kern, grid, block, lds, stream, ...)                                      \
+    do {                                                                                      \
+        const dim3 g_ = (grid), b_ = (block);                                                 \
+        if (tsdg::launch_fits(g_, b_, #kern)) hipLaunchKernelGGL(kern, g_, b_, lds, stream, __VA_ARGS__); \
+    } while (0)
+void hip_failed(const char* call, hipError_t e, const char* file, int line);  // sets the thread's error message
 #define TSDG_HIP(call)                                                                     \
     do {                                                                                   \
         hipError_t e_ = (call);                                                            \
         if (e_ != hipSuccess) {                                                            \
-            tsdg::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            tsdg::hip_failed(#call, e_, __FILE__, __LINE__);                               \
             return e_ == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EDEVICE;                   \
         }                                                                                  \
     } while (0)
@@ -131,16 +157,16 @@ ann_status launch_search_alg2(const Alg2Launch& a);
 
 ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries,
                      int64_t nq, int k, bool exclude_self, hipStream_t stream, int32_t* out_ids,
-                     float* out_s);
+                     float* out_s, const BuildCtx& ctx);
 
 // Approximate k-NN lists by neighbourhood propagation (descent.hip); lists in (s,id) order, -1 / +inf padded.
 ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int K, int S, int max_iters, float delta,
                        uint64_t seed, const int32_t* init_ids, hipStream_t stream, int32_t* out_ids, float* out_s,
-                       int* iters_done, int64_t* last_changed);
+                       int* iters_done, int64_t* last_changed, const BuildCtx& ctx);
 
 ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
                      const float* knn_s, float alpha_on_s, int lambda0, int rev_cap, hipStream_t stream,
-                     uint32_t* packed, int* max_lambda);
+                     uint32_t* packed, int* max_lambda, const BuildCtx& ctx);
 
 ann_status pack_graph(const int32_t* adj, const uint8_t* lam, int64_t N, int K, hipStream_t stream,
                       uint32_t* packed, int* max_lambda);

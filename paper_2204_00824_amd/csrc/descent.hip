@@ -291,15 +291,15 @@ struct DescentLaunch {
     bool init;
     template <typename T, int G, int C> void operator()()
     {
-        if (init) hipLaunchKernelGGL((descent_init_kernel<T, G, C>), folded_grid((int64_t)a.N), dim3(64), 0, stream, a);
-        else hipLaunchKernelGGL((descent_join_kernel<T, G, C>), folded_grid((int64_t)a.N), dim3(64), 0, stream, a);
+        if (init) TSDG_LAUNCH((descent_init_kernel<T, G, C>), folded_grid((int64_t)a.N), dim3(64), 0, stream, a);
+        else TSDG_LAUNCH((descent_join_kernel<T, G, C>), folded_grid((int64_t)a.N), dim3(64), 0, stream, a);
     }
 };
 }  // namespace
 
 ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int K, int S, int max_iters, float delta,
                        uint64_t seed, const int32_t* init_ids, hipStream_t stream, int32_t* out_ids, float* out_s,
-                       int* iters_done, int64_t* last_changed)
+                       int* iters_done, int64_t* last_changed, const BuildCtx& ctx)
 {
     int log2s = 0;
     while ((1 << log2s) < S) ++log2s;
@@ -338,26 +338,24 @@ ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int 
     ann_status rc = ANN_OK;
     auto fail = [&](ann_status s) { release(); return s; };
     if (!dispatch_row_shape(dtype, d, L)) { set_error("unsupported row shape d=%d", d); return fail(ANN_EUNSUPPORTED); }
-    if (hipGetLastError() != hipSuccess) { set_error("launch of the start lists failed"); return fail(ANN_EDEVICE); }
+    if (launch_error() != hipSuccess) { set_error("launch of the start lists failed"); return fail(ANN_EDEVICE); }
     uint64_t *cur = b0, *nxt = b1;
     int it = 0;
     int64_t ch = 0;
     L.init = false;
-    const char* prog_env = getenv("TSDG_PROGRESS");
-    const bool progress = prog_env && prog_env[0] == '1';
     for (; it < max_iters; ++it) {
-        hipLaunchKernelGGL(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rnew, (int64_t)ns, kRevEmpty);
-        hipLaunchKernelGGL(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rold, (int64_t)ns, kRevEmpty);
-        hipLaunchKernelGGL(fill_u64_kernel, dim3((2 * kChangedBins + 255) / 256), dim3(256), 0, stream,
+        TSDG_LAUNCH(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rnew, (int64_t)ns, kRevEmpty);
+        TSDG_LAUNCH(fill_u64_kernel, folded_grid((int64_t)((ns + 255) / 256)), dim3(256), 0, stream, rold, (int64_t)ns, kRevEmpty);
+        TSDG_LAUNCH(fill_u64_kernel, dim3((2 * kChangedBins + 255) / 256), dim3(256), 0, stream,
                            reinterpret_cast<uint64_t*>(changed), (int64_t)(2 * kChangedBins), 0ull);
         L.a.cur = cur;
         L.a.next = nxt;
-        hipLaunchKernelGGL(descent_reverse_kernel, folded_grid((N + 3) / 4), dim3(256), 0, stream, L.a);
+        TSDG_LAUNCH(descent_reverse_kernel, folded_grid((N + 3) / 4), dim3(256), 0, stream, L.a);
         dispatch_row_shape(dtype, d, L);
         unsigned long long h[2 * kChangedBins];
         hipError_t ce = hipMemcpyAsync(h, changed, sizeof(h), hipMemcpyDeviceToHost, stream);
         if (ce == hipSuccess) ce = hipStreamSynchronize(stream);
-        if (ce == hipSuccess) ce = hipGetLastError();
+        if (ce == hipSuccess) ce = launch_error();
         if (ce != hipSuccess) { set_error("neighbourhood propagation failed on the device: %s", hipGetErrorString(ce)); return fail(ANN_EDEVICE); }
         ch = 0;
         int64_t scored = 0;
@@ -366,17 +364,14 @@ ann_status knn_descent(const void* base, int64_t N, int d, ann_dtype dtype, int 
             scored += (int64_t)h[kChangedBins + i];
         }
         std::swap(cur, nxt);
-        if (progress) {
-            fprintf(stderr, "[tsdg] neighbourhood propagation: iteration %d, %lld rows scored, %lld list entries changed\n",
-                    it + 1, (long long)scored, (long long)ch);
-            fflush(stderr);
-        }
+        (void)scored;
+        ctx.report("descent", it + 1, max_iters);
         if ((double)ch <= (double)delta * (double)N * (double)K) { ++it; break; }
     }
-    hipLaunchKernelGGL(descent_export_kernel, folded_grid((int64_t)((nk + 255) / 256)), dim3(256), 0, stream, cur, (int64_t)nk,
+    TSDG_LAUNCH(descent_export_kernel, folded_grid((int64_t)((nk + 255) / 256)), dim3(256), 0, stream, cur, (int64_t)nk,
                        out_ids, out_s);
     hipError_t fe = hipStreamSynchronize(stream);
-    if (fe == hipSuccess) fe = hipGetLastError();
+    if (fe == hipSuccess) fe = launch_error();
     release();
     if (fe != hipSuccess) { set_error("neighbourhood propagation: %s", hipGetErrorString(fe)); return ANN_EDEVICE; }
     if (iters_done) *iters_done = it;

@@ -434,7 +434,7 @@ struct Stage1Launch {
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage1_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((stage1_kernel<T, G, C>), folded_grid(a.N), dim3(64), lds, stream, a);
+        TSDG_LAUNCH((stage1_kernel<T, G, C>), folded_grid(a.N), dim3(64), lds, stream, a);
     }
 };
 struct Stage2Launch {
@@ -450,15 +450,43 @@ struct Stage2Launch {
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage2_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL((stage2_kernel<T, G, C>), folded_grid(a.N), dim3(64), lds, stream, a);
+        TSDG_LAUNCH((stage2_kernel<T, G, C>), folded_grid(a.N), dim3(64), lds, stream, a);
     }
 };
 }  // namespace
 
+// sum of n 32-bit counts into *out (64-bit): one atomic per workgroup; only run when a build report is asked for
+__global__ __launch_bounds__(256) void sum_counts_kernel(const int32_t* __restrict__ v, int64_t n,
+                                                         unsigned long long* __restrict__ out)
+{
+    __shared__ unsigned long long part[4];
+    unsigned long long acc = 0;
+    const int64_t i0 = linear_block() * 1024, i1 = i0 + 1024 < n ? i0 + 1024 : n;
+    for (int64_t i = i0 + threadIdx.x; i < i1; i += 256) acc += (unsigned long long)v[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)acc, o, 64);
+        const unsigned hi = (unsigned)__shfl_xor((int)(unsigned)(acc >> 32), o, 64);
+        acc += ((unsigned long long)hi << 32) | lo;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(out, part[0] + part[1] + part[2] + part[3]);
+}
+
 ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K, const int32_t* knn_id,
                      const float* knn_s, float alpha_on_s, int lambda0, int rev_cap, hipStream_t stream, uint32_t* packed,
-                     int* max_lambda)
+                     int* max_lambda, const BuildCtx& ctx)
 {
+    // device time of the three steps for the caller's report: events on the build's stream
+    struct Marks {
+        hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+        ~Marks() { for (hipEvent_t e : ev) if (e) (void)hipEventDestroy(e); }
+    } marks;
+    const bool timed = ctx.stats != nullptr;
+    if (timed)
+        for (hipEvent_t& e : marks.ev) TSDG_HIP(hipEventCreate(&e));
+
     DevBuf g1_id, g1_s, g1_deg, indeg, cursor, start, bsums, rev_src, rev_s, g2_id, g2_s, g2_deg, mlam;
     const size_t nk = (size_t)N * K;
     TSDG_HIP(g1_id.alloc(nk * 4));
@@ -485,14 +513,14 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
         TSDG_HIP(notint.alloc(4));
         TSDG_HIP(hipMemsetAsync(notint.p, 0, 4, stream));
         if (dtype == ANN_U8)
-            hipLaunchKernelGGL((i8_prep_kernel<uint8_t>), folded_grid((N + 31) / 32), dim3(256), 0, stream,
+            TSDG_LAUNCH((i8_prep_kernel<uint8_t>), folded_grid((N + 31) / 32), dim3(256), 0, stream,
                                static_cast<const uint8_t*>(base), N, d, dp8, xc8.as<uint8_t>(), xn8.as<int>(),
                                notint.as<unsigned>());
         else
-            hipLaunchKernelGGL((i8_prep_kernel<float>), folded_grid((N + 31) / 32), dim3(256), 0, stream,
+            TSDG_LAUNCH((i8_prep_kernel<float>), folded_grid((N + 31) / 32), dim3(256), 0, stream,
                                static_cast<const float*>(base), N, d, dp8, xc8.as<uint8_t>(), xn8.as<int>(),
                                notint.as<unsigned>());
-        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(launch_error());
         unsigned h_notint = 1;
         TSDG_HIP(hipMemcpyAsync(&h_notint, notint.p, 4, hipMemcpyDeviceToHost, stream));
         TSDG_HIP(hipStreamSynchronize(stream));
@@ -500,6 +528,7 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     }
 
     // stage 1
+    if (timed) TSDG_HIP(hipEventRecord(marks.ev[0], stream));
     Stage1Launch s1;
     s1.a.base = base;
     s1.a.knn_id = knn_id;
@@ -519,24 +548,25 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
         return ANN_EUNSUPPORTED;
     }
     TSDG_HIP(s1.err);
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
 
     // reverse edges: scan of in-degrees, scatter, per-node merge
-    hipLaunchKernelGGL(scan_partial, dim3((unsigned)nb), dim3(256), 0, stream, indeg.as<unsigned>(), N,
+    if (timed) TSDG_HIP(hipEventRecord(marks.ev[1], stream));
+    TSDG_LAUNCH(scan_partial, dim3((unsigned)nb), dim3(256), 0, stream, indeg.as<unsigned>(), N,
                        bsums.as<uint64_t>());
-    hipLaunchKernelGGL(scan_block_sums, dim3(1), dim3(64), 0, stream, bsums.as<uint64_t>(), nb);
-    hipLaunchKernelGGL(scan_final, dim3((unsigned)nb), dim3(256), 0, stream, indeg.as<unsigned>(), N,
+    TSDG_LAUNCH(scan_block_sums, dim3(1), dim3(64), 0, stream, bsums.as<uint64_t>(), nb);
+    TSDG_LAUNCH(scan_final, dim3((unsigned)nb), dim3(256), 0, stream, indeg.as<unsigned>(), N,
                        bsums.as<uint64_t>(), start.as<uint64_t>());
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     uint64_t total = 0;
     TSDG_HIP(hipMemcpyAsync(&total, start.as<uint64_t>() + N, 8, hipMemcpyDeviceToHost, stream));
     TSDG_HIP(hipStreamSynchronize(stream));
     TSDG_HIP(rev_src.alloc((size_t)total * 4));
     TSDG_HIP(rev_s.alloc((size_t)total * 4));
-    hipLaunchKernelGGL(scatter_kernel, folded_grid((int64_t)((nk + 255) / 256)), dim3(256), 0, stream, g1_id.as<int32_t>(),
+    TSDG_LAUNCH(scatter_kernel, folded_grid((int64_t)((nk + 255) / 256)), dim3(256), 0, stream, g1_id.as<int32_t>(),
                        g1_s.as<float>(), (int64_t)nk, K, start.as<uint64_t>(), cursor.as<unsigned>(),
                        rev_src.as<int32_t>(), rev_s.as<float>());
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
 
     const size_t nr = (size_t)N * rev_cap;
     TSDG_HIP(g2_id.alloc(nr * 4));
@@ -555,10 +585,11 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     m.N = N;
     m.K = K;
     m.rev_cap = rev_cap;
-    hipLaunchKernelGGL(merge_kernel, folded_grid(N), dim3(64), (size_t)((rev_cap + 63) & ~63) * 8, stream, m);
-    TSDG_HIP(hipGetLastError());
+    TSDG_LAUNCH(merge_kernel, folded_grid(N), dim3(64), (size_t)((rev_cap + 63) & ~63) * 8, stream, m);
+    TSDG_HIP(launch_error());
 
     // stage 2
+    if (timed) TSDG_HIP(hipEventRecord(marks.ev[2], stream));
     Stage2Launch s2;
     s2.a.base = base;
     s2.a.g2_id = g2_id.as<int32_t>();
@@ -575,11 +606,34 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s2.stream = stream;
     dispatch_row_shape(dtype, d, s2);
     TSDG_HIP(s2.err);
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
+    if (timed) TSDG_HIP(hipEventRecord(marks.ev[3], stream));
     int h_lam[kLambdaSlots];
     TSDG_HIP(hipMemcpyAsync(h_lam, mlam.p, sizeof(h_lam), hipMemcpyDeviceToHost, stream));
+    unsigned long long h_rows[2] = {0, 0};
+    DevBuf rows;
+    if (timed) {
+        TSDG_HIP(rows.alloc(sizeof(h_rows)));
+        TSDG_HIP(hipMemsetAsync(rows.p, 0, sizeof(h_rows), stream));
+        // stage 1 reads each node's own row and the rows of its k-NN list (its length is K, short only when the
+        // propagation left a list unfilled: then the padding -1 entries are not read, counted here as read)
+        TSDG_LAUNCH(sum_counts_kernel, folded_grid((N + 1023) / 1024), dim3(256), 0, stream, g2_deg.as<int32_t>(), N,
+                    rows.as<unsigned long long>());
+        TSDG_HIP(launch_error());
+        TSDG_HIP(hipMemcpyAsync(h_rows, rows.p, sizeof(h_rows), hipMemcpyDeviceToHost, stream));
+    }
     TSDG_HIP(hipStreamSynchronize(stream));
     *max_lambda = *std::max_element(h_lam, h_lam + kLambdaSlots);
+    if (timed) {
+        ann_build_stats& st = *ctx.stats;
+        TSDG_HIP(hipEventElapsedTime(&st.stage1_ms, marks.ev[0], marks.ev[1]));
+        TSDG_HIP(hipEventElapsedTime(&st.reverse_ms, marks.ev[1], marks.ev[2]));
+        TSDG_HIP(hipEventElapsedTime(&st.stage2_ms, marks.ev[2], marks.ev[3]));
+        st.stage1_rows = (uint64_t)N * (uint64_t)(K + 1);
+        st.stage2_rows = (uint64_t)N + (uint64_t)h_rows[0];
+        st.reverse_edges = total;
+        st.gather_row_bytes = i8.xc8 ? dp8 : d * (dtype == ANN_U8 ? 1 : 4);
+    }
     return ANN_OK;
 }
 

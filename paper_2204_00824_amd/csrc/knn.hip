@@ -1163,34 +1163,37 @@ template <typename TQ, typename TB> struct RefineLaunch {
         const int Lp = (a.k + 63) & ~63;
         const size_t lds = (size_t)Lp * 8 + 64 * 8;
         if (!scan)
-            hipLaunchKernelGGL((refine_kernel<TQ, TB, G, C>), dim3((unsigned)a.nq), dim3(64), lds, stream, a);
+            TSDG_LAUNCH((refine_kernel<TQ, TB, G, C>), dim3((unsigned)a.nq), dim3(64), lds, stream, a);
         else
-            hipLaunchKernelGGL((scan_kernel<TQ, TB, G, C>), dim3(redo), dim3(64), lds, stream, a, N, self_offset);
+            TSDG_LAUNCH((scan_kernel<TQ, TB, G, C>), dim3(redo), dim3(64), lds, stream, a, N, self_offset);
     }
 };
 
 template <typename TQ, typename TB>
 ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ* queries, int64_t nq, int k,
-                     bool self, hipStream_t stream, int32_t* out_ids, float* out_s, bool allow_single, bool* retry)
+                     bool self, hipStream_t stream, int32_t* out_ids, float* out_s, bool allow_single, bool* retry,
+                     const BuildCtx& ctx)
 {
     *retry = false;   // set when the one-part filter left too many rows to the plain scan: run again without it
     int kprime = std::min(2 * k, k + 64);
     int cap = kprime + 192 <= 256 ? 256 : 512;
-    const int64_t row_block = 1ll << 21;  // query rows per sweep (bounds the candidate buffers: 4-8 GB)
+    // query rows per sweep (bounds the candidate buffers: 4-8 GB at the default)
+    const int64_t row_block = ctx.knn_row_block > 0 ? ctx.knn_row_block : 1ll << 21;
+    unsigned plain_scan_rows = 0;
 
     DevBuf xnorm, qnorm, info, tau, cnt, kept, ovf, buf, redo_cnt, redo_rows;
     TSDG_HIP(xnorm.alloc((size_t)N * 4));
     TSDG_HIP(info.alloc(4 * sizeof(unsigned)));
     TSDG_HIP(hipMemsetAsync(info.p, 0, 4 * sizeof(unsigned), stream));
-    hipLaunchKernelGGL((norms_kernel<TB>), folded_grid((N + 32 * kNormPasses - 1) / (32 * kNormPasses)), dim3(256), 0, stream, base, N, d,
+    TSDG_LAUNCH((norms_kernel<TB>), folded_grid((N + 32 * kNormPasses - 1) / (32 * kNormPasses)), dim3(256), 0, stream, base, N, d,
                        xnorm.as<float>(), info.as<unsigned>());
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     float* qn = xnorm.as<float>();
     if (!self) {
         TSDG_HIP(qnorm.alloc((size_t)nq * 4));
-        hipLaunchKernelGGL((norms_kernel<TQ>), folded_grid((nq + 32 * kNormPasses - 1) / (32 * kNormPasses)), dim3(256), 0, stream, queries, nq, d,
+        TSDG_LAUNCH((norms_kernel<TQ>), folded_grid((nq + 32 * kNormPasses - 1) / (32 * kNormPasses)), dim3(256), 0, stream, queries, nq, d,
                            qnorm.as<float>(), info.as<unsigned>() + 2);
-        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(launch_error());
         qn = qnorm.as<float>();
     }
     unsigned h_info[4];
@@ -1238,15 +1241,15 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     if (fast) {
         TSDG_HIP(xc8.alloc((size_t)N * dp8));
         TSDG_HIP(xn8.alloc((size_t)N * 4));
-        hipLaunchKernelGGL((i8_prep_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dp8,
+        TSDG_LAUNCH((i8_prep_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dp8,
                            xc8.as<uint8_t>(), xn8.as<int>(), static_cast<unsigned*>(nullptr));
         if (!self) {
             TSDG_HIP(qc8.alloc((size_t)nq * dp8));
             TSDG_HIP(qn8.alloc((size_t)nq * 4));
-            hipLaunchKernelGGL((i8_prep_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
+            TSDG_LAUNCH((i8_prep_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
                                dp8, qc8.as<uint8_t>(), qn8.as<int>(), static_cast<unsigned*>(nullptr));
         }
-        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(launch_error());
     }
 
     // integer rows of 129..1024 elements: centred, exact in bf16, so the staged kernel runs on one part
@@ -1257,15 +1260,15 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     if (iwide) {
         TSDG_HIP(xb16.alloc((size_t)N * dpi * 2));
         TSDG_HIP(xn16.alloc((size_t)N * 4));
-        hipLaunchKernelGGL((bf16_rows_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dpi,
+        TSDG_LAUNCH((bf16_rows_kernel<TB>), folded_grid((N + 31) / 32), dim3(256), 0, stream, base, N, d, dpi,
                            xb16.as<uint16_t>(), xn16.as<int>());
         if (!self) {
             TSDG_HIP(qb16.alloc((size_t)nq * dpi * 2));
             TSDG_HIP(qn16.alloc((size_t)nq * 4));
-            hipLaunchKernelGGL((bf16_rows_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
+            TSDG_LAUNCH((bf16_rows_kernel<TQ>), folded_grid((nq + 31) / 32), dim3(256), 0, stream, queries, nq, d,
                                dpi, qb16.as<uint16_t>(), qn16.as<int>());
         }
-        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(launch_error());
     }
 
     DevBuf xh, xl, qh, ql, csum, cmean, cxnorm, cqnorm, cinfo;
@@ -1279,15 +1282,15 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(cxnorm.alloc((size_t)N * 4));
         TSDG_HIP(hipMemsetAsync(csum.p, 0, (size_t)d * 8, stream));
         TSDG_HIP(hipMemsetAsync(cinfo.p, 0, 4, stream));
-        hipLaunchKernelGGL((colsum_kernel<TB>), dim3((unsigned)((N + 511) / 512)), dim3(128), 0, stream, base, N, d,
+        TSDG_LAUNCH((colsum_kernel<TB>), dim3((unsigned)((N + 511) / 512)), dim3(128), 0, stream, base, N, d,
                            csum.as<double>());
-        hipLaunchKernelGGL(mean_kernel, dim3((unsigned)((d + 63) / 64)), dim3(64), 0, stream, csum.as<double>(), d, N,
+        TSDG_LAUNCH(mean_kernel, dim3((unsigned)((d + 63) / 64)), dim3(64), 0, stream, csum.as<double>(), d, N,
                            cmean.as<float>());
         if (single)
-            hipLaunchKernelGGL((half_prep_kernel<TB>), folded_grid((N + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, base, N, d, dp,
+            TSDG_LAUNCH((half_prep_kernel<TB>), folded_grid((N + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, base, N, d, dp,
                                cmean.as<float>(), scale, xh.as<uint16_t>(), cxnorm.as<float>(), cinfo.as<unsigned>());
         else
-            hipLaunchKernelGGL((split_prep_kernel<TB>), folded_grid((N + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, base, N, d, dp,
+            TSDG_LAUNCH((split_prep_kernel<TB>), folded_grid((N + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, base, N, d, dp,
                                cmean.as<float>(), xh.as<uint16_t>(), xl.as<uint16_t>(), cxnorm.as<float>(),
                                cinfo.as<unsigned>());
         unsigned h_max = 0;
@@ -1297,15 +1300,15 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             if (!single) TSDG_HIP(ql.alloc((size_t)nq * dp * 2));
             TSDG_HIP(cqnorm.alloc((size_t)nq * 4));
             if (single)
-                hipLaunchKernelGGL((half_prep_kernel<TQ>), folded_grid((nq + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, queries, nq,
+                TSDG_LAUNCH((half_prep_kernel<TQ>), folded_grid((nq + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, queries, nq,
                                    d, dp, cmean.as<float>(), scale, qh.as<uint16_t>(), cqnorm.as<float>(),
                                    cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
             else
-                hipLaunchKernelGGL((split_prep_kernel<TQ>), folded_grid((nq + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, queries, nq,
+                TSDG_LAUNCH((split_prep_kernel<TQ>), folded_grid((nq + 4 * kPrepRowsPerWave - 1) / (4 * kPrepRowsPerWave)), dim3(256), 0, stream, queries, nq,
                                    d, dp, cmean.as<float>(), qh.as<uint16_t>(), ql.as<uint16_t>(), cqnorm.as<float>(),
                                    cinfo.as<unsigned>() /* max over queries is not needed; harmless */);
         }
-        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(launch_error());
         TSDG_HIP(hipStreamSynchronize(stream));
         std::memcpy(&split_xmax, &h_max, 4);
     }
@@ -1333,8 +1336,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         }
     }
 
-    const char* prog_env = getenv("TSDG_PROGRESS");
-    const bool progress = prog_env && prog_env[0] == '1';
+    const bool progress = ctx.progress != nullptr;
     const int64_t rb = std::min(row_block, nq);
     TSDG_HIP(tau.alloc((size_t)rb * 4));
     TSDG_HIP(cnt.alloc((size_t)rb * 4));
@@ -1350,7 +1352,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         TSDG_HIP(hipMemsetAsync(kept.p, 0, (size_t)nr * 4, stream));
         TSDG_HIP(hipMemsetAsync(ovf.p, 0, (size_t)nr * 4, stream));
         TSDG_HIP(hipMemsetAsync(redo_cnt.p, 0, 4, stream));
-        hipLaunchKernelGGL(fill_f32, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, stream, tau.as<float>(), nr, kInf);
+        TSDG_LAUNCH(fill_f32, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, stream, tau.as<float>(), nr, kInf);
 
         FilterArgs f;
         f.q = queries + r0 * d;
@@ -1400,7 +1402,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 fa.tiles_per_block = (int)std::min<int64_t>((nr + 255) / 256 >= 2048 ? 64 : 16, ftiles);
                 dim3 fgrid((unsigned)((nr + 255) / 256), (unsigned)((ftiles + fa.tiles_per_block - 1) / fa.tiles_per_block));
                 switch (ks8) {
-#define TSDG_KS(n) case n: hipLaunchKernelGGL((filter_i8_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
+#define TSDG_KS(n) case n: TSDG_LAUNCH((filter_i8_kernel<n>), fgrid, dim3(256), 0, stream, fa); break;
                     TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4)
 #undef TSDG_KS
                 }
@@ -1432,10 +1434,10 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     wa.ny = (int)((wtiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                     wa.q_group = 64;
                     if (single)
-                        hipLaunchKernelGGL(filter_wide_kernel<2>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                        TSDG_LAUNCH(filter_wide_kernel<2>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                            kWideLds, stream, wa);
                     else
-                        hipLaunchKernelGGL(filter_wide_kernel<1>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                        TSDG_LAUNCH(filter_wide_kernel<1>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                            kWideLds, stream, wa);
                 } else {
                     const int srows = split_tile_rows(ks, single);
@@ -1445,8 +1447,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                     dim3 sgrid((unsigned)((nr + qpb - 1) / qpb), (unsigned)((ftiles + sa.tiles_per_block - 1) / sa.tiles_per_block));
                     switch (ks) {
 #define TSDG_KS(n) case n: \
-    if (single) hipLaunchKernelGGL((filter_split_kernel<n, true>), sgrid, dim3(256), 0, stream, sa); \
-    else hipLaunchKernelGGL((filter_split_kernel<n, false>), sgrid, dim3(256), 0, stream, sa); \
+    if (single) TSDG_LAUNCH((filter_split_kernel<n, true>), sgrid, dim3(256), 0, stream, sa); \
+    else TSDG_LAUNCH((filter_split_kernel<n, false>), sgrid, dim3(256), 0, stream, sa); \
     break;
                         TSDG_KS(1) TSDG_KS(2) TSDG_KS(3) TSDG_KS(4) TSDG_KS(5) TSDG_KS(6) TSDG_KS(7) TSDG_KS(8)
 #undef TSDG_KS
@@ -1477,21 +1479,19 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 wa.q_tiles = (int)((nr + kTile - 1) / kTile);
                 wa.ny = (int)((wtiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                 wa.q_group = 64;
-                hipLaunchKernelGGL(filter_wide_kernel<0>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                TSDG_LAUNCH(filter_wide_kernel<0>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
                                    kWideLds, stream, wa);
             }
-            TSDG_HIP(hipGetLastError());
-            if (cap <= 256) hipLaunchKernelGGL(compact_kernel<4>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
-            else hipLaunchKernelGGL(compact_kernel<8>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
-            TSDG_HIP(hipGetLastError());
+            TSDG_HIP(launch_error());
+            if (cap <= 256) TSDG_LAUNCH(compact_kernel<4>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
+            else TSDG_LAUNCH(compact_kernel<8>, dim3((unsigned)((nr + 3) / 4)), dim3(256), 0, stream, c);
+            TSDG_HIP(launch_error());
             cb = ce;
             // next chunk as wide as everything seen so far, up to 2M columns per launch
             width = std::min<int64_t>(std::max<int64_t>(width, cb), 1ll << 21);
-            if (progress) {  // TSDG_PROGRESS=1: long sweeps report each finished chunk
+            if (progress) {  // long sweeps report each finished chunk
                 TSDG_HIP(hipStreamSynchronize(stream));
-                fprintf(stderr, "[tsdg] k-NN sweep: rows %lld..%lld, columns done %lld / %lld\n", (long long)r0,
-                        (long long)(r0 + nr), (long long)cb, (long long)N);
-                fflush(stderr);
+                ctx.report("knn-sweep", cb, N);
             }
         }
 
@@ -1524,28 +1524,29 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
             set_error("unsupported row shape d=%d", d);
             return ANN_EUNSUPPORTED;
         }
-        TSDG_HIP(hipGetLastError());
+        TSDG_HIP(launch_error());
         unsigned redo = 0;
         TSDG_HIP(hipMemcpyAsync(&redo, redo_cnt.p, 4, hipMemcpyDeviceToHost, stream));
         TSDG_HIP(hipStreamSynchronize(stream));
-        if (progress) {
-            fprintf(stderr, "[knn] rows %lld..%lld: %u left to the plain scan%s\n", (long long)r0, (long long)(r0 + nr), redo,
-                    single ? " (one binary16 part)" : "");
-            fflush(stderr);
-        }
+        ctx.report("knn-rows", r0 + nr, nq);
         // the plain scan costs N distances per row: past a few rows in a thousand the hi + lo filter is cheaper
         if (single && (int64_t)redo > nr / 256 + 64) {
             *retry = true;
             return ANN_OK;
         }
+        plain_scan_rows += redo;
         if (redo > 0) {
             rl.scan = true;
             rl.redo = redo;
             dispatch_row_shape(dtype, d, rl);
-            TSDG_HIP(hipGetLastError());
+            TSDG_HIP(launch_error());
         }
     }
     TSDG_HIP(hipStreamSynchronize(stream));
+    if (ctx.stats) {
+        ctx.stats->knn_contraction = fast ? 0 : (iwide ? 3 : (single ? 1 : 2));
+        ctx.stats->knn_plain_scan_rows = plain_scan_rows;
+    }
     return ANN_OK;
 }
 
@@ -1554,33 +1555,32 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 namespace {
 template <typename TQ, typename TB>
 ann_status knn_retrying(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ* queries, int64_t nq, int k, bool self,
-                        hipStream_t stream, int32_t* out_ids, float* out_s)
+                        hipStream_t stream, int32_t* out_ids, float* out_s, const BuildCtx& ctx)
 {
-    const char* env = getenv("TSDG_KNN_PRECISE");   // 1: never use the one-part filter (for comparisons)
-    const bool precise = env && env[0] == '1';
+    const bool precise = ctx.knn_filter == 1;   // never use the one-part filter
     bool retry = false;
-    ann_status rc = knn_typed<TQ, TB>(base, N, d, dtype, queries, nq, k, self, stream, out_ids, out_s, !precise, &retry);
+    ann_status rc = knn_typed<TQ, TB>(base, N, d, dtype, queries, nq, k, self, stream, out_ids, out_s, !precise, &retry, ctx);
     if (rc == ANN_OK && retry)
-        rc = knn_typed<TQ, TB>(base, N, d, dtype, queries, nq, k, self, stream, out_ids, out_s, false, &retry);
+        rc = knn_typed<TQ, TB>(base, N, d, dtype, queries, nq, k, self, stream, out_ids, out_s, false, &retry, ctx);
     return rc;
 }
 }  // namespace
 
 ann_status knn_exact(const void* base, int64_t N, int d, ann_dtype dtype, const float* queries, int64_t nq, int k,
-                     bool exclude_self, hipStream_t stream, int32_t* out_ids, float* out_s)
+                     bool exclude_self, hipStream_t stream, int32_t* out_ids, float* out_s, const BuildCtx& ctx)
 {
     if (exclude_self) {
         if (dtype == ANN_U8)
             return knn_retrying<uint8_t, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype,
-                                                  static_cast<const uint8_t*>(base), N, k, true, stream, out_ids, out_s);
+                                                  static_cast<const uint8_t*>(base), N, k, true, stream, out_ids, out_s, ctx);
         return knn_retrying<float, float>(static_cast<const float*>(base), N, d, dtype, static_cast<const float*>(base),
-                                          N, k, true, stream, out_ids, out_s);
+                                          N, k, true, stream, out_ids, out_s, ctx);
     }
     if (dtype == ANN_U8)
         return knn_retrying<float, uint8_t>(static_cast<const uint8_t*>(base), N, d, dtype, queries, nq, k, false, stream,
-                                            out_ids, out_s);
+                                            out_ids, out_s, ctx);
     return knn_retrying<float, float>(static_cast<const float*>(base), N, d, dtype, queries, nq, k, false, stream,
-                                      out_ids, out_s);
+                                      out_ids, out_s, ctx);
 }
 
 }  // namespace tsdg

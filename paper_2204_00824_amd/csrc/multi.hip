@@ -371,7 +371,7 @@ struct MultiDispatch {
     hipStream_t stream;
     template <typename T, int G, int C> void operator()()
     {
-        hipLaunchKernelGGL((multi_kernel<T, G, C>), dim3((unsigned)a.t0, (unsigned)nq), dim3(256), 0, stream, a);
+        TSDG_LAUNCH((multi_kernel<T, G, C>), dim3((unsigned)a.t0, (unsigned)nq), dim3(256), 0, stream, a);
     }
 };
 }  // namespace
@@ -398,7 +398,7 @@ ann_status launch_search_multi(const MultiLaunch& s)
         set_error("unsupported row shape: d=%d dtype=%d", s.d, (int)s.dtype);
         return ANN_EUNSUPPORTED;
     }
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     MultiMergeArgs m;
     m.scratch = s.scratch;
     m.out_ids = s.out_ids;
@@ -406,8 +406,8 @@ ann_status launch_search_multi(const MultiLaunch& s)
     m.stats = s.stats;
     m.t0 = s.t0;
     m.k = s.k;
-    hipLaunchKernelGGL(multi_merge_kernel, dim3((unsigned)s.nq), dim3(256), 0, s.stream, m);
-    TSDG_HIP(hipGetLastError());
+    TSDG_LAUNCH(multi_merge_kernel, dim3((unsigned)s.nq), dim3(256), 0, s.stream, m);
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 

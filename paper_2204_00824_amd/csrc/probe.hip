@@ -8,6 +8,7 @@
 // chunk (the access shape of RowDist), several rows per wave in flight; a row's
 // words are xor-folded into one word that is written out, so no load can be dropped.
 #include "common.hpp"
+#include "../../include/tsdg_probe.h"
 
 namespace tsdg {
 
@@ -134,7 +135,7 @@ extern "C" ann_status ann_probe_mfma(int kind, int blocks, int iters, float* out
     else if (kind == 1) probe_mfma_kernel<1, false><<<blocks, 256, 0, st>>>(iters, out);
     else if (kind == 2) probe_mfma_kernel<0, true><<<blocks, 256, 0, st>>>(iters, out);
     else probe_mfma_kernel<1, true><<<blocks, 256, 0, st>>>(iters, out);
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 
@@ -157,6 +158,6 @@ extern "C" ann_status ann_probe_gather(const void* base, int64_t N, int row_byte
     else if (chunks <= 64) probe_gather_kernel<16><<<blocks, 256, 0, st>>>(b, (uint32_t)N, chunks, ids, n, out);
     else if (chunks <= 128) probe_gather_kernel<32><<<blocks, 256, 0, st>>>(b, (uint32_t)N, chunks, ids, n, out);
     else probe_gather_kernel<64><<<blocks, 256, 0, st>>>(b, (uint32_t)N, chunks, ids, n, out);
-    TSDG_HIP(hipGetLastError());
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }

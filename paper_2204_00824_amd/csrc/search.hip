@@ -244,8 +244,8 @@ template <typename T, int G, int C, int WAVES> static ann_status launch_variant(
             return ANN_EDEVICE;
         }
     }
-    hipLaunchKernelGGL((search_kernel<T, G, C, WAVES>), dim3((unsigned)s.nq), dim3(64 * WAVES), lds, s.stream, a);
-    TSDG_HIP(hipGetLastError());
+    TSDG_LAUNCH((search_kernel<T, G, C, WAVES>), dim3((unsigned)s.nq), dim3(64 * WAVES), lds, s.stream, a);
+    TSDG_HIP(launch_error());
     return ANN_OK;
 }
 

@@ -7,12 +7,13 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "tsdg_ann.h")
+PROBE_HEADER = os.path.join(ROOT, "include", "tsdg_probe.h")
 
 
-def declared_functions():
-    text = open(HEADER).read()
+def declared_functions(header=HEADER):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ann_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(ann_[a-z0-9_]+)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")
@@ -29,8 +30,25 @@ def test_header_declares_the_boundary():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    for name in declared_functions():
+    names = declared_functions()
+    assert len(names) >= 20 and "ann_search_multi_static" in names and "ann_knn_ex" in names
+    for name in names:
         assert hasattr(lib, name), f"{name} declared in tsdg_ann.h but not exported"
+
+
+def test_probes_are_declared_apart_from_the_boundary(lib):
+    """The two measurement probes live in the library but are no part of the method's header."""
+    probes = declared_functions(PROBE_HEADER)
+    assert probes == ["ann_probe_gather", "ann_probe_mfma"]
+    assert not [n for n in declared_functions() if "probe" in n]
+    for name in probes:
+        assert hasattr(lib, name)
+
+
+def test_the_library_reads_no_environment_variables():
+    pkg = os.path.join(ROOT, "paper_2204_00824_amd", "csrc")
+    for f in os.listdir(pkg):
+        assert "getenv" not in open(os.path.join(pkg, f)).read(), f
 
 
 def test_defaults_and_host_side_validation(lib):
@@ -38,6 +56,9 @@ def test_defaults_and_host_side_validation(lib):
     bp = api._BuildParams()
     lib.ann_build_params_default(C.byref(bp))
     assert (bp.dtype, bp.lambda0, bp.rev_cap, bp.metric) == (0, 9, 0, 0) and abs(bp.alpha - 1.2) < 1e-6
+    assert (bp.knn_filter, bp.knn_row_block, bp.progress_user) == (0, 0, None) and not bp.progress and not bp.stats
+    assert lib.ann_search_multi_workspace_bytes(16, 128) == 16 * 128 * 33 * 8
+    assert lib.ann_search_multi_workspace_bytes(0, 5) == 0
     sp = api._SearchParams()
     lib.ann_search_params_default(C.byref(sp))
     assert (sp.mode, sp.lambda_visit, sp.n_seeds, sp.seed, sp.max_hops, sp.metric) == (0, 0, 32, 0, 0, 0)

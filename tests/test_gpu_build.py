@@ -93,16 +93,34 @@ def test_knn_uint8(gpu, orc):
 
 @pytest.mark.parametrize("precise", [False, True])
 @pytest.mark.parametrize("d", [8, 96, 128, 960])
-def test_knn_real_valued_shapes(gpu, orc, d, precise, monkeypatch):
-    """Real-valued rows pass the filter as one scaled binary16 part, or (TSDG_KNN_PRECISE=1, also the
+def test_knn_real_valued_shapes(gpu, orc, d, precise):
+    """Real-valued rows pass the filter as one scaled binary16 part, or (knn_filter = 1, also the
     library's own fallback) as bf16 hi + lo parts: the lists equal the oracle's either way."""
     step(f"ann_knn gaussian d={d} precise={precise}")
-    if precise:
-        monkeypatch.setenv("TSDG_KNN_PRECISE", "1")
     base = workloads.single_gaussian(3000 if d < 900 else 1500, d, seed=100 + d)
     ref = orc.knn(base, 16)
-    ids, s = gpu.ann_knn(dev(base), 16)
+    ids, s, st = gpu.ann_knn(dev(base), 16, knn_filter=1 if precise else 0, want_stats=True)
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"knn d={d}") == 0
+    assert st["knn_contraction"] == (2 if precise else 1) and st["knn_ms"] > 0   # the form asked for is the one that ran
+
+
+@pytest.mark.parametrize("kind", ["int8", "real", "wide"])
+def test_knn_in_several_row_blocks(gpu, orc, kind):
+    """The sweep over all columns is repeated per block of query rows (2^21 rows by default); a small
+    knn_row_block runs that loop several times on a small set, last block ragged."""
+    step(f"ann_knn in row blocks of 512: {kind}")
+    if kind == "int8":
+        base = workloads.sift_like(N=1800, nq=1, seed=9)[0]
+    else:
+        base = workloads.single_gaussian(1800, 32 if kind == "real" else 160, seed=12)
+    ref = orc.knn(base, 16)
+    calls = []
+    ids, s = gpu.ann_knn(dev(base), 16, knn_row_block=512, progress=lambda step_, done, total: calls.append((step_, done, total)))
+    assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"row blocks {kind}") == 0
+    assert [c[1] for c in calls if c[0] == "knn-rows"] == [512, 1024, 1536, 1800]
+    assert all(c[1] <= c[2] == 1800 for c in calls if c[0] == "knn-sweep")
+    with pytest.raises(gpu.AnnError):
+        gpu.ann_knn(dev(base), 16, knn_row_block=100)
 
 
 @pytest.mark.parametrize("d", [16, 200])
@@ -219,7 +237,7 @@ def test_build_parameters(gpu, orc, kw):
     step(f"ann_build_graph params {kw}")
     base = workloads.single_gaussian(3000, 6, seed=31)
     base = np.concatenate([base, np.zeros((3000, 2), np.float32)], axis=1)       # d = 8
-    check_graph(gpu, orc, base, 16, str(kw), **kw)
+    assert check_graph(gpu, orc, base, 16, str(kw), **kw) == 0
 
 
 def test_build_hub_node(gpu, orc):
@@ -231,7 +249,7 @@ def test_build_hub_node(gpu, orc):
     pts /= np.linalg.norm(pts, axis=1, keepdims=True)
     pts *= g.uniform(5.0, 6.0, size=(2000, 1)).astype(np.float32)
     pts[0] = 0
-    check_graph(gpu, orc, pts, 8, "hub")
+    assert check_graph(gpu, orc, pts, 8, "hub") == 0
 
 
 def test_build_then_search_end_to_end(gpu, orc):

@@ -43,7 +43,7 @@ def test_calls_run_on_the_given_stream(gpu, orc):
         "knn": gpu.ann_knn(b[:5000].contiguous(), 16, stream=side),
         "bf": gpu.ann_bruteforce(b, q[:64], 10, stream=side),
     }
-    gpu.ann_search_multi(g1, b, q[:16], 10, 8, stream=side)      # sizes the graph's scratch buffer once
+    ws = torch.empty(gpu.ann_search_multi_workspace_bytes(16, 8), dtype=torch.uint8, device="cuda")  # the caller's workspace
     side.synchronize()
     # the search calls allocate nothing: they must run beside a busy default stream and finish before it
     outs = {k: [torch.empty(t.shape, dtype=torch.from_numpy(t).dtype, device="cuda") for t in ref[k]]
@@ -55,7 +55,7 @@ def test_calls_run_on_the_given_stream(gpu, orc):
         busy = torch.tanh(busy @ busy * 1e-3)
     gpu.ann_search_ex(g1, b, q, 10, 32, mode=1, lambda_visit=5, stream=side, out=tuple(outs["large"]))
     gpu.ann_search_ex(g1, b, q16, 10, 64, mode=2, lambda_visit=10, stream=side, out=tuple(outs["small"]))
-    gpu.ann_search_multi(g1, b, q16, 10, 8, stream=side, out=tuple(outs["multi"]))
+    gpu.ann_search_multi(g1, b, q16, 10, 8, stream=side, out=tuple(outs["multi"]), workspace=ws)
     gpu.ann_search_alg2(g1, b, q, 16, 0.0, stream=side, out=tuple(outs["alg2"]))
     side.synchronize()                          # the default stream is NOT waited for
     default_still_busy = not torch.cuda.default_stream().query()

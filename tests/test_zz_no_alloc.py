@@ -31,8 +31,13 @@ def call(gpu, entry, g, b, q, k, t0, seed):
     lib.ann_search_params_default(C.byref(prm))
     prm.seed = seed
     prm.stream = int(torch.cuda.current_stream().cuda_stream)
-    rc = getattr(lib, entry)(g.ptr, b.data_ptr(), q.data_ptr(), nq, k, t0, C.byref(prm), ids.data_ptr(),
-                             s.data_ptr(), st.data_ptr())
+    if entry == "ann_search_multi":         # the existing entry point takes the caller's workspace
+        ws = torch.empty(max(lib.ann_search_multi_workspace_bytes(nq, t0), 8), dtype=torch.uint8, device="cuda")
+        rc = lib.ann_search_multi(g.ptr, b.data_ptr(), q.data_ptr(), nq, k, t0, C.byref(prm), ws.data_ptr(), ws.numel(),
+                                  ids.data_ptr(), s.data_ptr(), st.data_ptr())
+    else:
+        rc = lib.ann_search_multi_static(g.ptr, b.data_ptr(), q.data_ptr(), nq, k, t0, C.byref(prm), ids.data_ptr(),
+                                         s.data_ptr(), st.data_ptr())
     torch.cuda.synchronize()
     return rc, ids.cpu().numpy(), s.cpu().numpy(), st.cpu().numpy()
 
