@@ -228,6 +228,12 @@ def main():
     K, k, d = 32, 10, 128
     lambda_visit = 5            # large-batch prefix (paper Sec. 5.4)
 
+    # a first, tiny build loads every build kernel's code (a kernel's first launch in a process costs a
+    # millisecond or two on the host, which would sit inside the stage times of the measured build)
+    warm = torch.from_numpy(np.random.default_rng(0).integers(0, 256, size=(4096, d)).astype(np.float32)).to(dev)
+    P.ann_build_graph_ex(warm, K)
+    del warm
+
     # ---- build (once, outside the timed search region; reported separately) and ground truth
     W = Workload(P, torch, args.n, args.nq, K, k, d, knn_alone=True)
     base, queries, graph, adj, lam, gt_h = W.base, W.queries, W.graph, W.adj, W.lam, W.gt_h
