@@ -57,70 +57,14 @@ __device__ __forceinline__ void pairwise(RD& rd, const T* __restrict__ base, con
     }
 }
 
-// The same matrix for rows that are integers in [0,255], m <= 64: the list's rows (centred int8) are
-// gathered into LDS once and their Gram matrix comes from the integer matrix cores; s(x_i, x_j) =
-// |x_i'|^2 + |x_j'|^2 - 2 x_i'.x_j' is exact in int32, and its conversion to fp32 is the canonical
-// value (an exact sum rounded once).  rows: [64][dp8 + 16] bytes, nrm: [64]; one wavefront.
+// Rows that are integers in [0,255] (uint8 storage, or fp32 that passes the test) take their pairwise distances
+// from the integer matrix cores: with the centred int8 copies x' = x - 128, s(x_i, x_j) = |x_i'|^2 + |x_j'|^2 -
+// 2 x_i'.x_j' is exact in int32, and its conversion to fp32 is the canonical value (an exact sum rounded once).
 struct I8Rows {
     const uint8_t* xc8;   // [N, dp8] centred rows, or null: use the general routine
     const int* xn8;       // [N] |x'|^2
     int dp8;
 };
-__device__ __forceinline__ void pairwise_i8(const I8Rows& x, const int32_t* ids, int m, float* P, int stride,
-                                            uint8_t* rows, int* nrm, int lane)
-{
-    const int XS = x.dp8 + 16;
-    const int cpr = x.dp8 / 16;  // 16-byte chunks per row
-    // eight of a lane's chunks are requested before the first is stored, so the list's rows arrive in one
-    // round trip (two beyond 128 bytes per row) instead of one per chunk
-    for (int t0 = 0; t0 < cpr; t0 += 8) {
-        intx4 v[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int c = lane + 64 * (t0 + t);
-            const int r = c / cpr, k = c % cpr;
-            v[t] = intx4{0, 0, 0, 0};
-            if (c < 64 * cpr && r < m) v[t] = *reinterpret_cast<const intx4*>(x.xc8 + (size_t)ids[r] * x.dp8 + k * 16);
-        }
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int c = lane + 64 * (t0 + t);
-            const int r = c / cpr, k = c % cpr;
-            if (c < 64 * cpr) *reinterpret_cast<intx4*>(rows + r * XS + k * 16) = v[t];
-        }
-    }
-    nrm[lane] = lane < m ? x.xn8[ids[lane]] : 0;
-    __syncthreads();
-    // 32x32 blocks (0,0), (0,1), (1,1) of the upper triangle, all three finished in registers before the first
-    // result is written: P may then lie over the staged rows (see stage2_kernel)
-    intx16 acc[3];
-#pragma unroll
-    for (int blk = 0; blk < 3; ++blk) {
-        const int bi = blk >> 1, bj = (blk + 1) >> 1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[blk][r] = 0;
-        if (bj * 32 >= m) continue;
-        for (int ks = 0; ks < x.dp8 / 32; ++ks) {
-            const intx4 A = *reinterpret_cast<const intx4*>(rows + (bi * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5));
-            const intx4 B = *reinterpret_cast<const intx4*>(rows + (bj * 32 + (lane & 31)) * XS + ks * 32 + 16 * (lane >> 5));
-            acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A, B, acc[blk], 0, 0, 0);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int blk = 0; blk < 3; ++blk) {
-        const int bi = blk >> 1, bj = (blk + 1) >> 1;
-        if (bj * 32 >= m) continue;
-        // lane l, register r: row i = 8*(r/4) + 4*(l/32) + r%4 of block bi, column j = l%32 of block bj
-        const int j = bj * 32 + (lane & 31);
-        const int nj = nrm[j];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = bi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (i < j && j < m) P[i * stride + j] = (float)(nrm[i] + nj - 2 * acc[blk][r]);
-        }
-    }
-}
 
 // ------------------------------------------------------------------ stage 1
 struct Stage1Args {
@@ -162,11 +106,7 @@ __global__ __launch_bounds__(64) void stage1_kernel(Stage1Args a)
     const uint64_t used = ballot64(id >= 0);
     const int m = used ? 64 - __builtin_clzll(used) : 0;   // lists are prefixes
     __syncthreads();
-    if (a.i8.xc8) {
-        int* nrm = reinterpret_cast<int*>(ids + K);
-        uint8_t* rows = reinterpret_cast<uint8_t*>(sm) + ((((size_t)K * K + 2 * (size_t)K + 64) * 4 + 15) & ~(size_t)15);
-        pairwise_i8(a.i8, ids, m, P, K, rows, nrm, lane);
-    } else {
+    {
         RD rd;
         rd.init(a.d, lane);
         pairwise(rd, base, ids, m, P, K);
@@ -351,12 +291,8 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     using RD = RowDist<T, G, C>;
     extern __shared__ float sm[];
     const int R = a.rev_cap;
-    // P and, on integer rows, the int8 copies of the list's rows share the front of the LDS block: the rows
-    // are dead once the products sit in registers (pairwise_i8), which leaves room for half as many
-    // workgroups again on a CU
-    const int front = a.i8.xc8 ? max(R * R, 16 * (a.i8.dp8 + 16)) : R * R;   // floats
     float* P = sm;                                         // [R*R], upper triangle used
-    float* s0 = P + front;                                 // [R]
+    float* s0 = P + R * R;                                 // [R]
     int32_t* ids = reinterpret_cast<int32_t*>(s0 + R);     // [R]
     int* lam = reinterpret_cast<int*>(ids + R);            // [R]
     const int64_t x0 = linear_block();
@@ -370,10 +306,7 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     }
     for (int i = lane; i < a.K; i += 64) a.packed[x0 * a.K + i] = kPackPad;
     __syncthreads();
-    if (a.i8.xc8) {
-        int* nrm = lam + R;
-        pairwise_i8(a.i8, ids, m, P, R, reinterpret_cast<uint8_t*>(sm), nrm, lane);
-    } else {
+    {
         RD rd;
         rd.init(a.d, lane);
         pairwise(rd, base, ids, m, P, R);
@@ -414,6 +347,232 @@ __global__ __launch_bounds__(64) void stage2_kernel(Stage2Args a)
     if (lane == 0 && lmax > 0) atomicMax(&a.max_lambda[x0 % kLambdaSlots], lmax);
 }
 
+// ------------------------------------------------------------------ integer rows: both stages on the accumulators
+// For rows that are integers in [0,255] the pairwise distances of a list are a Gram matrix on the integer matrix
+// cores (pairwise_i8 above says why that is the canonical value).  These two kernels never write that matrix
+// anywhere: each decision of Eq. 2 / Eq. 1 is taken on the accumulator that holds its distance, so a node needs no
+// LDS beyond the staged rows (a third of the matrix form's footprint: more waves per CU to hide the two dependent
+// round trips ids -> rows), and the lambda counts / the order by (lambda, s, id) become ballots instead of loops
+// over LDS.  One wavefront per node, kI8Waves nodes per workgroup; the waves share nothing, so there is no
+// barrier.  NB = 1: lists of at most 32 entries (one 32x32 block), NB = 2: up to 64 (three blocks of the upper
+// triangle).
+//
+// What makes the upper triangle enough: both stages receive their list sorted by (s, id), so s0[i] <= s0[j] for
+// i < j.  Edge i can occlude edge j only if s0[i] < s0[j] (Eq. 1; Eq. 2 asks alpha^2 s0[i] < s0[j] with alpha >= 1),
+// which fails for every i >= j -- the tests below need no index comparison, and pairs below the diagonal never count.
+constexpr int kI8Waves = 4;
+
+struct I8Slice {          // one wavefront's part of the workgroup's LDS
+    uint8_t* rows;        // [32 * NB][dp8 + 16] centred rows of the list, zero beyond its length
+    float* s0;            // [32 * NB] distance of each entry to the node (+inf beyond the list)
+    int* nrm;             // [32 * NB] |x'|^2
+    int32_t* ids;         // [32 * NB]
+    int XS;
+};
+template <int NB> __host__ __device__ constexpr size_t i8_slice_bytes(int dp8) { return (size_t)32 * NB * (dp8 + 16) + 3 * 32 * NB * 4; }
+template <int NB> __device__ __forceinline__ I8Slice i8_slice(uint8_t* smem, int wave, int dp8)
+{
+    I8Slice z;
+    z.XS = dp8 + 16;
+    z.rows = smem + (size_t)wave * i8_slice_bytes<NB>(dp8);
+    z.s0 = reinterpret_cast<float*>(z.rows + 32 * NB * z.XS);
+    z.nrm = reinterpret_cast<int*>(z.s0 + 32 * NB);
+    z.ids = z.nrm + 32 * NB;
+    return z;
+}
+
+// Lane e brings entry e of the list (id < 0: none).  Fills the slice and leaves the Gram blocks (0,0), (0,1), (1,1)
+// of the list's centred rows in acc: lane l, register r of block (bi,bj) holds x_i'.x_j' for
+// i = 32 bi + 8 (r / 4) + 4 (l / 32) + r % 4 and j = 32 bj + l % 32.
+template <int NB>
+__device__ __forceinline__ void gram_of_list(const I8Rows& x, const I8Slice& z, int32_t id, float s, int m, int lane,
+                                             intx16 (&acc)[2 * NB - 1])
+{
+    constexpr int ROWS = 32 * NB;
+    if (lane < ROWS) {
+        z.ids[lane] = id;
+        z.s0[lane] = lane < m ? s : kInfD;
+        z.nrm[lane] = lane < m ? x.xn8[id] : 0;
+    }
+    wave_sync();
+    const int cpr = x.dp8 / 16;  // 16-byte chunks per row
+    // eight of a lane's chunks are requested before the first is stored, so the list's rows arrive in one round trip
+    for (int t0 = 0; t0 * 64 < ROWS * cpr; t0 += 8) {
+        intx4 v[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int c = lane + 64 * (t0 + t);
+            const int r = c / cpr, k = c % cpr;
+            v[t] = intx4{0, 0, 0, 0};
+            if (r < m) v[t] = *reinterpret_cast<const intx4*>(x.xc8 + (size_t)z.ids[r] * x.dp8 + k * 16);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int c = lane + 64 * (t0 + t);
+            const int r = c / cpr, k = c % cpr;
+            if (r < ROWS) *reinterpret_cast<intx4*>(z.rows + r * z.XS + k * 16) = v[t];
+        }
+    }
+    wave_sync();
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[blk][r] = 0;
+        if (bj * 32 >= m) continue;   // wave-uniform
+        for (int ks = 0; ks < x.dp8 / 32; ++ks) {
+            const intx4 A = *reinterpret_cast<const intx4*>(z.rows + (bi * 32 + (lane & 31)) * z.XS + ks * 32 + 16 * (lane >> 5));
+            const intx4 B = *reinterpret_cast<const intx4*>(z.rows + (bj * 32 + (lane & 31)) * z.XS + ks * 32 + 16 * (lane >> 5));
+            acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A, B, acc[blk], 0, 0, 0);
+        }
+    }
+}
+
+// Stage 1 (Sec. 3.2, Eq. 2 with the order rule of Sec. 3.1).  Column j's lane collects the set O_j of entries i that
+// would occlude j if kept (alpha^2 s0[i] < s0[j] and alpha^2 s(x_i,x_j) < s0[j], the same fp32 products as the
+// general kernel); the sequential part is then  kept_j = (O_j and kept) is empty  on 64-bit masks.
+template <int NB>
+__global__ __launch_bounds__(64 * kI8Waves) void stage1_i8_kernel(Stage1Args a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_i8[];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t x0 = linear_block() * kI8Waves + wave;
+    if (x0 >= a.N) return;  // no barrier below: a wave past the last node just leaves
+    const int K = a.K;
+    const I8Slice z = i8_slice<NB>(smem_i8, wave, a.i8.dp8);
+
+    int32_t id = -1;
+    float s = kInfD;
+    if (lane < K) {
+        id = a.knn_id[x0 * K + lane];
+        s = a.knn_s[x0 * K + lane];
+    }
+    const uint64_t used = ballot64(id >= 0);
+    const int m = used ? 64 - __builtin_clzll(used) : 0;   // lists are prefixes
+    intx16 acc[2 * NB - 1];
+    gram_of_list<NB>(a.i8, z, id, s, m, lane, acc);
+
+    uint32_t part[2 * NB - 1];
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+        part[blk] = 0u;
+        if (bj * 32 >= m) continue;
+        const int j = bj * 32 + (lane & 31);
+        const float sj = z.s0[j];
+        const int nj = z.nrm[j];
+        uint32_t bits = 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i0 = bi * 32 + 8 * q + 4 * (lane >> 5);
+            const float4 si = *reinterpret_cast<const float4*>(z.s0 + i0);
+            const intx4 ni = *reinterpret_cast<const intx4*>(z.nrm + i0);
+            const float sv[4] = {si.x, si.y, si.z, si.w};
+            const int nv[4] = {ni.x, ni.y, ni.z, ni.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float pij = (float)(nv[t] + nj - 2 * acc[blk][4 * q + t]);
+                const float a1 = a.alpha2 * sv[t];
+                const float a2 = a.alpha2 * pij;
+                bits |= (a1 < sj && a2 < sj) ? (1u << (8 * q + t)) : 0u;
+            }
+        }
+        bits <<= 4 * (lane >> 5);
+        part[blk] = bits | (uint32_t)__shfl_xor((int)bits, 32, 64);   // both halves of the rows of this column
+    }
+    // lane e now assembles O_e: entries 0..31 from block (0,0) (e < 32) or (0,1), entries 32..63 from block (1,1)
+    uint64_t occ = part[0];
+    if constexpr (NB == 2) occ = lane < 32 ? (uint64_t)part[0] : ((uint64_t)part[1] | ((uint64_t)part[2] << 32));
+    uint64_t kept = m > 0 ? 1ull : 0ull;
+    for (int j = 1; j < m; ++j) {
+        const uint64_t oj = readlane64(occ, j);
+        if ((oj & kept) == 0ull) kept |= 1ull << j;
+    }
+    const int deg = popc64(kept);
+    const bool mine = (kept >> lane) & 1ull;
+    const int pos = popc64(kept & lanes_below(lane));
+    if (lane < K && lane >= deg) {
+        a.g1_id[x0 * K + lane] = -1;
+        a.g1_s[x0 * K + lane] = kInfD;
+    }
+    if (mine) {
+        a.g1_id[x0 * K + pos] = id;
+        a.g1_s[x0 * K + pos] = s;
+        atomicAdd(&a.indeg[id], 1u);
+    }
+    if (lane == 0) a.g1_deg[x0] = deg;
+}
+
+// Stage 2 (Sec. 3.3): lambda_j = #{i : s0[i] < s0[j] and s(x_i,x_j) < s0[j]} (Eq. 1 over the whole list), counted by
+// column j's two lanes over their sixteen rows of every block; then the order by (lambda, s, id) -- the list is in
+// (s, id) order already, so an entry's rank is the number of entries with a smaller lambda plus those of equal
+// lambda before it: one ballot per lambda value up to lambda0.
+template <int NB>
+__global__ __launch_bounds__(64 * kI8Waves) void stage2_i8_kernel(Stage2Args a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_i8[];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t x0 = linear_block() * kI8Waves + wave;
+    if (x0 >= a.N) return;  // no barrier below
+    const int R = a.rev_cap;
+    const I8Slice z = i8_slice<NB>(smem_i8, wave, a.i8.dp8);
+
+    const int m = a.g2_deg[x0];
+    int32_t id = -1;
+    float s = kInfD;
+    if (lane < m) {
+        id = a.g2_id[x0 * R + lane];
+        s = a.g2_s[x0 * R + lane];
+    }
+    intx16 acc[2 * NB - 1];
+    gram_of_list<NB>(a.i8, z, id, s, m, lane, acc);
+
+    int part[2 * NB - 1];
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+        part[blk] = 0;
+        if (bj * 32 >= m) continue;
+        const int j = bj * 32 + (lane & 31);
+        const float sj = z.s0[j];
+        const int nj = z.nrm[j];
+        int c = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i0 = bi * 32 + 8 * q + 4 * (lane >> 5);
+            const float4 si = *reinterpret_cast<const float4*>(z.s0 + i0);
+            const intx4 ni = *reinterpret_cast<const intx4*>(z.nrm + i0);
+            const float sv[4] = {si.x, si.y, si.z, si.w};
+            const int nv[4] = {ni.x, ni.y, ni.z, ni.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float pij = (float)(nv[t] + nj - 2 * acc[blk][4 * q + t]);
+                c += (sv[t] < sj && pij < sj) ? 1 : 0;
+            }
+        }
+        part[blk] = c + __shfl_xor(c, 32, 64);
+    }
+    int lam = part[0];
+    if constexpr (NB == 2) lam = lane < 32 ? part[0] : part[1] + part[2];
+
+    // order by (lambda, s, id); entries with lambda <= lambda0 come first in it, cut to K
+    const bool have = lane < m;
+    int rank = -1, count = 0, lmax = 0;
+    for (int v = 0; v <= a.lambda0 && count < a.K; ++v) {
+        const uint64_t mv = ballot64(have && lam == v);
+        if (!mv) continue;
+        if (have && lam == v) rank = count + popc64(mv & lanes_below(lane));
+        count += popc64(mv);
+        lmax = v;   // some entry of this lambda has a rank below K
+    }
+    if (rank >= 0 && rank < a.K) a.packed[x0 * a.K + rank] = (uint32_t)id | ((uint32_t)lam << kIdBits);
+    const int filled = min(count, a.K);
+    for (int t = filled + lane; t < a.K; t += 64) a.packed[x0 * a.K + t] = kPackPad;
+    if (lane == 0 && lmax > 0) atomicMax(&a.max_lambda[x0 % kLambdaSlots], lmax);
+}
+
 // ------------------------------------------------------------------ host driver
 namespace {
 struct DevBuf {
@@ -430,7 +589,6 @@ struct Stage1Launch {
     template <typename T, int G, int C> void operator()()
     {
         size_t lds = (size_t)a.K * a.K * 4 + (size_t)a.K * 8;
-        if (a.i8.xc8) lds = ((lds + 64 * 4 + 15) & ~(size_t)15) + 64 * (size_t)(a.i8.dp8 + 16);
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage1_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -443,10 +601,7 @@ struct Stage2Launch {
     hipError_t err = hipSuccess;
     template <typename T, int G, int C> void operator()()
     {
-        size_t front = (size_t)a.rev_cap * a.rev_cap * 4;   // P; on integer rows also the 64 staged rows (stage2_kernel)
-        if (a.i8.xc8) front = std::max(front, 64 * (size_t)(a.i8.dp8 + 16));
-        size_t lds = front + (size_t)a.rev_cap * 12;
-        if (a.i8.xc8) lds += 64 * 4;
+        size_t lds = (size_t)a.rev_cap * a.rev_cap * 4 + (size_t)a.rev_cap * 12;
         if (lds > 64 * 1024)
             err = hipFuncSetAttribute(reinterpret_cast<const void*>(&stage2_kernel<T, G, C>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -543,7 +698,17 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s1.a.alpha2 = alpha_on_s;
     s1.a.i8 = i8;
     s1.stream = stream;
-    if (!dispatch_row_shape(dtype, d, s1)) {
+    const dim3 i8_grid = folded_grid((N + kI8Waves - 1) / kI8Waves);
+    if (i8.xc8 && kI8Waves * i8_slice_bytes<2>(dp8) > 64 * 1024) {   // only rows wider than 192 bytes get there
+        for (const void* f : {reinterpret_cast<const void*>(&stage1_i8_kernel<2>), reinterpret_cast<const void*>(&stage2_i8_kernel<2>)})
+            TSDG_HIP(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kI8Waves * i8_slice_bytes<2>(dp8))));
+    }
+    if (i8.xc8) {   // integer rows: decisions taken on the matrix cores' accumulators
+        if (K <= 32)
+            TSDG_LAUNCH(stage1_i8_kernel<1>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<1>(dp8), stream, s1.a);
+        else
+            TSDG_LAUNCH(stage1_i8_kernel<2>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<2>(dp8), stream, s1.a);
+    } else if (!dispatch_row_shape(dtype, d, s1)) {
         set_error("unsupported row shape d=%d", d);
         return ANN_EUNSUPPORTED;
     }
@@ -604,7 +769,14 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s2.a.lambda0 = lambda0;
     s2.a.i8 = i8;
     s2.stream = stream;
-    dispatch_row_shape(dtype, d, s2);
+    if (i8.xc8) {
+        if (rev_cap <= 32)
+            TSDG_LAUNCH(stage2_i8_kernel<1>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<1>(dp8), stream, s2.a);
+        else
+            TSDG_LAUNCH(stage2_i8_kernel<2>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<2>(dp8), stream, s2.a);
+    } else {
+        dispatch_row_shape(dtype, d, s2);
+    }
     TSDG_HIP(s2.err);
     TSDG_HIP(launch_error());
     if (timed) TSDG_HIP(hipEventRecord(marks.ev[3], stream));
