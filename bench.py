@@ -413,6 +413,30 @@ def main():
             log(f"batch {bs}: {rows}")
         result["small_batch"] = small
 
+    # ---- where the batch regimes cross on this row shape (Sec. 4: the division depends on the device and on d): both
+    # kernels at the same L and lambda prefix, hence the same ids; ann_search's automatic mode switches at 4,096 queries
+    # for rows of this length (the other row lengths: bench_configs.py --workload crossover)
+    if not args.skip_small:
+        rows = []
+        for bs in (256, 512, 1024, 2048, 4096, 8192):
+            qb = queries[:bs].contiguous()
+            o = (torch.empty((bs, k), dtype=torch.int32, device=dev), torch.empty((bs, k), dtype=torch.float32, device=dev))
+            row = {"batch": bs}
+            for label, kw in (("wave_per_query", dict(mode=1)), ("workgroup_2_waves", dict(mode=2, waves_per_query=2)),
+                              ("workgroup_4_waves", dict(mode=2, waves_per_query=4))):
+                P.ann_search_ex(graph, base, qb, k, L, lambda_visit=lambda_visit, out=o, **kw)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    P.ann_search_ex(graph, base, qb, k, L, lambda_visit=lambda_visit, out=o, **kw)
+                e1.record()
+                torch.cuda.synchronize()
+                row[label + "_qps"] = round(bs / (e0.elapsed_time(e1) / 10) * 1e3)
+            rows.append(row)
+        result["batch_regime_crossover"] = {"L": L, "lambda_visit": lambda_visit, "table": rows}
+        log(f"crossover: {rows}")
+
     # ---- small-batch multi-search (Alg. 1): t0 greedy searches per query on separate workgroups
     if not args.skip_small:
         multi = {}

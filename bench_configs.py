@@ -281,9 +281,48 @@ def run_descent_1m(args):
     print(json.dumps(out), flush=True)
 
 
+def run_crossover(args):
+    """Where the workgroup-per-query kernel (mode 2) stops paying and the wave-per-query kernel (mode 1) takes over, by
+    row shape: queries/s of both at the same L and lambda prefix (so both return the same ids) over batch sizes 128..8192.
+    Sec. 4 says the division depends on the device and on d; api.hip's automatic mode takes its thresholds from this."""
+    import torch
+    import workloads
+    import paper_2204_00824_amd as P
+    K, k, L = 32, 10, 64
+    out = {"workload": "small/large batch crossover", "K": K, "k": k, "L": L, "lambda_visit": 5, "shapes": []}
+    shapes = (("deep-like d=96 fp32 (384 B rows)", lambda: workloads.deep_like(N=args.n or 1_000_000, nq=8192), None),
+              ("sift-like d=128 fp32 (512 B rows)", lambda: workloads.sift_like(N=args.n or 1_000_000, nq=8192), None),
+              ("sift-like d=128 uint8 (128 B rows)", lambda: workloads.sift_like(N=args.n or 1_000_000, nq=8192), "u8"),
+              ("gist-like d=960 fp32 (3840 B rows)", lambda: workloads.gist_like(N=args.n or 250_000, nq=8192), None))
+    for name, make, cast in shapes:
+        base_h, q_h = make()
+        base = torch.from_numpy(base_h).cuda()
+        if cast == "u8":
+            base = base.to(torch.uint8)
+        queries = torch.from_numpy(q_h).cuda()
+        graph = P.ann_build_graph_ex(base, K, progress=progress)
+        rows = []
+        for bs in (128, 256, 512, 1024, 2048, 4096, 8192):
+            q = queries[:bs].contiguous()
+            o = (torch.empty((bs, k), dtype=torch.int32, device="cuda"), torch.empty((bs, k), dtype=torch.float32, device="cuda"))
+            row = {"batch": bs}
+            for label, kw in (("wave_per_query", dict(mode=1)), ("workgroup_2_waves", dict(mode=2, waves_per_query=2)),
+                              ("workgroup_4_waves", dict(mode=2, waves_per_query=4)), ("workgroup_8_waves", dict(mode=2, waves_per_query=8))):
+                ms = timed_search(lambda: P.ann_search_ex(graph, base, q, k, L, lambda_visit=5, out=o, **kw), reps=10)
+                row[label + "_qps"] = round(bs / ms * 1e3)
+            best = max((v, n) for n, v in row.items() if n.endswith("_qps"))
+            row["fastest"] = best[1][:-4]
+            rows.append(row)
+            log(f"{name}: {row}")
+        out["shapes"].append({"rows": name, "N": base.shape[0], "table": rows})
+        del base, queries, graph
+        torch.cuda.empty_cache()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m", "descent1m"])
+    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m", "descent1m", "crossover"])
     ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
     ap.add_argument("--iters", type=int, default=20, help="scale100m_one_graph: most iterations of the propagation")
     args = ap.parse_args()
@@ -301,6 +340,8 @@ def main():
         run_whole_u8(args)
     elif args.workload == "descent1m":
         run_descent_1m(args)
+    elif args.workload == "crossover":
+        run_crossover(args)
     else:
         run_sharded_u8(args)
 

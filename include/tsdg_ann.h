@@ -128,7 +128,8 @@ typedef struct {
 
 /* Search parameters.  Defaults (ann_search_params_default): fp32 rows, mode 0
  * (auto: small-batch kernel below a batch-size threshold, large-batch kernel
- * above), lambda_visit 0 meaning "by mode" (Sec. 5.4: 10 for small batches, 5
+ * above; the threshold was measured per row length: 1,024 queries for rows of up
+ * to 128 bytes, 4,096 up to 512 bytes, 16,384 up to 2,048 bytes, 32,768 beyond), lambda_visit 0 meaning "by mode" (Sec. 5.4: 10 for small batches, 5
  * for large ones), n_seeds 32 (Alg. 2), seed 0, max_hops 0 = unbounded (the hop
  * limit T of Alg. 2), visited_slots 0 = chosen from mode and L, waves_per_query 0 =
  * chosen from d, qi_offset 0, stream NULL.

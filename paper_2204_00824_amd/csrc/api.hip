@@ -260,8 +260,19 @@ __global__ __launch_bounds__(256) void ip_augment_kernel(const float* __restrict
     }
 }
 
-// Batch size from which one wavefront per query fills the GPU (256 CUs x 32 wave slots).
-constexpr int kLargeBatchThreshold = 2048;
+// Batch size from which one wavefront per query is the faster kernel (Sec. 4: the division between small and large
+// batches depends on the device and on the row length).  Measured on MI355X at K = 32, L = 64, same lambda prefix for
+// both kernels, batches of 128..8192 queries: rows of 128 bytes change over at 1,024 queries, rows of 384 and 512
+// bytes at 4,096 (two wavefronts per query still win at 2,048), rows of 3,840 bytes not below 8,192 (four wavefronts
+// per query stay 7 % ahead there, the gap halving with every doubling).  Between the measured row lengths the
+// thresholds are stepped.
+static int large_batch_threshold(int row_bytes)
+{
+    if (row_bytes <= 128) return 1024;
+    if (row_bytes <= 512) return 4096;
+    if (row_bytes <= 2048) return 16384;
+    return 32768;
+}
 
 static int pow2_at_least(int v)
 {
@@ -667,11 +678,13 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     // batch regime (Sec. 4): below the threshold a query gets a whole workgroup
     const int row_bytes = g->d * (p.dtype == ANN_U8 ? 1 : (p.dtype == ANN_F16 ? 2 : 4));
     int mode = p.mode;
-    if (mode == 0) mode = nq >= kLargeBatchThreshold ? 1 : 2;
+    if (mode == 0) mode = nq >= large_batch_threshold(row_bytes) ? 1 : 2;
     int waves = 1;
     if (mode == 2) {
         waves = p.waves_per_query;
-        if (waves == 0) waves = row_bytes <= 512 ? 2 : (row_bytes <= 2048 ? 4 : 8);
+        // same measurement: up to 512-byte rows two wavefronts do as well as four or eight; long rows take eight
+        // for batches up to 512 queries and four beyond
+        if (waves == 0) waves = row_bytes <= 512 ? 2 : (row_bytes <= 2048 || nq > 512 ? 4 : 8);
         if (waves != 1 && waves != 2 && waves != 4 && waves != 8) {
             set_error("ann_search: waves_per_query must be 0, 1, 2, 4 or 8");
             return ANN_EINVAL;

@@ -276,3 +276,21 @@ def test_binary16_storage(gpu, orc, d):
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "f16 alg2") == 0
     with pytest.raises(gpu.AnnError):      # not a type the build takes
         gpu.ann_build_graph_ex(hb, 8)
+
+
+def test_automatic_mode_by_row_length(gpu, orc):
+    """mode 0 picks the kernel from the batch size and the row length (thresholds measured per row length); whichever
+    it picks, with the visited prefix given the ids are those of either explicit mode."""
+    step("search: automatic batch regime")
+    base, queries, adj, lam, _ = sift_case(orc)
+    g = gpu.ann_graph_import(dev(adj), dev(lam), base.shape[1])
+    b = dev(base)
+    q = dev(np.tile(queries, (20, 1))[:5000])          # 5,000 queries: above the 4,096 of 512-byte rows
+    ref = gpu.ann_search_ex(g, b, q, 10, 32, mode=1, lambda_visit=5)
+    for nq in (5000, 4095, 300):
+        ids, s = gpu.ann_search_ex(g, b, q[:nq].contiguous(), 10, 32, mode=0, lambda_visit=5)
+        assert_bitwise(ids.cpu().numpy(), ref[0][:nq].cpu().numpy(), f"auto nq={nq}")
+    b8 = dev(base.astype(np.uint8))                    # 128-byte rows: the change-over is at 1,024 queries
+    ref8 = gpu.ann_search_ex(g, b8, q[:1500].contiguous(), 10, 32, mode=2, lambda_visit=5)
+    ids, s = gpu.ann_search_ex(g, b8, q[:1500].contiguous(), 10, 32, mode=0, lambda_visit=5)
+    assert_bitwise(ids.cpu().numpy(), ref8[0].cpu().numpy(), "auto uint8")
