@@ -573,6 +573,320 @@ __global__ __launch_bounds__(64 * kI8Waves) void stage2_i8_kernel(Stage2Args a)
     if (lane == 0 && lmax > 0) atomicMax(&a.max_lambda[x0 % kLambdaSlots], lmax);
 }
 
+// ------------------------------------------------------------------ real-valued rows: Gram matrix with an error band
+// The canonical distance of real-valued rows (fp32 difference, fp64 sum) has no exact matrix form, but the DECISIONS of
+// Eq. 2 / Eq. 1 only compare s(x_i,x_j) with s0[j], and most of those comparisons are not close.  So the pairwise
+// values come from the matrix cores as an approximation with a proven error band, and only a comparison that falls
+// inside the band is decided by the canonical distance of that one pair (computed by the whole wavefront).  The
+// adjacency that results is the one the general kernels (pairwise above) give; what changes is the work: each row
+// of a list is read once instead of once per four pairs, and 2,016 canonical distances per node shrink to a handful.
+//
+// Approximation.  With y_i = fl32(x_i - x_0) (x_0 the node's own row; |y_i|^2 is s0[i] up to rounding),
+// s(x_i,x_j) = |y_i|^2 + |y_j|^2 - 2 y_i.y_j up to rounding, and y_i.y_j is taken on v_mfma_f32_32x32x16_bf16 from
+// y = hi + lo (bf16 each) as hi.hi + hi.lo + lo.hi with fp32 accumulation.  Error of P~ = s0[i] + s0[j] - 2 dot against
+// the canonical s(x_i,x_j):
+//   parts dropped or rounded (lo.lo, the remainder of hi + lo):      2 * 1.6 * 2^-18 * sqrt(s0[i] s0[j])
+//   fp32 accumulation of 3 dp products:                              2 * 1.5 * dp * 2^-24 * sqrt(s0[i] s0[j])
+//   fl32 of the differences x_i - x_j against y_i - y_j, of s0, of P~: below 2^-20 (s0[i] + s0[j])
+// and sqrt(ab) <= (a + b) / 2, so |P~ - s| <= err * (s0[i] + s0[j]) with err = 1.5 * (1.6 * 2^-18 + 1.5 dp 2^-24 + 2^-20)
+// (1.5: margin), plus a floor of 1e-30 that sends data at the bottom of the fp32 range (flushed by the matrix cores)
+// to the exact path.  A value that is not finite (overflow of the products) counts as inside the band.  Both stages
+// need s0[i] < s0[j] (times alpha^2 in stage 1) exactly, which they have: the s0 are canonical values.
+constexpr int kSlab = 32;                 // elements of k per staging step
+constexpr int kSlabStride = kSlab + 8;    // bf16 elements per staged row: 80 bytes, conflict-free 16-byte fragment reads
+
+struct F32Slice {
+    uint16_t* hi;      // [32 * NB][kSlabStride]
+    uint16_t* lo;
+    float* s0;         // [32 * NB], +inf beyond the list
+    int32_t* ids;      // [32 * NB]
+    uint64_t* fix;     // [32 * NB] what the exact path adds for column j (a count in stage 2, a mask in stage 1)
+};
+template <int NB> __host__ __device__ constexpr size_t f32_slice_bytes() { return (size_t)32 * NB * (2 * kSlabStride * 2 + 4 + 4 + 8); }
+template <int NB> __device__ __forceinline__ F32Slice f32_slice(uint8_t* smem, int wave)
+{
+    F32Slice z;
+    uint8_t* p = smem + (size_t)wave * f32_slice_bytes<NB>();
+    z.fix = reinterpret_cast<uint64_t*>(p);
+    z.hi = reinterpret_cast<uint16_t*>(p + 32 * NB * 8);
+    z.lo = z.hi + 32 * NB * kSlabStride;
+    z.s0 = reinterpret_cast<float*>(z.lo + 32 * NB * kSlabStride);
+    z.ids = reinterpret_cast<int32_t*>(z.s0 + 32 * NB);
+    return z;
+}
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 dv_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float dv_floatx16;
+
+__device__ __forceinline__ uint32_t dv_bf16_rne(float v)
+{
+    const uint32_t b = __float_as_uint(v);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+// canonical s(x_a, x_b) by all 64 lanes: fp32 differences, squares summed in fp64, one rounding
+__device__ __forceinline__ float canonical_pair(const float* __restrict__ base, int d, int64_t a, int64_t b, int lane)
+{
+    double acc = 0.0;
+    for (int k = 4 * lane; k < d; k += 256) {
+        const float4 u = *reinterpret_cast<const float4*>(base + a * d + k);
+        const float4 v = *reinterpret_cast<const float4*>(base + b * d + k);
+        const float t0 = u.x - v.x, t1 = u.y - v.y, t2 = u.z - v.z, t3 = u.w - v.w;
+        acc += (double)t0 * (double)t0;
+        acc += (double)t1 * (double)t1;
+        acc += (double)t2 * (double)t2;
+        acc += (double)t3 * (double)t3;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += shfl_xor_f64(acc, o);
+    return (float)acc;
+}
+
+// Lane e brings entry e of the list.  Leaves y_i.y_j of the list's rows (centred at the node) in acc, laid out as in
+// gram_of_list: lane l, register r of block (bi,bj) holds the pair i = 32 bi + 8 (r / 4) + 4 (l / 32) + r % 4, j = 32 bj + l % 32.
+template <int NB>
+__device__ __forceinline__ void gram_of_list_f32(const float* __restrict__ base, int d, int64_t x0, const F32Slice& z,
+                                                 int32_t id, float s, int m, int lane, dv_floatx16 (&acc)[2 * NB - 1])
+{
+    constexpr int ROWS = 32 * NB;
+    constexpr int RT = ROWS / 8;   // rows this lane converts per slab
+    if (lane < ROWS) {
+        z.ids[lane] = lane < m ? id : (int32_t)x0;
+        z.s0[lane] = lane < m ? s : kInfD;
+        z.fix[lane] = 0ull;
+    }
+    wave_sync();
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[blk][r] = 0.f;
+    const int kc = lane & 7;   // this lane's 16-byte chunk of a slab row
+    int64_t rid[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) rid[t] = (int64_t)z.ids[(lane >> 3) + 8 * t];
+    for (int k0 = 0; k0 < d; k0 += kSlab) {
+        const int k = k0 + 4 * kc;
+        const bool in = k < d;
+        float4 c0 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (in) c0 = *reinterpret_cast<const float4*>(base + x0 * d + k);
+        float4 v[RT];
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            v[t] = c0;   // a row past the list, or a column past d, becomes a zero row / column
+            if (in && (lane >> 3) + 8 * t < m) v[t] = *reinterpret_cast<const float4*>(base + rid[t] * d + k);
+        }
+        wave_sync();   // the fragment reads of the slab before are done
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            const int r = (lane >> 3) + 8 * t;
+            const float y[4] = {v[t].x - c0.x, v[t].y - c0.y, v[t].z - c0.z, v[t].w - c0.w};
+            uint32_t h[4], l[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                h[e] = dv_bf16_rne(y[e]);
+                l[e] = dv_bf16_rne(y[e] - __uint_as_float(h[e] << 16));
+            }
+            *reinterpret_cast<uint2*>(z.hi + r * kSlabStride + 4 * kc) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            *reinterpret_cast<uint2*>(z.lo + r * kSlabStride + 4 * kc) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+        }
+        wave_sync();
+#pragma unroll
+        for (int ks = 0; ks < kSlab / 16; ++ks) {
+            dv_bf16x8 fh[NB], fl[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int off = (b * 32 + (lane & 31)) * kSlabStride + ks * 16 + 8 * (lane >> 5);
+                fh[b] = __builtin_bit_cast(dv_bf16x8, *reinterpret_cast<const uint4*>(z.hi + off));
+                fl[b] = __builtin_bit_cast(dv_bf16x8, *reinterpret_cast<const uint4*>(z.lo + off));
+            }
+#pragma unroll
+            for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+                const int bi = blk >> 1, bj = (blk + 1) >> 1;
+                if (bj * 32 >= m) continue;   // wave-uniform
+                acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[bi], fh[bj], acc[blk], 0, 0, 0);
+                acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[bi], fl[bj], acc[blk], 0, 0, 0);
+                acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[bi], fh[bj], acc[blk], 0, 0, 0);
+            }
+        }
+    }
+}
+
+// Decides "s(x_i,x_j) times f below s0[j]" (f = 1 in stage 2, alpha^2 in stage 1) for every pair of the list that
+// passes `first` (the exact half of the rule), from the banded approximation; returns per block the pairs that are
+// surely true (bit r of sure[blk]) and leaves the undecided ones in open[blk].
+template <int NB, typename First>
+__device__ __forceinline__ void banded_decisions(const F32Slice& z, const dv_floatx16 (&acc)[2 * NB - 1], int m, int lane, float f,
+                                                 float err, First first, uint32_t (&sure)[2 * NB - 1], uint32_t (&open)[2 * NB - 1])
+{
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+        sure[blk] = 0u;
+        open[blk] = 0u;
+        if (bj * 32 >= m) continue;
+        const float sj = z.s0[bj * 32 + (lane & 31)];
+        const bool column = bj * 32 + (lane & 31) < m;   // a column past the list has s0 = +inf: nothing to decide there
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 si = *reinterpret_cast<const float4*>(z.s0 + bi * 32 + 8 * q + 4 * (lane >> 5));
+            const float sv[4] = {si.x, si.y, si.z, si.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int r = 4 * q + t;
+                const float sum = sv[t] + sj;
+                const float p = sum - 2.f * acc[blk][r];
+                const float e = err * sum + 1.0e-30f;
+                const bool ft = column & first(sv[t], sj);
+                const bool yes = f * (p + e) < sj;              // the canonical value is below p + e: surely true
+                const bool no = f * fmaxf(p - e, 0.f) >= sj;    // and above p - e: surely false (false too when p is not finite)
+                sure[blk] |= (uint32_t)(ft & yes) << r;
+                open[blk] |= (uint32_t)(ft & !yes & !no) << r;
+            }
+        }
+    }
+}
+
+// Runs `decide(i, j, s)` (wave-uniform arguments, s the canonical distance) for every undecided pair.
+template <int NB, typename Decide>
+__device__ __forceinline__ void settle_open_pairs(const float* __restrict__ base, int d, const F32Slice& z,
+                                                  const uint32_t (&open)[2 * NB - 1], int lane, Decide decide)
+{
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        const int bi = blk >> 1, bj = (blk + 1) >> 1;
+        if (!ballot64(open[blk] != 0u)) continue;
+#pragma unroll 1
+        for (int r = 0; r < 16; ++r) {
+            for (uint64_t um = ballot64((open[blk] >> r) & 1u); um; um &= um - 1) {
+                const int l = ctz64(um);
+                const int i = bi * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), j = bj * 32 + (l & 31);
+                decide(i, j, canonical_pair(base, d, (int64_t)z.ids[i], (int64_t)z.ids[j], lane));
+            }
+        }
+    }
+}
+
+struct F32Extra {
+    float err;   // error band of the approximate pairwise distance, as a multiple of s0[i] + s0[j]
+};
+
+template <int NB>
+__global__ __launch_bounds__(64 * kI8Waves) void stage1_f32_kernel(Stage1Args a, F32Extra x)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_f32[];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t x0 = linear_block() * kI8Waves + wave;
+    if (x0 >= a.N) return;  // no barrier below
+    const int K = a.K;
+    const F32Slice z = f32_slice<NB>(smem_f32, wave);
+    const float* __restrict__ base = static_cast<const float*>(a.base);
+
+    int32_t id = -1;
+    float s = kInfD;
+    if (lane < K) {
+        id = a.knn_id[x0 * K + lane];
+        s = a.knn_s[x0 * K + lane];
+    }
+    const uint64_t used = ballot64(id >= 0);
+    const int m = used ? 64 - __builtin_clzll(used) : 0;
+    dv_floatx16 acc[2 * NB - 1];
+    gram_of_list_f32<NB>(base, a.d, x0, z, id, s, m, lane, acc);
+
+    const float alpha2 = a.alpha2;
+    uint32_t sure[2 * NB - 1], open[2 * NB - 1];
+    banded_decisions<NB>(z, acc, m, lane, alpha2, x.err, [alpha2](float si, float sj) { return alpha2 * si < sj; }, sure, open);
+    settle_open_pairs<NB>(base, a.d, z, open, lane, [&](int i, int j, float sij) {
+        if (lane == 0 && alpha2 * sij < z.s0[j]) z.fix[j] |= 1ull << i;
+    });
+    wave_sync();
+    uint32_t part[2 * NB - 1];
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        // register r of this lane is entry 8 (r / 4) + 4 (lane / 32) + r % 4 of the block's rows
+        uint32_t bits = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) bits |= ((sure[blk] >> r) & 1u) << (8 * (r >> 2) + (r & 3));
+        bits <<= 4 * (lane >> 5);
+        part[blk] = bits | (uint32_t)__shfl_xor((int)bits, 32, 64);
+    }
+    uint64_t occ = part[0];
+    if constexpr (NB == 2) occ = lane < 32 ? (uint64_t)part[0] : ((uint64_t)part[1] | ((uint64_t)part[2] << 32));
+    if (lane < 32 * NB) occ |= z.fix[lane];
+    uint64_t kept = m > 0 ? 1ull : 0ull;
+    for (int j = 1; j < m; ++j) {
+        const uint64_t oj = readlane64(occ, j);
+        if ((oj & kept) == 0ull) kept |= 1ull << j;
+    }
+    const int deg = popc64(kept);
+    const bool mine = (kept >> lane) & 1ull;
+    const int pos = popc64(kept & lanes_below(lane));
+    if (lane < K && lane >= deg) {
+        a.g1_id[x0 * K + lane] = -1;
+        a.g1_s[x0 * K + lane] = kInfD;
+    }
+    if (mine) {
+        a.g1_id[x0 * K + pos] = id;
+        a.g1_s[x0 * K + pos] = s;
+        atomicAdd(&a.indeg[id], 1u);
+    }
+    if (lane == 0) a.g1_deg[x0] = deg;
+}
+
+template <int NB>
+__global__ __launch_bounds__(64 * kI8Waves) void stage2_f32_kernel(Stage2Args a, F32Extra x)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_f32[];
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+    const int64_t x0 = linear_block() * kI8Waves + wave;
+    if (x0 >= a.N) return;  // no barrier below
+    const int R = a.rev_cap;
+    const F32Slice z = f32_slice<NB>(smem_f32, wave);
+    const float* __restrict__ base = static_cast<const float*>(a.base);
+
+    const int m = a.g2_deg[x0];
+    int32_t id = -1;
+    float s = kInfD;
+    if (lane < m) {
+        id = a.g2_id[x0 * R + lane];
+        s = a.g2_s[x0 * R + lane];
+    }
+    dv_floatx16 acc[2 * NB - 1];
+    gram_of_list_f32<NB>(base, a.d, x0, z, id, s, m, lane, acc);
+
+    uint32_t sure[2 * NB - 1], open[2 * NB - 1];
+    banded_decisions<NB>(z, acc, m, lane, 1.f, x.err, [](float si, float sj) { return si < sj; }, sure, open);
+    settle_open_pairs<NB>(base, a.d, z, open, lane, [&](int i, int j, float sij) {
+        (void)i;
+        if (lane == 0 && sij < z.s0[j]) z.fix[j] += 1ull;
+    });
+    wave_sync();
+    int part[2 * NB - 1];
+#pragma unroll
+    for (int blk = 0; blk < 2 * NB - 1; ++blk) {
+        const int c = __popc(sure[blk]);
+        part[blk] = c + __shfl_xor(c, 32, 64);
+    }
+    int lam = part[0];
+    if constexpr (NB == 2) lam = lane < 32 ? part[0] : part[1] + part[2];
+    if (lane < 32 * NB) lam += (int)z.fix[lane];
+
+    const bool have = lane < m;
+    int rank = -1, count = 0, lmax = 0;
+    for (int v = 0; v <= a.lambda0 && count < a.K; ++v) {
+        const uint64_t mv = ballot64(have && lam == v);
+        if (!mv) continue;
+        if (have && lam == v) rank = count + popc64(mv & lanes_below(lane));
+        count += popc64(mv);
+        lmax = v;
+    }
+    if (rank >= 0 && rank < a.K) a.packed[x0 * a.K + rank] = (uint32_t)id | ((uint32_t)lam << kIdBits);
+    const int filled = min(count, a.K);
+    for (int t = filled + lane; t < a.K; t += 64) a.packed[x0 * a.K + t] = kPackPad;
+    if (lane == 0 && lmax > 0) atomicMax(&a.max_lambda[x0 % kLambdaSlots], lmax);
+}
+
 // ------------------------------------------------------------------ host driver
 namespace {
 struct DevBuf {
@@ -699,6 +1013,12 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
     s1.a.i8 = i8;
     s1.stream = stream;
     const dim3 i8_grid = folded_grid((N + kI8Waves - 1) / kI8Waves);
+    const bool banded = !i8.xc8 && dtype == ANN_F32 && K <= 64 && rev_cap <= 64;
+    F32Extra fx;
+    {
+        const double dpad = (double)((d + kSlab - 1) / kSlab * kSlab);
+        fx.err = (float)(1.5 * (1.6 / 262144.0 + 1.5 * dpad / 16777216.0 + 1.0 / 1048576.0));
+    }
     if (i8.xc8 && kI8Waves * i8_slice_bytes<2>(dp8) > 64 * 1024) {   // only rows wider than 192 bytes get there
         for (const void* f : {reinterpret_cast<const void*>(&stage1_i8_kernel<2>), reinterpret_cast<const void*>(&stage2_i8_kernel<2>)})
             TSDG_HIP(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kI8Waves * i8_slice_bytes<2>(dp8))));
@@ -708,6 +1028,11 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
             TSDG_LAUNCH(stage1_i8_kernel<1>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<1>(dp8), stream, s1.a);
         else
             TSDG_LAUNCH(stage1_i8_kernel<2>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<2>(dp8), stream, s1.a);
+    } else if (banded) {   // real-valued fp32 rows, lists of at most 64: banded Gram matrix, exact only inside the band
+        if (K <= 32)
+            TSDG_LAUNCH(stage1_f32_kernel<1>, i8_grid, dim3(64 * kI8Waves), kI8Waves * f32_slice_bytes<1>(), stream, s1.a, fx);
+        else
+            TSDG_LAUNCH(stage1_f32_kernel<2>, i8_grid, dim3(64 * kI8Waves), kI8Waves * f32_slice_bytes<2>(), stream, s1.a, fx);
     } else if (!dispatch_row_shape(dtype, d, s1)) {
         set_error("unsupported row shape d=%d", d);
         return ANN_EUNSUPPORTED;
@@ -774,6 +1099,11 @@ ann_status diversify(const void* base, int64_t N, int d, ann_dtype dtype, int K,
             TSDG_LAUNCH(stage2_i8_kernel<1>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<1>(dp8), stream, s2.a);
         else
             TSDG_LAUNCH(stage2_i8_kernel<2>, i8_grid, dim3(64 * kI8Waves), kI8Waves * i8_slice_bytes<2>(dp8), stream, s2.a);
+    } else if (banded) {
+        if (rev_cap <= 32)
+            TSDG_LAUNCH(stage2_f32_kernel<1>, i8_grid, dim3(64 * kI8Waves), kI8Waves * f32_slice_bytes<1>(), stream, s2.a, fx);
+        else
+            TSDG_LAUNCH(stage2_f32_kernel<2>, i8_grid, dim3(64 * kI8Waves), kI8Waves * f32_slice_bytes<2>(), stream, s2.a, fx);
     } else {
         dispatch_row_shape(dtype, d, s2);
     }

@@ -240,6 +240,22 @@ def test_build_parameters(gpu, orc, kw):
     assert check_graph(gpu, orc, base, 16, str(kw), **kw) == 0
 
 
+@pytest.mark.parametrize("K,scale", [(16, 0.37), (40, 1.0 / 3.0)])
+def test_build_real_valued_near_ties(gpu, orc, K, scale):
+    """Real-valued rows take their pairwise distances from the matrix cores with an error band and decide a
+    comparison of Eq. 2 / Eq. 1 exactly only inside it.  A scaled integer lattice is all near-ties: equal lattice
+    offsets give distances that differ in the last bits (the scaled coordinates are rounded), so most comparisons
+    fall inside the band and are settled by the canonical distance; K = 40 runs the three-block (lists up to 64) form.
+    Exact copies of a row (distance 0) ride along."""
+    step(f"ann_build_graph real-valued lattice K={K}")
+    lat = workloads.integer_lattice(25).astype(np.float32)          # 625 points
+    pts = np.zeros((625 + 6, 4), np.float32)
+    pts[:625, :2] = lat * np.float32(scale)
+    pts[625:] = pts[[7, 7, 300, 300, 300, 624]]
+    assert not np.array_equal(pts, np.rint(pts))                     # not the integer-row path
+    assert check_graph(gpu, orc, pts, K, f"lattice x {scale}", lambda0=30 if K > 32 else 9) == 0
+
+
 def test_build_hub_node(gpu, orc):
     """A star: one centre that is the nearest neighbour of everybody gets an in-degree far
     above rev_cap; the cut must keep its (s,id)-smallest reverse edges."""
