@@ -927,28 +927,45 @@ struct CompactArgs {
 // entries below D all stay and of those equal to D as many as still fit (the dropped ones are not
 // below the new threshold, which is all the filter's invariant asks for).  No sorting, no LDS.
 template <int R>
-__device__ __forceinline__ float keep_smallest(uint64_t* __restrict__ g, const uint64_t (&e)[R], int kprime, int lane)
+__device__ __forceinline__ float keep_smallest(uint64_t* __restrict__ g, const uint64_t (&e)[R], int n, int kprime, int lane)
 {
     uint32_t dist[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) dist[r] = (uint32_t)(e[r] >> 32);
-    uint32_t lo = 0u, hi = 0x7F800000u;  // count(dist <= hi) >= kprime holds: real entries are finite
-    while (lo < hi) {
+    // The kprime-th smallest lies between the smallest and the largest distance present (n >= kprime entries, all
+    // finite), which for a row's candidates is a far narrower interval of bit patterns than [0, +inf): fewer
+    // bisection steps.  Register slots past the row's n entries (wave-uniform) are skipped in every count.
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r * 64 >= n) continue;
+        lo = min(lo, dist[r]);
+        if (dist[r] != 0xFFFFFFFFu) hi = max(hi, dist[r]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
+        hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
+    }
+    while (lo < hi) {   // invariant: count(dist <= hi) >= kprime
         const uint32_t mid = lo + (hi - lo) / 2u;
         int c = 0;
 #pragma unroll
-        for (int r = 0; r < R; ++r) c += popc64(ballot64(dist[r] <= mid));
+        for (int r = 0; r < R; ++r)
+            if (r * 64 < n) c += popc64(ballot64(dist[r] <= mid));
         if (c >= kprime) hi = mid;
         else lo = mid + 1u;
     }
     const uint32_t D = lo;
     int below = 0;
 #pragma unroll
-    for (int r = 0; r < R; ++r) below += popc64(ballot64(dist[r] < D));
+    for (int r = 0; r < R; ++r)
+        if (r * 64 < n) below += popc64(ballot64(dist[r] < D));
     const int need = kprime - below;  // >= 1 entries equal to D are kept
     int base = 0, ties = 0;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
+        if (r * 64 >= n) continue;
         const bool lt = dist[r] < D, eq = dist[r] == D;
         const uint64_t meq = ballot64(eq);
         const bool keep = lt || (eq && ties + popc64(meq & lanes_below(lane)) < need);
@@ -980,7 +997,7 @@ __global__ __launch_bounds__(256) void compact_kernel(CompactArgs a)
     uint64_t e[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) e[r] = lane + 64 * r < (int)n ? g[lane + 64 * r] : kKeyEmpty;
-    const float D = keep_smallest<R>(g, e, a.kprime, lane);
+    const float D = keep_smallest<R>(g, e, (int)n, a.kprime, lane);
     if (lane == 0) {
         a.cnt[row] = (unsigned)a.kprime;
         a.kept[row] = (unsigned)a.kprime;
