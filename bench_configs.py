@@ -322,7 +322,7 @@ def run_crossover(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", required=True, choices=["gist1m", "deep10m", "scale100m", "scale100m_one_graph", "glove1m", "descent1m", "crossover"])
+    ap.add_argument("--workload", required=True, choices=["gist1m", "gist1m_latent", "deep10m", "scale100m", "scale100m_one_graph", "glove1m", "descent1m", "crossover"])
     ap.add_argument("--n", type=int, default=0, help="override the number of base rows")
     ap.add_argument("--iters", type=int, default=20, help="scale100m_one_graph: most iterations of the propagation")
     args = ap.parse_args()
@@ -330,6 +330,9 @@ def main():
     if args.workload == "gist1m":
         base, q = workloads.gist_like(N=args.n or 1_000_000)
         run_single_graph(args, "gist-like", base, q, (10,), (32, 64, 128, 256, 512))
+    elif args.workload == "gist1m_latent":
+        base, q = workloads.gist_like_latent(N=args.n or 1_000_000)
+        run_single_graph(args, "gist-shaped, latent-factor recipe (ours)", base, q, (10,), (32, 64, 128, 256, 512))
     elif args.workload == "deep10m":
         base, q = workloads.deep_like(N=args.n or 10_000_000)
         run_single_graph(args, "deep-like", base, q, (10, 100), (64, 128, 256, 512))
