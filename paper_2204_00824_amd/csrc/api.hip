@@ -707,6 +707,9 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     if (slots == 0) {
         if (mode == 1) {
             slots = L <= 128 ? 1280 : 1024;
+            // byte rows of at most 128 elements run eight waves per SIMD (63 registers), so a CU holds 32
+            // queries when a query's LDS stays near 5 KB; re-scoring a 128-byte row is cheap
+            if (p.dtype == ANN_U8 && g->d <= 128 && L <= 128) slots = 768;
         } else if (nq <= 512) {
             slots = 8192;
         } else {

@@ -185,6 +185,72 @@ template <typename T, int G, int C> struct RowDist {
         return (float)group_sum(partial<FULL>(buf));
     }
 
+    // uint8 rows, q_int set: the integer route alone.  A kernel that calls this and distance_from
+    // (never distance) keeps no fp32 copy of the query in registers.
+    template <bool FULL = false> __device__ __forceinline__ float distance_int(const chunk_t (&buf)[C]) const
+    {
+        static_assert(sizeof(T) == 1, "integer route: uint8 rows only");
+        uint32_t xx = 0u, qx = 0u;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (FULL || has(c)) {
+                const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xx = __builtin_amdgcn_udot4(w[i], w[i], xx, false);
+                    qx = __builtin_amdgcn_udot4(qbytes[c * 4 + i], w[i], qx, false);
+                }
+            }
+        }
+        return (float)group_sum_u32(xx - 2u * qx + qq);
+    }
+    // uint8 rows, any query: the fp64 route with the query read from LDS at every use (qrow = the whole fp32
+    // query row, 16-byte aligned), four elements at a time in the element order of partial(): the same value,
+    // and no fp32 copy of the query held in registers.  The empty asm makes the address new at every use, so
+    // each read stays where it is written, one group of four in flight: this route is about registers, not speed.
+    template <bool FULL = false>
+    __device__ __forceinline__ float distance_from(const chunk_t (&buf)[C], const float* qrow) const
+    {
+        static_assert(sizeof(T) == 1, "uint8 rows only");
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        typedef const f32x4 __attribute__((address_space(3)))* lds_f32x4_ptr;
+        double acc = 0.0;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (FULL || has(c)) {
+                const uint32_t w[4] = {buf[c].x, buf[c].y, buf[c].z, buf[c].w};
+                lds_f32x4_ptr qc = (lds_f32x4_ptr)(qrow + (g + G * c) * PC);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    asm volatile("" : "+v"(qc));
+                    const f32x4 qv = qc[i];
+                    const float t0 = qv.x - (float)(w[i] & 0xFFu);
+                    const float t1 = qv.y - (float)((w[i] >> 8) & 0xFFu);
+                    const float t2 = qv.z - (float)((w[i] >> 16) & 0xFFu);
+                    const float t3 = qv.w - (float)(w[i] >> 24);
+                    acc += (double)t0 * (double)t0;
+                    acc += (double)t1 * (double)t1;
+                    acc += (double)t2 * (double)t2;
+                    acc += (double)t3 * (double)t3;
+                }
+            }
+        }
+        return (float)group_sum(acc);
+    }
+    // stores this lane's slices of the query at their places in qrow (call from one group of lanes)
+    __device__ __forceinline__ void store_query(float* qrow) const
+    {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            if (has(c)) {
+#pragma unroll
+                for (int e = 0; e < PC; e += 4)
+                    *reinterpret_cast<float4*>(qrow + (g + G * c) * PC + e) =
+                        make_float4(q[c * PC + e], q[c * PC + e + 1], q[c * PC + e + 2], q[c * PC + e + 3]);
+            }
+        }
+    }
+
     static __device__ __forceinline__ uint32_t group_sum_u32(uint32_t a)
     {
         a += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0xB1, 0xF, 0xF, false);

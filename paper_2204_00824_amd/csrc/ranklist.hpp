@@ -13,6 +13,14 @@ namespace tsdg {
 // lanes call.
 __device__ __forceinline__ int list_first_unexpanded(const uint64_t* list, int L, int lane, uint64_t* key_out)
 {
+    if (L <= 64) {  // one entry per lane
+        const uint64_t a = lane < L ? list[lane] : kKeyEmpty;
+        const uint64_t m = ballot64(a != kKeyEmpty && (a & 1ull) == 0ull);
+        if (!m) return -1;
+        const int b = ctz64(m);
+        *key_out = readlane64(a, b);
+        return b;
+    }
     for (int i0 = 0; i0 < L; i0 += 64) {
         const int i = i0 + lane;
         const uint64_t a = i < L ? list[i] : kKeyEmpty;

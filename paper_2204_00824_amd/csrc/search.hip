@@ -14,6 +14,8 @@
 // Per query, in LDS: the rank-list (L keys), the visited hash, and the hop's
 // compacted candidate ids / keys.  Global reads per hop: one packed adjacency
 // row, then the gathered base rows of the unvisited neighbours.
+#include <type_traits>
+
 #include "dist.hpp"
 #include "ranklist.hpp"
 
@@ -42,15 +44,19 @@ __device__ __forceinline__ uint32_t seed_node(uint64_t seed, uint64_t qi, uint32
     return (uint32_t)__umul64hi(x, N);
 }
 
-template <int WAVES> struct ListSync {
-    __device__ __forceinline__ void operator()() const
-    {
-        if constexpr (WAVES == 1) __syncthreads(); else wave_sync();
-    }
+// The list and the visited set belong to wave 0 alone: its LDS accesses are processed in issue order,
+// so ordering them takes no barrier.
+struct ListSync {
+    __device__ __forceinline__ void operator()() const { wave_sync(); }
 };
 
+// Byte rows of at most 128 elements need 63 registers once the fp32 query stays out of them: eight waves per
+// SIMD.  The bound keeps later changes from losing that silently (the build would show spills).
+template <typename T, int C, int WAVES>
+constexpr int kSearchMinWaves = (sizeof(T) == 1 && C == 1 && WAVES == 1) ? 8 : 1;
+
 template <typename T, int G, int C, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
+__global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void search_kernel(SearchArgs a)
 {
     using RD = RowDist<T, G, C>;
     using chunk_t = typename RD::chunk_t;
@@ -65,9 +71,10 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
     uint32_t* cid = reinterpret_cast<uint32_t*>(ckey + 64);  // [64]
     uint32_t* table = cid + 64;                              // [slots]
     int* ctl = reinterpret_cast<int*>(table + a.slots);      // [4]
+    float* qs = reinterpret_cast<float*>(ctl + 4);           // [d], byte rows only
 
     const int lane = lane_id();
-    const int wave = (int)(threadIdx.x >> 6);
+    const int wave = WAVES == 1 ? 0 : (int)(threadIdx.x >> 6);
     const int qi = (int)blockIdx.x;
     const T* __restrict__ base = static_cast<const T*>(a.base);
 
@@ -77,25 +84,42 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
     RD rd;
     rd.init(a.d, lane);
     rd.load_query_f32(a.queries + (size_t)qi * (size_t)a.d);  // S0
-    __syncthreads();
+    if constexpr (sizeof(T) == 1)
+        if (wave == 0 && rd.v == 0) rd.store_query(qs);
+    // With one wave per query nothing crosses waves: values that the waves of a workgroup hand each other
+    // through LDS (the hop's node, its candidate count) stay in registers, and a barrier is a fence.
+    auto block_sync = [&]() {
+        if constexpr (WAVES == 1) wave_sync(); else __syncthreads();
+    };
+    block_sync();
+    // Byte rows: an integer-valued query is scored on the integer route, and any other reads its fp32 elements
+    // from LDS at every use, so that neither keeps them in registers (seven waves per SIMD instead of five).
+    auto score = [&]<bool FULL>(const chunk_t (&b)[C], std::bool_constant<FULL>) -> float {
+        if constexpr (sizeof(T) == 1)
+            return rd.q_int ? rd.template distance_int<FULL>(b) : rd.template distance_from<FULL>(b, qs);
+        else
+            return rd.template distance<FULL>(b);
+    };
 
     uint32_t hops = 0, evals = 0, dedup = 0;
-    ListSync<WAVES> lsync;
+    ListSync lsync;
     // byte rows only (the fp32 kernels would pay for the second loop with a wave of occupancy)
     const bool full_rows = sizeof(T) == 1 && rd.nchunks == G * C;  // wave-uniform
 
     // Scores the hop's candidates (ids in `id`, one per lane of wave 0) and merges them.
     auto process = [&](uint32_t id, bool valid) {
+        int m = 0;
         if (wave == 0) {
             bool seen = false;
             if (valid) seen = visited_test_and_set(table, a.slots, id);  // S4
             const uint64_t nm = ballot64(valid && !seen);
             dedup += (uint32_t)popc64(ballot64(valid && seen));
             if (valid && !seen) cid[popc64(nm & lanes_below(lane))] = id;
-            if (lane == 0) ctl[1] = popc64(nm);
+            m = popc64(nm);
+            if (WAVES > 1 && lane == 0) ctl[1] = m;
         }
-        __syncthreads();
-        const int m = ctl[1];
+        block_sync();
+        if constexpr (WAVES > 1) m = ctl[1];
         if (m == 0) return;
         evals += (uint32_t)m;
         // S5: gather + distance.  Batch = U passes of VP rows; waves take batches in turn.
@@ -113,7 +137,7 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const float tot = rd.template distance<true>(buf[u]);
+                    const float tot = score(buf[u], std::true_type{});
                     const int c = b0 + u * VP + rd.v;
                     if (c < m && rd.g == 0) ckey[c] = make_key(tot, e[u]);
                 }
@@ -136,12 +160,12 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const float tot = rd.distance(buf[u]);
+                    const float tot = score(buf[u], std::false_type{});
                     if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
                 }
             }
         }
-        __syncthreads();
+        block_sync();
         if (wave == 0) {
             const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
             list_merge(list, L, key, lane, lsync);  // S6
@@ -166,20 +190,22 @@ __global__ __launch_bounds__(64 * WAVES) void search_kernel(SearchArgs a)
     }
 
     for (;;) {
+        int u = -1;
         if (wave == 0) {
             uint64_t key = kKeyEmpty;
             int idx = list_first_unexpanded(list, L, lane, &key);  // S2
             if (a.max_hops > 0 && (int)hops >= a.max_hops) idx = -1;
-            int u = -1;
             if (idx >= 0) {
                 u = (int)key_id(key);
                 if (lane == 0) list[idx] = key | 1ull;
                 lsync();
             }
-            if (lane == 0) ctl[0] = u;
+            if (WAVES > 1 && lane == 0) ctl[0] = u;
         }
-        __syncthreads();
-        const int u = ctl[0];
+        if constexpr (WAVES > 1) {
+            __syncthreads();
+            u = ctl[0];
+        }
         if (u < 0) break;
         ++hops;
         uint32_t id = 0;
@@ -235,7 +261,8 @@ template <typename T, int G, int C, int WAVES> static ann_status launch_variant(
     a.max_hops = s.max_hops;
     a.slots = s.visited_slots;
     const int Lp = (s.L + 63) & ~63;
-    const size_t lds = (size_t)Lp * 8 + 64 * 8 + 64 * 4 + (size_t)s.visited_slots * 4 + 16;
+    const size_t lds = (size_t)Lp * 8 + 64 * 8 + 64 * 4 + (size_t)s.visited_slots * 4 + 16 +
+                       (sizeof(T) == 1 ? (size_t)s.d * 4 : 0);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&search_kernel<T, G, C, WAVES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
