@@ -283,7 +283,7 @@ def run_descent_1m(args):
 
 def run_crossover(args):
     """Where the workgroup-per-query kernel (mode 2) stops paying and the wave-per-query kernel (mode 1) takes over, by
-    row shape: queries/s of both at the same L and lambda prefix (so both return the same ids) over batch sizes 128..8192.
+    row shape: queries/s of both at the same L and lambda prefix (so both return the same ids) over batch sizes 1..8192.
     Sec. 4 says the division depends on the device and on d; api.hip's automatic mode takes its thresholds from this."""
     import torch
     import workloads
@@ -302,7 +302,7 @@ def run_crossover(args):
         queries = torch.from_numpy(q_h).cuda()
         graph = P.ann_build_graph_ex(base, K, progress=progress)
         rows = []
-        for bs in (128, 256, 512, 1024, 2048, 4096, 8192):
+        for bs in (1, 16, 64, 128, 256, 512, 1024, 2048, 4096, 8192):
             q = queries[:bs].contiguous()
             o = (torch.empty((bs, k), dtype=torch.int32, device="cuda"), torch.empty((bs, k), dtype=torch.float32, device="cuda"))
             row = {"batch": bs}

@@ -262,10 +262,9 @@ __global__ __launch_bounds__(256) void ip_augment_kernel(const float* __restrict
 
 // Batch size from which one wavefront per query is the faster kernel (Sec. 4: the division between small and large
 // batches depends on the device and on the row length).  Measured on MI355X at K = 32, L = 64, same lambda prefix for
-// both kernels, batches of 128..8192 queries: rows of 128 bytes change over at 1,024 queries, rows of 384 and 512
-// bytes at 4,096 (two wavefronts per query still win at 2,048), rows of 3,840 bytes not below 8,192 (four wavefronts
-// per query stay 7 % ahead there, the gap halving with every doubling).  Between the measured row lengths the
-// thresholds are stepped.
+// both kernels, batches of 1..8192 queries: rows of 128 bytes change over between 1,024 and 2,048 queries, rows of
+// 384 and 512 bytes at 4,096 (two wavefronts per query still win at 2,048), rows of 3,840 bytes not below 8,192 (four
+// wavefronts per query stay 8 % ahead there).  Between the measured row lengths the thresholds are stepped.
 static int large_batch_threshold(int row_bytes)
 {
     if (row_bytes <= 128) return 1024;
@@ -682,9 +681,13 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     int waves = 1;
     if (mode == 2) {
         waves = p.waves_per_query;
-        // same measurement: up to 512-byte rows two wavefronts do as well as four or eight; long rows take eight
-        // for batches up to 512 queries and four beyond
-        if (waves == 0) waves = row_bytes <= 512 ? 2 : (row_bytes <= 2048 || nq > 512 ? 4 : 8);
+        // same measurement: up to 512 queries the gather passes of a hop are best spread over eight wavefronts
+        // (four for 128-byte rows, which need fewer passes); beyond, the CUs fill up and two wavefronts per
+        // query do best on rows of 384 and 512 bytes, four on shorter and on longer rows
+        if (waves == 0) {
+            if (nq <= 512) waves = row_bytes <= 128 ? 4 : 8;
+            else waves = (row_bytes <= 128 || row_bytes > 512) ? 4 : 2;
+        }
         if (waves != 1 && waves != 2 && waves != 4 && waves != 8) {
             set_error("ann_search: waves_per_query must be 0, 1, 2, 4 or 8");
             return ANN_EINVAL;
@@ -697,19 +700,19 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     if (lv > 31) lv = 32;
     s.lambda_visit = lv;
 
-    // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds:
-    // 1,280 slots is the most that keeps 20 workgroups on a CU with room to spare for lists of up
-    // to 128 entries, and measured fastest there (1,024: 1-3 % slower, re-scoring more rows; 1,536 and
-    // 2,048: slower from L = 128 on, by occupancy); longer lists take 1,024.  A workgroup per
-    // query has LDS to spare, and a batch that leaves
+    // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds, and a
+    // footprint that fills the LDS to the last kilobyte stalls placement.  Measured on 1M x 128 (L = 29..100, sizes
+    // 896..2,048 in steps of 128): fp32 rows are fastest at 1,408 to 1,536 slots while the list is in registers
+    // (L <= 64) and at 1,408 with the list in LDS up to 128 entries (1,536 is 7 % slower there, by occupancy);
+    // longer lists take 1,024.  Byte rows of at most 128 elements run eight waves per SIMD (63 registers), so a
+    // CU holds 32 queries when a query's LDS stays near 5 KB, and re-scoring a 128-byte row is cheap: 896 slots
+    // with the list in registers, 640 with it in LDS.  A workgroup per query has LDS to spare, and a batch that leaves
     // most CUs with one workgroup takes the largest set that still pays (fewer rows scored twice).
     int slots = p.visited_slots;
     if (slots == 0) {
         if (mode == 1) {
-            slots = L <= 128 ? 1280 : 1024;
-            // byte rows of at most 128 elements run eight waves per SIMD (63 registers), so a CU holds 32
-            // queries when a query's LDS stays near 5 KB; re-scoring a 128-byte row is cheap
-            if (p.dtype == ANN_U8 && g->d <= 128 && L <= 128) slots = 768;
+            slots = L <= 128 ? 1408 : 1024;
+            if (p.dtype == ANN_U8 && g->d <= 128 && L <= 128) slots = L <= 64 ? 896 : 640;
         } else if (nq <= 512) {
             slots = 8192;
         } else {

@@ -190,6 +190,45 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
     sync();
 }
 
+// ---- The same list held in registers: lane i of the wave holds entry i (L <= 64); lanes at L and beyond hold
+// anything and are masked out of every vote by lmask = the low L bits.  No LDS traffic at all: the pick is a
+// ballot, an insertion shifts the tail up by one lane with a whole-wave DPP shift.
+__device__ __forceinline__ uint64_t wave_shr1_u64(uint64_t v)
+{
+    const int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, 0x138, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(v >> 32), (int)(uint32_t)(v >> 32), 0x138, 0xF, 0xF, false);
+    return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;   // lane l receives lane l-1's value; lane 0 keeps its own
+}
+
+// S2 on the register list: index of the first entry not yet expanded, or -1; *key_out receives it.
+__device__ __forceinline__ int reglist_first_unexpanded(uint64_t rl, uint64_t lmask, uint64_t* key_out)
+{
+    const uint64_t m = ballot64(rl != kKeyEmpty && (rl & 1ull) == 0ull) & lmask;
+    if (!m) return -1;
+    const int b = ctz64(m);
+    *key_out = readlane64(rl, b);
+    return b;
+}
+
+// S6 on the register list: the candidates (one per lane, kKeyEmpty = none, ids distinct among the lanes) go in
+// one after the other, each at p = #{entries below it}; entries from p on move up one lane and the last falls
+// off.  A candidate that is not below the current last entry, or already listed, changes nothing.  The result
+// is the merged list that list_merge produces: the L smallest of the union, in order.
+__device__ __forceinline__ void reglist_merge(uint64_t& rl, int L, uint64_t lmask, uint64_t key, int lane)
+{
+    const uint64_t kk = key | 1ull;
+    const uint64_t worst = readlane64(rl, L - 1) | 1ull;
+    for (uint64_t vm = ballot64(kk < worst); vm; vm &= vm - 1) {
+        const uint64_t kj = readlane64(kk, ctz64(vm));
+        const uint64_t am1 = rl | 1ull;
+        const uint64_t lt = ballot64(am1 < kj) & lmask;      // a prefix of the lanes: the list is in order
+        if (ballot64(am1 == kj) & lmask) continue;             // already listed
+        const int p = popc64(lt);
+        const uint64_t up = wave_shr1_u64(rl);
+        rl = lane > p ? up : (lane == p ? (kj & ~1ull) : rl);
+    }
+}
+
 // S4: insert-if-absent into an open-addressed table of `slots` 32-bit ids (any size: the home
 // slot is the high half of hash x slots, and probing wraps round).  Returns true when the id was already there.  After kProbes full
 // slots the home slot is overwritten: the set then forgets an id (a later visit

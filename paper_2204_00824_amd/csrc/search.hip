@@ -55,7 +55,8 @@ struct ListSync {
 template <typename T, int C, int WAVES>
 constexpr int kSearchMinWaves = (sizeof(T) == 1 && C == 1 && WAVES == 1) ? 8 : 1;
 
-template <typename T, int G, int C, int WAVES>
+// RL: the rank-list lives in wave 0's registers (L <= 64) instead of LDS.
+template <typename T, int G, int C, int WAVES, bool RL>
 __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void search_kernel(SearchArgs a)
 {
     using RD = RowDist<T, G, C>;
@@ -65,8 +66,10 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
 
     extern __shared__ uint64_t smem[];
     const int L = a.L;
-    const int Lp = (L + 63) & ~63;
-    uint64_t* list = smem;                                   // [Lp]
+    const int Lp = RL ? 0 : (L + 63) & ~63;
+    uint64_t* list = smem;                                   // [Lp]; nothing with the list in registers
+    uint64_t rl = kKeyEmpty;                                 // RL: entry `lane` of the list (wave 0)
+    const uint64_t lmask = L >= 64 ? ~0ull : (1ull << L) - 1ull;
     uint64_t* ckey = list + Lp;                              // [64]
     uint32_t* cid = reinterpret_cast<uint32_t*>(ckey + 64);  // [64]
     uint32_t* table = cid + 64;                              // [slots]
@@ -122,34 +125,37 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
         if constexpr (WAVES > 1) m = ctl[1];
         if (m == 0) return;
         evals += (uint32_t)m;
-        // S5: gather + distance.  Batch = U passes of VP rows; waves take batches in turn.
+        // S5: gather + distance.  A pass is VP rows; the passes are dealt to the waves in turn and a wave has
+        // U of its passes in flight, so that a short candidate list is spread over all the waves.
         if (full_rows) {
             // every lane owns all its C chunks: no per-chunk test, and a slot past the last
             // candidate re-reads the last one (its result is dropped) instead of being predicated
-            for (int b0 = wave * U * VP; b0 < m; b0 += WAVES * U * VP) {
+            for (int b0 = wave * VP; b0 < m; b0 += WAVES * U * VP) {
                 chunk_t buf[U][C];
                 uint32_t e[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    e[u] = cid[min(b0 + u * VP + rd.v, m - 1)];
+                    if (WAVES > 1 && u > 0 && b0 + u * WAVES * VP >= m) break;  // wave-uniform: a pass with no candidate
+                    e[u] = cid[min(b0 + u * WAVES * VP + rd.v, m - 1)];
 #pragma unroll
                     for (int cc = 0; cc < C; ++cc) buf[u][cc] = rd.load(base, e[u], cc);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
+                    if (WAVES > 1 && u > 0 && b0 + u * WAVES * VP >= m) break;
                     const float tot = score(buf[u], std::true_type{});
-                    const int c = b0 + u * VP + rd.v;
+                    const int c = b0 + u * WAVES * VP + rd.v;
                     if (c < m && rd.g == 0) ckey[c] = make_key(tot, e[u]);
                 }
             }
         } else {
-            for (int b0 = wave * U * VP; b0 < m; b0 += WAVES * U * VP) {
+            for (int b0 = wave * VP; b0 < m; b0 += WAVES * U * VP) {
                 chunk_t buf[U][C];
                 uint32_t e[U];
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int c = b0 + u * VP + rd.v;
+                    const int c = b0 + u * WAVES * VP + rd.v;
                     ok[u] = c < m;
                     e[u] = ok[u] ? cid[c] : 0u;
 #pragma unroll
@@ -161,14 +167,15 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const float tot = score(buf[u], std::false_type{});
-                    if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
+                    if (ok[u] && rd.g == 0) ckey[b0 + u * WAVES * VP + rd.v] = make_key(tot, e[u]);
                 }
             }
         }
         block_sync();
         if (wave == 0) {
             const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
-            list_merge(list, L, key, lane, lsync);  // S6
+            if constexpr (RL) reglist_merge(rl, L, lmask, key, lane);  // S6
+            else list_merge(list, L, key, lane, lsync);
         }
     };
 
@@ -193,12 +200,18 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
         int u = -1;
         if (wave == 0) {
             uint64_t key = kKeyEmpty;
-            int idx = list_first_unexpanded(list, L, lane, &key);  // S2
+            int idx;
+            if constexpr (RL) idx = reglist_first_unexpanded(rl, lmask, &key);  // S2
+            else idx = list_first_unexpanded(list, L, lane, &key);
             if (a.max_hops > 0 && (int)hops >= a.max_hops) idx = -1;
             if (idx >= 0) {
                 u = (int)key_id(key);
-                if (lane == 0) list[idx] = key | 1ull;
-                lsync();
+                if constexpr (RL) {
+                    rl |= lane == idx ? 1ull : 0ull;
+                } else {
+                    if (lane == 0) list[idx] = key | 1ull;
+                    lsync();
+                }
             }
             if (WAVES > 1 && lane == 0) ctl[0] = u;
         }
@@ -225,7 +238,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     // S7
     if (wave == 0) {
         for (int t = lane; t < a.k; t += 64) {
-            const uint64_t key = list[t];
+            const uint64_t key = RL ? rl : list[t];
             const bool have = key != kKeyEmpty;
             a.out_ids[(size_t)qi * a.k + t] = have ? (int32_t)key_id(key) : -1;
             a.out_dists[(size_t)qi * a.k + t] = have ? key_dist(key) : __builtin_inff();
@@ -240,7 +253,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     }
 }
 
-template <typename T, int G, int C, int WAVES> static ann_status launch_variant(const SearchLaunch& s)
+template <typename T, int G, int C, int WAVES, bool RL> static ann_status launch_list_variant(const SearchLaunch& s)
 {
     SearchArgs a;
     a.packed = s.packed;
@@ -260,20 +273,26 @@ template <typename T, int G, int C, int WAVES> static ann_status launch_variant(
     a.n_seeds = s.n_seeds;
     a.max_hops = s.max_hops;
     a.slots = s.visited_slots;
-    const int Lp = (s.L + 63) & ~63;
+    const int Lp = RL ? 0 : (s.L + 63) & ~63;
     const size_t lds = (size_t)Lp * 8 + 64 * 8 + 64 * 4 + (size_t)s.visited_slots * 4 + 16 +
                        (sizeof(T) == 1 ? (size_t)s.d * 4 : 0);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&search_kernel<T, G, C, WAVES>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&search_kernel<T, G, C, WAVES, RL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) {
             set_error("hipFuncSetAttribute(%zu bytes of LDS) failed: %s", lds, hipGetErrorString(e));
             return ANN_EDEVICE;
         }
     }
-    TSDG_LAUNCH((search_kernel<T, G, C, WAVES>), dim3((unsigned)s.nq), dim3(64 * WAVES), lds, s.stream, a);
+    TSDG_LAUNCH((search_kernel<T, G, C, WAVES, RL>), dim3((unsigned)s.nq), dim3(64 * WAVES), lds, s.stream, a);
     TSDG_HIP(launch_error());
     return ANN_OK;
+}
+
+template <typename T, int G, int C, int WAVES> static ann_status launch_variant(const SearchLaunch& s)
+{
+    // a list of at most 64 entries fits one per lane (k <= L, so the output comes from the same registers)
+    return s.L <= 64 ? launch_list_variant<T, G, C, WAVES, true>(s) : launch_list_variant<T, G, C, WAVES, false>(s);
 }
 
 namespace {
