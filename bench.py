@@ -39,8 +39,8 @@ def log(msg):
 
 def search_kernel_name(L):
     """The instantiation the large-batch launch runs: 8 lanes per row, 4 chunks per lane, one wave per query; the last
-    argument says whether the rank-list sits in registers (lists of at most 64 entries)."""
-    return "search_kernel<float,8,4,1,%s>" % ("true" if L <= 64 else "false")
+    argument is the number of registers per lane that hold the rank-list (1 up to 64 entries, 2 up to 128, 0: in LDS)."""
+    return "search_kernel<float,8,4,1,%d>" % (1 if L <= 64 else 2 if L <= 128 else 0)
 
 
 def kernel_source_sha256():

@@ -190,9 +190,9 @@ __device__ __forceinline__ void list_merge(uint64_t* list, int L, uint64_t key, 
     sync();
 }
 
-// ---- The same list held in registers: lane i of the wave holds entry i (L <= 64); lanes at L and beyond hold
-// anything and are masked out of every vote by lmask = the low L bits.  No LDS traffic at all: the pick is a
-// ballot, an insertion shifts the tail up by one lane with a whole-wave DPP shift.
+// ---- The same list held in registers: lane i of the wave holds entry i (and entry 64 + i when B = 2), so lists of
+// up to 64 * B entries never touch LDS: the pick is a ballot, an insertion shifts the tail up by one lane with a
+// whole-wave DPP shift.  Lanes at L and beyond hold anything and are masked out of every vote.
 __device__ __forceinline__ uint64_t wave_shr1_u64(uint64_t v)
 {
     const int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, 0x138, 0xF, 0xF, false);
@@ -200,34 +200,83 @@ __device__ __forceinline__ uint64_t wave_shr1_u64(uint64_t v)
     return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;   // lane l receives lane l-1's value; lane 0 keeps its own
 }
 
-// S2 on the register list: index of the first entry not yet expanded, or -1; *key_out receives it.
-__device__ __forceinline__ int reglist_first_unexpanded(uint64_t rl, uint64_t lmask, uint64_t* key_out)
-{
-    const uint64_t m = ballot64(rl != kKeyEmpty && (rl & 1ull) == 0ull) & lmask;
-    if (!m) return -1;
-    const int b = ctz64(m);
-    *key_out = readlane64(rl, b);
-    return b;
-}
+template <int B> struct RegList {
+    static_assert(B == 1 || B == 2, "one or two entries per lane");
+    uint64_t e[B];    // e[b] of lane l = entry 64 b + l
+    uint64_t top;     // lanes of the last register that hold entries
+    int L;
 
-// S6 on the register list: the candidates (one per lane, kKeyEmpty = none, ids distinct among the lanes) go in
-// one after the other, each at p = #{entries below it}; entries from p on move up one lane and the last falls
-// off.  A candidate that is not below the current last entry, or already listed, changes nothing.  The result
-// is the merged list that list_merge produces: the L smallest of the union, in order.
-__device__ __forceinline__ void reglist_merge(uint64_t& rl, int L, uint64_t lmask, uint64_t key, int lane)
-{
-    const uint64_t kk = key | 1ull;
-    const uint64_t worst = readlane64(rl, L - 1) | 1ull;
-    for (uint64_t vm = ballot64(kk < worst); vm; vm &= vm - 1) {
-        const uint64_t kj = readlane64(kk, ctz64(vm));
-        const uint64_t am1 = rl | 1ull;
-        const uint64_t lt = ballot64(am1 < kj) & lmask;      // a prefix of the lanes: the list is in order
-        if (ballot64(am1 == kj) & lmask) continue;             // already listed
-        const int p = popc64(lt);
-        const uint64_t up = wave_shr1_u64(rl);
-        rl = lane > p ? up : (lane == p ? (kj & ~1ull) : rl);
+    __device__ __forceinline__ void init(int L_)
+    {
+        L = L_;
+        const int n = L_ - 64 * (B - 1);               // entries in the last register: 1..64
+        top = n >= 64 ? ~0ull : (1ull << n) - 1ull;
+#pragma unroll
+        for (int b = 0; b < B; ++b) e[b] = kKeyEmpty;
     }
-}
+    __device__ __forceinline__ uint64_t valid(int b) const { return b == B - 1 ? top : ~0ull; }
+
+    // S2: index of the first entry not yet expanded, or -1; *key_out receives it.
+    __device__ __forceinline__ int first_unexpanded(uint64_t* key_out) const
+    {
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const uint64_t m = ballot64(e[b] != kKeyEmpty && (e[b] & 1ull) == 0ull) & valid(b);
+            if (m) {
+                const int l = ctz64(m);
+                *key_out = readlane64(e[b], l);
+                return 64 * b + l;
+            }
+        }
+        return -1;
+    }
+    __device__ __forceinline__ void mark_expanded(int idx, int lane)
+    {
+#pragma unroll
+        for (int b = 0; b < B; ++b) e[b] |= (64 * b + lane == idx) ? 1ull : 0ull;
+    }
+    // entry t (t = 64 b + lane for the calling lane)
+    __device__ __forceinline__ uint64_t entry(int t) const { return B == 2 && t >= 64 ? e[B - 1] : e[0]; }
+
+    // S6: the candidates (one per lane, kKeyEmpty = none, ids distinct among the lanes) go in one after the
+    // other, each at p = #{entries below it}; entries from p on move up one place (lane 63 of the first
+    // register hands its entry to lane 0 of the second) and the last falls off.  A candidate that is not below
+    // the current last entry, or already listed, changes nothing.  The result is the merged list that
+    // list_merge produces: the L smallest of the union, in order.
+    __device__ __forceinline__ void merge(uint64_t key, int lane)
+    {
+        const uint64_t kk = key | 1ull;
+        const uint64_t worst = readlane64(e[B - 1], L - 64 * (B - 1) - 1) | 1ull;
+        for (uint64_t vm = ballot64(kk < worst); vm; vm &= vm - 1) {
+            const uint64_t kj = readlane64(kk, ctz64(vm));
+            uint64_t same = 0ull;
+            int p = 0;                                   // the entries below kj are a prefix: the list is in order
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const uint64_t am1 = e[b] | 1ull;
+                p += popc64(ballot64(am1 < kj) & valid(b));
+                same |= ballot64(am1 == kj) & valid(b);
+            }
+            if (same) continue;                          // already listed
+            const uint64_t in = kj & ~1ull;
+            if constexpr (B == 1) {
+                const uint64_t up = wave_shr1_u64(e[0]);
+                e[0] = lane > p ? up : (lane == p ? in : e[0]);
+            } else {
+                const uint64_t up1 = wave_shr1_u64(e[1]);
+                if (p < 64) {
+                    const uint64_t carry = readlane64(e[0], 63);
+                    const uint64_t up0 = wave_shr1_u64(e[0]);
+                    e[0] = lane > p ? up0 : (lane == p ? in : e[0]);
+                    e[1] = lane == 0 ? carry : up1;
+                } else {
+                    const int q = p - 64;
+                    e[1] = lane > q ? up1 : (lane == q ? in : e[1]);
+                }
+            }
+        }
+    }
+};
 
 // S4: insert-if-absent into an open-addressed table of `slots` 32-bit ids (any size: the home
 // slot is the high half of hash x slots, and probing wraps round).  Returns true when the id was already there.  After kProbes full

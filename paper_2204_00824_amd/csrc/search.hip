@@ -55,8 +55,8 @@ struct ListSync {
 template <typename T, int C, int WAVES>
 constexpr int kSearchMinWaves = (sizeof(T) == 1 && C == 1 && WAVES == 1) ? 8 : 1;
 
-// RL: the rank-list lives in wave 0's registers (L <= 64) instead of LDS.
-template <typename T, int G, int C, int WAVES, bool RL>
+// RL: registers per lane that hold the rank-list in wave 0 (1: L <= 64, 2: L <= 128); 0: the list is in LDS.
+template <typename T, int G, int C, int WAVES, int RL>
 __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void search_kernel(SearchArgs a)
 {
     using RD = RowDist<T, G, C>;
@@ -68,8 +68,8 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     const int L = a.L;
     const int Lp = RL ? 0 : (L + 63) & ~63;
     uint64_t* list = smem;                                   // [Lp]; nothing with the list in registers
-    uint64_t rl = kKeyEmpty;                                 // RL: entry `lane` of the list (wave 0)
-    const uint64_t lmask = L >= 64 ? ~0ull : (1ull << L) - 1ull;
+    RegList<RL ? RL : 1> rl;                                 // RL: the list (wave 0)
+    rl.init(RL ? L : 1);
     uint64_t* ckey = list + Lp;                              // [64]
     uint32_t* cid = reinterpret_cast<uint32_t*>(ckey + 64);  // [64]
     uint32_t* table = cid + 64;                              // [slots]
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
         block_sync();
         if (wave == 0) {
             const uint64_t key = lane < m ? ckey[lane] : kKeyEmpty;
-            if constexpr (RL) reglist_merge(rl, L, lmask, key, lane);  // S6
+            if constexpr (RL) rl.merge(key, lane);  // S6
             else list_merge(list, L, key, lane, lsync);
         }
     };
@@ -201,13 +201,13 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
         if (wave == 0) {
             uint64_t key = kKeyEmpty;
             int idx;
-            if constexpr (RL) idx = reglist_first_unexpanded(rl, lmask, &key);  // S2
+            if constexpr (RL) idx = rl.first_unexpanded(&key);  // S2
             else idx = list_first_unexpanded(list, L, lane, &key);
             if (a.max_hops > 0 && (int)hops >= a.max_hops) idx = -1;
             if (idx >= 0) {
                 u = (int)key_id(key);
                 if constexpr (RL) {
-                    rl |= lane == idx ? 1ull : 0ull;
+                    rl.mark_expanded(idx, lane);
                 } else {
                     if (lane == 0) list[idx] = key | 1ull;
                     lsync();
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     // S7
     if (wave == 0) {
         for (int t = lane; t < a.k; t += 64) {
-            const uint64_t key = RL ? rl : list[t];
+            const uint64_t key = RL ? rl.entry(t) : list[t];
             const bool have = key != kKeyEmpty;
             a.out_ids[(size_t)qi * a.k + t] = have ? (int32_t)key_id(key) : -1;
             a.out_dists[(size_t)qi * a.k + t] = have ? key_dist(key) : __builtin_inff();
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     }
 }
 
-template <typename T, int G, int C, int WAVES, bool RL> static ann_status launch_list_variant(const SearchLaunch& s)
+template <typename T, int G, int C, int WAVES, int RL> static ann_status launch_list_variant(const SearchLaunch& s)
 {
     SearchArgs a;
     a.packed = s.packed;
@@ -291,8 +291,10 @@ template <typename T, int G, int C, int WAVES, bool RL> static ann_status launch
 
 template <typename T, int G, int C, int WAVES> static ann_status launch_variant(const SearchLaunch& s)
 {
-    // a list of at most 64 entries fits one per lane (k <= L, so the output comes from the same registers)
-    return s.L <= 64 ? launch_list_variant<T, G, C, WAVES, true>(s) : launch_list_variant<T, G, C, WAVES, false>(s);
+    // a list of at most 128 entries fits one or two per lane (k <= L, so the output comes from the same registers)
+    if (s.L <= 64) return launch_list_variant<T, G, C, WAVES, 1>(s);
+    if (s.L <= 128) return launch_list_variant<T, G, C, WAVES, 2>(s);
+    return launch_list_variant<T, G, C, WAVES, 0>(s);
 }
 
 namespace {
