@@ -701,17 +701,20 @@ ann_status ann_search_ex(const ann_graph* graph, const void* base, const void* q
     s.lambda_visit = lv;
 
     // Visited set: with one wave per query the LDS footprint decides how many queries a CU holds, and a
-    // footprint that fills the LDS to the last kilobyte stalls placement.  Measured on 1M x 128 (L = 29..128, sizes
-    // 896..2,048): while the list is in registers (L <= 128) fp32 rows are fastest at 1,536 slots (1,408 within 1 %,
-    // 1,792 5 % slower by occupancy); longer lists, which live in LDS, take 1,024.  Byte rows of at most 128 elements
-    // run eight waves per SIMD (63 registers), so a CU holds 32 queries when a query's LDS stays near 5 KB, and
-    // re-scoring a 128-byte row is cheap: 896 slots (1,024 is 12 % slower).  A workgroup per query has LDS to spare,
-    // and a batch that leaves most CUs with one workgroup takes the largest set that still pays (fewer rows scored twice).
+    // footprint that fills the LDS to the last kilobyte stalls placement; against that, every slot saves rows from
+    // being scored twice, which costs more the longer the row.  Measured on 1M x 128 fp32 and uint8 and 4M x 96 fp32
+    // (L = 29..512, sizes 384..2,048): while the list is in registers (L <= 128) 1,536 slots are fastest on 384- and
+    // 512-byte rows (1,408 within 1 %, 1,792 5 % slower); with the list in LDS, 512-byte rows still take 1,536 (6 %
+    // ahead of 1,024 at L = 512), shorter rows 1,024 (at L = 256 on 384-byte rows 1,216 and more are 10 % slower).
+    // Byte rows of at most 128 elements run eight waves per SIMD (63 registers), so a CU holds 32 queries when a
+    // query's LDS stays near 5 KB, and re-scoring a 128-byte row is cheap: 896 slots with the list in registers
+    // (1,024 is 12 % slower), 384 with it in LDS (1,024 is 20 % slower at L = 256).  A workgroup per query has LDS to
+    // spare, and a batch that leaves most CUs with one workgroup takes the largest set that still pays.
     int slots = p.visited_slots;
     if (slots == 0) {
         if (mode == 1) {
-            slots = L <= 128 ? 1536 : 1024;
-            if (p.dtype == ANN_U8 && g->d <= 128 && L <= 128) slots = 896;
+            slots = (L <= 128 || row_bytes >= 512) ? 1536 : 1024;
+            if (p.dtype == ANN_U8 && g->d <= 128) slots = L <= 128 ? 896 : 384;
         } else if (nq <= 512) {
             slots = 8192;
         } else {
