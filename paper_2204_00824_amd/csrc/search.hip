@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     };
     block_sync();
     // Byte rows: an integer-valued query is scored on the integer route, and any other reads its fp32 elements
-    // from LDS at every use, so that neither keeps them in registers (seven waves per SIMD instead of five).
+    // from LDS at every use, so that neither keeps them in registers (eight waves per SIMD instead of five).
     auto score = [&]<bool FULL>(const chunk_t (&b)[C], std::bool_constant<FULL>) -> float {
         if constexpr (sizeof(T) == 1)
             return rd.q_int ? rd.template distance_int<FULL>(b) : rd.template distance_from<FULL>(b, qs);
@@ -155,6 +155,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
+                    if (u > 0 && b0 + u * WAVES * VP >= m) break;   // wave-uniform: a pass with no candidate
                     const int c = b0 + u * WAVES * VP + rd.v;
                     ok[u] = c < m;
                     e[u] = ok[u] ? cid[c] : 0u;
@@ -166,6 +167,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
+                    if (u > 0 && b0 + u * WAVES * VP >= m) break;
                     const float tot = score(buf[u], std::false_type{});
                     if (ok[u] && rd.g == 0) ckey[b0 + u * WAVES * VP + rd.v] = make_key(tot, e[u]);
                 }
