@@ -109,8 +109,10 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
     // byte rows only (the fp32 kernels would pay for the second loop with a wave of occupancy)
     const bool full_rows = sizeof(T) == 1 && rd.nchunks == G * C;  // wave-uniform
 
-    // Scores the hop's candidates (ids in `id`, one per lane of wave 0) and merges them.
-    auto process = [&](uint32_t id, bool valid) {
+    // Scores the hop's candidates (ids in `id`, one per lane of wave 0) and merges them.  `stop` (wave 0): there
+    // is no hop; the other waves learn it from the candidate count, which is the one thing they wait for, so a
+    // hop costs them two barriers.  Returns true when the search is over.
+    auto process = [&](uint32_t id, bool valid, bool stop) -> bool {
         int m = 0;
         if (wave == 0) {
             bool seen = false;
@@ -118,12 +120,13 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
             const uint64_t nm = ballot64(valid && !seen);
             dedup += (uint32_t)popc64(ballot64(valid && seen));
             if (valid && !seen) cid[popc64(nm & lanes_below(lane))] = id;
-            m = popc64(nm);
+            m = stop ? -1 : popc64(nm);
             if (WAVES > 1 && lane == 0) ctl[1] = m;
         }
         block_sync();
         if constexpr (WAVES > 1) m = ctl[1];
-        if (m == 0) return;
+        if (m < 0) return true;
+        if (m == 0) return false;
         evals += (uint32_t)m;
         // S5: gather + distance.  A pass is VP rows; the passes are dealt to the waves in turn and a wave has
         // U of its passes in flight, so that a short candidate list is spread over all the waves.
@@ -179,6 +182,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
             if constexpr (RL) rl.merge(key, lane);  // S6
             else list_merge(list, L, key, lane, lsync);
         }
+        return false;
     };
 
     // S1: seeds, 64 at a time; repeats inside a group of 64 are dropped here, repeats across
@@ -195,7 +199,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
                 if (o < lane && ido == id) valid = false;
             }
         }
-        process(id, valid);
+        process(id, valid, false);
     }
 
     for (;;) {
@@ -215,17 +219,12 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
                     lsync();
                 }
             }
-            if (WAVES > 1 && lane == 0) ctl[0] = u;
         }
-        if constexpr (WAVES > 1) {
-            __syncthreads();
-            u = ctl[0];
-        }
-        if (u < 0) break;
-        ++hops;
+        if (WAVES == 1 && u < 0) break;
         uint32_t id = 0;
         bool valid = false;
-        if (wave == 0) {  // S3: adjacency row, prefix with lambda < lambda_visit
+        if (wave == 0 && u >= 0) {  // S3: adjacency row, prefix with lambda < lambda_visit
+            ++hops;
             uint32_t w = kPackPad;
             if (lane < a.K) w = a.packed[(size_t)u * (size_t)a.K + lane];
             const bool ok = w != kPackPad && (int)(w >> kIdBits) < a.lambda_visit;
@@ -234,7 +233,7 @@ __global__ __launch_bounds__(64 * WAVES, (kSearchMinWaves<T, C, WAVES>)) void se
             valid = lane < deg;
             id = w & kIdMask;
         }
-        process(id, valid);
+        if (process(id, valid, u < 0)) break;
     }
 
     // S7
