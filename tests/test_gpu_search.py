@@ -42,7 +42,7 @@ def test_tiny_matches_oracle(gpu, orc, mode, waves, lv):
 
 @pytest.mark.parametrize("L,k,mode", [(16, 10, 1), (64, 10, 1), (65, 10, 1), (100, 10, 1), (128, 100, 1), (128, 10, 2),
                                       (129, 10, 1), (200, 100, 1), (257, 10, 2), (512, 10, 1), (512, 100, 2), (64, 10, 2),
-                                      (1, 1, 1)])
+                                      (1, 1, 1), (64, 64, 1), (65, 65, 2), (127, 127, 1), (128, 128, 2), (63, 63, 2)])
 def test_integer_data_matches_oracle_exactly(gpu, orc, L, k, mode):
     """d=128 integer-valued rows: every distance is an exact integer, so parity is zero-tolerance."""
     step(f"sift20k search L={L} k={k} mode={mode}")
@@ -117,9 +117,23 @@ def test_uint8_rows(gpu, orc):
     mixed = case[1].copy()
     mixed[::2] += np.float32(0.375)
     mixed[1, 0] = 300.0                                   # integer but outside the byte range
-    (ids, s, st), ref = run_both(gpu, orc, (case[0], mixed, case[2], case[3]), 10, 32, 10, 1)
-    assert_bitwise(ids, ref[0], "u8 mixed ids")
-    assert_bitwise(s, ref[1], "u8 mixed dists")
+    for L, mode in ((32, 1), (32, 2), (100, 1), (200, 1), (100, 2)):   # list in one register, two, in LDS
+        (ids, s, st), ref = run_both(gpu, orc, (case[0], mixed, case[2], case[3]), 10, L, 10, mode)
+        assert_bitwise(ids, ref[0], f"u8 mixed ids L={L} mode={mode}")
+        assert_bitwise(s, ref[1], f"u8 mixed dists L={L} mode={mode}")
+    # rows that do not fill the lanes' chunks (d = 48: three 16-byte chunks for eight lanes), both kinds of query
+    def make48():
+        base, queries = workloads.sift_like(N=6000, nq=60, d=48, seed=6)
+        b8 = base.astype(np.uint8)
+        adj, lam = orc.build_graph(b8, 16)
+        q = queries.copy()
+        q[::3] += np.float32(0.25)
+        return b8, q, adj, lam
+    case48 = cached("u8d48", make48)
+    for mode in (1, 2):
+        (ids, s, st), ref = run_both(gpu, orc, case48, 10, 40, 10, mode)
+        assert_bitwise(ids, ref[0], f"u8 d=48 ids mode={mode}")
+        assert_bitwise(s, ref[1], f"u8 d=48 dists mode={mode}")
 
 
 def test_degenerate_graphs_and_padding(gpu, orc):
