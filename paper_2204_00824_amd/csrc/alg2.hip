@@ -89,7 +89,9 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
     constexpr int VP = RD::VP;
     constexpr int U = (C >= 8) ? 1 : (C >= 3 ? 2 : 4);
     extern __shared__ uint64_t smem[];
-    uint64_t* Cseg = smem;                                          // [m_c * 32]
+    // byte rows: the fp32 query first (RowDist::distance_lds reads it 16 bytes at a time)
+    float* qs = reinterpret_cast<float*>(smem);                     // [d] for byte rows, else nothing
+    uint64_t* Cseg = smem + (sizeof(T) == 1 ? a.d / 2 : 0);         // [m_c * 32]
     uint64_t* ckey = Cseg + a.m_c * 32;                             // [64]
     uint32_t* cid = reinterpret_cast<uint32_t*>(ckey + 64);         // [64]
     uint32_t* V = cid + 64;                                         // [m_v * 32]
@@ -106,6 +108,8 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
     RD rd;
     rd.init(a.d, lane);
     rd.load_query_f32(a.queries + (size_t)qi * (size_t)a.d);
+    if constexpr (sizeof(T) == 1)
+        if (rd.v == 0) rd.store_query(qs);
     if (lane < 32) cid[lane] = seed_node_alg2(a.seed, (uint64_t)(a.qi_offset + qi), (uint32_t)lane, a.N);
     __syncthreads();
 
@@ -127,7 +131,7 @@ __global__ __launch_bounds__(64) void alg2_kernel(Alg2Args a)
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float tot = rd.distance(buf[u]);
+                const float tot = rd.distance_lds(buf[u], qs);
                 if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
             }
         }
@@ -272,7 +276,8 @@ struct Alg2Dispatch {
     hipStream_t stream;
     template <typename T, int G, int C> void operator()()
     {
-        const size_t lds = (size_t)a.m_c * 32 * 8 + 64 * 8 + 64 * 4 + (size_t)a.m_v * 32 * 4 + (size_t)(a.m_c + a.m_v) * 4;
+        const size_t lds = (size_t)a.m_c * 32 * 8 + 64 * 8 + 64 * 4 + (size_t)a.m_v * 32 * 4 + (size_t)(a.m_c + a.m_v) * 4 +
+                           (sizeof(T) == 1 ? (size_t)a.d * 4 : 0);
         TSDG_LAUNCH((alg2_kernel<T, G, C>), dim3((unsigned)nq), dim3(64), lds, stream, a);
     }
 };

@@ -237,6 +237,17 @@ template <typename T, int G, int C> struct RowDist {
         }
         return (float)group_sum(acc);
     }
+    // One call for kernels that keep a copy of the query in LDS (qs): byte rows take the integer route for an
+    // integer-valued query and the fp64 route reading qs otherwise, so their fp32 query leaves the registers
+    // after pack_query; other rows are scored from the registers as ever.
+    template <bool FULL = false>
+    __device__ __forceinline__ float distance_lds(const chunk_t (&buf)[C], const float* qs) const
+    {
+        if constexpr (sizeof(T) == 1)
+            return q_int ? distance_int<FULL>(buf) : distance_from<FULL>(buf, qs);
+        else
+            return distance<FULL>(buf);
+    }
     // stores this lane's slices of the query at their places in qrow (call from one group of lanes)
     __device__ __forceinline__ void store_query(float* qrow) const
     {

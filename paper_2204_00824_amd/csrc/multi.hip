@@ -62,6 +62,8 @@ __global__ __launch_bounds__(256) void multi_kernel(MultiArgs a)
     __shared__ uint32_t cid[64];
     __shared__ uint32_t nrow[64];  // adjacency row of the next node, fetched while R is updated
     __shared__ int ctl[4];
+    // byte rows: the fp32 query for the queries that are not integer-valued (RowDist::distance_lds)
+    __shared__ __attribute__((aligned(16))) float qs[sizeof(T) == 1 ? 16 * G * C : 4];
 
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
@@ -72,20 +74,23 @@ __global__ __launch_bounds__(256) void multi_kernel(MultiArgs a)
     RD rd;
     rd.init(a.d, lane);
     rd.load_query_f32(a.queries + (size_t)qi * (size_t)a.d);
+    if constexpr (sizeof(T) == 1)
+        if (wave == 0 && rd.v == 0) rd.store_query(qs);
     if (threadIdx.x < 32) {
         R[threadIdx.x] = kKeyEmpty;
         cid[threadIdx.x] = seed_node_multi(a.seed, (uint64_t)(a.qi_offset + qi), (uint32_t)(32 * j + (int)threadIdx.x), a.N);
     }
     __syncthreads();
 
-    auto score = [&](int m) {  // cid[0..m) -> ckey[0..m); waves take batches of U*VP rows in turn
-        for (int b0 = wave * U * VP; b0 < m; b0 += 4 * U * VP) {
+    auto score = [&](int m) {  // cid[0..m) -> ckey[0..m); passes of VP rows are dealt to the four waves in turn
+        for (int b0 = wave * VP; b0 < m; b0 += 4 * U * VP) {
             chunk_t buf[U][C];
             uint32_t e[U];
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int c = b0 + u * VP + rd.v;
+                if (u > 0 && b0 + u * 4 * VP >= m) break;   // wave-uniform: a pass with no candidate
+                const int c = b0 + u * 4 * VP + rd.v;
                 ok[u] = c < m;
                 e[u] = ok[u] ? cid[c] : 0u;
 #pragma unroll
@@ -96,8 +101,9 @@ __global__ __launch_bounds__(256) void multi_kernel(MultiArgs a)
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float tot = rd.distance(buf[u]);
-                if (ok[u] && rd.g == 0) ckey[b0 + u * VP + rd.v] = make_key(tot, e[u]);
+                if (u > 0 && b0 + u * 4 * VP >= m) break;
+                const float tot = rd.distance_lds(buf[u], qs);
+                if (ok[u] && rd.g == 0) ckey[b0 + u * 4 * VP + rd.v] = make_key(tot, e[u]);
             }
         }
     };

@@ -64,8 +64,15 @@ def test_tiny_and_shapes(gpu, orc):
         b8 = base.astype(np.uint8)
         adj, lam = orc.build_graph(b8, 16)
         return b8, queries, adj, lam
-    got, ref = run_both(gpu, orc, cached("u8", make8), 10, 40.0)
+    case8 = cached("u8", make8)
+    got, ref = run_both(gpu, orc, case8, 10, 40.0)
     check(got, ref, "u8")
+    # queries that are not integers (and one outside the byte range) take the fp64 route on the same byte rows
+    mixed = case8[1].copy()
+    mixed[::2] += np.float32(0.375)
+    mixed[1, 0] = 300.0
+    got, ref = run_both(gpu, orc, (case8[0], mixed, case8[2], case8[3]), 10, 40.0)
+    check(got, ref, "u8 mixed")
 
 
 def test_segment_overflow_star(gpu, orc):

@@ -64,9 +64,17 @@ def test_uint8_rows_and_wide_rows(gpu, orc):
         b8 = base.astype(np.uint8)
         adj, lam = orc.build_graph(b8, 16)
         return b8, queries, adj, lam
-    (ids, s, st), ref = run_both(gpu, orc, cached("u8", make), 10, 4)
+    case8 = cached("u8", make)
+    (ids, s, st), ref = run_both(gpu, orc, case8, 10, 4)
     assert_bitwise(ids, ref[0], "u8 ids")
     assert_bitwise(s, ref[1], "u8 dists")
+    # queries that are not integers (and one outside the byte range) take the fp64 route on the same byte rows
+    mixed = case8[1].copy()
+    mixed[::2] += np.float32(0.375)
+    mixed[1, 0] = 300.0
+    (ids, s, st), ref = run_both(gpu, orc, (case8[0], mixed, case8[2], case8[3]), 10, 4)
+    assert_bitwise(ids, ref[0], "u8 mixed ids")
+    assert_bitwise(s, ref[1], "u8 mixed dists")
     # K = 64: positions p and p+32 of a row compete for one slot
     def make64():
         base, queries = workloads.single_gaussian(2000, 8, seed=64, nq=40)
