@@ -131,8 +131,9 @@ typedef struct {
  * above; the threshold was measured per row length: 1,024 queries for rows of up
  * to 128 bytes, 4,096 up to 512 bytes, 16,384 up to 2,048 bytes, 32,768 beyond), lambda_visit 0 meaning "by mode" (Sec. 5.4: 10 for small batches, 5
  * for large ones), n_seeds 32 (Alg. 2), seed 0, max_hops 0 = unbounded (the hop
- * limit T of Alg. 2), visited_slots 0 = chosen from mode and L, waves_per_query 0 =
- * chosen from d, qi_offset 0, stream NULL.
+ * limit T of Alg. 2), visited_slots 0 = chosen from mode, L and the row length, waves_per_query 0 =
+ * chosen from the row length and the batch size (8 wavefronts up to 512 queries, 4 for rows of at most 128
+ * bytes; beyond, 2 for rows of 129..512 bytes and 4 otherwise), qi_offset 0, stream NULL.
  *   mode: 1 = large batch (one 64-lane wavefront per query),
  *         2 = small batch (one workgroup of several wavefronts per query).
  *   lambda_visit: edges with lambda < lambda_visit are followed; values above
