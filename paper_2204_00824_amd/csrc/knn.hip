@@ -680,6 +680,42 @@ struct WideArgs {
 // candidates (a 128 x 256 workgroup tile: a quarter fewer bytes fetched per MFMA), with hi + lo parts with 64
 constexpr int wide_x_blocks(int mode) { return mode == 1 ? 2 : 4; }
 
+// slab buffers: three where a workgroup's slabs are 24 KB (two on their way while one is multiplied, two workgroups
+// per compute unit), two for the 32 KB slabs of the hi + lo form
+constexpr int wide_buffers(int mode) { return mode == 1 ? 2 : 3; }
+constexpr size_t wide_lds_bytes(int mode)
+{
+    return (size_t)wide_buffers(mode) * (mode == 1 ? 2 : 1) * (kTile + 64 * wide_x_blocks(mode)) * kWideDK * sizeof(uint16_t);
+}
+
+// LDS-direct loads: the wave's 64 lanes x 16 (or 4) bytes land contiguously at the LDS address in m0, lane by lane.
+// Issued through inline assembly: the compiler would make every later LDS read wait for all of them, which takes
+// away the overlap of a slab's loads with the multiplications of the slabs before; the waits are explicit instead.
+// The address is a uniform 64-bit base plus a 32-bit unsigned byte offset per lane.  The wait states before the load
+// cover m0 and a base that the compiler may have moved into its scalar registers from a vector register just before
+// (it does not look into the assembly for what the load needs).
+__device__ __forceinline__ uint64_t uniform_address(const void* p)
+{
+    const uint64_t v = (uint64_t)(uintptr_t)p;   // (the builtin returns a signed int: widened as it is, a low half with
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);   // bit 31 set would flood the high half)
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | (uint64_t)lo;
+}
+__device__ __forceinline__ void lds_direct_b128(uint32_t lane_offset, const void* base, uint32_t lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_offset), "s"(uniform_address(base)), "s"(lds_byte_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void lds_direct_b32(uint32_t lane_offset, const void* base, uint32_t lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 4\n\tglobal_load_lds_dword %0, %1"
+                 ::"v"(lane_offset), "s"(uniform_address(base)), "s"(lds_byte_addr) : "memory", "m0");
+}
+template <typename P> __device__ __forceinline__ uint32_t lds_addr(P* p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(p);
+}
+
 // DK = 32 elements (64 bytes) per LDS row, no padding: 16-byte chunk c of row r sits at chunk c ^ ((r >> 2) & 3)
 template <int DK>
 __device__ __forceinline__ int wide_lds_offset(int row, int chunk)
@@ -700,7 +736,8 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     constexpr int DK = kWideDK;                   // elements of k per slab
     constexpr int XB = wide_x_blocks(MODE);      // 32-row candidate blocks per wave
     constexpr int XT = 2 * 32 * XB;              // candidate rows per workgroup tile (two waves side by side)
-    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [2][q parts: 128 * DK | x parts: XT * DK]
+    constexpr int NBUF = wide_buffers(MODE);
+    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [NBUF][q parts: 128 * DK | x parts: XT * DK]
     __shared__ __attribute__((aligned(16))) float xn[2][XT];
     __shared__ SurvivorQueue<kSplitQueue> queue;
     constexpr int QPART = kTile * DK, XPART = XT * DK;   // elements of one part of a slab, per operand
@@ -748,60 +785,73 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int nstage = w.dp / DK;
     const int G = ntiles * nstage;
 
-    // this thread's share of a slab: chunk fc of rows fr, fr + RP, ... of every part
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    constexpr int CH = DK / 8, RP = 256 / CH;          // chunks per row, rows per pass
-    constexpr int HQ = kTile / RP, HX = XT / RP;       // passes over the query rows and the candidate rows
-    const int fr = (int)threadIdx.x / CH, fc = (int)threadIdx.x % CH;
-    int64_t qrow[HQ];   // clamped: rows past the end are re-reads whose results are dropped
+    // A slab comes in by LDS-direct loads: the 64 lanes of one load fill 1 KB, i.e. 16 rows of 64 bytes; lane l
+    // fills place l & 3 of row l >> 2 of its group and so fetches the chunk that the swizzle keeps there.  No
+    // staging registers and no LDS stores, so NBUF - 1 slabs can be on their way while one is multiplied.
+    // Addresses are a scalar base (part, tile, slab: all uniform) plus a 32-bit offset per lane that does not change
+    // from slab to slab, so that a fetch costs the vector unit nothing but the loads themselves.
+    constexpr int GQ = kTile / 16 / 4, GX = XT / 16 / 4;   // 16-row groups per wave and part: queries, candidates
+    const int grow = lane >> 2;
+    const int gchunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 3;   // element offset inside the slab's 32
+    const uint32_t row_bytes = (uint32_t)w.dp * 2u;
+    uint32_t qoff[GQ], xoff[GX];   // xoff: for a tile whose XT rows all exist
 #pragma unroll
-    for (int h = 0; h < HQ; ++h) qrow[h] = min(q0 + fr + h * RP, a.nq - 1);
+    for (int h = 0; h < GQ; ++h)   // clamped: rows past the end are re-reads whose results are dropped
+        qoff[h] = (uint32_t)(min(q0 + 16 * (wave + 4 * h) + grow, a.nq - 1) - q0) * row_bytes + (uint32_t)gchunk * 2u;
+#pragma unroll
+    for (int h = 0; h < GX; ++h) xoff[h] = (uint32_t)(16 * (wave + 4 * h) + grow) * row_bytes + (uint32_t)gchunk * 2u;
+    const int xw = (wave * 64) % XT;   // this wave's share of the tile's norms (shares repeat where the tile has fewer than 256 rows)
     const int last_row = (int)(span1 - span0) - 1;
-    u32x4 stq[QPARTS][HQ], stx[QPARTS][HX];
-    float st_n = 0.f;
-    auto fetch = [&](int t, int sg) __attribute__((always_inline)) {
-        const int ko = sg * DK + fc * 8;
+    const uint32_t slab0 = lds_addr(wide_slabs), xn0 = lds_addr(&xn[0][0]);
+    // every call issues the same number of loads from every wave, so that "all but the last (NBUF - 2) calls' loads
+    // have landed" is one constant for s_waitcnt
+    auto fetch = [&](int buf, int t, int sg) __attribute__((always_inline)) {
+        const uint32_t base = slab0 + (uint32_t)(buf * SLAB) * 2u;
+        const int64_t qfirst = q0 * w.dp + sg * DK, xfirst = (span0 + (int64_t)t * XT) * w.dp + sg * DK;   // elements
+        const int lim = last_row - t * XT;   // last row of the tile that exists, counted from the tile's first
 #pragma unroll
-        for (int h = 0; h < HQ; ++h) {
-            stq[0][h] = *reinterpret_cast<const u32x4*>(a.qh + qrow[h] * w.dp + ko);
-            if constexpr (LO) stq[QPARTS - 1][h] = *reinterpret_cast<const u32x4*>(a.ql + qrow[h] * w.dp + ko);
+        for (int h = 0; h < GQ; ++h) {
+            const uint32_t at = __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave + 4 * h) * 16 * DK) * 2u);
+            lds_direct_b128(qoff[h], a.qh + qfirst, at);
+            if constexpr (LO) lds_direct_b128(qoff[h], a.ql + qfirst, at + (uint32_t)QPART * 2u);
+        }
+        uint32_t xo[GX], no = (uint32_t)(xw + lane) * 4u;
+#pragma unroll
+        for (int h = 0; h < GX; ++h) xo[h] = xoff[h];
+        if (lim < XT - 1) {   // the span's ragged last tile
+#pragma unroll
+            for (int h = 0; h < GX; ++h) xo[h] = (uint32_t)min(16 * (wave + 4 * h) + grow, lim) * row_bytes + (uint32_t)gchunk * 2u;
+            no = (uint32_t)min(xw + lane, lim) * 4u;
         }
 #pragma unroll
-        for (int h = 0; h < HX; ++h) {
-            const int64_t xr = span0 + min(t * XT + fr + h * RP, last_row);
-            stx[0][h] = *reinterpret_cast<const u32x4*>(a.xh + xr * w.dp + ko);
-            if constexpr (LO) stx[QPARTS - 1][h] = *reinterpret_cast<const u32x4*>(a.xl + xr * w.dp + ko);
+        for (int h = 0; h < GX; ++h) {
+            const uint32_t at = __builtin_amdgcn_readfirstlane(base + (uint32_t)(QPARTS * QPART + (wave + 4 * h) * 16 * DK) * 2u);
+            lds_direct_b128(xo[h], a.xh + xfirst, at);
+            if constexpr (LO) lds_direct_b128(xo[h], a.xl + xfirst, at + (uint32_t)XPART * 2u);
         }
-        if (threadIdx.x < XT) {
-            st_n = a.xnorm[span0 + min(t * XT + (int)threadIdx.x, last_row)];
-            if constexpr (FLT) st_n *= a.scale2;   // (the integer rows' norms are ints in these words)
-        }
+        // the tile's norms, again with every slab of it: the same words to the same place
+        lds_direct_b32(no, a.xnorm + span0 + (int64_t)t * XT, __builtin_amdgcn_readfirstlane(xn0 + (uint32_t)((t & 1) * XT + xw) * 4u));
     };
-    auto commit = [&](int buf, int t, int sg) __attribute__((always_inline)) {
-        uint16_t* slab = wide_slabs + buf * SLAB;
-#pragma unroll
-        for (int p = 0; p < QPARTS; ++p) {
-#pragma unroll
-            for (int h = 0; h < HQ; ++h)
-                *reinterpret_cast<u32x4*>(slab + p * QPART + wide_lds_offset<DK>(fr + h * RP, fc)) = stq[p][h];
-#pragma unroll
-            for (int h = 0; h < HX; ++h)
-                *reinterpret_cast<u32x4*>(slab + QPARTS * QPART + p * XPART + wide_lds_offset<DK>(fr + h * RP, fc)) = stx[p][h];
-        }
-        if (sg == 0 && threadIdx.x < XT) xn[t & 1][threadIdx.x] = st_n;
-    };
+    constexpr int AHEAD = NBUF - 1;                               // slabs on their way or landed beyond the current one
+    constexpr int kLoadsPerFetch = QPARTS * (GQ + GX) + 1;
+    constexpr int kWaitLeft = (AHEAD - 1) * kLoadsPerFetch;      // loads that may still be out when the current slab is needed
+    static_assert(kWaitLeft < 64, "s_waitcnt counts up to 63 vector memory operations");
 
     floatx16 acc[XB][2];
     int t = 0, sg = 0;       // slab being multiplied
-    int tn = 0, sn = 0;      // slab being fetched
-    fetch(0, 0);
-    commit(0, 0, 0);
-    __syncthreads();
+    int tn = 0, sn = 0;      // slab fetched last
+    fetch(0, 0, 0);
+#pragma unroll
+    for (int i = 1; i < AHEAD; ++i) {
+        if (i < G && ++sn == nstage) { sn = 0; ++tn; }
+        fetch(i, tn, sn);    // past the last slab this re-reads it, unused
+    }
     for (int g = 0; g < G; ++g) {
-        const int cur = g & 1;
-        const bool more = g + 1 < G;
-        if (more && ++sn == nstage) { sn = 0; ++tn; }
-        fetch(tn, sn);   // past the last slab this re-reads it, unused
+        const int cur = g % NBUF;
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLeft & 15) | ((kWaitLeft >> 4) << 14));   // vmcnt(kWaitLeft): this wave's share of slab g
+        __syncthreads();     // everyone's share; and every wave has left slab g - 1, whose buffer the next fetch fills
+        if (g + AHEAD < G && ++sn == nstage) { sn = 0; ++tn; }
+        fetch((g + AHEAD) % NBUF, tn, sn);
         if (sg == 0) {
 #pragma unroll
             for (int i = 0; i < XB; ++i)
@@ -852,8 +902,9 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * (32 * XB) + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                    if constexpr (FLT) {
-                        xv[4 * r4 + 0] = v.x; xv[4 * r4 + 1] = v.y; xv[4 * r4 + 2] = v.z; xv[4 * r4 + 3] = v.w;
+                    if constexpr (FLT) {   // in the accumulators' units
+                        xv[4 * r4 + 0] = v.x * a.scale2; xv[4 * r4 + 1] = v.y * a.scale2;
+                        xv[4 * r4 + 2] = v.z * a.scale2; xv[4 * r4 + 3] = v.w * a.scale2;
                     } else {  // the same words, read as the ints they are
                         xv[4 * r4 + 0] = __float_as_int(v.x); xv[4 * r4 + 1] = __float_as_int(v.y);
                         xv[4 * r4 + 2] = __float_as_int(v.z); xv[4 * r4 + 3] = __float_as_int(v.w);
@@ -867,11 +918,12 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                         if constexpr (FLT) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
                         else u[r] = xv[r] - 2 * (int)acc[i][j][r];
                     }
-                    V lo = u[0] < u[1] ? u[0] : u[1];
+                    V lo;   // (a float minimum that skips values that are no numbers: they pass no test below either)
+                    if constexpr (FLT) lo = __builtin_fminf(u[0], u[1]); else lo = min(u[0], u[1]);
 #pragma unroll
                     for (int r = 2; r < 16; r += 2) {
-                        const V p = u[r] < u[r + 1] ? u[r] : u[r + 1];
-                        lo = p < lo ? p : lo;
+                        if constexpr (FLT) lo = __builtin_fminf(lo, __builtin_fminf(u[r], u[r + 1]));
+                        else lo = min(lo, min(u[r], u[r + 1]));
                     }
                     if (ballot64(lo < tq[j])) {
                         uint32_t mask = 0;
@@ -896,14 +948,16 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
                 }
             }
         }
-        if (more) commit(cur ^ 1, tn, sn);
-        __syncthreads();
         if (tile_done) {
-            queue.flush(q0, a.cnt, a.buf, a.cap, !more);
+            __syncthreads();   // the tile's last push
+            queue.flush(q0, a.cnt, a.buf, a.cap, g + 1 == G);
+            sg = 0;
+            ++t;
+        } else {
+            ++sg;
         }
-        t = tn;
-        sg = sn;
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // the unused loads of the last rounds land before the workgroup's LDS is given back
 }
 
 // ---------------------------------------------------------------- per-row compaction
@@ -1340,8 +1394,9 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                                    : (float)(1.05 * (3.0 / 65536.0 + (6.0 * dp + 64.0) * 5.9604645e-8));
     const float split_err_const = single ? (float)(1.05 * (2.0 * delta * sq + 2.0 * dp * delta * delta) / (double)scale2) : 0.f;
 
-    // dynamic part, the slabs: two buffers of four parts 32 deep (hi + lo) or two parts 64 deep (one part)
-    constexpr size_t kWideLds = (size_t)2 * 4 * kTile * kWideDK * sizeof(uint16_t);
+    // dynamic part, the slabs
+    const int wmode = !wide ? 0 : single ? 2 : 1;
+    const size_t kWideLds = wide_lds_bytes(wmode);
     if (wide || iwide) {
         hipError_t e = hipFuncSetAttribute(!wide ? reinterpret_cast<const void*>(&filter_wide_kernel<0>)
                                            : single ? reinterpret_cast<const void*>(&filter_wide_kernel<2>)
