@@ -136,14 +136,15 @@ struct SurvivorQueue {
             if (pos < (unsigned)cap) buf[global_row * cap + pos] = k;
         }
     }
-    // all 256 threads, after a barrier that follows the last push; empties the queue once it is half full
+    // all THREADS threads of the workgroup, after a barrier that follows the last push; empties the queue once it is half full
     // (or holds anything and `last` is set).  row0 = global row of the workgroup's first query.
+    template <int THREADS = 256>
     __device__ __forceinline__ void flush(int64_t row0, unsigned* cnt, uint64_t* buf, int cap, bool last)
     {
         const unsigned queued = count;
         if (queued >= (unsigned)CAPQ / 2 || (last && queued > 0)) {
             const unsigned n = min(queued, (unsigned)CAPQ);
-            for (unsigned e = threadIdx.x; e < n; e += 256) {
+            for (unsigned e = threadIdx.x; e < n; e += THREADS) {
                 const int64_t r = row0 + row[e];
                 const unsigned pos = atomicAdd(&cnt[r], 1u);
                 if (pos < (unsigned)cap) buf[r * cap + pos] = key[e];
@@ -655,38 +656,43 @@ __global__ __launch_bounds__(256, (SINGLE && KS <= 6) ? 3 : 2) void filter_split
 // ---------------------------------------------------------------- rows wider than 128 elements
 // The same contraction when a query's fragments no longer fit the registers (MODE 1: hi + lo parts; MODE 2:
 // one scaled binary16 part; MODE 0: integer rows, which are exact in bf16, one part, one MFMA per k-step): both
-// operands go through LDS in slabs of 32 elements of the k dimension, double buffered, with
-// the loads of slab g+1 in flight during the MFMAs of slab g.  One workgroup owns a tile of
-// 128 queries x 128 candidates with hi + lo parts (4 waves, 64 x 64 each = 2 x 2 blocks of 32 x 32, 12 MFMAs
-// per 16 elements of k) and of 128 x 256 with one part per operand (64 x 128 per wave, 8 MFMAs per 16
-// elements of k); the filter runs once per tile, after the last slab, so it is amortised
-// over d / 16 k-steps and needs none of the tricks of the register kernels: u = |x|^2 - 2 q.x
-// is formed from the finished accumulators.
-// LDS rows are 64 bytes with no padding; the 16-byte chunk c of row r is stored at chunk
-// c ^ ((r >> 2) & 3), which spreads the 16 rows a fragment read touches per cycle over all banks.
+// operands go through LDS in slabs of the k dimension, two buffers, the LDS-direct loads of slab g+1 on
+// their way during the MFMAs of slab g (one barrier per slab).  The filter runs once per tile, after the last
+// slab, so it is amortised over d / 16 k-steps and needs none of the tricks of the register kernels:
+// u = |x|^2 - 2 q.x is formed from the finished accumulators.
 // Workgroups are numbered so that those resident together form a block of q_group query tiles
 // times a few candidate spans: the slabs they stream are then shared through the L2 caches
 // instead of each being fetched from memory once per workgroup.
-constexpr int kWideDK = 32;
+constexpr int kWidePad = 64;   // rows are padded with zeros to a multiple of this many elements (every slab depth divides it)
 
 struct WideArgs {
     SplitArgs s;
     int dp;            // padded row length (a multiple of the slab depth)
-    int q_tiles, ny;   // query tiles of 128 rows; candidate spans of tiles_per_block tiles
+    int q_tiles, ny;   // query tiles; candidate spans of tiles_per_block tiles
     int q_group;       // query tiles per group of the block numbering
 };
 
-// 32-row candidate blocks per wave: with one part per operand a wave multiplies its 64 queries with 128
-// candidates (a 128 x 256 workgroup tile: a quarter fewer bytes fetched per MFMA), with hi + lo parts with 64
-constexpr int wide_x_blocks(int mode) { return mode == 1 ? 2 : 4; }
-
-// slab buffers: three where a workgroup's slabs are 24 KB (two on their way while one is multiplied, two workgroups
-// per compute unit), two for the 32 KB slabs of the hi + lo form
-constexpr int wide_buffers(int mode) { return mode == 1 ? 2 : 3; }
-constexpr size_t wide_lds_bytes(int mode)
-{
-    return (size_t)wide_buffers(mode) * (mode == 1 ? 2 : 1) * (kTile + 64 * wide_x_blocks(mode)) * kWideDK * sizeof(uint16_t);
-}
+// The shape of a workgroup.  One part per operand (MODE 0, 2): eight waves, four along the queries and two along
+// the candidates, each 64 queries x 128 candidates (8 MFMAs per 6 fragment reads), a 256 x 256 tile, slabs 64 deep
+// (64 KB, two buffers, one workgroup per compute unit): a third fewer bytes fetched per MFMA than 128 x 256 and half
+// the barriers of slabs 32 deep.  hi + lo parts (MODE 1): four waves of 64 x 64, a 128 x 128 tile, slabs 32 deep.
+template <int MODE>
+struct WideShape {
+    static constexpr int WQ = MODE == 1 ? 2 : 4;         // waves along the queries, 64 rows each
+    static constexpr int XB = MODE == 1 ? 2 : 4;         // 32-row candidate blocks per wave
+    static constexpr int DK = MODE == 1 ? 32 : 64;       // elements of k per slab
+    static constexpr int NBUF = 2;                       // slab buffers
+    static constexpr int PARTS = MODE == 1 ? 2 : 1;
+    static constexpr int QT = 64 * WQ, XT = 64 * XB;     // rows of the tile: queries, candidates
+    static constexpr int THREADS = 128 * WQ;
+    static constexpr int SLAB = PARTS * (QT + XT) * DK;  // elements
+    static constexpr size_t lds_bytes = (size_t)NBUF * SLAB * sizeof(uint16_t);
+};
+struct WideLaunch { int qt, xt, threads; size_t lds; };
+template <int MODE> constexpr WideLaunch wide_launch_of() { using S = WideShape<MODE>; return {S::QT, S::XT, S::THREADS, S::lds_bytes}; }
+// candidate rows that one workgroup sweeps
+constexpr int wide_span_rows(int mode) { return mode == 1 ? 512 : 2048; }
+constexpr WideLaunch wide_launch(int mode) { return mode == 0 ? wide_launch_of<0>() : mode == 1 ? wide_launch_of<1>() : wide_launch_of<2>(); }
 
 // LDS-direct loads: the wave's 64 lanes x 16 (or 4) bytes land contiguously at the LDS address in m0, lane by lane.
 // Issued through inline assembly: the compiler would make every later LDS read wait for all of them, which takes
@@ -716,33 +722,40 @@ template <typename P> __device__ __forceinline__ uint32_t lds_addr(P* p)
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(p);
 }
 
-// DK = 32 elements (64 bytes) per LDS row, no padding: 16-byte chunk c of row r sits at chunk c ^ ((r >> 2) & 3)
+// LDS rows are DK elements with no padding; 16-byte chunk c of row r sits at chunk c ^ swizzle(r).  A 16-byte read
+// is served 16 lanes (here: 16 consecutive rows, one chunk) per cycle from 64 banks of 4 bytes, so the 16 slots have
+// to differ in byte address mod 256: with 64-byte rows four rows already do and the place changes every four rows;
+// with 128-byte rows two rows do and the place changes every two.  (Measured: places c ^ (r & 7) on 128-byte rows
+// cost one conflict cycle per access cycle; these cost none.)  The period is 16 rows in both.
+template <int DK> __device__ __forceinline__ int wide_swizzle(int row) { return DK == 32 ? (row >> 2) & 3 : (row >> 1) & 7; }
 template <int DK>
 __device__ __forceinline__ int wide_lds_offset(int row, int chunk)
 {
-    static_assert(DK == 32, "the swizzle is written for 64-byte rows");
-    return row * DK + ((chunk ^ ((row >> 2) & 3)) << 3);
+    static_assert(DK == 32 || DK == 64, "the swizzles are written for 64- and 128-byte rows");
+    return row * DK + ((chunk ^ wide_swizzle<DK>(row)) << 3);
 }
 
 // MODE 0: centred integer rows, one bf16 part, exact (filter in int32); 1: real-valued rows as bf16 hi + lo;
 // 2: real-valued rows as one scaled binary16 part (see filter_split_kernel's SINGLE).
 template <int MODE>
-__global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
+__global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kernel(WideArgs w)
 {
+    using S = WideShape<MODE>;
     constexpr bool LO = MODE == 1;    // lo parts staged and multiplied
     constexpr bool FLT = MODE != 0;   // float arithmetic with a rounding margin downstream
     using frag_t = std::conditional_t<MODE == 2, half8, bf16x8>;
     const SplitArgs& a = w.s;
-    constexpr int DK = kWideDK;                   // elements of k per slab
-    constexpr int XB = wide_x_blocks(MODE);      // 32-row candidate blocks per wave
-    constexpr int XT = 2 * 32 * XB;              // candidate rows per workgroup tile (two waves side by side)
-    constexpr int NBUF = wide_buffers(MODE);
-    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [NBUF][q parts: 128 * DK | x parts: XT * DK]
+    constexpr int DK = S::DK;                     // elements of k per slab
+    constexpr int XB = S::XB;                     // 32-row candidate blocks per wave
+    constexpr int QT = S::QT, XT = S::XT;         // rows of the workgroup's tile
+    constexpr int NW = 2 * S::WQ;                 // waves: WQ along the queries x two side by side along the candidates
+    constexpr int NBUF = S::NBUF;
+    extern __shared__ __attribute__((aligned(16))) uint16_t wide_slabs[];   // [NBUF][q parts: QT * DK | x parts: XT * DK]
     __shared__ __attribute__((aligned(16))) float xn[2][XT];
     __shared__ SurvivorQueue<kSplitQueue> queue;
-    constexpr int QPART = kTile * DK, XPART = XT * DK;   // elements of one part of a slab, per operand
-    constexpr int QPARTS = LO ? 2 : 1;
-    constexpr int SLAB = QPARTS * (QPART + XPART);
+    constexpr int QPART = QT * DK, XPART = XT * DK;   // elements of one part of a slab, per operand
+    constexpr int QPARTS = S::PARTS;
+    constexpr int SLAB = S::SLAB;
 
     // block numbering: groups of q_group query tiles, inside a group the query tile varies fastest
     const int64_t b = linear_block();
@@ -750,7 +763,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int64_t per_group = (int64_t)w.q_group * w.ny;
     const int64_t grp = b / per_group, within = b - grp * per_group;
     const int gq = (int)min((int64_t)w.q_group, (int64_t)w.q_tiles - grp * w.q_group);
-    const int64_t q0 = (grp * w.q_group + within % gq) * kTile;
+    const int64_t q0 = (grp * w.q_group + within % gq) * QT;
     const int64_t y = within / gq;
 
     const int lane = lane_id();
@@ -785,21 +798,24 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
     const int nstage = w.dp / DK;
     const int G = ntiles * nstage;
 
-    // A slab comes in by LDS-direct loads: the 64 lanes of one load fill 1 KB, i.e. 16 rows of 64 bytes; lane l
-    // fills place l & 3 of row l >> 2 of its group and so fetches the chunk that the swizzle keeps there.  No
-    // staging registers and no LDS stores, so NBUF - 1 slabs can be on their way while one is multiplied.
+    // A slab comes in by LDS-direct loads: the 64 lanes of one load fill 1 KB, i.e. GR rows of the slab; lane l fills
+    // place l % CPR of row l / CPR of its group and so fetches the chunk that the swizzle keeps there.  No staging
+    // registers and no LDS stores, so NBUF - 1 slabs can be on their way while one is multiplied.
     // Addresses are a scalar base (part, tile, slab: all uniform) plus a 32-bit offset per lane that does not change
     // from slab to slab, so that a fetch costs the vector unit nothing but the loads themselves.
-    constexpr int GQ = kTile / 16 / 4, GX = XT / 16 / 4;   // 16-row groups per wave and part: queries, candidates
-    const int grow = lane >> 2;
-    const int gchunk = ((lane & 3) ^ ((lane >> 4) & 3)) << 3;   // element offset inside the slab's 32
+    constexpr int CPR = DK / 8, GR = 64 / CPR;               // 16-byte chunks per slab row; rows per load
+    constexpr int GQ = QT / GR / NW, GX = XT / GR / NW;      // loads per wave and part: queries, candidates
+    static_assert(GQ * GR * NW == QT && GX * GR * NW == XT, "the loads tile the slab");
+    static_assert((GR * NW) % 16 == 0, "a wave's groups all start at the same place of the swizzle's 16-row period");
+    const int grow = lane / CPR;
+    const int gchunk = ((lane % CPR) ^ wide_swizzle<DK>(GR * wave + grow)) << 3;   // element offset inside the slab's DK
     const uint32_t row_bytes = (uint32_t)w.dp * 2u;
     uint32_t qoff[GQ], xoff[GX];   // xoff: for a tile whose XT rows all exist
 #pragma unroll
     for (int h = 0; h < GQ; ++h)   // clamped: rows past the end are re-reads whose results are dropped
-        qoff[h] = (uint32_t)(min(q0 + 16 * (wave + 4 * h) + grow, a.nq - 1) - q0) * row_bytes + (uint32_t)gchunk * 2u;
+        qoff[h] = (uint32_t)(min(q0 + GR * (wave + NW * h) + grow, a.nq - 1) - q0) * row_bytes + (uint32_t)gchunk * 2u;
 #pragma unroll
-    for (int h = 0; h < GX; ++h) xoff[h] = (uint32_t)(16 * (wave + 4 * h) + grow) * row_bytes + (uint32_t)gchunk * 2u;
+    for (int h = 0; h < GX; ++h) xoff[h] = (uint32_t)(GR * (wave + NW * h) + grow) * row_bytes + (uint32_t)gchunk * 2u;
     const int xw = (wave * 64) % XT;   // this wave's share of the tile's norms (shares repeat where the tile has fewer than 256 rows)
     const int last_row = (int)(span1 - span0) - 1;
     const uint32_t slab0 = lds_addr(wide_slabs), xn0 = lds_addr(&xn[0][0]);
@@ -811,7 +827,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         const int lim = last_row - t * XT;   // last row of the tile that exists, counted from the tile's first
 #pragma unroll
         for (int h = 0; h < GQ; ++h) {
-            const uint32_t at = __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave + 4 * h) * 16 * DK) * 2u);
+            const uint32_t at = __builtin_amdgcn_readfirstlane(base + (uint32_t)((wave + NW * h) * GR * DK) * 2u);
             lds_direct_b128(qoff[h], a.qh + qfirst, at);
             if constexpr (LO) lds_direct_b128(qoff[h], a.ql + qfirst, at + (uint32_t)QPART * 2u);
         }
@@ -820,12 +836,12 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         for (int h = 0; h < GX; ++h) xo[h] = xoff[h];
         if (lim < XT - 1) {   // the span's ragged last tile
 #pragma unroll
-            for (int h = 0; h < GX; ++h) xo[h] = (uint32_t)min(16 * (wave + 4 * h) + grow, lim) * row_bytes + (uint32_t)gchunk * 2u;
+            for (int h = 0; h < GX; ++h) xo[h] = (uint32_t)min(GR * (wave + NW * h) + grow, lim) * row_bytes + (uint32_t)gchunk * 2u;
             no = (uint32_t)min(xw + lane, lim) * 4u;
         }
 #pragma unroll
         for (int h = 0; h < GX; ++h) {
-            const uint32_t at = __builtin_amdgcn_readfirstlane(base + (uint32_t)(QPARTS * QPART + (wave + 4 * h) * 16 * DK) * 2u);
+            const uint32_t at = __builtin_amdgcn_readfirstlane(base + (uint32_t)(QPARTS * QPART + (wave + NW * h) * GR * DK) * 2u);
             lds_direct_b128(xo[h], a.xh + xfirst, at);
             if constexpr (LO) lds_direct_b128(xo[h], a.xl + xfirst, at + (uint32_t)XPART * 2u);
         }
@@ -852,46 +868,64 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         __syncthreads();     // everyone's share; and every wave has left slab g - 1, whose buffer the next fetch fills
         if (g + AHEAD < G && ++sn == nstage) { sn = 0; ++tn; }
         fetch((g + AHEAD) % NBUF, tn, sn);
-        if (sg == 0) {
-#pragma unroll
-            for (int i = 0; i < XB; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-        }
+        // The fragments of step k + 1 are asked for while step k multiplies: the queries' into a second set of
+        // registers at the start of the step, each candidate block's in place as soon as its two MFMAs are issued, so
+        // that every read has six MFMAs or more between itself and its first use.  (Left to itself the compiler keeps
+        // four fragments' worth of registers and waits for most reads right after issuing them.)
         const uint16_t* slab = wide_slabs + cur * SLAB;
-#pragma unroll
-        for (int k16 = 0; k16 < DK / 16; ++k16) {
+        constexpr int KS = DK / 16;
+        frag_t qh[2][2], ql[2][2], xh[XB], xl[XB];
+        auto read_q = [&](int k16, int b) __attribute__((always_inline)) {
             const int chunk = k16 * 2 + (lane >> 5);
-            frag_t qh[2], ql[2], xh[XB], xl[XB];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int qo = wide_lds_offset<DK>(wq * 64 + j * 32 + (lane & 31), chunk);
-                qh[j] = *reinterpret_cast<const frag_t*>(slab + qo);
-                if constexpr (LO) ql[j] = *reinterpret_cast<const frag_t*>(slab + QPART + qo);
+                qh[b][j] = *reinterpret_cast<const frag_t*>(slab + qo);
+                if constexpr (LO) ql[b][j] = *reinterpret_cast<const frag_t*>(slab + QPART + qo);
             }
+        };
+        auto read_x = [&](int k16, int i) __attribute__((always_inline)) {
+            const int chunk = k16 * 2 + (lane >> 5);
+            const int xo = wide_lds_offset<DK>(wc * (32 * XB) + i * 32 + (lane & 31), chunk);
+            xh[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + xo);
+            if constexpr (LO) xl[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + XPART + xo);
+        };
+        read_q(0, 0);
+#pragma unroll
+        for (int i = 0; i < XB; ++i) read_x(0, i);
+        // (a tile's first step takes zero as its third operand instead of accumulators set to zero beforehand)
+        auto step = [&](int k16, auto fresh) __attribute__((always_inline)) {
+            const int b = k16 & 1;
+            if (k16 + 1 < KS) read_q(k16 + 1, b ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
-                const int xo = wide_lds_offset<DK>(wc * (32 * XB) + i * 32 + (lane & 31), chunk);
-                xh[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + xo);
-                if constexpr (LO) xl[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + XPART + xo);
-            }
-#pragma unroll
-            for (int i = 0; i < XB; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
+                    floatx16 c = acc[i][j];
+                    if constexpr (decltype(fresh)::value) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) c[r] = 0.f;
+                    }
                     if constexpr (MODE == 2) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh[i], qh[j], acc[i][j], 0, 0, 0);
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh[i], qh[b][j], c, 0, 0, 0);
                     } else {
                         if constexpr (LO) {
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[j], acc[i][j], 0, 0, 0);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[j], acc[i][j], 0, 0, 0);
+                            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[b][j], c, 0, 0, 0);
+                            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[b][j], c, 0, 0, 0);
                         }
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[j], acc[i][j], 0, 0, 0);
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[b][j], c, 0, 0, 0);
                     }
+                    acc[i][j] = c;
                 }
-        }
+                if (k16 + 1 < KS) read_x(k16 + 1, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        if (sg == 0) step(0, std::true_type{});
+        else step(0, std::false_type{});
+#pragma unroll
+        for (int k16 = 1; k16 < KS; ++k16) step(k16, std::false_type{});
         const bool tile_done = sg == nstage - 1;
         if (tile_done) {
             // lane l, register r of block (i, j): candidate row 8*(r/4) + 4*(l/32) + r%4 of block i, query l%32 of block j
@@ -950,7 +984,7 @@ __global__ __launch_bounds__(256, 2) void filter_wide_kernel(WideArgs w)
         }
         if (tile_done) {
             __syncthreads();   // the tile's last push
-            queue.flush(q0, a.cnt, a.buf, a.cap, g + 1 == G);
+            queue.template flush<S::THREADS>(q0, a.cnt, a.buf, a.cap, g + 1 == G);
             sg = 0;
             ++t;
         } else {
@@ -1303,7 +1337,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
         else scale = std::ldexp(1.f, e);
     }
     const float scale2 = scale * scale;
-    const int wdk = kWideDK;   // slab depth of the staged kernel
+    const int wdk = kWidePad;   // the staged kernel's rows: whole slabs
     const int ks = (d + 15) / 16;
     const int dp = wide ? (d + wdk - 1) / wdk * wdk : ks * 16;
 
@@ -1326,7 +1360,7 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
     // integer rows of 129..1024 elements: centred, exact in bf16, so the staged kernel runs on one part
     // per row (one MFMA per k-step) and filters in int32
     const bool iwide = exact && !fast;
-    const int dpi = (d + kWideDK - 1) / kWideDK * kWideDK;
+    const int dpi = (d + kWidePad - 1) / kWidePad * kWidePad;
     DevBuf xb16, qb16, xn16, qn16;
     if (iwide) {
         TSDG_HIP(xb16.alloc((size_t)N * dpi * 2));
@@ -1396,7 +1430,8 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
 
     // dynamic part, the slabs
     const int wmode = !wide ? 0 : single ? 2 : 1;
-    const size_t kWideLds = wide_lds_bytes(wmode);
+    const WideLaunch wl = wide_launch(wmode);
+    const size_t kWideLds = wl.lds;
     if (wide || iwide) {
         hipError_t e = hipFuncSetAttribute(!wide ? reinterpret_cast<const void*>(&filter_wide_kernel<0>)
                                            : single ? reinterpret_cast<const void*>(&filter_wide_kernel<2>)
@@ -1498,18 +1533,17 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 sa.self_offset = f.self_offset;
                 sa.cap = cap;
                 if (wide) {
-                    const int xt = 64 * wide_x_blocks(single ? 2 : 1);   // candidate rows per workgroup tile
-                    const int64_t wtiles = (ce - cb + xt - 1) / xt;
-                    sa.tiles_per_block = (int)std::min<int64_t>(512 / xt, wtiles);
+                    const int64_t wtiles = (ce - cb + wl.xt - 1) / wl.xt;
+                    sa.tiles_per_block = (int)std::min<int64_t>(wide_span_rows(wmode) / wl.xt, wtiles);
                     wa.dp = dp;
-                    wa.q_tiles = (int)((nr + kTile - 1) / kTile);
+                    wa.q_tiles = (int)((nr + wl.qt - 1) / wl.qt);
                     wa.ny = (int)((wtiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                     wa.q_group = 64;
                     if (single)
-                        TSDG_LAUNCH(filter_wide_kernel<2>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                        TSDG_LAUNCH(filter_wide_kernel<2>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(wl.threads),
                                            kWideLds, stream, wa);
                     else
-                        TSDG_LAUNCH(filter_wide_kernel<1>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                        TSDG_LAUNCH(filter_wide_kernel<1>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(wl.threads),
                                            kWideLds, stream, wa);
                 } else {
                     const int srows = split_tile_rows(ks, single);
@@ -1544,14 +1578,13 @@ ann_status knn_typed(const TB* base, int64_t N, int d, ann_dtype dtype, const TQ
                 sa.c_end = ce;
                 sa.self_offset = f.self_offset;
                 sa.cap = cap;
-                const int xt = 64 * wide_x_blocks(0);
-                const int64_t wtiles = (ce - cb + xt - 1) / xt;
-                sa.tiles_per_block = (int)std::min<int64_t>(512 / xt, wtiles);
+                const int64_t wtiles = (ce - cb + wl.xt - 1) / wl.xt;
+                sa.tiles_per_block = (int)std::min<int64_t>(wide_span_rows(wmode) / wl.xt, wtiles);
                 wa.dp = dpi;
-                wa.q_tiles = (int)((nr + kTile - 1) / kTile);
+                wa.q_tiles = (int)((nr + wl.qt - 1) / wl.qt);
                 wa.ny = (int)((wtiles + sa.tiles_per_block - 1) / sa.tiles_per_block);
                 wa.q_group = 64;
-                TSDG_LAUNCH(filter_wide_kernel<0>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(256),
+                TSDG_LAUNCH(filter_wide_kernel<0>, folded_grid((int64_t)wa.q_tiles * wa.ny), dim3(wl.threads),
                                    kWideLds, stream, wa);
             }
             TSDG_HIP(launch_error());
