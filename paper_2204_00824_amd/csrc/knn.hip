@@ -595,26 +595,40 @@ __global__ __launch_bounds__(256, (SINGLE && KS <= 6) ? 3 : 2) void filter_split
                 }
             }
         }
+        // The half's 2 * KS fragment reads (step s: k-step s / 2, candidate block s % 2) run AHEAD steps before the
+        // MFMAs that use them, in a ring of AHEAD register sets, the order pinned: left to itself the compiler keeps
+        // one set and waits for every read right after issuing it.  (Two sets: 2 % faster at d = 64..128; three
+        // sets spill under the three-waves-per-SIMD register limit and lose it again.)
+        constexpr int AHEAD = 2, STEPS = 2 * KS;
+        frag_t fh[AHEAD], fl[SINGLE ? 1 : AHEAD];
+        auto read_step = [&](int st) __attribute__((always_inline)) {
+            const int ks = st >> 1, i = st & 1;
+            const int off = (h * 64 + i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
+            fh[st % AHEAD] = *reinterpret_cast<const frag_t*>(&Xs[cur][0][off]);
+            if constexpr (!SINGLE) fl[st % AHEAD] = *reinterpret_cast<const frag_t*>(&Xs[cur][PARTS - 1][off]);
+        };
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int st = 0; st < AHEAD && st < STEPS; ++st) read_step(st);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int off = (h * 64 + i * 32 + (lane & 31)) * XS + ks * 16 + 8 * (lane >> 5);
-                const frag_t xh = *reinterpret_cast<const frag_t*>(&Xs[cur][0][off]);
-                if constexpr (SINGLE) {
+        for (int st = 0; st < STEPS; ++st) {
+            const int ks = st >> 1, i = st & 1;
+            const frag_t xh = fh[st % AHEAD];
+            if constexpr (SINGLE) {
 #pragma unroll
-                    for (int j = 0; j < QB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
-                } else {
-                    const frag_t xl = *reinterpret_cast<const frag_t*>(&Xs[cur][PARTS - 1][off]);
+                for (int j = 0; j < QB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
+            } else {
+                const frag_t xl = fl[st % AHEAD];
 #pragma unroll
-                    for (int j = 0; j < QB; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[j][ks], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[j][ks], acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
-                    }
+                for (int j = 0; j < QB; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, qfh[j][ks], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfl[j][ks], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, qfh[j][ks], acc[i][j], 0, 0, 0);
                 }
             }
+            if (st + AHEAD < STEPS) read_step(st + AHEAD);
+            __builtin_amdgcn_sched_barrier(0);
         }
         const int64_t c0 = span0 + (int64_t)t * ROWS + h * 64;
 #pragma unroll
@@ -848,85 +862,93 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
         // the tile's norms, again with every slab of it: the same words to the same place
         lds_direct_b32(no, a.xnorm + span0 + (int64_t)t * XT, __builtin_amdgcn_readfirstlane(xn0 + (uint32_t)((t & 1) * XT + xw) * 4u));
     };
-    constexpr int AHEAD = NBUF - 1;                               // slabs on their way or landed beyond the current one
-    constexpr int kLoadsPerFetch = QPARTS * (GQ + GX) + 1;
-    constexpr int kWaitLeft = (AHEAD - 1) * kLoadsPerFetch;      // loads that may still be out when the current slab is needed
-    static_assert(kWaitLeft < 64, "s_waitcnt counts up to 63 vector memory operations");
+    static_assert(NBUF == 2, "the loop below is written for two buffers");
+    constexpr int KS = DK / 16;
+    static_assert(KS >= 2 && KS % 2 == 0, "query fragments alternate between two register sets, step 0 in set 0");
 
+    // Fragment reads.  The fragments of step k + 1 are asked for while step k multiplies: the queries' into the other
+    // of two register sets at the start of the step, each candidate block's in place as soon as its two MFMAs are
+    // issued, the order pinned, so that every read has six MFMAs or more between itself and its first use.  (Left to
+    // itself the compiler keeps four fragments' worth of registers and waits for most reads right after issuing them.)
+    frag_t qh[2][2], ql[2][2], xh[XB], xl[XB];
+    auto read_q = [&](const uint16_t* slab, int k16, int b) __attribute__((always_inline)) {
+        const int chunk = k16 * 2 + (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int qo = wide_lds_offset<DK>(wq * 64 + j * 32 + (lane & 31), chunk);
+            qh[b][j] = *reinterpret_cast<const frag_t*>(slab + qo);
+            if constexpr (LO) ql[b][j] = *reinterpret_cast<const frag_t*>(slab + QPART + qo);
+        }
+    };
+    auto read_x = [&](const uint16_t* slab, int k16, int i) __attribute__((always_inline)) {
+        const int chunk = k16 * 2 + (lane >> 5);
+        const int xo = wide_lds_offset<DK>(wc * (32 * XB) + i * 32 + (lane & 31), chunk);
+        xh[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + xo);
+        if constexpr (LO) xl[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + XPART + xo);
+    };
     floatx16 acc[XB][2];
+    // step k16 of the current slab; `from`, k_next: where the reads issued during it come from.
+    // A tile's first step takes zero as its third operand instead of accumulators cleared beforehand.
+    auto step = [&](int k16, const uint16_t* from, int k_next, auto fresh) __attribute__((always_inline)) {
+        const int b = k16 & 1;
+        read_q(from, k_next, b ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < XB; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                floatx16 c = acc[i][j];
+                if constexpr (decltype(fresh)::value) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) c[r] = 0.f;
+                }
+                if constexpr (MODE == 2) {
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh[i], qh[b][j], c, 0, 0, 0);
+                } else {
+                    if constexpr (LO) {
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[b][j], c, 0, 0, 0);
+                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[b][j], c, 0, 0, 0);
+                    }
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[b][j], c, 0, 0, 0);
+                }
+                acc[i][j] = c;
+            }
+            read_x(from, k_next, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto first_fragments = [&](const uint16_t* slab) __attribute__((always_inline)) {
+        read_q(slab, 0, 0);
+#pragma unroll
+        for (int i = 0; i < XB; ++i) read_x(slab, 0, i);
+    };
+
+    // The slab's one barrier does not stand at the slab's end but right after its last fragment reads, one step
+    // before: by then every wave has everything it needs of the slab in registers (the buffer is free for the slab
+    // after next) and has waited for its own loads of the next slab (which is then complete), and the MFMAs of the
+    // last step run while the barrier is crossed and the next slab's first fragments are on their way.
     int t = 0, sg = 0;       // slab being multiplied
     int tn = 0, sn = 0;      // slab fetched last
     fetch(0, 0, 0);
-#pragma unroll
-    for (int i = 1; i < AHEAD; ++i) {
-        if (i < G && ++sn == nstage) { sn = 0; ++tn; }
-        fetch(i, tn, sn);    // past the last slab this re-reads it, unused
-    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+    if (1 < G && ++sn == nstage) { sn = 0; ++tn; }
+    fetch(1, tn, sn);        // past the last slab a fetch re-reads it, unused
+    first_fragments(wide_slabs);
     for (int g = 0; g < G; ++g) {
-        const int cur = g % NBUF;
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (kWaitLeft & 15) | ((kWaitLeft >> 4) << 14));   // vmcnt(kWaitLeft): this wave's share of slab g
-        __syncthreads();     // everyone's share; and every wave has left slab g - 1, whose buffer the next fetch fills
-        if (g + AHEAD < G && ++sn == nstage) { sn = 0; ++tn; }
-        fetch((g + AHEAD) % NBUF, tn, sn);
-        // The fragments of step k + 1 are asked for while step k multiplies: the queries' into a second set of
-        // registers at the start of the step, each candidate block's in place as soon as its two MFMAs are issued, so
-        // that every read has six MFMAs or more between itself and its first use.  (Left to itself the compiler keeps
-        // four fragments' worth of registers and waits for most reads right after issuing them.)
+        const int cur = g & 1;
         const uint16_t* slab = wide_slabs + cur * SLAB;
-        constexpr int KS = DK / 16;
-        frag_t qh[2][2], ql[2][2], xh[XB], xl[XB];
-        auto read_q = [&](int k16, int b) __attribute__((always_inline)) {
-            const int chunk = k16 * 2 + (lane >> 5);
+        const uint16_t* next = wide_slabs + (cur ^ 1) * SLAB;
+        const bool tile_done = sg == nstage - 1, more = g + 1 < G;
+        if (sg == 0) step(0, slab, 1, std::true_type{});
+        else step(0, slab, 1, std::false_type{});
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int qo = wide_lds_offset<DK>(wq * 64 + j * 32 + (lane & 31), chunk);
-                qh[b][j] = *reinterpret_cast<const frag_t*>(slab + qo);
-                if constexpr (LO) ql[b][j] = *reinterpret_cast<const frag_t*>(slab + QPART + qo);
-            }
-        };
-        auto read_x = [&](int k16, int i) __attribute__((always_inline)) {
-            const int chunk = k16 * 2 + (lane >> 5);
-            const int xo = wide_lds_offset<DK>(wc * (32 * XB) + i * 32 + (lane & 31), chunk);
-            xh[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + xo);
-            if constexpr (LO) xl[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + XPART + xo);
-        };
-        read_q(0, 0);
-#pragma unroll
-        for (int i = 0; i < XB; ++i) read_x(0, i);
-        // (a tile's first step takes zero as its third operand instead of accumulators set to zero beforehand)
-        auto step = [&](int k16, auto fresh) __attribute__((always_inline)) {
-            const int b = k16 & 1;
-            if (k16 + 1 < KS) read_q(k16 + 1, b ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < XB; ++i) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    floatx16 c = acc[i][j];
-                    if constexpr (decltype(fresh)::value) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) c[r] = 0.f;
-                    }
-                    if constexpr (MODE == 2) {
-                        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh[i], qh[b][j], c, 0, 0, 0);
-                    } else {
-                        if constexpr (LO) {
-                            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl[i], qh[b][j], c, 0, 0, 0);
-                            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], ql[b][j], c, 0, 0, 0);
-                        }
-                        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh[i], qh[b][j], c, 0, 0, 0);
-                    }
-                    acc[i][j] = c;
-                }
-                if (k16 + 1 < KS) read_x(k16 + 1, i);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        };
-        if (sg == 0) step(0, std::true_type{});
-        else step(0, std::false_type{});
-#pragma unroll
-        for (int k16 = 1; k16 < KS; ++k16) step(k16, std::false_type{});
-        const bool tile_done = sg == nstage - 1;
+        for (int k16 = 1; k16 + 1 < KS; ++k16) step(k16, slab, k16 + 1, std::false_type{});
+        __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0), lgkmcnt(0): the slab's last fragments and this wave's share of the next slab are there
+        __syncthreads();
+        if (g + 2 < G && ++sn == nstage) { sn = 0; ++tn; }
+        fetch(cur, tn, sn);
+        step(KS - 1, more ? next : slab, 0, std::false_type{});   // (after the last slab: reads of the same slab again, unused)
         if (tile_done) {
             // lane l, register r of block (i, j): candidate row 8*(r/4) + 4*(l/32) + r%4 of block i, query l%32 of block j
             const int64_t c0 = span0 + (int64_t)t * XT + wc * (32 * XB);
