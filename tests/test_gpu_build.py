@@ -153,6 +153,28 @@ def test_knn_real_valued_wide_rows(gpu, orc, d, N):
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"wide bf d={d}") == 0
 
 
+@pytest.mark.parametrize("kind", ["real", "integer"])
+def test_knn_wide_rows_over_several_spans(gpu, orc, kind):
+    """Wide rows on a set large enough that one launch holds 25 query tiles of 256 rows (the last with 56) and more
+    than one candidate span of 2,048 rows (the last span ending in a ragged tile): 6,200 x 264."""
+    step(f"ann_knn wide rows over several spans, {kind}")
+    N, d = 6200, 264
+    g = np.random.default_rng(77)
+    protos = g.normal(0, 1, size=(40, d))
+    base = protos[g.integers(0, 40, size=N)] + 0.4 * g.standard_normal((N, d))
+    if kind == "integer":
+        base = np.clip(np.rint(base * 30 + 128), 0, 255)
+    base = base.astype(np.float32)
+    ref = orc.knn(base, 24)
+    ids, s = gpu.ann_knn(dev(base), 24)
+    if kind == "integer":
+        assert_bitwise(ids.cpu().numpy(), ref[0], "ids")
+        assert_bitwise(s.cpu().numpy(), ref[1], "dists")
+    else:
+        assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], "several spans") == 0
+        assert_bitwise(s.cpu().numpy(), ref[1], "dists")
+
+
 @pytest.mark.parametrize("d", [208, 320, 1024, 1100])
 def test_knn_integer_wide_rows(gpu, orc, d):
     """Integer rows in [0,255] wider than 128 elements: centred they are exact in bf16 and, up to d = 1024,
