@@ -153,10 +153,10 @@ def test_knn_real_valued_wide_rows(gpu, orc, d, N):
     assert compare_topk(ids.cpu().numpy(), s.cpu().numpy(), ref[0], ref[1], f"wide bf d={d}") == 0
 
 
-@pytest.mark.parametrize("kind", ["real", "integer"])
+@pytest.mark.parametrize("kind", ["real", "real, hi + lo parts", "integer"])
 def test_knn_wide_rows_over_several_spans(gpu, orc, kind):
-    """Wide rows on a set large enough that one launch holds 25 query tiles of 256 rows (the last with 56) and more
-    than one candidate span of 2,048 rows (the last span ending in a ragged tile): 6,200 x 264."""
+    """Wide rows on a set large enough that one launch holds 25 query tiles of 256 rows (the last with 56; 49 of 128
+    rows with hi + lo parts) and more than one candidate span (the last ending in a ragged tile): 6,200 x 264."""
     step(f"ann_knn wide rows over several spans, {kind}")
     N, d = 6200, 264
     g = np.random.default_rng(77)
@@ -166,7 +166,7 @@ def test_knn_wide_rows_over_several_spans(gpu, orc, kind):
         base = np.clip(np.rint(base * 30 + 128), 0, 255)
     base = base.astype(np.float32)
     ref = orc.knn(base, 24)
-    ids, s = gpu.ann_knn(dev(base), 24)
+    ids, s = gpu.ann_knn(dev(base), 24, knn_filter=1 if "hi + lo" in kind else 0)
     if kind == "integer":
         assert_bitwise(ids.cpu().numpy(), ref[0], "ids")
         assert_bitwise(s.cpu().numpy(), ref[1], "dists")
