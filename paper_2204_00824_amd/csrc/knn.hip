@@ -833,8 +833,8 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
     const int xw = (wave * 64) % XT;   // this wave's share of the tile's norms (shares repeat where the tile has fewer than 256 rows)
     const int last_row = (int)(span1 - span0) - 1;
     const uint32_t slab0 = lds_addr(wide_slabs), xn0 = lds_addr(&xn[0][0]);
-    // every call issues the same number of loads from every wave, so that "all but the last (NBUF - 2) calls' loads
-    // have landed" is one constant for s_waitcnt
+    // one slab (and its tile's norms) into buffer buf; every wave waits for its own share with vmcnt(0) before the
+    // slab's barrier
     auto fetch = [&](int buf, int t, int sg) __attribute__((always_inline)) {
         const uint32_t base = slab0 + (uint32_t)(buf * SLAB) * 2u;
         const int64_t qfirst = q0 * w.dp + sg * DK, xfirst = (span0 + (int64_t)t * XT) * w.dp + sg * DK;   // elements
