@@ -887,6 +887,7 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
         if constexpr (LO) xl[i] = *reinterpret_cast<const frag_t*>(slab + QPARTS * QPART + XPART + xo);
     };
     floatx16 acc[XB][2];
+    int t = 0, sg = 0;       // tile and slab being multiplied
     // step k16 of the current slab; `from`, k_next: where the reads issued during it come from.
     // A tile's first step takes zero as its third operand instead of accumulators cleared beforehand.
     auto step = [&](int k16, const uint16_t* from, int k_next, auto fresh) __attribute__((always_inline)) {
@@ -895,12 +896,27 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < XB; ++i) {
+            // Float modes: a tile's accumulators start at -|x|^2 / 2 of their rows (lane l, register r: row
+            // 8*(r/4) + 4*(l/32) + r%4 of the block) and end as q.x - |x|^2 / 2 = -u / 2, so the filter is a maximum
+            // and one compare per block with no arithmetic on the accumulators; the same sums, scaled by -1/2, as in
+            // the register kernel, whose error bound is the one in use.  The integer mode starts at zero (half an odd
+            // norm is no integer) and forms u in its filter.
+            float start[16];
+            if constexpr (decltype(fresh)::value && FLT) {
+                const float half = -0.5f * a.scale2;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * (32 * XB) + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
+                    start[4 * r4 + 0] = v.x * half; start[4 * r4 + 1] = v.y * half;
+                    start[4 * r4 + 2] = v.z * half; start[4 * r4 + 3] = v.w * half;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 floatx16 c = acc[i][j];
                 if constexpr (decltype(fresh)::value) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) c[r] = 0.f;
+                    for (int r = 0; r < 16; ++r) c[r] = FLT ? start[r] : 0.f;
                 }
                 if constexpr (MODE == 2) {
                     c = __builtin_amdgcn_mfma_f32_32x32x16_f16(xh[i], qh[b][j], c, 0, 0, 0);
@@ -927,7 +943,6 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
     // before: by then every wave has everything it needs of the slab in registers (the buffer is free for the slab
     // after next) and has waited for its own loads of the next slab (which is then complete), and the MFMAs of the
     // last step run while the barrier is crossed and the next slab's first fragments are on their way.
-    int t = 0, sg = 0;       // slab being multiplied
     int tn = 0, sn = 0;      // slab fetched last
     fetch(0, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
@@ -955,23 +970,23 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
 #pragma unroll
             for (int i = 0; i < XB; ++i) {
                 V xv[16];
+                if constexpr (!FLT) {
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * (32 * XB) + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
-                    if constexpr (FLT) {   // in the accumulators' units
-                        xv[4 * r4 + 0] = v.x * a.scale2; xv[4 * r4 + 1] = v.y * a.scale2;
-                        xv[4 * r4 + 2] = v.z * a.scale2; xv[4 * r4 + 3] = v.w * a.scale2;
-                    } else {  // the same words, read as the ints they are
+                    for (int r4 = 0; r4 < 4; ++r4) {   // the norms' words, read as the ints they are
+                        const float4 v = *reinterpret_cast<const float4*>(&xn[t & 1][wc * (32 * XB) + i * 32 + 8 * r4 + 4 * (lane >> 5)]);
                         xv[4 * r4 + 0] = __float_as_int(v.x); xv[4 * r4 + 1] = __float_as_int(v.y);
                         xv[4 * r4 + 2] = __float_as_int(v.z); xv[4 * r4 + 3] = __float_as_int(v.w);
                     }
                 }
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
+                    // u = |x|^2 - 2 q.x against tq; the float modes hold -u / 2 in the accumulators and test
+                    // u / 2 against tq / 2 (exact scalings; the sign rides on the instructions' operands)
+                    const V tqj = FLT ? (V)(0.5f * (float)tq[j]) : tq[j];
                     V u[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        if constexpr (FLT) u[r] = __builtin_fmaf(-2.f, acc[i][j][r], xv[r]);
+                        if constexpr (FLT) u[r] = -acc[i][j][r];
                         else u[r] = xv[r] - 2 * (int)acc[i][j][r];
                     }
                     V lo;   // (a float minimum that skips values that are no numbers: they pass no test below either)
@@ -981,10 +996,10 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
                         if constexpr (FLT) lo = __builtin_fminf(lo, __builtin_fminf(u[r], u[r + 1]));
                         else lo = min(lo, min(u[r], u[r + 1]));
                     }
-                    if (ballot64(lo < tq[j])) {
+                    if (ballot64(lo < tqj)) {
                         uint32_t mask = 0;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) mask |= (u[r] < tq[j]) ? (1u << r) : 0u;
+                        for (int r = 0; r < 16; ++r) mask |= (u[r] < tqj) ? (1u << r) : 0u;
 #pragma unroll 1
                         while (ballot64(mask != 0u)) {
                             const int rr = mask ? (int)__builtin_ctz(mask) : 16;
@@ -995,7 +1010,7 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
                             const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                             const int64_t c = c0 + m;
                             if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
-                                const float sf = FLT ? fmaxf((float)(uv + qn[j]), 0.f) * a.inv_scale2 : (float)max((int)(uv + qn[j]), 0);
+                                const float sf = FLT ? fmaxf(2.f * (float)uv + (float)qn[j], 0.f) * a.inv_scale2 : (float)max((int)(uv + qn[j]), 0);
                                 const uint64_t key = ((uint64_t)__float_as_uint(sf) << 32) | (uint64_t)(uint32_t)c;
                                 queue.push(key, wq * 64 + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                             }
