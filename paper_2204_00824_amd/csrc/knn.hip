@@ -980,37 +980,40 @@ __global__ __launch_bounds__(WideShape<MODE>::THREADS, 2) void filter_wide_kerne
                 }
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    // u = |x|^2 - 2 q.x against tq; the float modes hold -u / 2 in the accumulators and test
-                    // u / 2 against tq / 2 (exact scalings; the sign rides on the instructions' operands)
-                    const V tqj = FLT ? (V)(0.5f * (float)tq[j]) : tq[j];
-                    V u[16];
+                    // u = |x|^2 - 2 q.x against tq.  The float modes hold -u / 2 in the accumulators and test the largest
+                    // of them against -tq / 2 (exact scalings); w[] is what the test looks at, `below` says which way.
+                    V w[16], lim, ext;
+                    if constexpr (FLT) {
+                        lim = (V)(-0.5f * (float)tq[j]);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        if constexpr (FLT) u[r] = -acc[i][j][r];
-                        else u[r] = xv[r] - 2 * (int)acc[i][j][r];
-                    }
-                    V lo;   // (a float minimum that skips values that are no numbers: they pass no test below either)
-                    if constexpr (FLT) lo = __builtin_fminf(u[0], u[1]); else lo = min(u[0], u[1]);
+                        for (int r = 0; r < 16; ++r) w[r] = acc[i][j][r];
+                        ext = __builtin_fmaxf(w[0], w[1]);   // (a maximum that skips values that are no numbers: they pass no test below either)
 #pragma unroll
-                    for (int r = 2; r < 16; r += 2) {
-                        if constexpr (FLT) lo = __builtin_fminf(lo, __builtin_fminf(u[r], u[r + 1]));
-                        else lo = min(lo, min(u[r], u[r + 1]));
+                        for (int r = 2; r < 16; r += 2) ext = __builtin_fmaxf(__builtin_fmaxf(ext, w[r]), w[r + 1]);
+                    } else {
+                        lim = tq[j];
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) w[r] = xv[r] - 2 * (int)acc[i][j][r];
+                        ext = min(w[0], w[1]);
+#pragma unroll
+                        for (int r = 2; r < 16; r += 2) ext = min(ext, min(w[r], w[r + 1]));
                     }
-                    if (ballot64(lo < tqj)) {
+                    auto passes = [&](V v) __attribute__((always_inline)) { return FLT ? v > lim : v < lim; };
+                    if (ballot64(passes(ext))) {
                         uint32_t mask = 0;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) mask |= (u[r] < tqj) ? (1u << r) : 0u;
+                        for (int r = 0; r < 16; ++r) mask |= passes(w[r]) ? (1u << r) : 0u;
 #pragma unroll 1
                         while (ballot64(mask != 0u)) {
                             const int rr = mask ? (int)__builtin_ctz(mask) : 16;
                             mask &= mask - 1u;
                             V uv = 0;
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) uv = rr == r ? u[r] : uv;
+                            for (int r = 0; r < 16; ++r) uv = rr == r ? w[r] : uv;
                             const int m = i * 32 + 8 * (rr >> 2) + 4 * (lane >> 5) + (rr & 3);
                             const int64_t c = c0 + m;
                             if (rr < 16 && c < span1 && c != a.self_offset + qg[j]) {
-                                const float sf = FLT ? fmaxf(2.f * (float)uv + (float)qn[j], 0.f) * a.inv_scale2 : (float)max((int)(uv + qn[j]), 0);
+                                const float sf = FLT ? fmaxf((float)qn[j] - 2.f * (float)uv, 0.f) * a.inv_scale2 : (float)max((int)(uv + qn[j]), 0);
                                 const uint64_t key = ((uint64_t)__float_as_uint(sf) << 32) | (uint64_t)(uint32_t)c;
                                 queue.push(key, wq * 64 + j * 32 + (lane & 31), qg[j], a.cnt, a.buf, a.cap);
                             }
