@@ -323,7 +323,11 @@ def main():
             "kernel": search_kernel_name(L2), "kernel_ms": round(k2ms, 4), "launches_timed": len(kern2),
             "algorithmic_bytes_per_launch": round(b2), "dist_evals_per_query": round(evals2, 2),
             "hops_per_query": round(hops2, 2), "base_bytes": args.large_base_n * d * 4,
-            "build_seconds": WL.build["seconds"], "build_stage1": WL.build["stage1"], "build_stage2": WL.build["stage2"]}
+            "build_seconds": WL.build["seconds"], "build_stage1": WL.build["stage1"], "build_stage2": WL.build["stage2"],
+            # the exact k-NN inside that build (device time of its kernels) against the dense int8 MFMA peak
+            "build_knn_device_ms": WL.build["knn_in_build_device_ms"],
+            "build_knn_mfma_frac_of_int8_peak": round(2.0 * args.large_base_n * args.large_base_n * d
+                                                      / (WL.build["knn_in_build_device_ms"] * 1e-3) / 1e12 / MFMA_I8_PEAK_TOPS, 4)}
         log(f"large base: {result['roofline_large_base']}")
         del WL
         torch.cuda.empty_cache()
